@@ -1,0 +1,150 @@
+/*
+ * dfp4.h - C ABI of libdfp4: BlockDialect / DialectFP4 hot path on AMD MI355X (gfx950).
+ *
+ * The library implements, as HIP kernels, the per-block online quantizer of
+ * the paper (Section 3.2: preprocessing and two-stage dialect selection;
+ * Section 3.3: rounding to the selected dialect), its inverse (Section 3.3,
+ * dequantization through the table of representable values) and the
+ * block-scaled integer matrix multiply that consumes quantized operands
+ * (Section 3.3: 4-bit integer products accumulated as integers inside a
+ * block pair, one exponent sum per block pair, floating-point accumulation
+ * across blocks), plus the MXFP4 format the paper compares against
+ * (Section 4.1, baseline).
+ *
+ * Conventions for every call
+ *   - Every data pointer is a DEVICE pointer owned by the caller.  The library
+ *     never allocates, frees or keeps user memory and never synchronizes.
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL is the
+ *     default stream) of the current device.
+ *   - Return value: DFP4_OK (0), or a negative DFP4_ERR_* code; on error nothing
+ *     has been enqueued.  dfp4_strerror() names a code.
+ *   - A block is 32 consecutive elements along K (the contraction dimension,
+ *     Appendix C: every operand is quantized along its multiplication
+ *     dimension).  K must be a multiple of 32.
+ *   - Inputs must be finite; the method does not define NaN or infinity.
+ *
+ * Storage of a quantized tensor [rows, K]  (Section 3.1: 1 sign bit + 3-bit
+ * index per element, 4-bit dialect identifier and a shared exponent per block;
+ * the byte layout is this library's choice)
+ *   codes    uint8 [rows, K/2]   element 2j in bits 3:0 of byte j, element 2j+1
+ *                                in bits 7:4; a 4-bit code is (sign << 3) | index,
+ *                                index = ascending rank of the magnitude in the
+ *                                dialect (0 -> 0.0, 7 -> largest)
+ *   dialect  uint8 [rows, K/32]  dialect identifier 0..15 (absent for MXFP4)
+ *   exponent uint8 [rows, K/32]  shared exponent e stored as e + 127, with
+ *                                e = clamp(floor(log2(block max)) - 2, -127, 127);
+ *                                an all-zero block stores 0
+ *   All three arrays are dense row-major (no padding between rows).
+ */
+#ifndef DFP4_H
+#define DFP4_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define DFP4_BLOCK 32
+
+enum {
+    DFP4_OK = 0,
+    DFP4_ERR_NULL = -1,       /* a required pointer is NULL */
+    DFP4_ERR_SHAPE = -2,      /* K % 32 != 0, negative size, A.K != W.K, ld < K, size above limit */
+    DFP4_ERR_ALIGN = -3,      /* pointer or leading dimension not aligned as documented */
+    DFP4_ERR_DTYPE = -4,      /* unknown dtype selector */
+    DFP4_ERR_WORKSPACE = -5,  /* workspace missing or too small */
+    DFP4_ERR_LAUNCH = -6      /* the HIP runtime refused the launch */
+};
+
+enum { DFP4_F32 = 0, DFP4_BF16 = 1 };
+
+typedef struct dfp4_tensor {
+    uint8_t* codes;     /* device, [rows, K/2],  4-byte aligned */
+    uint8_t* dialect;   /* device, [rows, K/32]; ignored (may be NULL) by mxfp4_* */
+    uint8_t* exponent;  /* device, [rows, K/32] */
+    int64_t rows;
+    int64_t K;
+} dfp4_tensor;
+
+/*
+ * Online DialectFP4 quantization (Section 3.2 and 3.3).
+ *   x_bf16   device, bf16 [rows, K] row-major with leading dimension ld_elems
+ *            (elements, >= K, multiple of 8); 16-byte aligned.
+ *   out      receives codes / dialect / exponent; out.rows and out.K must equal
+ *            rows and K.
+ * Per block: shared exponent from the block maximum; 5-bit magnitudes
+ * floor(4|x|/2^e); stage 1 picks the dialect pair whose largest value equals the
+ * block maximum rounded (half up) to a multiple of 0.5 (a rounded maximum of 8.0
+ * uses the 7.5 pair); stage 2 counts elements in each dialect's beneficial
+ * range, the larger count wins and the even dialect wins ties; each element
+ * takes the index of the nearest value of the chosen dialect, halfway cases
+ * going to the larger value.  rows == 0 is a no-op.
+ */
+int dfp4_quantize(const void* x_bf16, int64_t rows, int64_t K, int64_t ld_elems,
+                  dfp4_tensor out, void* stream);
+
+/*
+ * Dequantization (Section 3.3): y[r, k] = (-1)^sign * 0.5 * u[dialect][index] * 2^e.
+ *   y        device, [rows, K] with leading dimension ld_elems (>= K, multiple of 8),
+ *            16-byte aligned; y_dtype selects DFP4_F32 or DFP4_BF16 (both exact).
+ */
+int dfp4_dequantize(dfp4_tensor in, void* y, int y_dtype, int64_t ld_elems, void* stream);
+
+/*
+ * Block-scaled matrix multiply (Section 3.3): out = A * W^T,
+ *   out[m, n] = sum over blocks kb of 2^(ea[m,kb] + ew[n,kb] - 2) *
+ *               sum over k in kb of (+-ua[m,k]) * (+-uw[n,k])
+ * with u the 4-bit unsigned integers (half-units) the codes index.  The inner
+ * sums run on the int8 matrix cores with int32 accumulation and are exact;
+ * the outer sum is accumulated in fp32.
+ *   A        quantized [M, K]; W quantized [N, K] (both blocked along K)
+ *   out      device, [M, N] row-major, leading dimension ldc (elements, >= N);
+ *            out_dtype DFP4_F32 or DFP4_BF16 (round to nearest even)
+ *   workspace, workspace_bytes   device scratch of at least
+ *            dfp4_gemm_workspace_bytes(M, N, K) bytes, 256-byte aligned; may be
+ *            NULL when that size is 0.  Contents are undefined afterwards.
+ * M == 0 or N == 0 is a no-op.
+ */
+int dfp4_gemm(dfp4_tensor A, dfp4_tensor W, void* out, int out_dtype, int64_t ldc,
+              void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * The same product for `batch` independent problems of equal shape (attention
+ * score and context matmuls, Appendix C).  Problem b uses
+ *   A.codes + b * strideA_rows * K/2, A.dialect/exponent + b * strideA_rows * K/32
+ * (and likewise W with strideW_rows), and out + b * strideC elements.
+ * A.rows = M and W.rows = N are the per-problem sizes.
+ */
+int dfp4_gemm_batched(dfp4_tensor A, dfp4_tensor W, void* out, int out_dtype, int64_t ldc,
+                      int64_t batch, int64_t strideA_rows, int64_t strideW_rows, int64_t strideC,
+                      void* workspace, size_t workspace_bytes, void* stream);
+
+size_t dfp4_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
+
+/*
+ * MXFP4 comparison path (Section 4.1, baseline): FP4 E2M1 elements
+ * {0, 0.5, 1, 1.5, 2, 3, 4, 6} with the same shared exponent; elements are
+ * rounded to nearest, ties to the even code, magnitudes above 6 saturate.
+ * Same layouts; the dialect member of dfp4_tensor is ignored.
+ */
+int mxfp4_quantize(const void* x_bf16, int64_t rows, int64_t K, int64_t ld_elems,
+                   dfp4_tensor out, void* stream);
+int mxfp4_dequantize(dfp4_tensor in, void* y, int y_dtype, int64_t ld_elems, void* stream);
+int mxfp4_gemm(dfp4_tensor A, dfp4_tensor W, void* out, int out_dtype, int64_t ldc,
+               void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * The formatbook in use (Section 3.1): out[d * 8 + i] = half-unit magnitude
+ * (value = 0.5 * out[...]) of index i in dialect d, ascending.  `out` is a HOST
+ * pointer to 128 bytes.
+ */
+int dfp4_formatbook(uint8_t* out);
+
+const char* dfp4_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DFP4_H */

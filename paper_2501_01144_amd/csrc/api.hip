@@ -1,0 +1,140 @@
+// extern "C" entry points of libdfp4 (see include/dfp4.h): argument checks
+// and dispatch to the kernels.  No device memory is allocated here.
+#include <mutex>
+
+#include "common.h"
+#include "formatbook.h"
+
+namespace dfp4 {
+
+int device_cu_count() {
+    static std::mutex mu;
+    static int cached[64] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    std::lock_guard<std::mutex> lock(mu);
+    if (cached[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+            n = 256;
+        cached[dev] = n;
+    }
+    return cached[dev];
+}
+
+int check_quant_args(const void* dense, int64_t rows, int64_t K, int64_t ld, const dfp4_tensor& q,
+                     bool need_dialect) {
+    if (rows < 0 || K < 0 || K % kBlock != 0 || ld < K || q.rows != rows || q.K != K) return DFP4_ERR_SHAPE;
+    if (rows == 0 || K == 0) return DFP4_OK;
+    if (!dense || !q.codes || !q.exponent || (need_dialect && !q.dialect)) return DFP4_ERR_NULL;
+    if (ld % 8 != 0 || !aligned(dense, 16) || !aligned(q.codes, 4)) return DFP4_ERR_ALIGN;
+    return DFP4_OK;
+}
+
+static int check_gemm_args(const dfp4_tensor& A, const dfp4_tensor& W, const void* out, int out_dtype,
+                           int64_t ldc, bool need_dialect, const void* workspace, size_t workspace_bytes) {
+    if (A.rows < 0 || W.rows < 0 || A.K < 0 || A.K != W.K || A.K % kBlock != 0) return DFP4_ERR_SHAPE;
+    if (out_dtype != DFP4_F32 && out_dtype != DFP4_BF16) return DFP4_ERR_DTYPE;
+    if (A.rows == 0 || W.rows == 0) return DFP4_OK;
+    if (ldc < W.rows) return DFP4_ERR_SHAPE;
+    if (!out) return DFP4_ERR_NULL;
+    if (A.K > 0) {
+        if (!A.codes || !A.exponent || !W.codes || !W.exponent) return DFP4_ERR_NULL;
+        if (need_dialect && (!A.dialect || !W.dialect)) return DFP4_ERR_NULL;
+        if (!aligned(A.codes, 16) || !aligned(W.codes, 16)) return DFP4_ERR_ALIGN;
+    }
+    const size_t need = gemm_workspace_bytes(A.rows, W.rows, A.K);
+    if (need > 0) {
+        if (!workspace || workspace_bytes < need) return DFP4_ERR_WORKSPACE;
+        if (!aligned(workspace, 256)) return DFP4_ERR_ALIGN;
+    }
+    return DFP4_OK;
+}
+
+}  // namespace dfp4
+
+using namespace dfp4;
+
+extern "C" {
+
+int dfp4_quantize(const void* x_bf16, int64_t rows, int64_t K, int64_t ld_elems, dfp4_tensor out,
+                  void* stream) {
+    const int rc = check_quant_args(x_bf16, rows, K, ld_elems, out, true);
+    if (rc != DFP4_OK) return rc;
+    return launch_quantize(false, x_bf16, rows, K, ld_elems, out, static_cast<hipStream_t>(stream));
+}
+
+int mxfp4_quantize(const void* x_bf16, int64_t rows, int64_t K, int64_t ld_elems, dfp4_tensor out,
+                   void* stream) {
+    const int rc = check_quant_args(x_bf16, rows, K, ld_elems, out, false);
+    if (rc != DFP4_OK) return rc;
+    return launch_quantize(true, x_bf16, rows, K, ld_elems, out, static_cast<hipStream_t>(stream));
+}
+
+static int dequantize_common(bool mx, dfp4_tensor in, void* y, int y_dtype, int64_t ld, void* stream) {
+    if (y_dtype != DFP4_F32 && y_dtype != DFP4_BF16) return DFP4_ERR_DTYPE;
+    const int rc = check_quant_args(y, in.rows, in.K, ld, in, !mx);
+    if (rc != DFP4_OK) return rc;
+    return launch_dequantize(mx, in, y, y_dtype, ld, static_cast<hipStream_t>(stream));
+}
+
+int dfp4_dequantize(dfp4_tensor in, void* y, int y_dtype, int64_t ld_elems, void* stream) {
+    return dequantize_common(false, in, y, y_dtype, ld_elems, stream);
+}
+
+int mxfp4_dequantize(dfp4_tensor in, void* y, int y_dtype, int64_t ld_elems, void* stream) {
+    return dequantize_common(true, in, y, y_dtype, ld_elems, stream);
+}
+
+int dfp4_gemm(dfp4_tensor A, dfp4_tensor W, void* out, int out_dtype, int64_t ldc, void* workspace,
+              size_t workspace_bytes, void* stream) {
+    const int rc = check_gemm_args(A, W, out, out_dtype, ldc, true, workspace, workspace_bytes);
+    if (rc != DFP4_OK) return rc;
+    return launch_gemm(false, A, W, out, out_dtype, ldc, 1, 0, 0, 0, workspace, workspace_bytes,
+                       static_cast<hipStream_t>(stream));
+}
+
+int mxfp4_gemm(dfp4_tensor A, dfp4_tensor W, void* out, int out_dtype, int64_t ldc, void* workspace,
+               size_t workspace_bytes, void* stream) {
+    const int rc = check_gemm_args(A, W, out, out_dtype, ldc, false, workspace, workspace_bytes);
+    if (rc != DFP4_OK) return rc;
+    return launch_gemm(true, A, W, out, out_dtype, ldc, 1, 0, 0, 0, workspace, workspace_bytes,
+                       static_cast<hipStream_t>(stream));
+}
+
+int dfp4_gemm_batched(dfp4_tensor A, dfp4_tensor W, void* out, int out_dtype, int64_t ldc, int64_t batch,
+                      int64_t strideA_rows, int64_t strideW_rows, int64_t strideC, void* workspace,
+                      size_t workspace_bytes, void* stream) {
+    if (batch < 0 || strideA_rows < 0 || strideW_rows < 0 || strideC < 0) return DFP4_ERR_SHAPE;
+    const int rc = check_gemm_args(A, W, out, out_dtype, ldc, true, workspace, workspace_bytes);
+    if (rc != DFP4_OK) return rc;
+    return launch_gemm(false, A, W, out, out_dtype, ldc, batch, strideA_rows, strideW_rows, strideC,
+                       workspace, workspace_bytes, static_cast<hipStream_t>(stream));
+}
+
+size_t dfp4_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K) {
+    if (M < 0 || N < 0 || K < 0) return 0;
+    return gemm_workspace_bytes(M, N, K);
+}
+
+int dfp4_formatbook(uint8_t* out) {
+    if (!out) return DFP4_ERR_NULL;
+    for (int d = 0; d < kDialects; ++d)
+        for (int j = 0; j < 8; ++j) out[d * 8 + j] = kBook[d][j];
+    return DFP4_OK;
+}
+
+const char* dfp4_strerror(int code) {
+    switch (code) {
+        case DFP4_OK: return "ok";
+        case DFP4_ERR_NULL: return "null pointer";
+        case DFP4_ERR_SHAPE: return "bad shape (K % 32, negative size, mismatched K, ld < K or size above limit)";
+        case DFP4_ERR_ALIGN: return "misaligned pointer or leading dimension";
+        case DFP4_ERR_DTYPE: return "unknown dtype";
+        case DFP4_ERR_WORKSPACE: return "workspace missing or too small";
+        case DFP4_ERR_LAUNCH: return "kernel launch failed";
+        default: return "unknown error";
+    }
+}
+
+}  // extern "C"

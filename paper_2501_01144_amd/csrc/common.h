@@ -1,0 +1,32 @@
+// Shared host-side helpers of libdfp4 (argument checks, device properties).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/dfp4.h"
+
+namespace dfp4 {
+
+// Number of compute units of the current device (cached per device).
+int device_cu_count();
+
+inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+inline int check_launch() {
+    return hipGetLastError() == hipSuccess ? DFP4_OK : DFP4_ERR_LAUNCH;
+}
+
+// Argument checks shared by the quantize / dequantize entry points.
+int check_quant_args(const void* dense, int64_t rows, int64_t K, int64_t ld, const dfp4_tensor& q,
+                     bool need_dialect);
+
+// kernels (defined in the .hip files)
+int launch_quantize(bool mx, const void* x, int64_t rows, int64_t K, int64_t ld, dfp4_tensor out,
+                    hipStream_t stream);
+int launch_dequantize(bool mx, dfp4_tensor in, void* y, int y_dtype, int64_t ld, hipStream_t stream);
+int launch_gemm(bool mx, dfp4_tensor A, dfp4_tensor W, void* out, int out_dtype, int64_t ldc,
+                int64_t batch, int64_t strideA_rows, int64_t strideW_rows, int64_t strideC,
+                void* workspace, size_t workspace_bytes, hipStream_t stream);
+size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
+
+}  // namespace dfp4

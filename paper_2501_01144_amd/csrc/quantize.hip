@@ -1,0 +1,208 @@
+// Online DialectFP4 / MXFP4 quantizer for gfx950 (paper Sections 3.2 and 3.3).
+//
+// Mapping.  A block is 32 bf16 = 64 bytes; four lanes own one block, each lane
+// holds 8 elements (one 16-byte load), so a wavefront load instruction reads
+// 1 KiB contiguously.  A wavefront handles 4 such loads (64 blocks) per loop
+// iteration; all four are issued before any arithmetic.  Block reductions
+// (maximum, stage-2 votes) are two DPP quad-permute steps.
+//
+// Arithmetic per element (all exact):
+//   t = floor(4 |x| / 2^e)  as  cvt_u32(ldexp(|x|, 129 - exponent_byte))
+// The odd element of a bf16 pair is used with the even element's bits still in
+// the low half of the dword: that adds less than one bf16 ulp, which cannot
+// cross a multiple of 0.25 because every multiple of 0.25 below 8 is a bf16 value.
+// Index and vote lookups go through LDS tables keyed by two 5-bit magnitudes
+// (tables are built at compile time from the formatbook, see formatbook.h).
+#include "common.h"
+#include "formatbook.h"
+
+namespace dfp4 {
+
+__device__ const QuantTables g_quant_tables = make_quant_tables();
+
+namespace {
+
+constexpr int kThreads = 1024;
+constexpr int kWaves = kThreads / 64;
+constexpr int kPasses = 4;             // 16-byte loads per lane per iteration
+constexpr int kBlocksPerPass = 16;     // 64 lanes / 4 lanes per block
+
+__device__ __forceinline__ float as_f(uint32_t u) { return __builtin_bit_cast(float, u); }
+__device__ __forceinline__ uint32_t as_u(float f) { return __builtin_bit_cast(uint32_t, f); }
+
+// value of the lane's quad neighbour: XOR 1 (0xB1) and XOR 2 (0x4E)
+template <int CTRL>
+__device__ __forceinline__ uint32_t quad(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xf, 0xf, true);
+}
+
+__device__ __forceinline__ uint32_t sign_nibbles(const uint32_t (&w)[4]) {
+    // bf16 sign bits (bit 15 / bit 31 of dword j) -> bit 3 / bit 7 of code byte j
+    uint32_t s = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        s |= (((w[j] >> 12) & 0x8u) | ((w[j] >> 24) & 0x80u)) << (8 * j);
+    return s;
+}
+
+// Block maximum over the quad's 32 elements, as bf16 bits (sign cleared).
+__device__ __forceinline__ uint32_t block_amax_bits(const uint32_t (&w)[4]) {
+    float m = 0.0f;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        m = __builtin_fmaxf(m, __builtin_fabsf(as_f(w[j] << 16)));
+        m = __builtin_fmaxf(m, __builtin_fabsf(as_f(w[j])));
+    }
+    m = __builtin_fmaxf(m, as_f(quad<0xB1>(as_u(m))));
+    m = __builtin_fmaxf(m, as_f(quad<0x4E>(as_u(m))));
+    return as_u(m) >> 16;
+}
+
+// One lane's share (8 elements) of one DialectFP4 block.
+__device__ __forceinline__ void dfp4_pass(const uint4& wv, const uint8_t* __restrict__ lut_s,
+                                          const uint8_t* __restrict__ lut_q, uint32_t& code,
+                                          uint32_t& ebyte, uint32_t& dial) {
+    const uint32_t w[4] = {wv.x, wv.y, wv.z, wv.w};
+    const uint32_t ab = block_amax_bits(w);
+    // exponent byte = biased exponent of the maximum, minus 2, floored at 0
+    const int byte = max((int)(ab >> 7) - 2, 0);
+    const int n = 129 - byte;                       // 4 |x| / 2^e = |x| * 2^n
+    // stage 1: block maximum rounded half-up to a multiple of 0.5 selects the pair
+    const uint32_t tmax = (uint32_t)ldexpf(as_f(ab << 16), n);
+    const uint32_t r = min(max((tmax + 1u) >> 1, 8u), 15u);
+    const uint32_t pair = 15u - r;
+    uint32_t key[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const uint32_t t0 = (uint32_t)ldexpf(__builtin_fabsf(as_f(w[j] << 16)), n);
+        const uint32_t t1 = (uint32_t)ldexpf(__builtin_fabsf(as_f(w[j])), n);
+        key[j] = t0 | (t1 << 5);
+    }
+    // stage 2: votes of this lane's 8 elements, then of the quad
+    const uint8_t* s = lut_s + pair * 1024u;
+    const uint32_t cnt = (uint32_t)s[key[0]] + s[key[1]] + s[key[2]] + s[key[3]];
+    uint32_t v = (cnt & 0xfu) | ((cnt & 0xf0u) << 12);
+    v += quad<0xB1>(v);
+    v += quad<0x4E>(v);
+    dial = 2u * pair + ((v >> 16) > (v & 0xffffu) ? 1u : 0u);
+    const uint8_t* q = lut_q + dial * 1024u;
+    code = (uint32_t)q[key[0]] | ((uint32_t)q[key[1]] << 8) | ((uint32_t)q[key[2]] << 16) |
+           ((uint32_t)q[key[3]] << 24) | sign_nibbles(w);
+    ebyte = (uint32_t)byte;
+}
+
+// One lane's share of one MXFP4 block: E2M1, round to nearest, ties to even code.
+__device__ __forceinline__ void mxfp4_pass(const uint4& wv, const uint8_t* __restrict__ lut_mx,
+                                           uint32_t& code, uint32_t& ebyte) {
+    const uint32_t w[4] = {wv.x, wv.y, wv.z, wv.w};
+    const uint32_t ab = block_amax_bits(w);
+    const int byte = max((int)(ab >> 7) - 2, 0);
+    const int n = 129 - byte;
+    uint32_t c = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const float v0 = ldexpf(__builtin_fabsf(as_f(w[j] << 16)), n);
+        const float v1 = ldexpf(__builtin_fabsf(as_f(w[j] & 0xffff0000u)), n);
+        const uint32_t t0 = (uint32_t)v0, t1 = (uint32_t)v1;
+        const uint32_t k0 = 2u * t0 + ((float)t0 != v0 ? 1u : 0u);
+        const uint32_t k1 = 2u * t1 + ((float)t1 != v1 ? 1u : 0u);
+        c |= ((uint32_t)lut_mx[k0] | ((uint32_t)lut_mx[k1] << 4)) << (8 * j);
+    }
+    code = c | sign_nibbles(w);
+    ebyte = (uint32_t)byte;
+}
+
+template <bool MX, bool CONTIG>
+__global__ __launch_bounds__(kThreads) void quantize_kernel(
+    const uint16_t* __restrict__ x, int64_t ld, uint32_t blocks_per_row, uint32_t nblocks,
+    uint32_t* __restrict__ codes, uint8_t* __restrict__ dialect, uint8_t* __restrict__ exponent) {
+    __shared__ __attribute__((aligned(16))) uint8_t lds_q[MX ? 64 : kDialects * 1024];
+    __shared__ __attribute__((aligned(16))) uint8_t lds_s[MX ? 16 : kPairs * 1024];
+    if constexpr (MX) {
+        if (threadIdx.x < 64) lds_q[threadIdx.x] = g_quant_tables.mx[threadIdx.x];
+    } else {
+        const uint4* gq = reinterpret_cast<const uint4*>(g_quant_tables.q);
+        const uint4* gs = reinterpret_cast<const uint4*>(g_quant_tables.s);
+        reinterpret_cast<uint4*>(lds_q)[threadIdx.x] = gq[threadIdx.x];          // 1024 x 16 B
+        if (threadIdx.x < 512) reinterpret_cast<uint4*>(lds_s)[threadIdx.x] = gs[threadIdx.x];
+    }
+    __syncthreads();
+
+    const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+    const uint32_t quad_id = lane >> 2, sub = lane & 3u;
+    const uint32_t nsuper = (nblocks + 63u) / 64u;
+    const uint32_t stride = gridDim.x * kWaves;
+    for (uint32_t sc = blockIdx.x * kWaves + wave; sc < nsuper; sc += stride) {
+        uint4 w[kPasses];
+        uint32_t blk[kPasses];
+#pragma unroll
+        for (int p = 0; p < kPasses; ++p) {
+            blk[p] = sc * 64u + p * kBlocksPerPass + quad_id;
+            if (blk[p] < nblocks) {
+                int64_t off;
+                if constexpr (CONTIG) {
+                    off = (int64_t)blk[p] * kBlock + sub * 8;
+                } else {
+                    const uint32_t row = blk[p] / blocks_per_row;
+                    off = (int64_t)row * ld + (int64_t)(blk[p] - row * blocks_per_row) * kBlock + sub * 8;
+                }
+                w[p] = *reinterpret_cast<const uint4*>(x + off);
+            } else {
+                w[p] = make_uint4(0, 0, 0, 0);
+            }
+        }
+        uint32_t eb[kPasses], dl[kPasses];
+#pragma unroll
+        for (int p = 0; p < kPasses; ++p) {
+            uint32_t code;
+            if constexpr (MX) {
+                mxfp4_pass(w[p], lds_q, code, eb[p]);
+                dl[p] = 0;
+            } else {
+                dfp4_pass(w[p], lds_s, lds_q, code, eb[p], dl[p]);
+            }
+            if (blk[p] < nblocks) codes[(size_t)blk[p] * 4u + sub] = code;
+        }
+        // lane (quad_id, sub) stores the per-block bytes of pass `sub`:
+        // one byte-store instruction covers the wave's 64 consecutive blocks
+        const uint32_t e_sel = sub == 0 ? eb[0] : sub == 1 ? eb[1] : sub == 2 ? eb[2] : eb[3];
+        const uint32_t bm = sc * 64u + sub * kBlocksPerPass + quad_id;
+        if (bm < nblocks) {
+            exponent[bm] = (uint8_t)e_sel;
+            if constexpr (!MX) {
+                const uint32_t d_sel = sub == 0 ? dl[0] : sub == 1 ? dl[1] : sub == 2 ? dl[2] : dl[3];
+                dialect[bm] = (uint8_t)d_sel;
+            }
+        }
+    }
+}
+
+}  // namespace
+
+int launch_quantize(bool mx, const void* x, int64_t rows, int64_t K, int64_t ld, dfp4_tensor out,
+                    hipStream_t stream) {
+    const int64_t nblocks64 = rows * (K / kBlock);
+    if (nblocks64 == 0) return DFP4_OK;
+    if (nblocks64 >= (int64_t)1 << 31) return DFP4_ERR_SHAPE;
+    const uint32_t nblocks = (uint32_t)nblocks64;
+    const uint32_t nsuper = (nblocks + 63u) / 64u;
+    const uint32_t want = (nsuper + kWaves - 1) / kWaves;
+    const uint32_t cap = (uint32_t)device_cu_count() * 2u;
+    const uint32_t grid = want < cap ? want : cap;
+    const bool contig = (ld == K);
+    const uint16_t* xp = static_cast<const uint16_t*>(x);
+    uint32_t* cp = reinterpret_cast<uint32_t*>(out.codes);
+    const uint32_t kb = (uint32_t)(K / kBlock);
+#define DFP4_LAUNCH(MXV, CV)                                                                    \
+    hipLaunchKernelGGL((quantize_kernel<MXV, CV>), dim3(grid), dim3(kThreads), 0, stream, xp, ld, \
+                       kb, nblocks, cp, out.dialect, out.exponent)
+    if (mx) {
+        if (contig) DFP4_LAUNCH(true, true); else DFP4_LAUNCH(true, false);
+    } else {
+        if (contig) DFP4_LAUNCH(false, true); else DFP4_LAUNCH(false, false);
+    }
+#undef DFP4_LAUNCH
+    return check_launch();
+}
+
+}  // namespace dfp4

@@ -1,0 +1,190 @@
+"""ctypes binding of libdfp4.so: the same calls as include/dfp4.h, taking torch
+tensors for device memory and the current torch stream.  Argument marshalling
+only: every step of the path runs in the HIP kernels.  There is no fallback;
+if the library is missing or a call fails, an exception is raised.
+"""
+import ctypes
+import os
+from dataclasses import dataclass
+
+import torch
+
+BLOCK = 32
+F32, BF16 = 0, 1
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libdfp4.so")
+_lib = None
+
+
+class Dfp4Error(RuntimeError):
+    pass
+
+
+class _CTensor(ctypes.Structure):
+    _fields_ = [("codes", ctypes.c_void_p), ("dialect", ctypes.c_void_p), ("exponent", ctypes.c_void_p),
+                ("rows", ctypes.c_int64), ("K", ctypes.c_int64)]
+
+
+SYMBOLS = [
+    "dfp4_quantize", "dfp4_dequantize", "dfp4_gemm", "dfp4_gemm_batched", "dfp4_gemm_workspace_bytes",
+    "mxfp4_quantize", "mxfp4_dequantize", "mxfp4_gemm", "dfp4_formatbook", "dfp4_strerror",
+]
+
+
+def lib_path():
+    return _LIB_PATH
+
+
+def load():
+    """Load libdfp4.so (built by `python -m paper_2501_01144_amd.build`)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise Dfp4Error(f"{_LIB_PATH} not found: build it with `python -m paper_2501_01144_amd.build`")
+    lib = ctypes.CDLL(_LIB_PATH)
+    i64, vp, ci = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
+    lib.dfp4_quantize.argtypes = [vp, i64, i64, i64, _CTensor, vp]
+    lib.mxfp4_quantize.argtypes = [vp, i64, i64, i64, _CTensor, vp]
+    lib.dfp4_dequantize.argtypes = [_CTensor, vp, ci, i64, vp]
+    lib.mxfp4_dequantize.argtypes = [_CTensor, vp, ci, i64, vp]
+    lib.dfp4_gemm.argtypes = [_CTensor, _CTensor, vp, ci, i64, vp, ctypes.c_size_t, vp]
+    lib.mxfp4_gemm.argtypes = [_CTensor, _CTensor, vp, ci, i64, vp, ctypes.c_size_t, vp]
+    lib.dfp4_gemm_batched.argtypes = [_CTensor, _CTensor, vp, ci, i64, i64, i64, i64, i64, vp,
+                                      ctypes.c_size_t, vp]
+    lib.dfp4_gemm_workspace_bytes.argtypes = [i64, i64, i64]
+    lib.dfp4_gemm_workspace_bytes.restype = ctypes.c_size_t
+    lib.dfp4_formatbook.argtypes = [vp]
+    lib.dfp4_strerror.argtypes = [ci]
+    lib.dfp4_strerror.restype = ctypes.c_char_p
+    for name in ("dfp4_quantize", "mxfp4_quantize", "dfp4_dequantize", "mxfp4_dequantize", "dfp4_gemm",
+                 "mxfp4_gemm", "dfp4_gemm_batched", "dfp4_formatbook"):
+        getattr(lib, name).restype = ci
+    _lib = lib
+    return lib
+
+
+def strerror(code):
+    return load().dfp4_strerror(int(code)).decode()
+
+
+def _check(rc, what):
+    if rc != 0:
+        raise Dfp4Error(f"{what} failed: {strerror(rc)} ({rc})")
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ptr(t):
+    return ctypes.c_void_p(t.data_ptr() if t is not None and t.numel() > 0 else 0) if t is not None \
+        else ctypes.c_void_p(0)
+
+
+@dataclass
+class QTensor:
+    """A quantized [rows, K] tensor on the device (layouts in include/dfp4.h)."""
+    codes: torch.Tensor            # uint8 [rows, K/2]
+    dialect: torch.Tensor          # uint8 [rows, K/32] or None (MXFP4)
+    exponent: torch.Tensor         # uint8 [rows, K/32]
+    rows: int
+    K: int
+
+    def c(self):
+        return _CTensor(_ptr(self.codes).value, _ptr(self.dialect).value, _ptr(self.exponent).value,
+                        self.rows, self.K)
+
+
+def empty_qtensor(rows, K, device, mx=False):
+    return QTensor(torch.empty((rows, K // 2), dtype=torch.uint8, device=device),
+                   None if mx else torch.empty((rows, K // BLOCK), dtype=torch.uint8, device=device),
+                   torch.empty((rows, K // BLOCK), dtype=torch.uint8, device=device), rows, K)
+
+
+def _quantize(fn, what, x, out, mx):
+    assert x.dtype == torch.bfloat16 and x.dim() == 2 and x.is_cuda and x.stride(1) == 1
+    rows, K = x.shape
+    if out is None:
+        out = empty_qtensor(rows, K, x.device, mx)
+    ld = x.stride(0) if rows > 1 else K
+    _check(fn(_ptr(x), rows, K, ld, out.c(), _stream()), what)
+    return out
+
+
+def quantize(x, out=None):
+    """dfp4_quantize: bf16 [rows, K] (row stride allowed) -> QTensor."""
+    return _quantize(load().dfp4_quantize, "dfp4_quantize", x, out, False)
+
+
+def mxfp4_quantize(x, out=None):
+    return _quantize(load().mxfp4_quantize, "mxfp4_quantize", x, out, True)
+
+
+def _dequantize(fn, what, q, dtype, out):
+    if out is None:
+        out = torch.empty((q.rows, q.K), dtype=dtype, device=q.codes.device)
+    assert out.dtype in (torch.float32, torch.bfloat16) and out.stride(1) == 1
+    ld = out.stride(0) if q.rows > 1 else q.K
+    _check(fn(q.c(), _ptr(out), F32 if out.dtype == torch.float32 else BF16, ld, _stream()), what)
+    return out
+
+
+def dequantize(q, dtype=torch.float32, out=None):
+    return _dequantize(load().dfp4_dequantize, "dfp4_dequantize", q, dtype, out)
+
+
+def mxfp4_dequantize(q, dtype=torch.float32, out=None):
+    return _dequantize(load().mxfp4_dequantize, "mxfp4_dequantize", q, dtype, out)
+
+
+def gemm_workspace_bytes(M, N, K):
+    return int(load().dfp4_gemm_workspace_bytes(M, N, K))
+
+
+def _workspace(M, N, K, device, workspace):
+    need = gemm_workspace_bytes(M, N, K)
+    if workspace is None and need > 0:
+        workspace = torch.empty(need, dtype=torch.uint8, device=device)
+    return workspace, (workspace.numel() if workspace is not None else 0)
+
+
+def _gemm(fn, what, a, w, dtype, out, workspace):
+    if out is None:
+        out = torch.empty((a.rows, w.rows), dtype=dtype, device=a.codes.device)
+    assert out.dtype in (torch.float32, torch.bfloat16) and out.stride(1) == 1
+    workspace, nbytes = _workspace(a.rows, w.rows, a.K, out.device, workspace)
+    ldc = out.stride(0) if a.rows > 1 else w.rows
+    _check(fn(a.c(), w.c(), _ptr(out), F32 if out.dtype == torch.float32 else BF16, ldc,
+              _ptr(workspace), nbytes, _stream()), what)
+    return out
+
+
+def gemm(a, w, dtype=torch.float32, out=None, workspace=None):
+    """dfp4_gemm: out[M, N] = A[M, K] * W[N, K]^T on quantized operands."""
+    return _gemm(load().dfp4_gemm, "dfp4_gemm", a, w, dtype, out, workspace)
+
+
+def mxfp4_gemm(a, w, dtype=torch.float32, out=None, workspace=None):
+    return _gemm(load().mxfp4_gemm, "mxfp4_gemm", a, w, dtype, out, workspace)
+
+
+def gemm_batched(a, w, batch, M, N, dtype=torch.float32, out=None, workspace=None):
+    """dfp4_gemm_batched: a holds batch*M rows, w batch*N rows (problem after problem);
+    out [batch, M, N]."""
+    if out is None:
+        out = torch.empty((batch, M, N), dtype=dtype, device=a.codes.device)
+    assert out.is_contiguous()
+    ac, wc = a.c(), w.c()
+    ac.rows, wc.rows = M, N
+    workspace, nbytes = _workspace(M, N, a.K, out.device, workspace)
+    _check(load().dfp4_gemm_batched(ac, wc, _ptr(out), F32 if out.dtype == torch.float32 else BF16, N,
+                                    batch, M, N, M * N, _ptr(workspace), nbytes, _stream()),
+           "dfp4_gemm_batched")
+    return out
+
+
+def formatbook():
+    """The library's formatbook as a 16 x 8 list of half-unit magnitudes."""
+    buf = (ctypes.c_uint8 * 128)()
+    _check(load().dfp4_formatbook(ctypes.cast(buf, ctypes.c_void_p)), "dfp4_formatbook")
+    return [[int(buf[d * 8 + j]) for j in range(8)] for d in range(16)]

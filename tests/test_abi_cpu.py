@@ -1,0 +1,84 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports
+every function include/dfp4.h declares, reports the formatbook the oracle
+uses, and rejects bad arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from oracle import dfp4_oracle as O
+from paper_2501_01144_amd import dfp4
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(dfp4.lib_path()):
+        from paper_2501_01144_amd.build import build_library
+        build_library(verbose=False)
+    return dfp4.load()
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "dfp4.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b((?:dfp4|mxfp4)_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = _declared_functions()
+    assert len(names) >= 10
+    assert sorted(dfp4.SYMBOLS) == names
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_formatbook_matches_the_oracle_table(lib):
+    assert dfp4.formatbook() == O.FORMATBOOK_HALF_UNITS.tolist()
+
+
+def test_strerror(lib):
+    assert dfp4.strerror(0) == "ok"
+    for code in range(-6, 0):
+        assert dfp4.strerror(code) not in ("ok", "unknown error")
+    assert dfp4.strerror(-99) == "unknown error"
+
+
+def _t(codes=0, dialect=0, exponent=0, rows=0, K=0):
+    return dfp4._CTensor(codes, dialect, exponent, rows, K)
+
+
+def test_argument_errors_are_reported_without_a_device(lib):
+    vp = ctypes.c_void_p
+    # K not a multiple of 32, negative rows, ld < K, mismatched out shape
+    assert lib.dfp4_quantize(vp(16), 4, 48, 48, _t(16, 16, 16, 4, 48), vp(0)) == -2
+    assert lib.dfp4_quantize(vp(16), -1, 64, 64, _t(16, 16, 16, -1, 64), vp(0)) == -2
+    assert lib.dfp4_quantize(vp(16), 4, 64, 32, _t(16, 16, 16, 4, 64), vp(0)) == -2
+    assert lib.dfp4_quantize(vp(16), 4, 64, 64, _t(16, 16, 16, 4, 32), vp(0)) == -2
+    # null pointers
+    assert lib.dfp4_quantize(vp(0), 4, 64, 64, _t(16, 16, 16, 4, 64), vp(0)) == -1
+    assert lib.dfp4_quantize(vp(16), 4, 64, 64, _t(16, 0, 16, 4, 64), vp(0)) == -1
+    assert lib.mxfp4_quantize(vp(16), 4, 64, 64, _t(0, 0, 16, 4, 64), vp(0)) == -1
+    # alignment: x must be 16-byte aligned, ld a multiple of 8
+    assert lib.dfp4_quantize(vp(8), 4, 64, 64, _t(16, 16, 16, 4, 64), vp(0)) == -3
+    assert lib.dfp4_quantize(vp(16), 4, 64, 68, _t(16, 16, 16, 4, 64), vp(0)) == -3
+    # dtype
+    assert lib.dfp4_dequantize(_t(16, 16, 16, 4, 64), vp(16), 7, 64, vp(0)) == -4
+    assert lib.dfp4_gemm(_t(16, 16, 16, 4, 64), _t(16, 16, 16, 4, 64), vp(16), 9, 4, vp(0), 0, vp(0)) == -4
+    # gemm: mismatched K, ldc < N, null output
+    assert lib.dfp4_gemm(_t(16, 16, 16, 4, 64), _t(16, 16, 16, 4, 96), vp(16), 0, 4, vp(0), 0, vp(0)) == -2
+    assert lib.dfp4_gemm(_t(16, 16, 16, 4, 64), _t(16, 16, 16, 8, 64), vp(16), 0, 4, vp(0), 0, vp(0)) == -2
+    assert lib.dfp4_gemm(_t(16, 16, 16, 4, 64), _t(16, 16, 16, 4, 64), vp(0), 0, 4, vp(0), 0, vp(0)) == -1
+    # empty problems succeed as no-ops
+    assert lib.dfp4_quantize(vp(0), 0, 64, 64, _t(0, 0, 0, 0, 64), vp(0)) == 0
+    assert lib.dfp4_gemm(_t(0, 0, 0, 0, 64), _t(16, 16, 16, 4, 64), vp(0), 0, 4, vp(0), 0, vp(0)) == 0
+    assert lib.dfp4_formatbook(vp(0)) == -1
+
+
+def test_binding_refuses_to_run_without_the_library(monkeypatch):
+    monkeypatch.setattr(dfp4, "_lib", None)
+    monkeypatch.setattr(dfp4, "_LIB_PATH", "/nonexistent/libdfp4.so")
+    with pytest.raises(dfp4.Dfp4Error):
+        dfp4.load()

@@ -1,0 +1,263 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on
+the same seeded inputs.  Quantizer outputs (codes, dialect ids, exponent
+bytes) must match bit for bit; dequantization is exact; the GEMM must satisfy
+|out - ref| <= 1e-5 * sum_k |A^[m,k]| |W^[n,k]| with ref the float64 product of
+the oracle's dequantized operands."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import dfp4_oracle as O
+from oracle import mxfp4_oracle as MX
+from paper_2501_01144_amd import dfp4, synth
+
+pytestmark = pytest.mark.gpu
+GEMM_RTOL = 1e-5
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _library():
+    assert torch.cuda.is_available(), "GPU tests need a device"
+    dfp4.load()
+
+
+def _dev(x):
+    return x.cuda()
+
+
+def _np(t):
+    return t.cpu().numpy()
+
+
+def _assert_quant_equal(q, ref, what):
+    codes, dialect, expo = ref
+    got_e, got_d, got_c = _np(q.exponent), _np(q.dialect), _np(q.codes)
+    assert np.array_equal(got_e, expo), f"{what}: exponent bytes differ at {np.argwhere(got_e != expo)[:4]}"
+    assert np.array_equal(got_d, dialect), f"{what}: dialect ids differ at {np.argwhere(got_d != dialect)[:4]}"
+    assert np.array_equal(got_c, codes), f"{what}: codes differ at {np.argwhere(got_c != codes)[:4]}"
+
+
+def _check_quantize(x_bf16, what):
+    print(f"quantize parity: {what} shape={tuple(x_bf16.shape)}", flush=True)
+    q = dfp4.quantize(_dev(x_bf16))
+    torch.cuda.synchronize()
+    _assert_quant_equal(q, O.dfp4_quantize(synth.to_f64(x_bf16)), what)
+    qm = dfp4.mxfp4_quantize(_dev(x_bf16))
+    torch.cuda.synchronize()
+    codes, expo = MX.mxfp4_quantize(synth.to_f64(x_bf16))
+    assert np.array_equal(_np(qm.exponent), expo), f"{what}: mx exponent"
+    assert np.array_equal(_np(qm.codes), codes), f"{what}: mx codes at {np.argwhere(_np(qm.codes) != codes)[:4]}"
+    return q, qm
+
+
+# --------------------------------------------------------------------------
+# quantizer
+# --------------------------------------------------------------------------
+def test_quantize_single_linear_activation():
+    a, _ = synth.single_linear(seed=0)
+    _check_quantize(a, "config1 A")
+
+
+@pytest.mark.parametrize("rows,K", [(1, 32), (3, 96), (5, 2048), (65, 64), (127, 4096), (1000, 1056)])
+def test_quantize_ragged_shapes(rows, K):
+    # sizes that end inside a wavefront's 64-block group and inside a 16-block load
+    _check_quantize(synth.student_t(rows, K, 3.0, seed=rows + K), f"t3 {rows}x{K}")
+
+
+def test_quantize_every_bf16_value():
+    x = synth.all_bf16_bit_patterns()                       # [2040, 32]: one block per row
+    _check_quantize(x, "all finite bf16 patterns")
+    # each value also as a lone element next to a larger block maximum
+    g = torch.Generator().manual_seed(1)
+    y = x[torch.randperm(x.shape[0], generator=g)].reshape(-1, 64)
+    _check_quantize(y, "all finite bf16 patterns, shuffled pairs of rows")
+
+
+def test_quantize_degenerate_blocks():
+    x = torch.zeros(8, 128, dtype=torch.bfloat16)
+    x[1, 5] = -0.0
+    x[2, 40] = 1.0                                          # single nonzero
+    x[3, :32] = 7.875                                       # rounded maximum 8.0
+    x[3, 32:64] = 7.75
+    x[4, 64:96] = torch.tensor(2.0 ** -133).to(torch.bfloat16)   # smallest subnormal
+    x[5, :] = torch.tensor(3.3895e38).to(torch.bfloat16)    # largest finite
+    x[6, ::3] = -1.5
+    x[7, 96:] = torch.linspace(-8, 8, 32).to(torch.bfloat16)
+    _check_quantize(x, "degenerate blocks")
+
+
+def test_quantize_wide_dynamic_range_and_ties():
+    g = torch.Generator().manual_seed(4)
+    x = torch.randn(256, 512, generator=g) * torch.exp2(torch.randint(-120, 120, (256, 16), generator=g)
+                                                        .repeat_interleave(32, dim=1).float())
+    _check_quantize(x.to(torch.bfloat16), "wide range")
+    ties = (torch.randint(-64, 64, (256, 512), generator=g).float() / 8).to(torch.bfloat16)
+    _check_quantize(ties, "multiples of 1/8 (every rounding tie)")
+
+
+def test_quantize_strided_rows():
+    base = synth.student_t(64, 1024, 3.0, seed=9)
+    view = base[:, 128:128 + 512]                           # ld = 1024, K = 512
+    q = dfp4.quantize(_dev(base)[:, 128:128 + 512])
+    torch.cuda.synchronize()
+    _assert_quant_equal(q, O.dfp4_quantize(synth.to_f64(view.contiguous())), "strided")
+
+
+def test_quantize_streaming_tensor_sampled_rows():
+    # full-size streaming tensor in the benchmark's launch configuration;
+    # the oracle checks a seeded sample of rows
+    x = synth.student_t(8192, 4096, 3.0, seed=3)
+    q = dfp4.quantize(_dev(x))
+    qm = dfp4.mxfp4_quantize(_dev(x))
+    torch.cuda.synchronize()
+    rows = np.sort(np.random.default_rng(0).choice(8192, 96, replace=False))
+    rows = np.concatenate([rows, [0, 8191]])
+    ref = O.dfp4_quantize(synth.to_f64(x[rows]))
+    assert np.array_equal(_np(q.codes)[rows], ref[0])
+    assert np.array_equal(_np(q.dialect)[rows], ref[1])
+    assert np.array_equal(_np(q.exponent)[rows], ref[2])
+    refm = MX.mxfp4_quantize(synth.to_f64(x[rows]))
+    assert np.array_equal(_np(qm.codes)[rows], refm[0])
+    assert np.array_equal(_np(qm.exponent)[rows], refm[1])
+    # properties that hold at any size: ids in range, exponent = max exponent field - 2
+    assert int(q.dialect.max()) <= 15
+    amax = x.abs().view(8192, -1, 32).amax(dim=2).float()
+    _, ex = torch.frexp(amax)                               # amax = m * 2^ex, m in [0.5, 1)
+    want = torch.where(amax == 0, torch.zeros_like(ex), torch.clamp(ex - 1 - 2 + 127, min=0)).to(torch.uint8)
+    assert torch.equal(q.exponent.cpu(), want)
+
+
+# --------------------------------------------------------------------------
+# dequantizer
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_dequantize_exact(dtype):
+    x = torch.cat([synth.student_t(37, 1088, 3.0, seed=12),
+                   synth.all_bf16_bit_patterns().reshape(-1, 1088)])
+    xf = synth.to_f64(x)
+    q = dfp4.quantize(_dev(x))
+    y = dfp4.dequantize(q, dtype)
+    torch.cuda.synchronize()
+    ref = O.dfp4_dequantize(*O.dfp4_quantize(xf))
+    got = y.cpu().to(torch.float64).numpy()
+    assert np.array_equal(got, ref)
+    assert np.array_equal(np.signbit(got), np.signbit(ref))
+    qm = dfp4.mxfp4_quantize(_dev(x))
+    ym = dfp4.mxfp4_dequantize(qm, dtype)
+    torch.cuda.synchronize()
+    assert np.array_equal(ym.cpu().to(torch.float64).numpy(), MX.mxfp4_dequantize(*MX.mxfp4_quantize(xf)))
+
+
+def test_dequantize_strided_output():
+    x = synth.gaussian(16, 256, 1.0, seed=5)
+    q = dfp4.quantize(_dev(x))
+    buf = torch.full((16, 512), 99.0, dtype=torch.float32, device="cuda")
+    dfp4.dequantize(q, out=buf[:, 64:64 + 256])
+    torch.cuda.synchronize()
+    ref = O.dfp4_dequantize(*O.dfp4_quantize(synth.to_f64(x)))
+    assert np.array_equal(buf[:, 64:320].cpu().double().numpy(), ref)
+    assert (buf[:, :64] == 99).all() and (buf[:, 320:] == 99).all()
+
+
+# --------------------------------------------------------------------------
+# GEMM
+# --------------------------------------------------------------------------
+def _gemm_ref(a_f64, w_f64, mx=False):
+    if mx:
+        ad = MX.mxfp4_dequantize(*MX.mxfp4_quantize(a_f64))
+        wd = MX.mxfp4_dequantize(*MX.mxfp4_quantize(w_f64))
+    else:
+        ad = O.dfp4_dequantize(*O.dfp4_quantize(a_f64))
+        wd = O.dfp4_dequantize(*O.dfp4_quantize(w_f64))
+    return ad @ wd.T, np.abs(ad) @ np.abs(wd).T
+
+
+def _assert_gemm_close(got, ref, absdot, what, bf16=False):
+    got = got.cpu().to(torch.float64).numpy()
+    if bf16:
+        want = torch.from_numpy(ref).to(torch.bfloat16).to(torch.float64).numpy()
+        ulp = np.exp2(np.floor(np.log2(np.maximum(np.abs(want), 1e-300))) - 7)
+        assert (np.abs(got - want) <= ulp + GEMM_RTOL * absdot).all(), what
+        return
+    err = np.abs(got - ref)
+    bad = err > GEMM_RTOL * absdot
+    assert not bad.any(), f"{what}: {bad.sum()} outputs off, worst {np.max(err / np.maximum(absdot, 1e-300)):.3e}"
+
+
+def test_gemm_single_linear_full():
+    a, w = synth.single_linear(seed=0)
+    print("gemm parity: config1 32x4096x4096", flush=True)
+    out = dfp4.gemm(dfp4.quantize(_dev(a)), dfp4.quantize(_dev(w)))
+    torch.cuda.synchronize()
+    ref, absdot = _gemm_ref(synth.to_f64(a), synth.to_f64(w))
+    _assert_gemm_close(out, ref, absdot, "config1")
+    outm = dfp4.mxfp4_gemm(dfp4.mxfp4_quantize(_dev(a)), dfp4.mxfp4_quantize(_dev(w)))
+    torch.cuda.synchronize()
+    refm, absm = _gemm_ref(synth.to_f64(a), synth.to_f64(w), mx=True)
+    _assert_gemm_close(outm, refm, absm, "config1 mxfp4")
+
+
+@pytest.mark.parametrize("M,N,K", [(1, 1, 32), (70, 200, 160), (129, 257, 96), (300, 130, 1024)])
+def test_gemm_ragged_shapes(M, N, K):
+    print(f"gemm parity: ragged {M}x{N}x{K}", flush=True)
+    a = synth.gaussian_outlier_channels(M, K, max(1, K // 100), 50.0, 1.0, seed=M)
+    w = synth.student_t(N, K, 3.0, seed=N)
+    qa, qw = dfp4.quantize(_dev(a)), dfp4.quantize(_dev(w))
+    ref, absdot = _gemm_ref(synth.to_f64(a), synth.to_f64(w))
+    out = dfp4.gemm(qa, qw)
+    torch.cuda.synchronize()
+    _assert_gemm_close(out, ref, absdot, "f32")
+    outb = dfp4.gemm(qa, qw, dtype=torch.bfloat16)
+    torch.cuda.synchronize()
+    _assert_gemm_close(outb, ref, absdot, "bf16", bf16=True)
+    # leading dimension larger than N, surroundings untouched
+    buf = torch.full((M, N + 24), -7.0, dtype=torch.float32, device="cuda")
+    dfp4.gemm(qa, qw, out=buf[:, 8:8 + N])
+    torch.cuda.synchronize()
+    _assert_gemm_close(buf[:, 8:8 + N], ref, absdot, "ldc")
+    assert (buf[:, :8] == -7).all() and (buf[:, 8 + N:] == -7).all()
+
+
+def test_gemm_wide_exponent_spread():
+    # blocks whose exponents differ by tens of binades along K
+    g = torch.Generator().manual_seed(6)
+    scale = torch.exp2(torch.randint(-30, 30, (96, 8), generator=g).repeat_interleave(32, dim=1).float())
+    a = (torch.randn(96, 256, generator=g) * scale).to(torch.bfloat16)
+    w = (torch.randn(160, 256, generator=g) * scale[:1]).to(torch.bfloat16)
+    out = dfp4.gemm(dfp4.quantize(_dev(a)), dfp4.quantize(_dev(w)))
+    torch.cuda.synchronize()
+    ref, absdot = _gemm_ref(synth.to_f64(a), synth.to_f64(w))
+    _assert_gemm_close(out, ref, absdot, "wide spread")
+
+
+def test_gemm_batched():
+    B, M, N, K = 3, 80, 144, 128
+    a = synth.gaussian_outlier_channels(B * M, K, 2, 30.0, 1.0, seed=31)
+    w = synth.gaussian_outlier_channels(B * N, K, 2, 30.0, 1.0, seed=32)
+    out = dfp4.gemm_batched(dfp4.quantize(_dev(a)), dfp4.quantize(_dev(w)), B, M, N)
+    torch.cuda.synchronize()
+    for b in range(B):
+        ref, absdot = _gemm_ref(synth.to_f64(a[b * M:(b + 1) * M]), synth.to_f64(w[b * N:(b + 1) * N]))
+        _assert_gemm_close(out[b], ref, absdot, f"batch {b}")
+
+
+def test_gemm_mlp_prefill_sampled_outputs():
+    # LLaMA-3-8B gate projection at full size, in the benchmark's launch
+    # configuration; the oracle computes a seeded sample of rows x columns
+    ops = synth.llama3_8b_mlp(seed=2)
+    x, w = ops["x"], ops["w_gate"]
+    print("gemm parity: 2048x14336x4096 sampled", flush=True)
+    out = dfp4.gemm(dfp4.quantize(_dev(x)), dfp4.quantize(_dev(w)))
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(1)
+    rows = np.sort(rng.choice(x.shape[0], 24, replace=False))
+    cols = np.sort(rng.choice(w.shape[0], 192, replace=False))
+    ref, absdot = _gemm_ref(synth.to_f64(x[rows]), synth.to_f64(w[cols]))
+    _assert_gemm_close(out[rows][:, cols], ref, absdot, "mlp gate sampled")
+    # down projection, K = 14336
+    h, wd = ops["h"], ops["w_down"]
+    out = dfp4.gemm(dfp4.quantize(_dev(h)), dfp4.quantize(_dev(wd)))
+    torch.cuda.synchronize()
+    cols = np.sort(rng.choice(wd.shape[0], 64, replace=False))
+    ref, absdot = _gemm_ref(synth.to_f64(h[rows]), synth.to_f64(wd[cols]))
+    _assert_gemm_close(out[rows][:, cols], ref, absdot, "mlp down sampled")
