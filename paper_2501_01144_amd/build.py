@@ -18,7 +18,7 @@ FLAGS = [
     "-fconstexpr-steps=200000000",
     # keep hipcc from forming packed-fp32 instructions
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-    "-Wall", "-Wno-unused-function",
+    "-Wall", "-Wno-unused-function", "-Wno-inline-asm",
 ]
 
 

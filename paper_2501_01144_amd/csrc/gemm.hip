@@ -1,57 +1,140 @@
 // Block-scaled integer GEMM on DialectFP4 / MXFP4 operands for gfx950
 // (paper Section 3.3): out = A * W^T with
 //   out[m,n] = sum_kb 2^(ea[m,kb]+ew[n,kb]-2) * sum_{k in kb} (+-ua)(+-uw).
-// The inner sum over one block of 32 is exactly one v_mfma_i32_32x32x32_i8:
-// 4-bit codes are expanded to signed int8 half-units through the dialect's
-// 8-entry table (v_perm_b32 = four lookups per instruction), the int32 block
-// sums are exact, and each is scaled by its exponent pair and added in fp32.
 //
-// The order of the 32 elements inside an MFMA operand does not matter as
-// long as A and W use the same order; both go through unpack16() below.
+// The paper accumulates the products of one block pair as integers and
+// applies the exponent sum once per block pair.  On gfx950 the per-block
+// floating-point step would dominate (one convert + scale + add per output
+// and block on the vector ALU against 32 int8 MACs per output and block on
+// the matrix core), so this kernel moves the exponents into the operands:
+//
+//   * every row of A and of W gets a reference exponent ref = its smallest
+//     block exponent; block (row, kb) has offset delta = e - ref >= 0;
+//   * delta = 4 c + d.  The shift d in 0..3 is folded into the int8 operand
+//     (|u| <= 15, so |u << d| <= 120); the "class" c selects a pass;
+//   * passes run from the highest class down, and between classes the int32
+//     accumulators are shifted left by 4 (Horner's scheme), so that all of K
+//     is summed exactly in ONE int32 accumulator per output and the only
+//     rounding is the final int32 -> fp32 conversion, scaled by
+//     2^(refA[m] + refW[n] - 2).
+//   A block appears once for every class present among the rows that share
+//   the tile (its other rows contribute zeros).  With activations that have
+//   outlier channels, that is a second visit for the few outlier blocks.
+//
+// Three kernels per call:
+//   gemm_prepare_kernel  per-row references; per-(256 rows, block) class masks
+//                        and A expanded to pre-shifted int8 in MFMA fragment
+//                        order (A is the small operand); one byte per W block
+//                        naming its table (dialect, shift); W stays 4-bit in HBM;
+//   gemm_fast_kernel     512 x 128 outputs per workgroup, 4 waves, each wave
+//                        512 x 32 with 256 accumulator registers (one wave per
+//                        SIMD); every operand byte moves global -> LDS without
+//                        passing through registers; each wave expands its own
+//                        32 rows of W from 4-bit codes (v_perm_b32 lookups);
+//                        three LDS stages: loads two steps ahead, W expansion
+//                        one step ahead of the MFMAs.  A lone wave issues one
+//                        instruction per 4 cycles, so the step is laid out to
+//                        keep the non-MFMA instruction count per MFMA below
+//                        what fits in the MFMA's shadow;
+//   gemm_block_kernel    always-correct per-block-flush kernel; it only runs
+//                        for tiles the fast kernel declined (exponent spread
+//                        above 3 classes, W rows spreading over more than one
+//                        class, K too long for the int32 bound).
+//
+// The order of the elements inside an MFMA operand does not matter as long
+// as A and W use the same order; both sides go through unpack8() below.
 #include "common.h"
 #include "formatbook.h"
 
 namespace dfp4 {
 
-// book rows as two dwords of magnitudes and two dwords of negated magnitudes
-struct SignedBook { uint32_t pos[kDialects][2]; uint32_t neg[kDialects][2]; };
-constexpr SignedBook make_signed_book() {
-    SignedBook b{};
+// [dialect][shift] -> {magnitudes lo, hi, negated magnitudes lo, hi}, bytes u << shift
+struct ShiftedBook { uint32_t w[kDialects][4][4]; };
+constexpr ShiftedBook make_shifted_book() {
+    ShiftedBook b{};
     for (int d = 0; d < kDialects; ++d)
-        for (int j = 0; j < 8; ++j) {
-            b.pos[d][j / 4] |= (uint32_t)kBook[d][j] << (8 * (j % 4));
-            b.neg[d][j / 4] |= (uint32_t)((256 - kBook[d][j]) & 0xff) << (8 * (j % 4));
-        }
+        for (int s = 0; s < 4; ++s)
+            for (int j = 0; j < 8; ++j) {
+                const uint32_t u = (uint32_t)kBook[d][j] << s;
+                b.w[d][s][j / 4] |= u << (8 * (j % 4));
+                b.w[d][s][2 + j / 4] |= ((256u - u) & 0xffu) << (8 * (j % 4));
+            }
     return b;
 }
-__device__ const SignedBook g_signed_book = make_signed_book();
+__device__ const ShiftedBook g_shifted_book = make_shifted_book();
 
 namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
-constexpr int kThreads = 256;
-constexpr int kTileM = 128, kTileN = 128;
+constexpr int kTileM = 512, kTileN = 128;   // fast kernel: outputs per workgroup
+constexpr int kGroups = kTileM / 32;        // 32-row groups per tile
+constexpr int kMaxKB = 512;           // fast path: K <= 16384
+constexpr int kMaxClass = 2;          // classes 0..2, i.e. exponent offsets 0..11
+constexpr int kIntBound = 4660;       // n0 + 16 n1 + 256 n2 <= 2^31 / (32 * 120 * 120)
+constexpr int kPrepChunk = 8;         // blocks per round of the A expansion
+constexpr int kPrepWRows = 8;         // W rows per workgroup of the prepass
+// one LDS stage of the fast kernel: A fragments of a pair of blocks for 512 rows,
+// the four waves' W codes, the four waves' W table offsets
+constexpr int kStageA = kGroups * 2 * 1024, kStageW = 4 * 1024, kStageM = 4 * 256;
+constexpr int kStageBytes = kStageA + kStageW + kStageM;
+constexpr int kStages = 3;
 
-// 8 codes (one dword) -> 8 signed int8: returns {even elements, odd elements}
+struct GemmParams {
+    const uint8_t *a_codes, *a_dial, *a_exp, *w_codes, *w_dial, *w_exp;
+    void* out;
+    int M, N, KB;
+    int64_t ldc, strideA_rows, strideW_rows, strideC;
+    // workspace (per batch entry: ws + batch * ws_stride)
+    uint8_t* ws;
+    int64_t ws_stride, off_refa, off_refw, off_spreadw, off_wmeta, off_mask, off_flag, off_a8;
+    int tiles_m, tiles_n;             // 512 x 128 output tiles
+};
+
+struct Layout {
+    int64_t off_refa, off_refw, off_spreadw, off_wmeta, off_mask, off_flag, off_a8, total;
+};
+__host__ __device__ inline int64_t align256(int64_t x) { return (x + 255) & ~(int64_t)255; }
+inline Layout make_layout(int64_t M, int64_t N, int64_t KB) {
+    const int64_t tm = (M + kTileM - 1) / kTileM, tn = (N + kTileN - 1) / kTileN;
+    Layout l{};
+    l.off_refa = 0;
+    l.off_refw = align256(l.off_refa + tm * kTileM);
+    l.off_spreadw = align256(l.off_refw + tn * kTileN);
+    l.off_wmeta = align256(l.off_spreadw + tn * kTileN);
+    l.off_mask = align256(l.off_wmeta + N * KB * 4);          // one table offset (dword) per W block
+    l.off_flag = align256(l.off_mask + tm * KB);
+    l.off_a8 = align256(l.off_flag + tm * tn);
+    // A fragments: [class][tile][group][block 0..KB][1 KiB]; block KB of class 0 is all zeros
+    l.total = align256(l.off_a8 + (kMaxClass + 1) * tm * kGroups * (KB + 1) * 1024);
+    return l;
+}
+
+// 8 codes (one dword) -> 8 signed int8 through one dialect table:
+// returns the even-numbered elements in one dword and the odd ones in another.
+// Magnitudes and negated magnitudes are looked up with v_perm_b32 (selector =
+// 3-bit index); the per-byte choice between them uses v_perm_b32's
+// sign-replication selectors (8..11 = 0x00 / 0xff from bit 7 of bytes 1, 3, 5, 7
+// of the source pair), which turn the code's sign bits into byte masks.
 __device__ __forceinline__ void unpack8(uint32_t c, uint32_t plo, uint32_t phi, uint32_t nlo,
                                         uint32_t nhi, uint32_t& even, uint32_t& odd) {
     const uint32_t ie = c & 0x07070707u, io = (c >> 4) & 0x07070707u;
     const uint32_t pe = __builtin_amdgcn_perm(phi, plo, ie), po = __builtin_amdgcn_perm(phi, plo, io);
     const uint32_t ne = __builtin_amdgcn_perm(nhi, nlo, ie), no = __builtin_amdgcn_perm(nhi, nlo, io);
-    const uint32_t se = (c >> 3) & 0x01010101u, so = (c >> 7) & 0x01010101u;
-    const uint32_t me = (se << 8) - se, mo = (so << 8) - so;      // 0xff per negative byte
+    // result byte k <- sign of byte k of x: bytes 1, 3 come from x, bytes 0, 2 from x << 8
+    constexpr uint32_t kSignSel = 0x090b080au;
+    const uint32_t c4 = c << 4;                                   // index sign bit 3 -> bit 7
+    const uint32_t mo = __builtin_amdgcn_perm(c << 8, c, kSignSel);
+    const uint32_t me = __builtin_amdgcn_perm(c4 << 8, c4, kSignSel);
     even = (ne & me) | (pe & ~me);
     odd = (no & mo) | (po & ~mo);
 }
 
-__device__ __forceinline__ v4i unpack16(uint2 c, uint32_t d) {
-    const uint32_t plo = g_signed_book.pos[d][0], phi = g_signed_book.pos[d][1];
-    const uint32_t nlo = g_signed_book.neg[d][0], nhi = g_signed_book.neg[d][1];
+__device__ __forceinline__ v4i unpack16(uint32_t c0, uint32_t c1, uint4 tab) {
     uint32_t a, b, e, f;
-    unpack8(c.x, plo, phi, nlo, nhi, a, b);
-    unpack8(c.y, plo, phi, nlo, nhi, e, f);
+    unpack8(c0, tab.x, tab.y, tab.z, tab.w, a, b);
+    unpack8(c1, tab.x, tab.y, tab.z, tab.w, e, f);
     return v4i{(int)a, (int)b, (int)e, (int)f};
 }
 
@@ -61,32 +144,416 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
     return (uint16_t)(u >> 16);
 }
 
-// Reference-quality kernel: one workgroup = 128 x 128 outputs, 4 waves of 64 x 64,
-// operands read straight from global memory, one flush per block of 32.
+// smallest and largest byte of row[start], row[start + step], ...
+__device__ __forceinline__ void row_min_max(const uint8_t* row, int n, int start, int step, int& mn, int& mx) {
+    for (int k = start; k < n; k += step) {
+        const int v = row[k];
+        mn = min(mn, v);
+        mx = max(mx, v);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Prepass.  grid.y < tiles_m: expand 512 rows of A for a range of blocks
+// (grid.x splits K).  grid.y >= tiles_m: references and table offsets of 8 rows of W.
+// ---------------------------------------------------------------------------
+template <bool MX>
+__global__ __launch_bounds__(256) void gemm_prepare_kernel(GemmParams p) {
+    __shared__ uint8_t s_ref[kTileM];
+    __shared__ uint32_t s_cls[kPrepChunk];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t bz = blockIdx.z;
+    uint8_t* ws = p.ws + bz * p.ws_stride;
+    const int KB = p.KB;
+
+    if ((int)blockIdx.y >= p.tiles_m) {
+        // ---- W rows: reference exponent, spread, and one table offset per block
+        const int g = ((int)blockIdx.y - p.tiles_m) * gridDim.x + blockIdx.x;
+        uint32_t* wmeta = reinterpret_cast<uint32_t*>(ws + p.off_wmeta);
+#pragma unroll 1
+        for (int rr = 0; rr < kPrepWRows / 4; ++rr) {
+            const int n = g * kPrepWRows + wave * (kPrepWRows / 4) + rr;
+            if (n >= p.N) return;
+            const int64_t row = (bz * p.strideW_rows + n) * KB;
+            int mn = 255, mx = 0;
+            row_min_max(p.w_exp + row, KB, lane, 64, mn, mx);
+#pragma unroll
+            for (int s = 1; s < 64; s <<= 1) {
+                mn = min(mn, __shfl_xor(mn, s));
+                mx = max(mx, __shfl_xor(mx, s));
+            }
+            if (lane == 0) {
+                ws[p.off_refw + n] = (uint8_t)mn;
+                ws[p.off_spreadw + n] = (uint8_t)min(mx - mn, 255);
+            }
+            for (int kb = lane; kb < KB; kb += 64) {
+                const uint32_t dial = MX ? 7u : ((uint32_t)p.w_dial[row + kb] & 15u);
+                const uint32_t sh = ((uint32_t)p.w_exp[row + kb] - (uint32_t)mn) & 3u;
+                wmeta[(int64_t)n * KB + kb] = (dial * 4u + sh) * 16u;
+            }
+        }
+        return;
+    }
+
+    // ---- A rows, pass 1: reference exponent of each of the tile's rows
+    const int tile = blockIdx.y;
+#pragma unroll
+    for (int rr = 0; rr < kTileM / 256; ++rr) {
+        const int lr = rr * 256 + tid, row = tile * kTileM + lr;
+        int mn = 255, mx = 0;
+        if (row < p.M) row_min_max(p.a_exp + (bz * p.strideA_rows + row) * KB, KB, 0, 1, mn, mx);
+        s_ref[lr] = (uint8_t)mn;
+        if (blockIdx.x == 0) ws[p.off_refa + tile * kTileM + lr] = (uint8_t)mn;
+    }
+    if (blockIdx.x == 0) {
+        // the all-zero block (index KB) of every group of this tile, class 0
+        for (int i = tid; i < kGroups * 64; i += 256) {
+            uint8_t* dst = ws + p.off_a8 + (((int64_t)tile * kGroups + (i >> 6)) * (KB + 1) + KB) * 1024 + (i & 63) * 16;
+            *reinterpret_cast<uint4*>(dst) = make_uint4(0, 0, 0, 0);
+        }
+    }
+    if (tid < kPrepChunk) s_cls[tid] = 0;
+    __syncthreads();
+
+    // ---- pass 2: rounds of kPrepChunk blocks; lane = (t, r): row r of a 32-row group,
+    // elements 16t .. 16t+15; wave w owns groups 4w .. 4w+3
+    constexpr int kGW = kGroups / 4;
+    const int r = lane & 31, t = lane >> 5;
+    const int per = (KB + gridDim.x - 1) / gridDim.x;
+    const int k0 = blockIdx.x * per, k1 = min(KB, k0 + per);
+    for (int kc = k0; kc < k1; kc += kPrepChunk) {
+        const int nk = min(kPrepChunk, k1 - kc);
+        // classes present in the tile, per block
+        for (int it = 0; it < kGW * nk; ++it) {
+            const int sub = wave * kGW + (it % kGW), kb = kc + it / kGW;
+            const int row = tile * kTileM + sub * 32 + r;
+            const bool valid = row < p.M;
+            const int64_t arow = bz * p.strideA_rows + min(row, p.M - 1);
+            const int delta = (int)p.a_exp[arow * KB + kb] - (int)s_ref[sub * 32 + r];
+            const int cls = min(delta >> 2, kMaxClass + 1);
+            uint32_t present = 0;
+#pragma unroll
+            for (int cc = 0; cc <= kMaxClass + 1; ++cc)
+                if (__ballot(valid && cls == cc) != 0ull) present |= 1u << cc;
+            if (lane == 0 && present) atomicOr(&s_cls[it / kGW], present);
+        }
+        __syncthreads();
+        for (int it = 0; it < kGW * nk; ++it) {
+            const int sub = wave * kGW + (it % kGW), kb = kc + it / kGW;
+            const int row = tile * kTileM + sub * 32 + r;
+            const bool valid = row < p.M;
+            const int64_t arow = bz * p.strideA_rows + min(row, p.M - 1);
+            const int delta = (int)p.a_exp[arow * KB + kb] - (int)s_ref[sub * 32 + r];
+            const int cls = min(delta >> 2, kMaxClass + 1), sh = delta & 3;
+            const uint32_t dial = MX ? 7u : ((uint32_t)p.a_dial[arow * KB + kb] & 15u);
+            const uint2 c = *reinterpret_cast<const uint2*>(p.a_codes + (arow * KB + kb) * 16 + t * 8);
+            const uint4 tab = *reinterpret_cast<const uint4*>(g_shifted_book.w[dial][sh]);
+            const v4i data = unpack16(c.x, c.y, tab);
+            const uint32_t present = s_cls[it / kGW];
+            if (sub == 0 && lane == 0) ws[p.off_mask + (int64_t)tile * KB + kb] = (uint8_t)present;
+#pragma unroll
+            for (int cc = 0; cc <= kMaxClass; ++cc)
+                if (present & (1u << cc)) {
+                    const v4i v = (valid && cls == cc) ? data : v4i{0, 0, 0, 0};
+                    uint8_t* dst = ws + p.off_a8 +
+                                   ((((int64_t)cc * p.tiles_m + tile) * kGroups + sub) * (KB + 1) + kb) * 1024 +
+                                   t * 512 + r * 16;
+                    *reinterpret_cast<v4i*>(dst) = v;
+                }
+        }
+        __syncthreads();
+        if (tid < kPrepChunk) s_cls[tid] = 0;
+        __syncthreads();
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Fast kernel: 512 x 128 outputs per workgroup, one int32 accumulator per output
+// ---------------------------------------------------------------------------
 template <bool MX, bool BF16>
-__global__ __launch_bounds__(kThreads) void gemm_block_kernel(
-    const uint8_t* __restrict__ a_codes, const uint8_t* __restrict__ a_dial,
-    const uint8_t* __restrict__ a_exp, const uint8_t* __restrict__ w_codes,
-    const uint8_t* __restrict__ w_dial, const uint8_t* __restrict__ w_exp, void* __restrict__ out,
-    int M, int N, int KB, int64_t ldc, int64_t strideA_rows, int64_t strideW_rows, int64_t strideC) {
-    __shared__ uint8_t s_exp[2][kTileM + kTileN];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+__global__ __launch_bounds__(256, 1) void gemm_fast_kernel(GemmParams p) {
+    // per stage: A fragments [group][t][h][r][16] | W codes [wave][lane][16] | W table offsets [wave][lane][4]
+    __shared__ __attribute__((aligned(16))) uint8_t s_stage[kStages][kStageBytes];
+    __shared__ __attribute__((aligned(16))) uint32_t s_tab[kDialects * 4 * 4];
+    __shared__ uint32_t s_va[(kMaxClass + 1) * (kMaxKB + 8) + 8];   // per visit: byte offset of its A fragments
+    __shared__ uint16_t s_vl[(kMaxClass + 1) * (kMaxKB + 8) + 8];   // per visit: block index
+    __shared__ uint8_t s_refa[kTileM], s_refw[kTileN];
+    __shared__ int s_ctl[8];          // group ends (entries), feasibility
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int KB = p.KB;
     const int m0 = blockIdx.y * kTileM, n0 = blockIdx.x * kTileN;
     const int64_t bz = blockIdx.z;
-    const int64_t a_row0 = bz * strideA_rows, w_row0 = bz * strideW_rows;
+    uint8_t* ws = p.ws + bz * p.ws_stride;
+    uint8_t* flag = ws + p.off_flag + (int64_t)blockIdx.y * p.tiles_n + blockIdx.x;
+
+    // ---- prologue: tables, references, list of (block, class) visits
+    for (int i = tid; i < kDialects * 16; i += 256) s_tab[i] = (&g_shifted_book.w[0][0][0])[i];
+    {
+        for (int i = tid; i < kTileM; i += 256) s_refa[i] = ws[p.off_refa + m0 + i];
+        int spread = 0;
+        if (tid < kTileN) {
+            const int ncol = n0 + tid;
+            s_refw[tid] = ncol < p.N ? ws[p.off_refw + ncol] : 0;
+            spread = ncol < p.N ? ws[p.off_spreadw + ncol] : 0;
+        }
+        if (tid < 8) s_ctl[tid] = 0;
+        __syncthreads();
+        if (spread > 3) s_ctl[4] = 1;                                 // a W row spans more than one class
+    }
+    if (wave == 0) {
+        const uint8_t* mask = ws + p.off_mask + (int64_t)blockIdx.y * KB;
+        int pos = 0;
+        for (int c = kMaxClass; c >= 0; --c) {
+            for (int base = 0; base < KB; base += 64) {
+                const int kb = base + lane;
+                const uint32_t mk = kb < KB ? mask[kb] : 0u;
+                if (mk & (1u << (kMaxClass + 1))) s_ctl[4] = 1;       // offset beyond the classes kept
+                const bool f = (mk >> c) & 1u;
+                const unsigned long long bal = __ballot(f);
+                if (f) s_vl[pos + __popcll(bal & ((1ull << lane) - 1ull))] = (uint16_t)kb;
+                pos += __popcll(bal);
+            }
+            if (pos & 3) {                                            // pad the class to two pairs
+                const int padn = 4 - (pos & 3);
+                if (lane < padn) s_vl[pos + lane] = 0xffffu;
+                pos += padn;
+            }
+            if (lane == 0) s_ctl[kMaxClass - c] = pos;                // s_ctl[0..2]: end of class 2, 1, 0
+        }
+        if (lane < 4) s_vl[pos + lane] = 0xffffu;                     // two padding pairs for the prefetch
+    }
+    __syncthreads();
+    const int end2 = s_ctl[0] / 2, end1 = s_ctl[1] / 2, total = s_ctl[2] / 2;   // in pairs
+    {
+        const int n2 = s_ctl[0], n1 = s_ctl[1] - s_ctl[0], n0c = s_ctl[2] - s_ctl[1];
+        const int64_t a8_bytes = (int64_t)(kMaxClass + 1) * p.tiles_m * kGroups * (KB + 1) * 1024;
+        const bool ok = s_ctl[4] == 0 && (n0c + 16 * n1 + 256 * n2) <= kIntBound &&
+                        a8_bytes < ((int64_t)1 << 32) && (int64_t)p.N * KB * 16 < ((int64_t)1 << 32);
+        if (tid == 0) *flag = ok ? 0 : 1;
+        if (!ok) return;
+    }
+    // byte offset (from the start of the A fragments) of each visit's fragments for this tile's
+    // group 0; padding visits use the all-zero block of class 0 (and block 0 of W)
+    {
+        const uint32_t grp_stride = (uint32_t)(KB + 1) * 1024u;
+        const uint32_t cls_stride = (uint32_t)p.tiles_m * kGroups * grp_stride;
+        const uint32_t tile_off = (uint32_t)blockIdx.y * kGroups * grp_stride;
+        for (int i = tid; i < 2 * total + 4; i += 256) {
+            const uint32_t e = s_vl[i];
+            const uint32_t cls = i < 2 * end2 ? 2u : (i < 2 * end1 ? 1u : 0u);
+            s_va[i] = e == 0xffffu ? tile_off + (uint32_t)KB * 1024u : cls * cls_stride + tile_off + e * 1024u;
+            if (e == 0xffffu) s_vl[i] = 0;
+        }
+    }
+    __syncthreads();
+
+    // ---- main loop over pairs of (block, class) visits
+    const int h = lane >> 5, r = lane & 31;            // MFMA operand: K half h, row / column r
+    const uint32_t wave_u = (uint32_t)__builtin_amdgcn_readfirstlane(wave);
+    const uint32_t lds0 = (uint32_t)__builtin_amdgcn_readfirstlane(
+        (int)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)&s_stage[0][0]);
+    // Every operand byte goes from global memory straight into LDS.  The loads are issued
+    // from inline assembly so that their completion is waited for exactly once per step.
+    // A: one wave instruction fills the 1 KiB fragment (group, t): lanes 0..31 take block
+    // h = 0 of the pair, lanes 32..63 block h = 1; wave w fills groups 4w .. 4w+3.
+    // W: each wave fetches the codes of its own 32 rows (lane = (h, row)) and their table offsets.
+    const uint32_t grp_stride = (uint32_t)(KB + 1) * 1024u;
+    const uint8_t* a8 = ws + p.off_a8;                 // uniform
+    const uint8_t* wcodes = p.w_codes + bz * p.strideW_rows * KB * 16;   // uniform
+    const uint8_t* wmeta = ws + p.off_wmeta;           // uniform
+    const int ncol = min(n0 + wave * 32 + r, p.N - 1);
+    const uint32_t w_row_codes = (uint32_t)ncol * (uint32_t)KB * 16u;
+    const uint32_t w_row_meta = (uint32_t)ncol * (uint32_t)KB * 4u;
+    const uint32_t a_lane = wave_u * 4u * grp_stride + (uint32_t)r * 16u;
+
+    v16i acc[kGroups];
+#pragma unroll
+    for (int i = 0; i < kGroups; ++i)
+#pragma unroll
+        for (int x = 0; x < 16; ++x) acc[i][x] = 0;
+
+#define DFP4_LDS_DMA(INSTR, DST, VOFF, SBASE)                                                   \
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\t" INSTR " %1, %2" :: "s"(DST), "v"(VOFF), "s"(SBASE) : "m0", "memory")
+    // issue the loads of pair `vc` (pairs at and beyond `total` are padding) into the stage at LDS address `st`
+    auto issue_loads = [&](int vc, uint32_t st) {
+        const uint32_t voff = s_va[2 * vc + h] + a_lane;
+        const uint32_t kb = s_vl[2 * vc + h];
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                const uint8_t* base = a8 + (uint64_t)g * grp_stride + t * 512u;
+                const uint32_t dst = st + ((wave_u * 4u + g) * 2u + t) * 1024u;
+                DFP4_LDS_DMA("global_load_lds_dwordx4", dst, voff, base);
+            }
+        const uint32_t vc_off = w_row_codes + kb * 16u, vm_off = w_row_meta + kb * 4u;
+        const uint32_t dc = st + kStageA + wave_u * 1024u, dm = st + kStageA + kStageW + wave_u * 256u;
+        DFP4_LDS_DMA("global_load_lds_dwordx4", dc, vc_off, wcodes);
+        DFP4_LDS_DMA("global_load_lds_dword", dm, vm_off, wmeta);
+    };
+#undef DFP4_LDS_DMA
+    // stage rotation: cur holds pair vc, nxt pair vc+1, ld receives pair vc+2
+    uint32_t st_cur = 0, st_nxt = kStageBytes, st_ld = 2 * kStageBytes;
+    // one step: loads for pair vc+2, expansion of W for pair vc+1, MFMAs of pair vc
+    auto step = [&](int vc, const v4i (&b_cur)[2], v4i (&b_nxt)[2]) {
+#ifndef DFP4_EXP_NODMA
+        issue_loads(vc + 2, lds0 + st_ld);
+#endif
+        // loads complete in order: all but the 10 just issued have landed, in particular
+        // everything this wave fetched for pair vc+1
+        asm volatile("s_waitcnt vmcnt(10)" ::: "memory");
+        __builtin_amdgcn_sched_barrier(0);
+        // this wave's W rows of pair vc+1: codes, table offset, table
+        const uint8_t* sn = &s_stage[0][0] + st_nxt;
+        const uint4 c = *reinterpret_cast<const uint4*>(sn + kStageA + wave * 1024 + lane * 16);
+        const uint32_t meta = *reinterpret_cast<const uint32_t*>(sn + kStageA + kStageW + wave * 256 + lane * 4);
+        const uint4 tab = *reinterpret_cast<const uint4*>(reinterpret_cast<const uint8_t*>(s_tab) + meta);
+        __builtin_amdgcn_sched_barrier(0);
+        // The 32 MFMAs of pair vc, in program order, each followed by what fits in its shadow
+        // (a lone wave issues one instruction per 4 cycles, an MFMA occupies the matrix core
+        // for 8 such slots): the LDS read of the A fragment needed kDepth MFMAs later and one
+        // piece (two instructions) of the expansion of W for pair vc+1.  A scheduling fence
+        // after every slot keeps this order.
+        constexpr int kDepth = 8;
+        const uint8_t* sa = &s_stage[0][0] + st_cur + lane * 16;
+        v4i af[kDepth];
+#pragma unroll
+        for (int d = 0; d < kDepth; ++d) af[d] = *reinterpret_cast<const v4i*>(sa + ((d & 15) * 2 + (d >> 4)) * 1024);
+        const uint32_t cw[4] = {c.x, c.y, c.z, c.w};
+        uint32_t ie = 0, io = 0, c4 = 0, c8 = 0, c12 = 0, sh = 0, pe = 0, ne = 0, po = 0, no = 0, mo = 0, me = 0;
+        uint32_t ev[4], od[4];
+        constexpr uint32_t kSignSel = 0x090b080au;
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int k = 0; k < 32; ++k) {
+            const int g = k & 15, t = k >> 4;
+            acc[g] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[k % kDepth], b_cur[t], acc[g], 0, 0, 0);
+            if (k + kDepth < 32) {
+                const int kk = k + kDepth;
+                af[k % kDepth] = *reinterpret_cast<const v4i*>(sa + ((kk & 15) * 2 + (kk >> 4)) * 1024);
+            }
+            if (k < 28) {                                   // expansion of dword k / 7, piece k % 7 (see unpack8)
+                const int d = k / 7;
+                switch (k % 7) {
+                    case 0: ie = cw[d] & 0x07070707u; c4 = cw[d] << 4; break;
+                    case 1: sh = cw[d] >> 4; c8 = cw[d] << 8; break;
+                    case 2: io = sh & 0x07070707u; c12 = c4 << 8; break;
+                    case 3: pe = __builtin_amdgcn_perm(tab.y, tab.x, ie); ne = __builtin_amdgcn_perm(tab.w, tab.z, ie); break;
+                    case 4: po = __builtin_amdgcn_perm(tab.y, tab.x, io); no = __builtin_amdgcn_perm(tab.w, tab.z, io); break;
+                    case 5: mo = __builtin_amdgcn_perm(c8, cw[d], kSignSel); me = __builtin_amdgcn_perm(c12, c4, kSignSel); break;
+                    default: ev[d] = (ne & me) | (pe & ~me); od[d] = (no & mo) | (po & ~mo); break;
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        b_nxt[0] = v4i{(int)ev[0], (int)od[0], (int)ev[1], (int)od[1]};
+        b_nxt[1] = v4i{(int)ev[2], (int)od[2], (int)ev[3], (int)od[3]};
+#ifndef DFP4_EXP_NOBARRIER
+        __syncthreads();                               // A of pair vc+1 is visible to every wave
+#endif
+        const uint32_t tmp = st_cur;
+        st_cur = st_nxt; st_nxt = st_ld; st_ld = tmp;
+    };
+    auto horner = [&]() {
+#pragma unroll
+        for (int g = 0; g < kGroups; ++g) {
+#pragma unroll
+            for (int x = 0; x < 16; ++x) acc[g][x] = (int)((uint32_t)acc[g][x] << 4);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+    v4i b0[2], b1[2];
+    issue_loads(0, lds0);
+    issue_loads(1, lds0 + kStageBytes);
+    asm volatile("s_waitcnt vmcnt(10)" ::: "memory");
+    {
+        const uint8_t* sn = &s_stage[0][0];
+        const uint4 c = *reinterpret_cast<const uint4*>(sn + kStageA + wave * 1024 + lane * 16);
+        const uint32_t meta = *reinterpret_cast<const uint32_t*>(sn + kStageA + kStageW + wave * 256 + lane * 4);
+        const uint4 tab = *reinterpret_cast<const uint4*>(reinterpret_cast<const uint8_t*>(s_tab) + meta);
+        b0[0] = unpack16(c.x, c.y, tab);
+        b0[1] = unpack16(c.z, c.w, tab);
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    // invariant at the top of a step for pair vc: b(vc&1) = W operands of vc, stage cur holds
+    // A of vc (visible to all waves), stage nxt the loads of vc+1 (landed or in flight)
+    int vc = 0;
+#pragma unroll 1
+    for (int seg = 0; seg < 3; ++seg) {
+#ifdef DFP4_EXP_NOLOOP
+        const int seg_end = 0;
+#else
+        const int seg_end = seg == 0 ? end2 : (seg == 1 ? end1 : total);
+#endif
+#pragma unroll 1
+        while (vc < seg_end) {                         // every class holds an even number of pairs
+            step(vc, b0, b1);
+            step(vc + 1, b1, b0);
+            vc += 2;
+        }
+        // Horner step: everything summed so far belongs to classes above the next segment's
+        if (seg < 2 && vc > 0) horner();
+    }
+
+    // ---- epilogue: the one rounding of the whole product
+    {
+        const int n = n0 + wave * 32 + r;
+        const int ew = s_refw[wave * 32 + r];
+#pragma unroll
+        for (int g = 0; g < kGroups; ++g)
+#pragma unroll
+            for (int x = 0; x < 16; ++x) {
+                const int ml = g * 32 + 8 * (x >> 2) + 4 * h + (x & 3);
+                const int m = m0 + ml;
+#ifdef DFP4_EXP_NOSTORE
+                if (m < p.M && n < p.N && acc[g][x] == 0x12345678) {
+#else
+                if (m < p.M && n < p.N) {
+#endif
+                    const float v = ldexpf((float)acc[g][x], (int)s_refa[ml] + ew - 256);
+                    const int64_t o = bz * p.strideC + (int64_t)m * p.ldc + n;
+                    if constexpr (BF16)
+                        static_cast<uint16_t*>(p.out)[o] = f32_to_bf16_rne(v);
+                    else
+                        static_cast<float*>(p.out)[o] = v;
+                }
+            }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Per-block-flush kernel (always correct): 128 x 128 outputs per workgroup,
+// operands straight from global memory, one fp32 scale-and-add per block.
+// When `flags` is set it only computes tiles the fast kernel declined.
+// ---------------------------------------------------------------------------
+template <bool MX, bool BF16>
+__global__ __launch_bounds__(256) void gemm_block_kernel(GemmParams p, int use_flags) {
+    __shared__ uint8_t s_exp[2][256];
+    const int KB = p.KB;
+    const int64_t bz = blockIdx.z;
+    if (use_flags) {
+        const uint8_t* flag = p.ws + bz * p.ws_stride + p.off_flag + (int64_t)(blockIdx.y / 4) * p.tiles_n +
+                              blockIdx.x;
+        if (*flag == 0) return;
+    }
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int m0 = blockIdx.y * 128, n0 = blockIdx.x * 128;
+    const int64_t a_row0 = bz * p.strideA_rows, w_row0 = bz * p.strideW_rows;
     const int half = lane >> 5, l32 = lane & 31;
 
     int64_t a_row[2], w_row[2];
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
-        a_row[i] = a_row0 + min(m0 + wm * 64 + i * 32 + l32, M - 1);
-        w_row[i] = w_row0 + min(n0 + wn * 64 + i * 32 + l32, N - 1);
+        a_row[i] = a_row0 + min(m0 + wm * 64 + i * 32 + l32, p.M - 1);
+        w_row[i] = w_row0 + min(n0 + wn * 64 + i * 32 + l32, p.N - 1);
     }
-    // exponent staging: thread t < 128 fetches an A row's byte, t >= 128 a W row's byte
     const int t = threadIdx.x;
-    const int64_t e_row = t < kTileM ? a_row0 + min(m0 + t, M - 1) : w_row0 + min(n0 + t - kTileM, N - 1);
-    const uint8_t* e_src = (t < kTileM ? a_exp : w_exp) + e_row * KB;
+    const int64_t e_row = t < 128 ? a_row0 + min(m0 + t, p.M - 1) : w_row0 + min(n0 + t - 128, p.N - 1);
+    const uint8_t* e_src = (t < 128 ? p.a_exp : p.w_exp) + e_row * KB;
 
     float acc[2][2][16];
 #pragma unroll
@@ -94,7 +561,7 @@ __global__ __launch_bounds__(kThreads) void gemm_block_kernel(
 #pragma unroll
         for (int j = 0; j < 2; ++j)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+            for (int x = 0; x < 16; ++x) acc[i][j][x] = 0.0f;
 
     for (int kb = 0; kb < KB; ++kb) {
         uint8_t* se = s_exp[kb & 1];
@@ -102,26 +569,26 @@ __global__ __launch_bounds__(kThreads) void gemm_block_kernel(
         v4i a[2], b[2];
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
-            const uint2 ca = *reinterpret_cast<const uint2*>(a_codes + (a_row[i] * KB + kb) * 16 + half * 8);
-            const uint2 cw = *reinterpret_cast<const uint2*>(w_codes + (w_row[i] * KB + kb) * 16 + half * 8);
-            const uint32_t da = MX ? 7u : ((uint32_t)a_dial[a_row[i] * KB + kb] & 15u);
-            const uint32_t dw = MX ? 7u : ((uint32_t)w_dial[w_row[i] * KB + kb] & 15u);
-            a[i] = unpack16(ca, da);
-            b[i] = unpack16(cw, dw);
+            const uint2 ca = *reinterpret_cast<const uint2*>(p.a_codes + (a_row[i] * KB + kb) * 16 + half * 8);
+            const uint2 cw = *reinterpret_cast<const uint2*>(p.w_codes + (w_row[i] * KB + kb) * 16 + half * 8);
+            const uint32_t da = MX ? 7u : ((uint32_t)p.a_dial[a_row[i] * KB + kb] & 15u);
+            const uint32_t dw = MX ? 7u : ((uint32_t)p.w_dial[w_row[i] * KB + kb] & 15u);
+            a[i] = unpack16(ca.x, ca.y, *reinterpret_cast<const uint4*>(g_shifted_book.w[da][0]));
+            b[i] = unpack16(cw.x, cw.y, *reinterpret_cast<const uint4*>(g_shifted_book.w[dw][0]));
         }
         __syncthreads();
 #pragma unroll
         for (int i = 0; i < 2; ++i)
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
-                v16i p = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-                p = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i], b[j], p, 0, 0, 0);
-                const int ew = se[kTileM + wn * 64 + j * 32 + l32];
+                v16i pr = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+                pr = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i], b[j], pr, 0, 0, 0);
+                const int ew = se[128 + wn * 64 + j * 32 + l32];
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int row = 8 * (r >> 2) + 4 * half + (r & 3);
+                for (int x = 0; x < 16; ++x) {
+                    const int row = 8 * (x >> 2) + 4 * half + (x & 3);
                     const int ea = se[wm * 64 + i * 32 + row];
-                    acc[i][j][r] += ldexpf((float)p[r], ea + ew - 256);
+                    acc[i][j][x] += ldexpf((float)pr[x], ea + ew - 256);
                 }
             }
     }
@@ -132,14 +599,14 @@ __global__ __launch_bounds__(kThreads) void gemm_block_kernel(
         for (int j = 0; j < 2; ++j) {
             const int n = n0 + wn * 64 + j * 32 + l32;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int m = m0 + wm * 64 + i * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-                if (m < M && n < N) {
-                    const int64_t o = bz * strideC + (int64_t)m * ldc + n;
+            for (int x = 0; x < 16; ++x) {
+                const int m = m0 + wm * 64 + i * 32 + 8 * (x >> 2) + 4 * half + (x & 3);
+                if (m < p.M && n < p.N) {
+                    const int64_t o = bz * p.strideC + (int64_t)m * p.ldc + n;
                     if constexpr (BF16)
-                        static_cast<uint16_t*>(out)[o] = f32_to_bf16_rne(acc[i][j][r]);
+                        static_cast<uint16_t*>(p.out)[o] = f32_to_bf16_rne(acc[i][j][x]);
                     else
-                        static_cast<float*>(out)[o] = acc[i][j][r];
+                        static_cast<float*>(p.out)[o] = acc[i][j][x];
                 }
             }
         }
@@ -147,24 +614,60 @@ __global__ __launch_bounds__(kThreads) void gemm_block_kernel(
 
 }  // namespace
 
-size_t gemm_workspace_bytes(int64_t, int64_t, int64_t) { return 0; }
+size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K) {
+    if (M == 0 || N == 0) return 0;
+    return (size_t)make_layout(M, N, K / kBlock).total;
+}
 
 int launch_gemm(bool mx, dfp4_tensor A, dfp4_tensor W, void* out, int out_dtype, int64_t ldc,
                 int64_t batch, int64_t strideA_rows, int64_t strideW_rows, int64_t strideC,
-                void* /*workspace*/, size_t /*workspace_bytes*/, hipStream_t stream) {
+                void* workspace, size_t workspace_bytes, hipStream_t stream) {
     const int64_t M = A.rows, N = W.rows, KB = A.K / kBlock;
     if (M == 0 || N == 0 || batch == 0) return DFP4_OK;
     if (M >= (1 << 30) || N >= (1 << 30) || KB >= (1 << 26) || batch > 65535) return DFP4_ERR_SHAPE;
-    dim3 grid((unsigned)((N + kTileN - 1) / kTileN), (unsigned)((M + kTileM - 1) / kTileM), (unsigned)batch);
-    if (grid.y > 65535) return DFP4_ERR_SHAPE;
-#define DFP4_LAUNCH(MXV, BV)                                                                        \
-    hipLaunchKernelGGL((gemm_block_kernel<MXV, BV>), grid, dim3(kThreads), 0, stream, A.codes,      \
-                       A.dialect, A.exponent, W.codes, W.dialect, W.exponent, out, (int)M, (int)N,  \
-                       (int)KB, ldc, strideA_rows, strideW_rows, strideC)
+    const Layout lay = make_layout(M, N, KB);
+    if ((size_t)lay.total * (size_t)batch > workspace_bytes) return DFP4_ERR_WORKSPACE;
+
+    GemmParams p{};
+    p.a_codes = A.codes; p.a_dial = A.dialect; p.a_exp = A.exponent;
+    p.w_codes = W.codes; p.w_dial = W.dialect; p.w_exp = W.exponent;
+    p.out = out; p.M = (int)M; p.N = (int)N; p.KB = (int)KB;
+    p.ldc = ldc; p.strideA_rows = strideA_rows; p.strideW_rows = strideW_rows; p.strideC = strideC;
+    p.ws = static_cast<uint8_t*>(workspace); p.ws_stride = lay.total;
+    p.off_refa = lay.off_refa; p.off_refw = lay.off_refw; p.off_spreadw = lay.off_spreadw;
+    p.off_wmeta = lay.off_wmeta; p.off_mask = lay.off_mask; p.off_flag = lay.off_flag;
+    p.off_a8 = lay.off_a8;
+    p.tiles_m = (int)((M + kTileM - 1) / kTileM); p.tiles_n = (int)((N + kTileN - 1) / kTileN);
+    if (p.tiles_m > 16383 || p.tiles_n > (1 << 20)) return DFP4_ERR_SHAPE;
+
+    const bool bf16 = out_dtype == DFP4_BF16;
+    const bool fast = KB > 0 && KB <= kMaxKB;
+    if (fast) {
+        int ksplit = (int)((KB + kPrepChunk - 1) / kPrepChunk);
+        if (ksplit > 256) ksplit = 256;
+        const int64_t w_groups = (N + kPrepWRows - 1) / kPrepWRows;
+        const int64_t w_rows_y = (w_groups + ksplit - 1) / ksplit;
+        if (p.tiles_m + w_rows_y > 65535) return DFP4_ERR_SHAPE;
+        dim3 gp((unsigned)ksplit, (unsigned)(p.tiles_m + w_rows_y), (unsigned)batch);
+        if (mx) hipLaunchKernelGGL((gemm_prepare_kernel<true>), gp, dim3(256), 0, stream, p);
+        else hipLaunchKernelGGL((gemm_prepare_kernel<false>), gp, dim3(256), 0, stream, p);
+    }
+    dim3 gf((unsigned)p.tiles_n, (unsigned)p.tiles_m, (unsigned)batch);
+    dim3 gb((unsigned)((N + 127) / 128), (unsigned)((M + 127) / 128), (unsigned)batch);
+    if (gb.y > 65535) return DFP4_ERR_SHAPE;
+#define DFP4_LAUNCH(MXV, BV)                                                                     \
+    do {                                                                                         \
+        if (fast) {                                                                              \
+            hipLaunchKernelGGL((gemm_fast_kernel<MXV, BV>), gf, dim3(256), 0, stream, p);        \
+            hipLaunchKernelGGL((gemm_block_kernel<MXV, BV>), gb, dim3(256), 0, stream, p, 1);    \
+        } else {                                                                                 \
+            hipLaunchKernelGGL((gemm_block_kernel<MXV, BV>), gb, dim3(256), 0, stream, p, 0);    \
+        }                                                                                        \
+    } while (0)
     if (mx) {
-        if (out_dtype == DFP4_BF16) DFP4_LAUNCH(true, true); else DFP4_LAUNCH(true, false);
+        if (bf16) DFP4_LAUNCH(true, true); else DFP4_LAUNCH(true, false);
     } else {
-        if (out_dtype == DFP4_BF16) DFP4_LAUNCH(false, true); else DFP4_LAUNCH(false, false);
+        if (bf16) DFP4_LAUNCH(false, true); else DFP4_LAUNCH(false, false);
     }
 #undef DFP4_LAUNCH
     return check_launch();

@@ -141,8 +141,8 @@ def gemm_workspace_bytes(M, N, K):
     return int(load().dfp4_gemm_workspace_bytes(M, N, K))
 
 
-def _workspace(M, N, K, device, workspace):
-    need = gemm_workspace_bytes(M, N, K)
+def _workspace(M, N, K, device, workspace, batch=1):
+    need = gemm_workspace_bytes(M, N, K) * batch
     if workspace is None and need > 0:
         workspace = torch.empty(need, dtype=torch.uint8, device=device)
     return workspace, (workspace.numel() if workspace is not None else 0)
@@ -176,7 +176,7 @@ def gemm_batched(a, w, batch, M, N, dtype=torch.float32, out=None, workspace=Non
     assert out.is_contiguous()
     ac, wc = a.c(), w.c()
     ac.rows, wc.rows = M, N
-    workspace, nbytes = _workspace(M, N, a.K, out.device, workspace)
+    workspace, nbytes = _workspace(M, N, a.K, out.device, workspace, batch)
     _check(load().dfp4_gemm_batched(ac, wc, _ptr(out), F32 if out.dtype == torch.float32 else BF16, N,
                                     batch, M, N, M * N, _ptr(workspace), nbytes, _stream()),
            "dfp4_gemm_batched")
