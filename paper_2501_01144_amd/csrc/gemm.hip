@@ -21,11 +21,12 @@
 //   the tile (its other rows contribute zeros).  With activations that have
 //   outlier channels, that is a second visit for the few outlier blocks.
 //
-// Three kernels per call:
-//   gemm_prepare_kernel  per-row references; per-(256 rows, block) class masks
-//                        and A expanded to pre-shifted int8 in MFMA fragment
-//                        order (A is the small operand); one byte per W block
-//                        naming its table (dialect, shift); W stays 4-bit in HBM;
+// Four kernels per call:
+//   gemm_rowstat_kernel  per-row reference exponents; for W also the spread and
+//                        one dword per block naming its table (dialect, shift);
+//   gemm_expand_kernel   per-(512 rows, block) class masks and A expanded to
+//                        pre-shifted int8 in MFMA fragment order (A is the
+//                        small operand; W stays 4-bit in HBM);
 //   gemm_fast_kernel     512 x 128 outputs per workgroup, 4 waves, each wave
 //                        512 x 32 with 256 accumulator registers (one wave per
 //                        SIMD); every operand byte moves global -> LDS without
@@ -45,6 +46,7 @@
 // as A and W use the same order; both sides go through unpack8() below.
 #include "common.h"
 #include "formatbook.h"
+#include "gemm_step_asm.inc"
 
 namespace dfp4 {
 
@@ -73,13 +75,12 @@ constexpr int kGroups = kTileM / 32;        // 32-row groups per tile
 constexpr int kMaxKB = 512;           // fast path: K <= 16384
 constexpr int kMaxClass = 2;          // classes 0..2, i.e. exponent offsets 0..11
 constexpr int kIntBound = 4660;       // n0 + 16 n1 + 256 n2 <= 2^31 / (32 * 120 * 120)
-constexpr int kPrepChunk = 8;         // blocks per round of the A expansion
-constexpr int kPrepWRows = 8;         // W rows per workgroup of the prepass
+constexpr int kPrepChunk = 2;         // blocks per workgroup of the A expansion
 // one LDS stage of the fast kernel: A fragments of a pair of blocks for 512 rows,
 // the four waves' W codes, the four waves' W table offsets
 constexpr int kStageA = kGroups * 2 * 1024, kStageW = 4 * 1024, kStageM = 4 * 256;
 constexpr int kStageBytes = kStageA + kStageW + kStageM;
-constexpr int kStages = 3;
+constexpr int kStages = 4;
 
 struct GemmParams {
     const uint8_t *a_codes, *a_dial, *a_exp, *w_codes, *w_dial, *w_exp;
@@ -144,67 +145,71 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
     return (uint16_t)(u >> 16);
 }
 
-// smallest and largest byte of row[start], row[start + step], ...
-__device__ __forceinline__ void row_min_max(const uint8_t* row, int n, int start, int step, int& mn, int& mx) {
-    for (int k = start; k < n; k += step) {
-        const int v = row[k];
+// ---------------------------------------------------------------------------
+// Prepass 1: per-row statistics, one wave per row (A rows first, then W rows).
+//   A row: reference exponent (smallest block exponent of the row)
+//   W row: reference exponent, spread, and one table offset (dword) per block
+// ---------------------------------------------------------------------------
+template <bool MX>
+__global__ __launch_bounds__(256) void gemm_rowstat_kernel(GemmParams p) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t bz = blockIdx.z;
+    uint8_t* ws = p.ws + bz * p.ws_stride;
+    const int KB = p.KB;
+    const int64_t row_id = (int64_t)blockIdx.x * 4 + wave;
+    const int m_pad = p.tiles_m * kTileM;
+    if (row_id >= (int64_t)m_pad + p.N) return;
+    const bool is_w = row_id >= m_pad;
+    const int row = is_w ? (int)(row_id - m_pad) : (int)row_id;
+    if (!is_w && row >= p.M) {                        // padding rows of the last A tile
+        if (lane == 0) ws[p.off_refa + row] = 0;
+        return;
+    }
+    const int64_t base = ((is_w ? bz * p.strideW_rows : bz * p.strideA_rows) + row) * KB;
+    const uint8_t* e = (is_w ? p.w_exp : p.a_exp) + base;
+    int mn = 255, mx = 0;
+    for (int kb = lane; kb < KB; kb += 64) {
+        const int v = e[kb];
         mn = min(mn, v);
         mx = max(mx, v);
+    }
+#pragma unroll
+    for (int s = 1; s < 64; s <<= 1) {
+        mn = min(mn, __shfl_xor(mn, s));
+        mx = max(mx, __shfl_xor(mx, s));
+    }
+    if (!is_w) {
+        if (lane == 0) ws[p.off_refa + row] = (uint8_t)mn;
+        return;
+    }
+    if (lane == 0) {
+        ws[p.off_refw + row] = (uint8_t)mn;
+        ws[p.off_spreadw + row] = (uint8_t)min(mx - mn, 255);
+    }
+    uint32_t* wmeta = reinterpret_cast<uint32_t*>(ws + p.off_wmeta) + (int64_t)row * KB;
+    for (int kb = lane; kb < KB; kb += 64) {
+        const uint32_t dial = MX ? 7u : ((uint32_t)p.w_dial[base + kb] & 15u);
+        const uint32_t sh = ((uint32_t)e[kb] - (uint32_t)mn) & 3u;
+        wmeta[kb] = (dial * 4u + sh) * 16u;
     }
 }
 
 // ---------------------------------------------------------------------------
-// Prepass.  grid.y < tiles_m: expand 512 rows of A for a range of blocks
-// (grid.x splits K).  grid.y >= tiles_m: references and table offsets of 8 rows of W.
+// Prepass 2: expand A.  grid = (chunks of kPrepChunk blocks, 512-row tiles, batch).
+// For every block of the chunk: which classes occur among the tile's rows, then
+// for each such class the 16 fragments (rows of other classes contribute zeros).
 // ---------------------------------------------------------------------------
 template <bool MX>
-__global__ __launch_bounds__(256) void gemm_prepare_kernel(GemmParams p) {
+__global__ __launch_bounds__(256) void gemm_expand_kernel(GemmParams p) {
     __shared__ uint8_t s_ref[kTileM];
     __shared__ uint32_t s_cls[kPrepChunk];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int64_t bz = blockIdx.z;
     uint8_t* ws = p.ws + bz * p.ws_stride;
     const int KB = p.KB;
-
-    if ((int)blockIdx.y >= p.tiles_m) {
-        // ---- W rows: reference exponent, spread, and one table offset per block
-        const int g = ((int)blockIdx.y - p.tiles_m) * gridDim.x + blockIdx.x;
-        uint32_t* wmeta = reinterpret_cast<uint32_t*>(ws + p.off_wmeta);
-#pragma unroll 1
-        for (int rr = 0; rr < kPrepWRows / 4; ++rr) {
-            const int n = g * kPrepWRows + wave * (kPrepWRows / 4) + rr;
-            if (n >= p.N) return;
-            const int64_t row = (bz * p.strideW_rows + n) * KB;
-            int mn = 255, mx = 0;
-            row_min_max(p.w_exp + row, KB, lane, 64, mn, mx);
-#pragma unroll
-            for (int s = 1; s < 64; s <<= 1) {
-                mn = min(mn, __shfl_xor(mn, s));
-                mx = max(mx, __shfl_xor(mx, s));
-            }
-            if (lane == 0) {
-                ws[p.off_refw + n] = (uint8_t)mn;
-                ws[p.off_spreadw + n] = (uint8_t)min(mx - mn, 255);
-            }
-            for (int kb = lane; kb < KB; kb += 64) {
-                const uint32_t dial = MX ? 7u : ((uint32_t)p.w_dial[row + kb] & 15u);
-                const uint32_t sh = ((uint32_t)p.w_exp[row + kb] - (uint32_t)mn) & 3u;
-                wmeta[(int64_t)n * KB + kb] = (dial * 4u + sh) * 16u;
-            }
-        }
-        return;
-    }
-
-    // ---- A rows, pass 1: reference exponent of each of the tile's rows
     const int tile = blockIdx.y;
-#pragma unroll
-    for (int rr = 0; rr < kTileM / 256; ++rr) {
-        const int lr = rr * 256 + tid, row = tile * kTileM + lr;
-        int mn = 255, mx = 0;
-        if (row < p.M) row_min_max(p.a_exp + (bz * p.strideA_rows + row) * KB, KB, 0, 1, mn, mx);
-        s_ref[lr] = (uint8_t)mn;
-        if (blockIdx.x == 0) ws[p.off_refa + tile * kTileM + lr] = (uint8_t)mn;
-    }
+    for (int i = tid; i < kTileM; i += 256) s_ref[i] = ws[p.off_refa + tile * kTileM + i];
+    if (tid < kPrepChunk) s_cls[tid] = 0;
     if (blockIdx.x == 0) {
         // the all-zero block (index KB) of every group of this tile, class 0
         for (int i = tid; i < kGroups * 64; i += 256) {
@@ -212,58 +217,52 @@ __global__ __launch_bounds__(256) void gemm_prepare_kernel(GemmParams p) {
             *reinterpret_cast<uint4*>(dst) = make_uint4(0, 0, 0, 0);
         }
     }
-    if (tid < kPrepChunk) s_cls[tid] = 0;
     __syncthreads();
 
-    // ---- pass 2: rounds of kPrepChunk blocks; lane = (t, r): row r of a 32-row group,
-    // elements 16t .. 16t+15; wave w owns groups 4w .. 4w+3
+    // lane = (t, r): row r of a 32-row group, elements 16t .. 16t+15; wave w owns groups 4w .. 4w+3
     constexpr int kGW = kGroups / 4;
     const int r = lane & 31, t = lane >> 5;
-    const int per = (KB + gridDim.x - 1) / gridDim.x;
-    const int k0 = blockIdx.x * per, k1 = min(KB, k0 + per);
-    for (int kc = k0; kc < k1; kc += kPrepChunk) {
-        const int nk = min(kPrepChunk, k1 - kc);
-        // classes present in the tile, per block
-        for (int it = 0; it < kGW * nk; ++it) {
-            const int sub = wave * kGW + (it % kGW), kb = kc + it / kGW;
-            const int row = tile * kTileM + sub * 32 + r;
-            const bool valid = row < p.M;
-            const int64_t arow = bz * p.strideA_rows + min(row, p.M - 1);
-            const int delta = (int)p.a_exp[arow * KB + kb] - (int)s_ref[sub * 32 + r];
-            const int cls = min(delta >> 2, kMaxClass + 1);
-            uint32_t present = 0;
+    const int kc = blockIdx.x * kPrepChunk;
+    const int nk = min(kPrepChunk, KB - kc);
+    int cls_of[kGW * kPrepChunk], sh_of[kGW * kPrepChunk];
 #pragma unroll
-            for (int cc = 0; cc <= kMaxClass + 1; ++cc)
-                if (__ballot(valid && cls == cc) != 0ull) present |= 1u << cc;
-            if (lane == 0 && present) atomicOr(&s_cls[it / kGW], present);
-        }
-        __syncthreads();
-        for (int it = 0; it < kGW * nk; ++it) {
-            const int sub = wave * kGW + (it % kGW), kb = kc + it / kGW;
-            const int row = tile * kTileM + sub * 32 + r;
-            const bool valid = row < p.M;
-            const int64_t arow = bz * p.strideA_rows + min(row, p.M - 1);
-            const int delta = (int)p.a_exp[arow * KB + kb] - (int)s_ref[sub * 32 + r];
-            const int cls = min(delta >> 2, kMaxClass + 1), sh = delta & 3;
-            const uint32_t dial = MX ? 7u : ((uint32_t)p.a_dial[arow * KB + kb] & 15u);
-            const uint2 c = *reinterpret_cast<const uint2*>(p.a_codes + (arow * KB + kb) * 16 + t * 8);
-            const uint4 tab = *reinterpret_cast<const uint4*>(g_shifted_book.w[dial][sh]);
-            const v4i data = unpack16(c.x, c.y, tab);
-            const uint32_t present = s_cls[it / kGW];
-            if (sub == 0 && lane == 0) ws[p.off_mask + (int64_t)tile * KB + kb] = (uint8_t)present;
+    for (int it = 0; it < kGW * kPrepChunk; ++it) {
+        const int sub = wave * kGW + (it % kGW), kbl = it / kGW;
+        const int row = tile * kTileM + sub * 32 + r;
+        const bool valid = row < p.M && kbl < nk;
+        const int64_t arow = bz * p.strideA_rows + min(row, p.M - 1);
+        const int delta = valid ? (int)p.a_exp[arow * KB + kc + kbl] - (int)s_ref[sub * 32 + r] : 0;
+        cls_of[it] = valid ? min(delta >> 2, kMaxClass + 1) : -1;
+        sh_of[it] = delta & 3;
+        uint32_t present = 0;
 #pragma unroll
-            for (int cc = 0; cc <= kMaxClass; ++cc)
-                if (present & (1u << cc)) {
-                    const v4i v = (valid && cls == cc) ? data : v4i{0, 0, 0, 0};
-                    uint8_t* dst = ws + p.off_a8 +
-                                   ((((int64_t)cc * p.tiles_m + tile) * kGroups + sub) * (KB + 1) + kb) * 1024 +
-                                   t * 512 + r * 16;
-                    *reinterpret_cast<v4i*>(dst) = v;
-                }
-        }
-        __syncthreads();
-        if (tid < kPrepChunk) s_cls[tid] = 0;
-        __syncthreads();
+        for (int cc = 0; cc <= kMaxClass + 1; ++cc)
+            if (__ballot(cls_of[it] == cc) != 0ull) present |= 1u << cc;
+        if (lane == 0 && present) atomicOr(&s_cls[kbl], present);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int it = 0; it < kGW * kPrepChunk; ++it) {
+        const int sub = wave * kGW + (it % kGW), kbl = it / kGW;
+        if (kbl >= nk) continue;
+        const int kb = kc + kbl;
+        const int row = tile * kTileM + sub * 32 + r;
+        const int64_t arow = bz * p.strideA_rows + min(row, p.M - 1);
+        const uint32_t dial = MX ? 7u : ((uint32_t)p.a_dial[arow * KB + kb] & 15u);
+        const uint2 c = *reinterpret_cast<const uint2*>(p.a_codes + (arow * KB + kb) * 16 + t * 8);
+        const uint4 tab = *reinterpret_cast<const uint4*>(g_shifted_book.w[dial][sh_of[it]]);
+        const v4i data = unpack16(c.x, c.y, tab);
+        const uint32_t present = s_cls[kbl];
+        if (sub == 0 && lane == 0) ws[p.off_mask + (int64_t)tile * KB + kb] = (uint8_t)present;
+#pragma unroll
+        for (int cc = 0; cc <= kMaxClass; ++cc)
+            if (present & (1u << cc)) {
+                const v4i v = cls_of[it] == cc ? data : v4i{0, 0, 0, 0};
+                uint8_t* dst = ws + p.off_a8 +
+                               ((((int64_t)cc * p.tiles_m + tile) * kGroups + sub) * (KB + 1) + kb) * 1024 +
+                               t * 512 + r * 16;
+                *reinterpret_cast<v4i*>(dst) = v;
+            }
     }
 }
 
@@ -321,7 +320,7 @@ __global__ __launch_bounds__(256, 1) void gemm_fast_kernel(GemmParams p) {
             }
             if (lane == 0) s_ctl[kMaxClass - c] = pos;                // s_ctl[0..2]: end of class 2, 1, 0
         }
-        if (lane < 4) s_vl[pos + lane] = 0xffffu;                     // two padding pairs for the prefetch
+        if (lane < 6) s_vl[pos + lane] = 0xffffu;                     // three padding pairs for the prefetch
     }
     __syncthreads();
     const int end2 = s_ctl[0] / 2, end1 = s_ctl[1] / 2, total = s_ctl[2] / 2;   // in pairs
@@ -339,7 +338,7 @@ __global__ __launch_bounds__(256, 1) void gemm_fast_kernel(GemmParams p) {
         const uint32_t grp_stride = (uint32_t)(KB + 1) * 1024u;
         const uint32_t cls_stride = (uint32_t)p.tiles_m * kGroups * grp_stride;
         const uint32_t tile_off = (uint32_t)blockIdx.y * kGroups * grp_stride;
-        for (int i = tid; i < 2 * total + 4; i += 256) {
+        for (int i = tid; i < 2 * total + 6; i += 256) {
             const uint32_t e = s_vl[i];
             const uint32_t cls = i < 2 * end2 ? 2u : (i < 2 * end1 ? 1u : 0u);
             s_va[i] = e == 0xffffu ? tile_off + (uint32_t)KB * 1024u : cls * cls_stride + tile_off + e * 1024u;
@@ -353,174 +352,148 @@ __global__ __launch_bounds__(256, 1) void gemm_fast_kernel(GemmParams p) {
     const uint32_t wave_u = (uint32_t)__builtin_amdgcn_readfirstlane(wave);
     const uint32_t lds0 = (uint32_t)__builtin_amdgcn_readfirstlane(
         (int)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)&s_stage[0][0]);
-    // Every operand byte goes from global memory straight into LDS.  The loads are issued
-    // from inline assembly so that their completion is waited for exactly once per step.
+    const uint32_t lds_tab = (uint32_t)__builtin_amdgcn_readfirstlane(
+        (int)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)&s_tab[0]);
+    // Every operand byte goes from global memory straight into LDS (no registers).
     // A: one wave instruction fills the 1 KiB fragment (group, t): lanes 0..31 take block
     // h = 0 of the pair, lanes 32..63 block h = 1; wave w fills groups 4w .. 4w+3.
     // W: each wave fetches the codes of its own 32 rows (lane = (h, row)) and their table offsets.
     const uint32_t grp_stride = (uint32_t)(KB + 1) * 1024u;
-    const uint8_t* a8 = ws + p.off_a8;                 // uniform
+    const uint8_t* a8 = ws + p.off_a8 + (uint64_t)wave_u * 4u * grp_stride;   // uniform per wave
+    const uint8_t* a_base[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) a_base[j] = a8 + (uint64_t)(j >> 1) * grp_stride + (j & 1) * 512u;
     const uint8_t* wcodes = p.w_codes + bz * p.strideW_rows * KB * 16;   // uniform
     const uint8_t* wmeta = ws + p.off_wmeta;           // uniform
     const int ncol = min(n0 + wave * 32 + r, p.N - 1);
     const uint32_t w_row_codes = (uint32_t)ncol * (uint32_t)KB * 16u;
     const uint32_t w_row_meta = (uint32_t)ncol * (uint32_t)KB * 4u;
-    const uint32_t a_lane = wave_u * 4u * grp_stride + (uint32_t)r * 16u;
+    const uint32_t a_lane = (uint32_t)r * 16u;
+    // LDS byte addresses inside a stage (add the stage's base)
+    const uint32_t m0a_off = wave_u * 8u * 1024u;
+    const uint32_t m0w_off = kStageA + wave_u * 1024u;
+    const uint32_t m0m_off = kStageA + kStageW + wave_u * 256u;
+    const uint32_t sa_lane = (uint32_t)lane * 16u;
+    const uint32_t swc_lane = kStageA + (uint32_t)wave * 1024u + (uint32_t)lane * 16u;
+    const uint32_t swm_lane = kStageA + kStageW + (uint32_t)wave * 256u + (uint32_t)lane * 4u;
+    const uint32_t sign_sel = 0x090b080au;
 
-    v16i acc[kGroups];
-#pragma unroll
-    for (int i = 0; i < kGroups; ++i)
-#pragma unroll
-        for (int x = 0; x < 16; ++x) acc[i][x] = 0;
+    // The accumulators live in a[0:255] and belong to the assembly blocks (gemm_step_asm.inc).
+    asm volatile(DFP4_ACC_ZERO_ASM ::: DFP4_ACC_CLOBBERS);
 
 #define DFP4_LDS_DMA(INSTR, DST, VOFF, SBASE)                                                   \
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\t" INSTR " %1, %2" :: "s"(DST), "v"(VOFF), "s"(SBASE) : "m0", "memory")
-    // issue the loads of pair `vc` (pairs at and beyond `total` are padding) into the stage at LDS address `st`
+    // prologue loads of pair `vc` into the stage at LDS address `st` (the steady state issues
+    // them from inside the step)
     auto issue_loads = [&](int vc, uint32_t st) {
         const uint32_t voff = s_va[2 * vc + h] + a_lane;
         const uint32_t kb = s_vl[2 * vc + h];
 #pragma unroll
-        for (int g = 0; g < 4; ++g)
-#pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                const uint8_t* base = a8 + (uint64_t)g * grp_stride + t * 512u;
-                const uint32_t dst = st + ((wave_u * 4u + g) * 2u + t) * 1024u;
-                DFP4_LDS_DMA("global_load_lds_dwordx4", dst, voff, base);
-            }
+        for (int j = 0; j < 8; ++j) {
+            const uint32_t dst = st + m0a_off + j * 1024u;
+            DFP4_LDS_DMA("global_load_lds_dwordx4", dst, voff, a_base[j]);
+        }
         const uint32_t vc_off = w_row_codes + kb * 16u, vm_off = w_row_meta + kb * 4u;
-        const uint32_t dc = st + kStageA + wave_u * 1024u, dm = st + kStageA + kStageW + wave_u * 256u;
+        const uint32_t dc = st + m0w_off, dm = st + m0m_off;
         DFP4_LDS_DMA("global_load_lds_dwordx4", dc, vc_off, wcodes);
         DFP4_LDS_DMA("global_load_lds_dword", dm, vm_off, wmeta);
     };
 #undef DFP4_LDS_DMA
-    // stage rotation: cur holds pair vc, nxt pair vc+1, ld receives pair vc+2
-    uint32_t st_cur = 0, st_nxt = kStageBytes, st_ld = 2 * kStageBytes;
-    // one step: loads for pair vc+2, expansion of W for pair vc+1, MFMAs of pair vc
-    auto step = [&](int vc, const v4i (&b_cur)[2], v4i (&b_nxt)[2]) {
-#ifndef DFP4_EXP_NODMA
-        issue_loads(vc + 2, lds0 + st_ld);
-#endif
-        // loads complete in order: all but the 10 just issued have landed, in particular
-        // everything this wave fetched for pair vc+1
-        asm volatile("s_waitcnt vmcnt(10)" ::: "memory");
-        __builtin_amdgcn_sched_barrier(0);
-        // this wave's W rows of pair vc+1: codes, table offset, table
-        const uint8_t* sn = &s_stage[0][0] + st_nxt;
-        const uint4 c = *reinterpret_cast<const uint4*>(sn + kStageA + wave * 1024 + lane * 16);
-        const uint32_t meta = *reinterpret_cast<const uint32_t*>(sn + kStageA + kStageW + wave * 256 + lane * 4);
-        const uint4 tab = *reinterpret_cast<const uint4*>(reinterpret_cast<const uint8_t*>(s_tab) + meta);
-        __builtin_amdgcn_sched_barrier(0);
-        // The 32 MFMAs of pair vc, in program order, each followed by what fits in its shadow
-        // (a lone wave issues one instruction per 4 cycles, an MFMA occupies the matrix core
-        // for 8 such slots): the LDS read of the A fragment needed kDepth MFMAs later and one
-        // piece (two instructions) of the expansion of W for pair vc+1.  A scheduling fence
-        // after every slot keeps this order.
-        constexpr int kDepth = 8;
-        const uint8_t* sa = &s_stage[0][0] + st_cur + lane * 16;
-        v4i af[kDepth];
-#pragma unroll
-        for (int d = 0; d < kDepth; ++d) af[d] = *reinterpret_cast<const v4i*>(sa + ((d & 15) * 2 + (d >> 4)) * 1024);
-        const uint32_t cw[4] = {c.x, c.y, c.z, c.w};
-        uint32_t ie = 0, io = 0, c4 = 0, c8 = 0, c12 = 0, sh = 0, pe = 0, ne = 0, po = 0, no = 0, mo = 0, me = 0;
-        uint32_t ev[4], od[4];
-        constexpr uint32_t kSignSel = 0x090b080au;
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int k = 0; k < 32; ++k) {
-            const int g = k & 15, t = k >> 4;
-            acc[g] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[k % kDepth], b_cur[t], acc[g], 0, 0, 0);
-            if (k + kDepth < 32) {
-                const int kk = k + kDepth;
-                af[k % kDepth] = *reinterpret_cast<const v4i*>(sa + ((kk & 15) * 2 + (kk >> 4)) * 1024);
-            }
-            if (k < 28) {                                   // expansion of dword k / 7, piece k % 7 (see unpack8)
-                const int d = k / 7;
-                switch (k % 7) {
-                    case 0: ie = cw[d] & 0x07070707u; c4 = cw[d] << 4; break;
-                    case 1: sh = cw[d] >> 4; c8 = cw[d] << 8; break;
-                    case 2: io = sh & 0x07070707u; c12 = c4 << 8; break;
-                    case 3: pe = __builtin_amdgcn_perm(tab.y, tab.x, ie); ne = __builtin_amdgcn_perm(tab.w, tab.z, ie); break;
-                    case 4: po = __builtin_amdgcn_perm(tab.y, tab.x, io); no = __builtin_amdgcn_perm(tab.w, tab.z, io); break;
-                    case 5: mo = __builtin_amdgcn_perm(c8, cw[d], kSignSel); me = __builtin_amdgcn_perm(c12, c4, kSignSel); break;
-                    default: ev[d] = (ne & me) | (pe & ~me); od[d] = (no & mo) | (po & ~mo); break;
-                }
-            }
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        b_nxt[0] = v4i{(int)ev[0], (int)od[0], (int)ev[1], (int)od[1]};
-        b_nxt[1] = v4i{(int)ev[2], (int)od[2], (int)ev[3], (int)od[3]};
-#ifndef DFP4_EXP_NOBARRIER
-        __syncthreads();                               // A of pair vc+1 is visible to every wave
-#endif
-        const uint32_t tmp = st_cur;
-        st_cur = st_nxt; st_nxt = st_ld; st_ld = tmp;
-    };
-    auto horner = [&]() {
-#pragma unroll
-        for (int g = 0; g < kGroups; ++g) {
-#pragma unroll
-            for (int x = 0; x < 16; ++x) acc[g][x] = (int)((uint32_t)acc[g][x] << 4);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-    };
 
-    v4i b0[2], b1[2];
-    issue_loads(0, lds0);
-    issue_loads(1, lds0 + kStageBytes);
-    asm volatile("s_waitcnt vmcnt(10)" ::: "memory");
+    // stage rotation (LDS byte addresses): cur holds pair vc, nxt pair vc+1, nx2 pair vc+2
+    // (landing), ld receives pair vc+3
+    uint32_t st_cur = lds0, st_nxt = lds0 + kStageBytes, st_nx2 = lds0 + 2 * kStageBytes,
+             st_ld = lds0 + 3 * kStageBytes;
+    v4i bA0, bA1, bB0, bB1;            // int8 W operands, two sets used alternately (fixed registers)
+    issue_loads(0, st_cur);
+    issue_loads(1, st_nxt);
+    issue_loads(2, st_nx2);
+    asm volatile("s_waitcnt vmcnt(20)" ::: "memory");
     {
         const uint8_t* sn = &s_stage[0][0];
         const uint4 c = *reinterpret_cast<const uint4*>(sn + kStageA + wave * 1024 + lane * 16);
         const uint32_t meta = *reinterpret_cast<const uint32_t*>(sn + kStageA + kStageW + wave * 256 + lane * 4);
         const uint4 tab = *reinterpret_cast<const uint4*>(reinterpret_cast<const uint8_t*>(s_tab) + meta);
-        b0[0] = unpack16(c.x, c.y, tab);
-        b0[1] = unpack16(c.z, c.w, tab);
+        bA0 = unpack16(c.x, c.y, tab);
+        bA1 = unpack16(c.z, c.w, tab);
     }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    asm volatile("s_waitcnt vmcnt(10)" ::: "memory");
     __syncthreads();
-    // invariant at the top of a step for pair vc: b(vc&1) = W operands of vc, stage cur holds
-    // A of vc (visible to all waves), stage nxt the loads of vc+1 (landed or in flight)
+
+    // One step (see gen_gemm_step.py): MFMAs of pair vc from stage cur with the current W
+    // operands; expansion of pair vc+1's W codes (stage nxt) into the other operand set;
+    // loads of pair vc+3 into stage ld; barrier.
+#define DFP4_STEP(ASM, IN0, IN1, OUT0, OUT1, RIN0, RIN1, ROUT0, ROUT1)                               \
+    do {                                                                                             \
+        const uint32_t voff = s_va[2 * (vc + 3) + h] + a_lane;                                       \
+        const uint32_t kb = s_vl[2 * (vc + 3) + h];                                                  \
+        const uint32_t vcoff = w_row_codes + kb * 16u, vmoff = w_row_meta + kb * 4u;                 \
+        const uint32_t sa = st_cur + sa_lane, swc = st_nxt + swc_lane, swm = st_nxt + swm_lane;      \
+        const uint32_t m0a = st_ld + m0a_off, m0w = st_ld + m0w_off, m0m = st_ld + m0m_off;          \
+        asm volatile(ASM                                                                             \
+                     : "=&{" ROUT0 "}"(OUT0), "=&{" ROUT1 "}"(OUT1)                                  \
+                     : "{" RIN0 "}"(IN0), "{" RIN1 "}"(IN1), [sa] "v"(sa), [swc] "v"(swc),           \
+                       [swm] "v"(swm), [voff] "v"(voff), [vcoff] "v"(vcoff), [vmoff] "v"(vmoff),     \
+                       [tabb] "s"(lds_tab), [sel] "s"(sign_sel), [m0a] "s"(m0a), [m0w] "s"(m0w),     \
+                       [m0m] "s"(m0m), [a0] "s"(a_base[0]), [a1] "s"(a_base[1]), [a2] "s"(a_base[2]), \
+                       [a3] "s"(a_base[3]), [a4] "s"(a_base[4]), [a5] "s"(a_base[5]),                \
+                       [a6] "s"(a_base[6]), [a7] "s"(a_base[7]), [wc] "s"(wcodes), [wm] "s"(wmeta)   \
+                     : DFP4_STEP_VGPR_CLOBBERS, DFP4_ACC_CLOBBERS, "m0", "scc", "memory");           \
+        const uint32_t tmp = st_cur;                                                                 \
+        st_cur = st_nxt; st_nxt = st_nx2; st_nx2 = st_ld; st_ld = tmp;                               \
+        ++vc;                                                                                        \
+    } while (0)
+
     int vc = 0;
 #pragma unroll 1
     for (int seg = 0; seg < 3; ++seg) {
-#ifdef DFP4_EXP_NOLOOP
-        const int seg_end = 0;
-#else
         const int seg_end = seg == 0 ? end2 : (seg == 1 ? end1 : total);
-#endif
 #pragma unroll 1
         while (vc < seg_end) {                         // every class holds an even number of pairs
-            step(vc, b0, b1);
-            step(vc + 1, b1, b0);
-            vc += 2;
+            DFP4_STEP(DFP4_STEP_ASM_X, bA0, bA1, bB0, bB1, "v[128:131]", "v[132:135]", "v[136:139]", "v[140:143]");
+            DFP4_STEP(DFP4_STEP_ASM_Y, bB0, bB1, bA0, bA1, "v[136:139]", "v[140:143]", "v[128:131]", "v[132:135]");
         }
         // Horner step: everything summed so far belongs to classes above the next segment's
-        if (seg < 2 && vc > 0) horner();
+        if (seg < 2 && vc > 0)
+            asm volatile(DFP4_ACC_SHIFT4_ASM ::: DFP4_SHIFT_VGPR_CLOBBERS, DFP4_ACC_CLOBBERS);
     }
+#undef DFP4_STEP
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the padding pairs' loads
+    asm volatile(DFP4_ACC_DRAIN_ASM);
 
     // ---- epilogue: the one rounding of the whole product
     {
         const int n = n0 + wave * 32 + r;
         const int ew = s_refw[wave * 32 + r];
-#pragma unroll
-        for (int g = 0; g < kGroups; ++g)
+        auto store_group = [&](int g, const int (&v)[16]) {
 #pragma unroll
             for (int x = 0; x < 16; ++x) {
                 const int ml = g * 32 + 8 * (x >> 2) + 4 * h + (x & 3);
                 const int m = m0 + ml;
-#ifdef DFP4_EXP_NOSTORE
-                if (m < p.M && n < p.N && acc[g][x] == 0x12345678) {
-#else
                 if (m < p.M && n < p.N) {
-#endif
-                    const float v = ldexpf((float)acc[g][x], (int)s_refa[ml] + ew - 256);
+                    const float f = ldexpf((float)v[x], (int)s_refa[ml] + ew - 256);
                     const int64_t o = bz * p.strideC + (int64_t)m * p.ldc + n;
                     if constexpr (BF16)
-                        static_cast<uint16_t*>(p.out)[o] = f32_to_bf16_rne(v);
+                        static_cast<uint16_t*>(p.out)[o] = f32_to_bf16_rne(f);
                     else
-                        static_cast<float*>(p.out)[o] = v;
+                        static_cast<float*>(p.out)[o] = f;
                 }
             }
+        };
+#define DFP4_READ_GROUP(G)                                                                          \
+    do {                                                                                            \
+        int v[16];                                                                                  \
+        asm volatile(DFP4_ACC_READ_ASM_##G                                                          \
+                     : "=v"(v[0]), "=v"(v[1]), "=v"(v[2]), "=v"(v[3]), "=v"(v[4]), "=v"(v[5]),      \
+                       "=v"(v[6]), "=v"(v[7]), "=v"(v[8]), "=v"(v[9]), "=v"(v[10]), "=v"(v[11]),    \
+                       "=v"(v[12]), "=v"(v[13]), "=v"(v[14]), "=v"(v[15]));                         \
+        store_group(G, v);                                                                          \
+    } while (0)
+        DFP4_READ_GROUP(0); DFP4_READ_GROUP(1); DFP4_READ_GROUP(2); DFP4_READ_GROUP(3);
+        DFP4_READ_GROUP(4); DFP4_READ_GROUP(5); DFP4_READ_GROUP(6); DFP4_READ_GROUP(7);
+        DFP4_READ_GROUP(8); DFP4_READ_GROUP(9); DFP4_READ_GROUP(10); DFP4_READ_GROUP(11);
+        DFP4_READ_GROUP(12); DFP4_READ_GROUP(13); DFP4_READ_GROUP(14); DFP4_READ_GROUP(15);
+#undef DFP4_READ_GROUP
     }
 }
 
@@ -643,14 +616,16 @@ int launch_gemm(bool mx, dfp4_tensor A, dfp4_tensor W, void* out, int out_dtype,
     const bool bf16 = out_dtype == DFP4_BF16;
     const bool fast = KB > 0 && KB <= kMaxKB;
     if (fast) {
-        int ksplit = (int)((KB + kPrepChunk - 1) / kPrepChunk);
-        if (ksplit > 256) ksplit = 256;
-        const int64_t w_groups = (N + kPrepWRows - 1) / kPrepWRows;
-        const int64_t w_rows_y = (w_groups + ksplit - 1) / ksplit;
-        if (p.tiles_m + w_rows_y > 65535) return DFP4_ERR_SHAPE;
-        dim3 gp((unsigned)ksplit, (unsigned)(p.tiles_m + w_rows_y), (unsigned)batch);
-        if (mx) hipLaunchKernelGGL((gemm_prepare_kernel<true>), gp, dim3(256), 0, stream, p);
-        else hipLaunchKernelGGL((gemm_prepare_kernel<false>), gp, dim3(256), 0, stream, p);
+        const int64_t rows = (int64_t)p.tiles_m * kTileM + N;
+        dim3 gs((unsigned)((rows + 3) / 4), 1, (unsigned)batch);
+        dim3 ge((unsigned)((KB + kPrepChunk - 1) / kPrepChunk), (unsigned)p.tiles_m, (unsigned)batch);
+        if (mx) {
+            hipLaunchKernelGGL((gemm_rowstat_kernel<true>), gs, dim3(256), 0, stream, p);
+            hipLaunchKernelGGL((gemm_expand_kernel<true>), ge, dim3(256), 0, stream, p);
+        } else {
+            hipLaunchKernelGGL((gemm_rowstat_kernel<false>), gs, dim3(256), 0, stream, p);
+            hipLaunchKernelGGL((gemm_expand_kernel<false>), ge, dim3(256), 0, stream, p);
+        }
     }
     dim3 gf((unsigned)p.tiles_n, (unsigned)p.tiles_m, (unsigned)batch);
     dim3 gb((unsigned)((N + 127) / 128), (unsigned)((M + 127) / 128), (unsigned)batch);
