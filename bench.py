@@ -31,15 +31,36 @@ def _events(n, torch):
     return [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
 
 
+def measured_traffic(key):
+    """Per-launch HBM-side bytes measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+    (scaled by a plain copy of known size); the summary is kept under profiles/."""
+    path = os.path.join(ROOT, "profiles", "bench_mlp_prefill_hbm_traffic.txt")
+    try:
+        for line in open(path):
+            if line.startswith(key + " = "):
+                return float(line.split("=")[1]) * 1e6
+    except OSError:
+        pass
+    return None
+
+
 def quant_bytes(rows, K, mx=False):
     """Algorithmic bytes of one quantizer launch: 2 B/element in, 0.5 B codes +
     one exponent byte (+ one dialect byte) per 32 out."""
     return rows * K * (2.0 + 0.5 + (1.0 if mx else 2.0) / 32.0)
 
 
-def cpu_baseline(ops, tokens=768, cols=256):
-    """The oracle as it stands, timed on the host on a sample of the step:
-    `tokens` rows of x and h, `cols` rows of each weight matrix."""
+def gemm_bytes(M, N, K, out_bytes=4):
+    """Algorithmic bytes of one GEMM launch: both quantized operands once
+    (4-bit codes + exponent and dialect bytes per 32) and the output once."""
+    return (M + N) * K * (0.5 + 2.0 / 32.0) + M * N * out_bytes
+
+
+def cpu_baseline(ops, target_seconds=25.0):
+    """The oracle as it stands, timed on the host on a sample of the step: the first
+    `tokens` rows of x and h against the first `cols` rows of each weight matrix.
+    A short calibration run picks the sample so that the timed part takes roughly
+    `target_seconds` on this machine."""
     import numpy as np
     from oracle import dfp4_oracle as O
     from paper_2501_01144_amd import synth
@@ -48,15 +69,25 @@ def cpu_baseline(ops, tokens=768, cols=256):
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     except Exception:
         cores = 1
-    x, h = synth.to_f64(ops["x"][:tokens]), synth.to_f64(ops["h"][:tokens])
-    wq = {k: O.dfp4_quantize(synth.to_f64(ops[k][:cols])) for k in ("w_gate", "w_up", "w_down")}
-    t0 = time.perf_counter()
-    qx = O.dfp4_quantize(x)
-    O.dfp4_gemm(qx, wq["w_gate"])
-    O.dfp4_gemm(qx, wq["w_up"])
-    qh = O.dfp4_quantize(h)
-    O.dfp4_gemm(qh, wq["w_down"])
-    dt = time.perf_counter() - t0
+    def run(tokens, cols):
+        x, h = synth.to_f64(ops["x"][:tokens]), synth.to_f64(ops["h"][:tokens])
+        wq = {k: O.dfp4_quantize(synth.to_f64(ops[k][:cols])) for k in ("w_gate", "w_up", "w_down")}
+        t0 = time.perf_counter()
+        qx = O.dfp4_quantize(x)
+        O.dfp4_gemm(qx, wq["w_gate"])
+        O.dfp4_gemm(qx, wq["w_up"])
+        qh = O.dfp4_quantize(h)
+        O.dfp4_gemm(qh, wq["w_down"])
+        return time.perf_counter() - t0, x, h
+
+    run(32, 32)                                   # first-call costs stay out of the calibration
+    tokens, cols = 128, 512
+    dt, x, h = run(tokens, cols)
+    grow = max(1.0, target_seconds / dt)
+    new_tokens = int(min(ops["x"].shape[0], tokens * grow))
+    grow /= new_tokens / tokens
+    tokens, cols = new_tokens, int(min(2048, cols * max(1.0, grow)))
+    dt, x, h = run(tokens, cols)
     int_ops = 2.0 * tokens * cols * (2 * x.shape[1] + h.shape[1])
     return {"value": int_ops / dt / 1e12, "unit": "TOP/s", "cores": int(cores), "kind": "oracle",
             "seconds": round(dt, 3),
@@ -72,6 +103,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-stream-quant", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 256 MiB device copy (a known-size kernel to scale "
+                         "rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
@@ -99,6 +133,13 @@ def main():
     ws_bytes = max(dfp4.gemm_workspace_bytes(M, I, H), dfp4.gemm_workspace_bytes(M, H, I))
     ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=dev)
     torch.cuda.synchronize()
+
+    if args.calibrate_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     names = ["quantize_x", "gemm_gate", "gemm_up", "quantize_h", "gemm_down"]
 
@@ -153,7 +194,10 @@ def main():
         "quantize_in_step_GBps": round(q_bytes / (q_ms * 1e-3) / 1e9, 1),
         "roofline": {"bound": "mfma", "kernel": "dfp4_gemm (3 launches per step)",
                      "achieved": round(gemm_tops, 3), "peak": INT8_PEAK_TOPS, "unit": "TOP/s",
-                     "frac": round(gemm_tops / INT8_PEAK_TOPS, 4), "traffic": None},
+                     "frac": round(gemm_tops / INT8_PEAK_TOPS, 4),
+                     "traffic": measured_traffic("gemm_fast_kernel_avg_MB_per_launch"),
+                     "algorithmic_bytes_per_launch": round(
+                         (2 * gemm_bytes(M, I, H) + gemm_bytes(M, H, I)) / 3)},
     }
 
     if not args.no_stream_quant:

@@ -75,7 +75,7 @@ constexpr int kGroups = kTileM / 32;        // 32-row groups per tile
 constexpr int kMaxKB = 512;           // fast path: K <= 16384
 constexpr int kMaxClass = 2;          // classes 0..2, i.e. exponent offsets 0..11
 constexpr int kIntBound = 4660;       // n0 + 16 n1 + 256 n2 <= 2^31 / (32 * 120 * 120)
-constexpr int kPrepChunk = 2;         // blocks per workgroup of the A expansion
+constexpr int kPrepChunk = 4;         // blocks per workgroup of the A expansion (4 blocks = one 64-byte line of codes per row)
 // one LDS stage of the fast kernel: A fragments of a pair of blocks for 512 rows,
 // the four waves' W codes, the four waves' W table offsets
 constexpr int kStageA = kGroups * 2 * 1024, kStageW = 4 * 1024, kStageM = 4 * 256;
@@ -89,24 +89,37 @@ struct GemmParams {
     int64_t ldc, strideA_rows, strideW_rows, strideC;
     // workspace (per batch entry: ws + batch * ws_stride)
     uint8_t* ws;
-    int64_t ws_stride, off_refa, off_refw, off_spreadw, off_wmeta, off_mask, off_flag, off_a8;
+    int64_t ws_stride, off_refa, off_refw, off_spreadw, off_wmeta, off_mask, off_flag, off_cnt, off_part, off_a8;
     int tiles_m, tiles_n;             // 512 x 128 output tiles
+    int ksplit;                       // workgroups sharing one output tile (each takes a range of K)
 };
 
 struct Layout {
-    int64_t off_refa, off_refw, off_spreadw, off_wmeta, off_mask, off_flag, off_a8, total;
+    int64_t off_refa, off_refw, off_spreadw, off_wmeta, off_mask, off_flag, off_cnt, off_part, off_a8, total;
+    int ksplit;
 };
 __host__ __device__ inline int64_t align256(int64_t x) { return (x + 255) & ~(int64_t)255; }
+// Workgroups per output tile: when there are fewer tiles than compute units, K is split
+// between 2, 4 or 8 workgroups whose exact int32 partial sums are added by the last to finish.
+inline int choose_ksplit(int64_t tiles, int64_t KB) {
+    const int64_t cu = device_cu_count();
+    int s = 1;
+    while (s < 8 && tiles * s * 2 <= cu && KB / (2 * s) >= 16) s *= 2;
+    return s;
+}
 inline Layout make_layout(int64_t M, int64_t N, int64_t KB) {
     const int64_t tm = (M + kTileM - 1) / kTileM, tn = (N + kTileN - 1) / kTileN;
     Layout l{};
+    l.ksplit = choose_ksplit(tm * tn, KB);
     l.off_refa = 0;
     l.off_refw = align256(l.off_refa + tm * kTileM);
     l.off_spreadw = align256(l.off_refw + tn * kTileN);
     l.off_wmeta = align256(l.off_spreadw + tn * kTileN);
     l.off_mask = align256(l.off_wmeta + N * KB * 4);          // one table offset (dword) per W block
     l.off_flag = align256(l.off_mask + tm * KB);
-    l.off_a8 = align256(l.off_flag + tm * tn);
+    l.off_cnt = align256(l.off_flag + tm * tn);
+    l.off_part = align256(l.off_cnt + tm * tn * 4);
+    l.off_a8 = align256(l.off_part + (l.ksplit > 1 ? (int64_t)l.ksplit * tm * tn * kTileM * kTileN * 4 : 0));
     // A fragments: [class][tile][group][block 0..KB][1 KiB]; block KB of class 0 is all zeros
     l.total = align256(l.off_a8 + (kMaxClass + 1) * tm * kGroups * (KB + 1) * 1024);
     return l;
@@ -156,6 +169,14 @@ __global__ __launch_bounds__(256) void gemm_rowstat_kernel(GemmParams p) {
     const int64_t bz = blockIdx.z;
     uint8_t* ws = p.ws + bz * p.ws_stride;
     const int KB = p.KB;
+    if (blockIdx.x == 0) {
+        // per-tile state of the fast kernel: "declined" flags and split-K arrival counters
+        const int tiles = p.tiles_m * p.tiles_n;
+        for (int i = threadIdx.x; i < tiles; i += 256) {
+            ws[p.off_flag + i] = 0;
+            reinterpret_cast<uint32_t*>(ws + p.off_cnt)[i] = 0;
+        }
+    }
     const int64_t row_id = (int64_t)blockIdx.x * 4 + wave;
     const int m_pad = p.tiles_m * kTileM;
     if (row_id >= (int64_t)m_pad + p.N) return;
@@ -282,9 +303,15 @@ __global__ __launch_bounds__(256, 1) void gemm_fast_kernel(GemmParams p) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int KB = p.KB;
     const int m0 = blockIdx.y * kTileM, n0 = blockIdx.x * kTileN;
-    const int64_t bz = blockIdx.z;
+    const int S = p.ksplit, sidx = (int)(blockIdx.z % (unsigned)S);
+    const int64_t bz = blockIdx.z / (unsigned)S;
     uint8_t* ws = p.ws + bz * p.ws_stride;
-    uint8_t* flag = ws + p.off_flag + (int64_t)blockIdx.y * p.tiles_n + blockIdx.x;
+    const int tile_id = blockIdx.y * p.tiles_n + blockIdx.x;
+    volatile uint8_t* flag = ws + p.off_flag + tile_id;
+    uint32_t* counter = reinterpret_cast<uint32_t*>(ws + p.off_cnt) + tile_id;
+    // this workgroup's range of blocks
+    const int kb_per = (KB + S - 1) / S;
+    const int kb_lo = sidx * kb_per, kb_hi = min(KB, kb_lo + kb_per);
 
     // ---- prologue: tables, references, list of (block, class) visits
     for (int i = tid; i < kDialects * 16; i += 256) s_tab[i] = (&g_shifted_book.w[0][0][0])[i];
@@ -304,9 +331,9 @@ __global__ __launch_bounds__(256, 1) void gemm_fast_kernel(GemmParams p) {
         const uint8_t* mask = ws + p.off_mask + (int64_t)blockIdx.y * KB;
         int pos = 0;
         for (int c = kMaxClass; c >= 0; --c) {
-            for (int base = 0; base < KB; base += 64) {
+            for (int base = kb_lo; base < kb_hi; base += 64) {
                 const int kb = base + lane;
-                const uint32_t mk = kb < KB ? mask[kb] : 0u;
+                const uint32_t mk = kb < kb_hi ? mask[kb] : 0u;
                 if (mk & (1u << (kMaxClass + 1))) s_ctl[4] = 1;       // offset beyond the classes kept
                 const bool f = (mk >> c) & 1u;
                 const unsigned long long bal = __ballot(f);
@@ -327,10 +354,17 @@ __global__ __launch_bounds__(256, 1) void gemm_fast_kernel(GemmParams p) {
     {
         const int n2 = s_ctl[0], n1 = s_ctl[1] - s_ctl[0], n0c = s_ctl[2] - s_ctl[1];
         const int64_t a8_bytes = (int64_t)(kMaxClass + 1) * p.tiles_m * kGroups * (KB + 1) * 1024;
-        const bool ok = s_ctl[4] == 0 && (n0c + 16 * n1 + 256 * n2) <= kIntBound &&
+        const bool ok = s_ctl[4] == 0 && (n0c + 16 * n1 + 256 * n2) * S <= kIntBound &&
                         a8_bytes < ((int64_t)1 << 32) && (int64_t)p.N * KB * 16 < ((int64_t)1 << 32);
-        if (tid == 0) *flag = ok ? 0 : 1;
-        if (!ok) return;
+        if (!ok) {
+            // decline the tile (the block-flush kernel computes it); still count as arrived
+            if (tid == 0) {
+                *flag = 1;
+                __threadfence();
+                if (S > 1) atomicAdd(counter, 1u);
+            }
+            return;
+        }
     }
     // byte offset (from the start of the A fragments) of each visit's fragments for this tile's
     // group 0; padding visits use the all-zero block of class 0 (and block 0 of W)
@@ -461,11 +495,48 @@ __global__ __launch_bounds__(256, 1) void gemm_fast_kernel(GemmParams p) {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the padding pairs' loads
     asm volatile(DFP4_ACC_DRAIN_ASM);
 
-    // ---- epilogue: the one rounding of the whole product
+    // ---- epilogue
+#define DFP4_READ_GROUP(G, V)                                                                       \
+    asm volatile(DFP4_ACC_READ_ASM_##G                                                              \
+                 : "=v"(V[0]), "=v"(V[1]), "=v"(V[2]), "=v"(V[3]), "=v"(V[4]), "=v"(V[5]),          \
+                   "=v"(V[6]), "=v"(V[7]), "=v"(V[8]), "=v"(V[9]), "=v"(V[10]), "=v"(V[11]),        \
+                   "=v"(V[12]), "=v"(V[13]), "=v"(V[14]), "=v"(V[15]))
+#define DFP4_FOR_GROUPS(F)                                                                          \
+    F(0) F(1) F(2) F(3) F(4) F(5) F(6) F(7) F(8) F(9) F(10) F(11) F(12) F(13) F(14) F(15)
+    int* part = reinterpret_cast<int*>(ws + p.off_part) + (int64_t)tile_id * S * (kTileM * kTileN);
+    if (S > 1) {
+        // K is shared with other workgroups: publish this one's exact int32 sums; the last
+        // workgroup of the tile to arrive adds the others' and finishes the tile
+        int* mine = part + (int64_t)sidx * (kTileM * kTileN);
+#define DFP4_PUBLISH(G)                                                                             \
+        {                                                                                           \
+            int v[16];                                                                              \
+            DFP4_READ_GROUP(G, v);                                                                  \
+            _Pragma("unroll") for (int x = 0; x < 16; ++x) mine[(G * 16 + x) * 256 + tid] = v[x];   \
+        }
+        DFP4_FOR_GROUPS(DFP4_PUBLISH)
+#undef DFP4_PUBLISH
+        __threadfence();
+        __syncthreads();
+        if (tid == 0) s_ctl[5] = (int)atomicAdd(counter, 1u);
+        __syncthreads();
+        if (s_ctl[5] != S - 1) return;
+        __threadfence();
+        if (*flag != 0) return;                        // another range declined: the whole tile falls back
+    }
     {
+        // the one rounding of the whole product: int32 -> fp32, scaled by 2^(refA + refW - 2)
         const int n = n0 + wave * 32 + r;
         const int ew = s_refw[wave * 32 + r];
-        auto store_group = [&](int g, const int (&v)[16]) {
+        auto store_group = [&](int g, int (&v)[16]) {
+            if (S > 1) {
+                for (int o = 0; o < S; ++o)
+                    if (o != sidx) {
+                        const int* other = part + (int64_t)o * (kTileM * kTileN);
+#pragma unroll
+                        for (int x = 0; x < 16; ++x) v[x] += other[(g * 16 + x) * 256 + tid];
+                    }
+            }
 #pragma unroll
             for (int x = 0; x < 16; ++x) {
                 const int ml = g * 32 + 8 * (x >> 2) + 4 * h + (x & 3);
@@ -480,21 +551,17 @@ __global__ __launch_bounds__(256, 1) void gemm_fast_kernel(GemmParams p) {
                 }
             }
         };
-#define DFP4_READ_GROUP(G)                                                                          \
-    do {                                                                                            \
-        int v[16];                                                                                  \
-        asm volatile(DFP4_ACC_READ_ASM_##G                                                          \
-                     : "=v"(v[0]), "=v"(v[1]), "=v"(v[2]), "=v"(v[3]), "=v"(v[4]), "=v"(v[5]),      \
-                       "=v"(v[6]), "=v"(v[7]), "=v"(v[8]), "=v"(v[9]), "=v"(v[10]), "=v"(v[11]),    \
-                       "=v"(v[12]), "=v"(v[13]), "=v"(v[14]), "=v"(v[15]));                         \
-        store_group(G, v);                                                                          \
-    } while (0)
-        DFP4_READ_GROUP(0); DFP4_READ_GROUP(1); DFP4_READ_GROUP(2); DFP4_READ_GROUP(3);
-        DFP4_READ_GROUP(4); DFP4_READ_GROUP(5); DFP4_READ_GROUP(6); DFP4_READ_GROUP(7);
-        DFP4_READ_GROUP(8); DFP4_READ_GROUP(9); DFP4_READ_GROUP(10); DFP4_READ_GROUP(11);
-        DFP4_READ_GROUP(12); DFP4_READ_GROUP(13); DFP4_READ_GROUP(14); DFP4_READ_GROUP(15);
-#undef DFP4_READ_GROUP
+#define DFP4_FINISH(G)                                                                              \
+        {                                                                                           \
+            int v[16];                                                                              \
+            DFP4_READ_GROUP(G, v);                                                                  \
+            store_group(G, v);                                                                      \
+        }
+        DFP4_FOR_GROUPS(DFP4_FINISH)
+#undef DFP4_FINISH
     }
+#undef DFP4_FOR_GROUPS
+#undef DFP4_READ_GROUP
 }
 
 // ---------------------------------------------------------------------------
@@ -609,7 +676,7 @@ int launch_gemm(bool mx, dfp4_tensor A, dfp4_tensor W, void* out, int out_dtype,
     p.ws = static_cast<uint8_t*>(workspace); p.ws_stride = lay.total;
     p.off_refa = lay.off_refa; p.off_refw = lay.off_refw; p.off_spreadw = lay.off_spreadw;
     p.off_wmeta = lay.off_wmeta; p.off_mask = lay.off_mask; p.off_flag = lay.off_flag;
-    p.off_a8 = lay.off_a8;
+    p.off_cnt = lay.off_cnt; p.off_part = lay.off_part; p.off_a8 = lay.off_a8;
     p.tiles_m = (int)((M + kTileM - 1) / kTileM); p.tiles_n = (int)((N + kTileN - 1) / kTileN);
     if (p.tiles_m > 16383 || p.tiles_n > (1 << 20)) return DFP4_ERR_SHAPE;
 
@@ -627,7 +694,11 @@ int launch_gemm(bool mx, dfp4_tensor A, dfp4_tensor W, void* out, int out_dtype,
             hipLaunchKernelGGL((gemm_expand_kernel<false>), ge, dim3(256), 0, stream, p);
         }
     }
-    dim3 gf((unsigned)p.tiles_n, (unsigned)p.tiles_m, (unsigned)batch);
+    // more problems in the batch means more tiles: never split K more than the layout provides for
+    p.ksplit = choose_ksplit((int64_t)p.tiles_m * p.tiles_n * batch, KB);
+    if (p.ksplit > lay.ksplit) p.ksplit = lay.ksplit;
+    if (batch * p.ksplit > 65535) return DFP4_ERR_SHAPE;
+    dim3 gf((unsigned)p.tiles_n, (unsigned)p.tiles_m, (unsigned)(batch * p.ksplit));
     dim3 gb((unsigned)((N + 127) / 128), (unsigned)((M + 127) / 128), (unsigned)batch);
     if (gb.y > 65535) return DFP4_ERR_SHAPE;
 #define DFP4_LAUNCH(MXV, BV)                                                                     \
