@@ -100,7 +100,7 @@ int dfp4_dequantize(dfp4_tensor in, void* y, int y_dtype, int64_t ld_elems, void
  * sums run on the int8 matrix cores with int32 accumulation and are exact;
  * the outer sum is accumulated in fp32.
  *   A        quantized [M, K]; W quantized [N, K] (both blocked along K)
- *   out      device, [M, N] row-major, leading dimension ldc (elements, >= N);
+ *   out      device, [M, N] row-major, leading dimension ldc (elements, N <= ldc < 2^27);
  *            out_dtype DFP4_F32 or DFP4_BF16 (round to nearest even)
  *   workspace, workspace_bytes   device scratch of at least
  *            dfp4_gemm_workspace_bytes(M, N, K) bytes, 256-byte aligned; may be

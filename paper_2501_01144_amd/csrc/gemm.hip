@@ -44,6 +44,7 @@
 //
 // The order of the elements inside an MFMA operand does not matter as long
 // as A and W use the same order; both sides go through unpack8() below.
+#include <type_traits>
 #include "common.h"
 #include "formatbook.h"
 #include "gemm_step_asm.inc"
@@ -75,7 +76,6 @@ constexpr int kGroups = kTileM / 32;        // 32-row groups per tile
 constexpr int kMaxKB = 512;           // fast path: K <= 16384
 constexpr int kMaxClass = 2;          // classes 0..2, i.e. exponent offsets 0..11
 constexpr int kIntBound = 4660;       // n0 + 16 n1 + 256 n2 <= 2^31 / (32 * 120 * 120)
-constexpr int kPrepChunk = 4;         // blocks per workgroup of the A expansion (4 blocks = one 64-byte line of codes per row)
 // one LDS stage of the fast kernel: A fragments of a pair of blocks for 512 rows,
 // the four waves' W codes, the four waves' W table offsets
 constexpr int kStageA = kGroups * 2 * 1024, kStageW = 4 * 1024, kStageM = 4 * 256;
@@ -89,18 +89,18 @@ struct GemmParams {
     int64_t ldc, strideA_rows, strideW_rows, strideC;
     // workspace (per batch entry: ws + batch * ws_stride)
     uint8_t* ws;
-    int64_t ws_stride, off_refa, off_refw, off_spreadw, off_wmeta, off_mask, off_flag, off_cnt, off_part, off_a8;
+    int64_t ws_stride, off_refa, off_refw, off_spreadw, off_wmeta, off_mask, off_flag, off_part, off_a8;
     int tiles_m, tiles_n;             // 512 x 128 output tiles
     int ksplit;                       // workgroups sharing one output tile (each takes a range of K)
 };
 
 struct Layout {
-    int64_t off_refa, off_refw, off_spreadw, off_wmeta, off_mask, off_flag, off_cnt, off_part, off_a8, total;
+    int64_t off_refa, off_refw, off_spreadw, off_wmeta, off_mask, off_flag, off_part, off_a8, total;
     int ksplit;
 };
 __host__ __device__ inline int64_t align256(int64_t x) { return (x + 255) & ~(int64_t)255; }
 // Workgroups per output tile: when there are fewer tiles than compute units, K is split
-// between 2, 4 or 8 workgroups whose exact int32 partial sums are added by the last to finish.
+// between 2, 4 or 8 workgroups whose exact int32 partial sums the follow-up kernel adds.
 inline int choose_ksplit(int64_t tiles, int64_t KB) {
     const int64_t cu = device_cu_count();
     int s = 1;
@@ -117,8 +117,7 @@ inline Layout make_layout(int64_t M, int64_t N, int64_t KB) {
     l.off_wmeta = align256(l.off_spreadw + tn * kTileN);
     l.off_mask = align256(l.off_wmeta + N * KB * 4);          // one table offset (dword) per W block
     l.off_flag = align256(l.off_mask + tm * KB);
-    l.off_cnt = align256(l.off_flag + tm * tn);
-    l.off_part = align256(l.off_cnt + tm * tn * 4);
+    l.off_part = align256(l.off_flag + tm * tn);
     l.off_a8 = align256(l.off_part + (l.ksplit > 1 ? (int64_t)l.ksplit * tm * tn * kTileM * kTileN * 4 : 0));
     // A fragments: [class][tile][group][block 0..KB][1 KiB]; block KB of class 0 is all zeros
     l.total = align256(l.off_a8 + (kMaxClass + 1) * tm * kGroups * (KB + 1) * 1024);
@@ -159,131 +158,202 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
 }
 
 // ---------------------------------------------------------------------------
-// Prepass 1: per-row statistics, one wave per row (A rows first, then W rows).
-//   A row: reference exponent (smallest block exponent of the row)
-//   W row: reference exponent, spread, and one table offset (dword) per block
+// Prepass (one launch, 1024 threads per workgroup).  Workgroups [0, n_a) expand A,
+// the others compute the per-row statistics of W.
+//
+// A workgroup = (512-row tile, chunk of 8 blocks); wave w owns the tile's 32-row
+// group w.  Each wave first finds its rows' reference exponents (smallest block
+// exponent of the whole row; the chunk-0 workgroup publishes them), then the
+// classes present in each block of the chunk among all 512 rows (one 32-bit word
+// in LDS: bit 4*block + class), then writes, for every class present, the 1 KiB
+// fragment of its group: rows of other classes contribute zeros.  The 4-bit codes
+// are read as whole 128-byte lines (8 lanes per row) and redistributed through LDS
+// to the fragment order (lane = (t, row): elements 16t .. 16t+15 of the block).
+//
+// W rows: reference exponent, spread, and one table offset (dword) per block.
 // ---------------------------------------------------------------------------
-template <bool MX>
-__global__ __launch_bounds__(256) void gemm_rowstat_kernel(GemmParams p) {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int64_t bz = blockIdx.z;
-    uint8_t* ws = p.ws + bz * p.ws_stride;
-    const int KB = p.KB;
-    if (blockIdx.x == 0) {
-        // per-tile state of the fast kernel: "declined" flags and split-K arrival counters
-        const int tiles = p.tiles_m * p.tiles_n;
-        for (int i = threadIdx.x; i < tiles; i += 256) {
-            ws[p.off_flag + i] = 0;
-            reinterpret_cast<uint32_t*>(ws + p.off_cnt)[i] = 0;
-        }
-    }
-    const int64_t row_id = (int64_t)blockIdx.x * 4 + wave;
-    const int m_pad = p.tiles_m * kTileM;
-    if (row_id >= (int64_t)m_pad + p.N) return;
-    const bool is_w = row_id >= m_pad;
-    const int row = is_w ? (int)(row_id - m_pad) : (int)row_id;
-    if (!is_w && row >= p.M) {                        // padding rows of the last A tile
-        if (lane == 0) ws[p.off_refa + row] = 0;
-        return;
-    }
-    const int64_t base = ((is_w ? bz * p.strideW_rows : bz * p.strideA_rows) + row) * KB;
-    const uint8_t* e = (is_w ? p.w_exp : p.a_exp) + base;
-    int mn = 255, mx = 0;
-    for (int kb = lane; kb < KB; kb += 64) {
-        const int v = e[kb];
-        mn = min(mn, v);
-        mx = max(mx, v);
-    }
-#pragma unroll
-    for (int s = 1; s < 64; s <<= 1) {
-        mn = min(mn, __shfl_xor(mn, s));
-        mx = max(mx, __shfl_xor(mx, s));
-    }
-    if (!is_w) {
-        if (lane == 0) ws[p.off_refa + row] = (uint8_t)mn;
-        return;
-    }
-    if (lane == 0) {
-        ws[p.off_refw + row] = (uint8_t)mn;
-        ws[p.off_spreadw + row] = (uint8_t)min(mx - mn, 255);
-    }
-    uint32_t* wmeta = reinterpret_cast<uint32_t*>(ws + p.off_wmeta) + (int64_t)row * KB;
-    for (int kb = lane; kb < KB; kb += 64) {
-        const uint32_t dial = MX ? 7u : ((uint32_t)p.w_dial[base + kb] & 15u);
-        const uint32_t sh = ((uint32_t)e[kb] - (uint32_t)mn) & 3u;
-        wmeta[kb] = (dial * 4u + sh) * 16u;
-    }
+__device__ __forceinline__ int min_bytes(uint32_t x) {
+    return min(min((int)(x & 0xffu), (int)((x >> 8) & 0xffu)), min((int)((x >> 16) & 0xffu), (int)(x >> 24)));
+}
+__device__ __forceinline__ int max_bytes(uint32_t x) {
+    return max(max((int)(x & 0xffu), (int)((x >> 8) & 0xffu)), max((int)((x >> 16) & 0xffu), (int)(x >> 24)));
+}
+// up to 8 bytes starting at q (the first n are read), little-endian in a 64-bit word
+__device__ __forceinline__ uint64_t load_bytes8(const uint8_t* q, int n, bool vec) {
+    if (vec && n == 8) return *reinterpret_cast<const uint64_t*>(q);
+    uint64_t v = 0;
+    for (int i = 0; i < n; ++i) v |= (uint64_t)q[i] << (8 * i);
+    return v;
 }
 
-// ---------------------------------------------------------------------------
-// Prepass 2: expand A.  grid = (chunks of kPrepChunk blocks, 512-row tiles, batch).
-// For every block of the chunk: which classes occur among the tile's rows, then
-// for each such class the 16 fragments (rows of other classes contribute zeros).
-// ---------------------------------------------------------------------------
 template <bool MX>
-__global__ __launch_bounds__(256) void gemm_expand_kernel(GemmParams p) {
-    __shared__ uint8_t s_ref[kTileM];
-    __shared__ uint32_t s_cls[kPrepChunk];
+__global__ __launch_bounds__(1024) void gemm_prep_kernel(GemmParams p, int n_a, int chunks_a) {
+    constexpr int kPitch = 144;                       // LDS bytes per row of staged codes (8 blocks = 128 + pad)
+    __shared__ __attribute__((aligned(16))) uint8_t s_codes[16][32 * kPitch];
+    __shared__ __attribute__((aligned(16))) uint32_t s_tab[kDialects * 16];
+    __shared__ uint32_t s_present;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int64_t bz = blockIdx.z;
     uint8_t* ws = p.ws + bz * p.ws_stride;
     const int KB = p.KB;
-    const int tile = blockIdx.y;
-    for (int i = tid; i < kTileM; i += 256) s_ref[i] = ws[p.off_refa + tile * kTileM + i];
-    if (tid < kPrepChunk) s_cls[tid] = 0;
-    if (blockIdx.x == 0) {
-        // the all-zero block (index KB) of every group of this tile, class 0
-        for (int i = tid; i < kGroups * 64; i += 256) {
-            uint8_t* dst = ws + p.off_a8 + (((int64_t)tile * kGroups + (i >> 6)) * (KB + 1) + KB) * 1024 + (i & 63) * 16;
-            *reinterpret_cast<uint4*>(dst) = make_uint4(0, 0, 0, 0);
+
+    if ((int)blockIdx.x >= n_a) {
+        // ---- W rows: `segs` lanes per row, 16 blocks per lane
+        int segs = 1;
+        while (segs * 16 < KB) segs <<= 1;            // <= 32: the fast path has KB <= 512
+        const int rows_per_wave = 64 / segs;
+        const int row = (((int)blockIdx.x - n_a) * 16 + wave) * rows_per_wave + lane / segs;
+        const int seg = lane % segs;
+        const bool valid = row < p.N;
+        const int64_t base = (bz * p.strideW_rows + min(row, p.N - 1)) * KB;
+        const int k0 = seg * 16, nb = max(0, min(16, KB - k0));
+        const bool vec = (KB & 15) == 0 && ((reinterpret_cast<uintptr_t>(p.w_exp) |
+                         (MX ? 0 : reinterpret_cast<uintptr_t>(p.w_dial))) & 15) == 0;
+        uint32_t e[4] = {0, 0, 0, 0}, d[4] = {0x07070707u, 0x07070707u, 0x07070707u, 0x07070707u};
+        if (vec && nb == 16) {
+            const uint4 ev = *reinterpret_cast<const uint4*>(p.w_exp + base + k0);
+            e[0] = ev.x; e[1] = ev.y; e[2] = ev.z; e[3] = ev.w;
+            if (!MX) {
+                const uint4 dv = *reinterpret_cast<const uint4*>(p.w_dial + base + k0);
+                d[0] = dv.x; d[1] = dv.y; d[2] = dv.z; d[3] = dv.w;
+            }
+        } else {
+            for (int j = 0; j < nb; ++j) {
+                e[j >> 2] |= (uint32_t)p.w_exp[base + k0 + j] << (8 * (j & 3));
+                if (!MX) d[j >> 2] = (d[j >> 2] & ~(0xffu << (8 * (j & 3)))) |
+                                     ((uint32_t)p.w_dial[base + k0 + j] << (8 * (j & 3)));
+            }
         }
+        int mn = 255, mx = 0;
+        if (nb == 16) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { mn = min(mn, min_bytes(e[i])); mx = max(mx, max_bytes(e[i])); }
+        } else {
+            for (int j = 0; j < nb; ++j) {
+                const int v = (e[j >> 2] >> (8 * (j & 3))) & 0xff;
+                mn = min(mn, v); mx = max(mx, v);
+            }
+        }
+        for (int s = 1; s < segs; s <<= 1) {
+            mn = min(mn, __shfl_xor(mn, s));
+            mx = max(mx, __shfl_xor(mx, s));
+        }
+        if (!valid) return;
+        if (seg == 0) {
+            ws[p.off_refw + row] = (uint8_t)mn;
+            ws[p.off_spreadw + row] = (uint8_t)min(mx - mn, 255);
+        }
+        uint32_t* wmeta = reinterpret_cast<uint32_t*>(ws + p.off_wmeta) + (int64_t)row * KB + k0;
+        if (nb == 16) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                uint32_t o[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const uint32_t ee = (e[i] >> (8 * j)) & 0xffu, dd = (d[i] >> (8 * j)) & 15u;
+                    o[j] = (dd * 4u + ((ee - (uint32_t)mn) & 3u)) * 16u;
+                }
+                *reinterpret_cast<uint4*>(wmeta + 4 * i) = make_uint4(o[0], o[1], o[2], o[3]);
+            }
+        } else {
+            for (int j = 0; j < nb; ++j) {
+                const uint32_t ee = (e[j >> 2] >> (8 * (j & 3))) & 0xffu, dd = (d[j >> 2] >> (8 * (j & 3))) & 15u;
+                wmeta[j] = (dd * 4u + ((ee - (uint32_t)mn) & 3u)) * 16u;
+            }
+        }
+        return;
+    }
+
+    // ---- A: tile, chunk of 8 blocks
+    const int tile = (int)blockIdx.x / chunks_a, chunk = (int)blockIdx.x % chunks_a;
+    const int kc = chunk * 8, nk = min(8, KB - kc);
+    for (int i = tid; i < kDialects * 16; i += 1024) s_tab[i] = (&g_shifted_book.w[0][0][0])[i];
+    if (tid == 0) s_present = 0;
+    if (blockIdx.x == 0) {
+        // per-tile "declined" flags of the fast kernel
+        const int tiles = p.tiles_m * p.tiles_n;
+        for (int i = tid; i < tiles; i += 1024) ws[p.off_flag + i] = 0;
     }
     __syncthreads();
 
-    // lane = (t, r): row r of a 32-row group, elements 16t .. 16t+15; wave w owns groups 4w .. 4w+3
-    constexpr int kGW = kGroups / 4;
     const int r = lane & 31, t = lane >> 5;
-    const int kc = blockIdx.x * kPrepChunk;
-    const int nk = min(kPrepChunk, KB - kc);
-    int cls_of[kGW * kPrepChunk], sh_of[kGW * kPrepChunk];
+    const int row0 = tile * kTileM + wave * 32;
+    const bool group_valid = row0 < p.M;              // wave-uniform
+    const bool vec = (KB & 15) == 0 && ((reinterpret_cast<uintptr_t>(p.a_exp) |
+                     (MX ? 0 : reinterpret_cast<uintptr_t>(p.a_dial))) & 15) == 0;
+    int cls[8], sh[8];
+    uint64_t d8 = 0x0707070707070707ull;
+    if (group_valid) {
+        // codes: lane (row q*8 + lane/8, block lane%8) reads one block; 8 lanes cover a 128-byte line
+        uint4 craw[4];
 #pragma unroll
-    for (int it = 0; it < kGW * kPrepChunk; ++it) {
-        const int sub = wave * kGW + (it % kGW), kbl = it / kGW;
-        const int row = tile * kTileM + sub * 32 + r;
-        const bool valid = row < p.M && kbl < nk;
-        const int64_t arow = bz * p.strideA_rows + min(row, p.M - 1);
-        const int delta = valid ? (int)p.a_exp[arow * KB + kc + kbl] - (int)s_ref[sub * 32 + r] : 0;
-        cls_of[it] = valid ? min(delta >> 2, kMaxClass + 1) : -1;
-        sh_of[it] = delta & 3;
-        uint32_t present = 0;
+        for (int q = 0; q < 4; ++q) {
+            const int k8 = lane & 7;
+            const int64_t rq = bz * p.strideA_rows + min(row0 + q * 8 + (lane >> 3), p.M - 1);
+            craw[q] = k8 < nk ? *reinterpret_cast<const uint4*>(p.a_codes + (rq * KB + kc + k8) * 16)
+                              : make_uint4(0, 0, 0, 0);
+        }
+        const int64_t arow = bz * p.strideA_rows + min(row0 + r, p.M - 1);
+        const uint64_t e8 = load_bytes8(p.a_exp + arow * KB + kc, nk, vec);
+        if (!MX) d8 = load_bytes8(p.a_dial + arow * KB + kc, nk, vec);
+        // reference exponent of the row: lane (t, r) scans every other 16-byte piece
+        int mn = 255;
+        const uint8_t* erow = p.a_exp + arow * KB;
+        if (vec) {
+            const int n16 = KB >> 4;
+            for (int i0 = 0; i0 < n16; i0 += 8) {
+                uint4 v[4];
 #pragma unroll
-        for (int cc = 0; cc <= kMaxClass + 1; ++cc)
-            if (__ballot(cls_of[it] == cc) != 0ull) present |= 1u << cc;
-        if (lane == 0 && present) atomicOr(&s_cls[kbl], present);
+                for (int u = 0; u < 4; ++u)
+                    v[u] = *reinterpret_cast<const uint4*>(erow + 16 * min(i0 + 2 * u + t, n16 - 1));
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    mn = min(mn, min(min(min_bytes(v[u].x), min_bytes(v[u].y)), min(min_bytes(v[u].z), min_bytes(v[u].w))));
+            }
+        } else {
+            for (int i = t; i < KB; i += 2) mn = min(mn, (int)erow[i]);
+        }
+        mn = min(mn, __shfl_xor(mn, 32));
+        const bool row_valid = row0 + r < p.M;
+        if (chunk == 0 && t == 0) ws[p.off_refa + row0 + r] = row_valid ? (uint8_t)mn : (uint8_t)0;
+        uint32_t word = 0;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int delta = (int)((e8 >> (8 * k)) & 0xffu) - mn;
+            const bool on = k < nk && row_valid;
+            cls[k] = on ? min(delta >> 2, kMaxClass + 1) : -1;
+            sh[k] = on ? (delta & 3) : 0;
+            if (on) word |= 1u << (4 * k + cls[k]);
+        }
+#pragma unroll
+        for (int s = 1; s < 64; s <<= 1) word |= (uint32_t)__shfl_xor((int)word, s);
+        if (lane == 0) atomicOr(&s_present, word);
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            *reinterpret_cast<uint4*>(&s_codes[wave][(q * 8 + (lane >> 3)) * kPitch + (lane & 7) * 16]) = craw[q];
+    } else if (chunk == 0 && t == 0) {
+        ws[p.off_refa + row0 + r] = 0;                // padding rows of the last tile
     }
     __syncthreads();
+    const uint32_t present = s_present;
+    if (wave == 0 && lane < nk) ws[p.off_mask + (int64_t)tile * KB + kc + lane] = (uint8_t)((present >> (4 * lane)) & 15u);
+    const int64_t grp = (int64_t)tile * kGroups + wave;
+    if (chunk == 0)                                   // the all-zero block (index KB) of this group, class 0
+        *reinterpret_cast<uint4*>(ws + p.off_a8 + (grp * (KB + 1) + KB) * 1024 + lane * 16) = make_uint4(0, 0, 0, 0);
+    if (!group_valid) return;
+    const int64_t cls_stride = (int64_t)p.tiles_m * kGroups * (KB + 1) * 1024;
 #pragma unroll
-    for (int it = 0; it < kGW * kPrepChunk; ++it) {
-        const int sub = wave * kGW + (it % kGW), kbl = it / kGW;
-        if (kbl >= nk) continue;
-        const int kb = kc + kbl;
-        const int row = tile * kTileM + sub * 32 + r;
-        const int64_t arow = bz * p.strideA_rows + min(row, p.M - 1);
-        const uint32_t dial = MX ? 7u : ((uint32_t)p.a_dial[arow * KB + kb] & 15u);
-        const uint2 c = *reinterpret_cast<const uint2*>(p.a_codes + (arow * KB + kb) * 16 + t * 8);
-        const uint4 tab = *reinterpret_cast<const uint4*>(g_shifted_book.w[dial][sh_of[it]]);
+    for (int k = 0; k < 8; ++k) {
+        if (k >= nk) break;
+        const uint2 c = *reinterpret_cast<const uint2*>(&s_codes[wave][r * kPitch + k * 16 + t * 8]);
+        const uint32_t dial = (uint32_t)(d8 >> (8 * k)) & 15u;
+        const uint4 tab = *reinterpret_cast<const uint4*>(&s_tab[(dial * 4 + sh[k]) * 4]);
         const v4i data = unpack16(c.x, c.y, tab);
-        const uint32_t present = s_cls[kbl];
-        if (sub == 0 && lane == 0) ws[p.off_mask + (int64_t)tile * KB + kb] = (uint8_t)present;
+        uint8_t* dst = ws + p.off_a8 + (grp * (KB + 1) + kc + k) * 1024 + t * 512 + r * 16;
 #pragma unroll
         for (int cc = 0; cc <= kMaxClass; ++cc)
-            if (present & (1u << cc)) {
-                const v4i v = cls_of[it] == cc ? data : v4i{0, 0, 0, 0};
-                uint8_t* dst = ws + p.off_a8 +
-                               ((((int64_t)cc * p.tiles_m + tile) * kGroups + sub) * (KB + 1) + kb) * 1024 +
-                               t * 512 + r * 16;
-                *reinterpret_cast<v4i*>(dst) = v;
-            }
+            if ((present >> (4 * k + cc)) & 1u)
+                *reinterpret_cast<v4i*>(dst + cc * cls_stride) = cls[k] == cc ? data : v4i{0, 0, 0, 0};
     }
 }
 
@@ -308,7 +378,6 @@ __global__ __launch_bounds__(256, 1) void gemm_fast_kernel(GemmParams p) {
     uint8_t* ws = p.ws + bz * p.ws_stride;
     const int tile_id = blockIdx.y * p.tiles_n + blockIdx.x;
     volatile uint8_t* flag = ws + p.off_flag + tile_id;
-    uint32_t* counter = reinterpret_cast<uint32_t*>(ws + p.off_cnt) + tile_id;
     // this workgroup's range of blocks
     const int kb_per = (KB + S - 1) / S;
     const int kb_lo = sidx * kb_per, kb_hi = min(KB, kb_lo + kb_per);
@@ -357,12 +426,8 @@ __global__ __launch_bounds__(256, 1) void gemm_fast_kernel(GemmParams p) {
         const bool ok = s_ctl[4] == 0 && (n0c + 16 * n1 + 256 * n2) * S <= kIntBound &&
                         a8_bytes < ((int64_t)1 << 32) && (int64_t)p.N * KB * 16 < ((int64_t)1 << 32);
         if (!ok) {
-            // decline the tile (the block-flush kernel computes it); still count as arrived
-            if (tid == 0) {
-                *flag = 1;
-                __threadfence();
-                if (S > 1) atomicAdd(counter, 1u);
-            }
+            // decline the tile: the block-flush kernel computes it
+            if (tid == 0) *flag = 1;
             return;
         }
     }
@@ -505,8 +570,8 @@ __global__ __launch_bounds__(256, 1) void gemm_fast_kernel(GemmParams p) {
     F(0) F(1) F(2) F(3) F(4) F(5) F(6) F(7) F(8) F(9) F(10) F(11) F(12) F(13) F(14) F(15)
     int* part = reinterpret_cast<int*>(ws + p.off_part) + (int64_t)tile_id * S * (kTileM * kTileN);
     if (S > 1) {
-        // K is shared with other workgroups: publish this one's exact int32 sums; the last
-        // workgroup of the tile to arrive adds the others' and finishes the tile
+        // K is shared with other workgroups: publish this one's exact int32 sums (the sum of
+        // all ranges is exact and does not depend on their order)
         int* mine = part + (int64_t)sidx * (kTileM * kTileN);
 #define DFP4_PUBLISH(G)                                                                             \
         {                                                                                           \
@@ -516,38 +581,59 @@ __global__ __launch_bounds__(256, 1) void gemm_fast_kernel(GemmParams p) {
         }
         DFP4_FOR_GROUPS(DFP4_PUBLISH)
 #undef DFP4_PUBLISH
-        __threadfence();
-        __syncthreads();
-        if (tid == 0) s_ctl[5] = (int)atomicAdd(counter, 1u);
-        __syncthreads();
-        if (s_ctl[5] != S - 1) return;
-        __threadfence();
-        if (*flag != 0) return;                        // another range declined: the whole tile falls back
+        return;                                        // gemm_block_kernel adds the ranges up and stores the tile
     }
     {
-        // the one rounding of the whole product: int32 -> fp32, scaled by 2^(refA + refW - 2)
-        const int n = n0 + wave * 32 + r;
-        const int ew = s_refw[wave * 32 + r];
-        auto store_group = [&](int g, int (&v)[16]) {
-            if (S > 1) {
-                for (int o = 0; o < S; ++o)
-                    if (o != sidx) {
-                        const int* other = part + (int64_t)o * (kTileM * kTileN);
+        // The one rounding of the whole product: int32 -> fp32, scaled by 2^(refA + refW - 2).
+        // Accumulator x of lane (h, r) of group g is output row g*32 + 8*(x>>2) + 4*h + (x&3),
+        // column wave*32 + r.  Row addresses are wave-uniform (scalar registers); the lane adds a
+        // constant byte offset, so a store costs a handful of instructions.
+        constexpr int kEsz = BF16 ? 2 : 4;
+        const int ew = (int)s_refw[wave * 32 + r] - 256;
+        const int col0 = n0 + (int)wave_u * 32;
+        uint8_t* tile_out = static_cast<uint8_t*>(p.out) +
+                            (bz * p.strideC + (int64_t)m0 * p.ldc + col0) * kEsz;          // uniform
+        const int64_t row_bytes = p.ldc * kEsz;                                              // uniform
+        const bool full = m0 + kTileM <= p.M && col0 + 32 <= p.N;                            // uniform
+        // bf16: lanes exchange values in pairs so that every lane stores two adjacent columns of
+        // one row (even lanes the even row of a row pair, odd lanes the odd row)
+        const bool pairs = BF16 && full && (p.ldc & 1) == 0 && ((p.strideC * kEsz) & 3) == 0 &&
+                           (reinterpret_cast<uintptr_t>(p.out) & 3) == 0;                    // uniform
+        const uint32_t lane_off = pairs ? (uint32_t)((4 * h + (r & 1)) * row_bytes + (r & ~1) * kEsz)
+                                        : (uint32_t)(4 * h * row_bytes + r * kEsz);
+        auto store_group = [&](auto full_c, auto pairs_c, int g, int (&v)[16]) {
+            constexpr bool kFull = decltype(full_c)::value, kPairs = decltype(pairs_c)::value;
+            uint8_t* grp_out = tile_out + (int64_t)g * 32 * row_bytes;
 #pragma unroll
-                        for (int x = 0; x < 16; ++x) v[x] += other[(g * 16 + x) * 256 + tid];
+            for (int q = 0; q < 4; ++q) {
+                const uint32_t e4 = *reinterpret_cast<const uint32_t*>(&s_refa[g * 32 + 8 * q + 4 * h]);
+                float f[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    f[j] = ldexpf((float)v[4 * q + j], (int)((e4 >> (8 * j)) & 0xffu) + ew);
+                uint8_t* rowp = grp_out + (int64_t)(8 * q) * row_bytes;                     // uniform
+                if constexpr (BF16 && kPairs) {
+                    {
+#pragma unroll
+                        for (int j = 0; j < 4; j += 2) {
+                            const uint32_t b0 = f32_to_bf16_rne(f[j]), b1 = f32_to_bf16_rne(f[j + 1]);
+                            const uint32_t send = (r & 1) ? b0 : b1;
+                            const uint32_t recv = (uint32_t)__builtin_amdgcn_mov_dpp((int)send, 0xB1, 0xf, 0xf, true);
+                            const uint32_t word = (r & 1) ? (recv | (b1 << 16)) : (b0 | (recv << 16));
+                            *reinterpret_cast<uint32_t*>(rowp + (int64_t)j * row_bytes + lane_off) = word;
+                        }
+                        continue;
                     }
-            }
+                }
 #pragma unroll
-            for (int x = 0; x < 16; ++x) {
-                const int ml = g * 32 + 8 * (x >> 2) + 4 * h + (x & 3);
-                const int m = m0 + ml;
-                if (m < p.M && n < p.N) {
-                    const float f = ldexpf((float)v[x], (int)s_refa[ml] + ew - 256);
-                    const int64_t o = bz * p.strideC + (int64_t)m * p.ldc + n;
-                    if constexpr (BF16)
-                        static_cast<uint16_t*>(p.out)[o] = f32_to_bf16_rne(f);
-                    else
-                        static_cast<float*>(p.out)[o] = f;
+                for (int j = 0; j < 4; ++j) {
+                    if (kFull || (m0 + g * 32 + 8 * q + 4 * h + j < p.M && col0 + r < p.N)) {
+                        uint8_t* dst = rowp + (int64_t)j * row_bytes + lane_off;
+                        if constexpr (BF16)
+                            *reinterpret_cast<uint16_t*>(dst) = f32_to_bf16_rne(f[j]);
+                        else
+                            *reinterpret_cast<float*>(dst) = f[j];
+                    }
                 }
             }
         };
@@ -555,13 +641,67 @@ __global__ __launch_bounds__(256, 1) void gemm_fast_kernel(GemmParams p) {
         {                                                                                           \
             int v[16];                                                                              \
             DFP4_READ_GROUP(G, v);                                                                  \
-            store_group(G, v);                                                                      \
+            store_group(kFullC, kPairsC, G, v);                                                     \
         }
-        DFP4_FOR_GROUPS(DFP4_FINISH)
+        if (pairs) {
+            constexpr std::true_type kFullC{}, kPairsC{};
+            DFP4_FOR_GROUPS(DFP4_FINISH)
+        } else if (full) {
+            constexpr std::true_type kFullC{};
+            constexpr std::false_type kPairsC{};
+            DFP4_FOR_GROUPS(DFP4_FINISH)
+        } else {
+            constexpr std::false_type kFullC{}, kPairsC{};
+            DFP4_FOR_GROUPS(DFP4_FINISH)
+        }
 #undef DFP4_FINISH
     }
 #undef DFP4_FOR_GROUPS
 #undef DFP4_READ_GROUP
+}
+
+// ---------------------------------------------------------------------------
+// Sum of the K ranges of one 128 x 128 piece of a fast-kernel tile (split K):
+// the exact int32 partial sums the ranges published are added, converted once
+// and stored.  Thread t of the fast kernel holds column (t / 64) * 32 + (t % 32);
+// its accumulator x of group g is row g*32 + 8*(x/4) + 4*((t % 64) / 32) + x % 4.
+// ---------------------------------------------------------------------------
+template <bool BF16>
+__device__ __forceinline__ void reduce_ranges(const GemmParams& p) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int h = lane >> 5, r = lane & 31;
+    const int64_t bz = blockIdx.z;
+    const uint8_t* ws = p.ws + bz * p.ws_stride;
+    const int tile_m = blockIdx.y >> 2, gq = blockIdx.y & 3, S = p.ksplit;
+    const int tile_id = tile_m * p.tiles_n + blockIdx.x;
+    const int* part = reinterpret_cast<const int*>(ws + p.off_part) + (int64_t)tile_id * S * (kTileM * kTileN);
+    const int n = blockIdx.x * kTileN + wave * 32 + r;
+    const int ew = n < p.N ? (int)ws[p.off_refw + n] - 256 : 0;
+#pragma unroll
+    for (int gi = 0; gi < 4; ++gi) {
+        const int g = gq * 4 + gi;
+        int v[16];
+#pragma unroll
+        for (int x = 0; x < 16; ++x) v[x] = part[(g * 16 + x) * 256 + tid];
+        for (int s = 1; s < S; ++s) {
+            const int* other = part + (int64_t)s * (kTileM * kTileN);
+#pragma unroll
+            for (int x = 0; x < 16; ++x) v[x] += other[(g * 16 + x) * 256 + tid];
+        }
+#pragma unroll
+        for (int x = 0; x < 16; ++x) {
+            const int ml = g * 32 + 8 * (x >> 2) + 4 * h + (x & 3);
+            const int m = tile_m * kTileM + ml;
+            if (m < p.M && n < p.N) {
+                const float f = ldexpf((float)v[x], (int)ws[p.off_refa + m] + ew);
+                const int64_t o = bz * p.strideC + (int64_t)m * p.ldc + n;
+                if constexpr (BF16)
+                    static_cast<uint16_t*>(p.out)[o] = f32_to_bf16_rne(f);
+                else
+                    static_cast<float*>(p.out)[o] = f;
+            }
+        }
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -577,7 +717,10 @@ __global__ __launch_bounds__(256) void gemm_block_kernel(GemmParams p, int use_f
     if (use_flags) {
         const uint8_t* flag = p.ws + bz * p.ws_stride + p.off_flag + (int64_t)(blockIdx.y / 4) * p.tiles_n +
                               blockIdx.x;
-        if (*flag == 0) return;
+        if (*flag == 0) {
+            if (p.ksplit > 1) reduce_ranges<BF16>(p);
+            return;
+        }
     }
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = wave >> 1, wn = wave & 1;
@@ -664,7 +807,8 @@ int launch_gemm(bool mx, dfp4_tensor A, dfp4_tensor W, void* out, int out_dtype,
                 void* workspace, size_t workspace_bytes, hipStream_t stream) {
     const int64_t M = A.rows, N = W.rows, KB = A.K / kBlock;
     if (M == 0 || N == 0 || batch == 0) return DFP4_OK;
-    if (M >= (1 << 30) || N >= (1 << 30) || KB >= (1 << 26) || batch > 65535) return DFP4_ERR_SHAPE;
+    if (M >= (1 << 30) || N >= (1 << 30) || KB >= (1 << 26) || batch > 65535 || ldc >= (1 << 27))
+        return DFP4_ERR_SHAPE;
     const Layout lay = make_layout(M, N, KB);
     if ((size_t)lay.total * (size_t)batch > workspace_bytes) return DFP4_ERR_WORKSPACE;
 
@@ -676,23 +820,23 @@ int launch_gemm(bool mx, dfp4_tensor A, dfp4_tensor W, void* out, int out_dtype,
     p.ws = static_cast<uint8_t*>(workspace); p.ws_stride = lay.total;
     p.off_refa = lay.off_refa; p.off_refw = lay.off_refw; p.off_spreadw = lay.off_spreadw;
     p.off_wmeta = lay.off_wmeta; p.off_mask = lay.off_mask; p.off_flag = lay.off_flag;
-    p.off_cnt = lay.off_cnt; p.off_part = lay.off_part; p.off_a8 = lay.off_a8;
+    p.off_part = lay.off_part; p.off_a8 = lay.off_a8;
     p.tiles_m = (int)((M + kTileM - 1) / kTileM); p.tiles_n = (int)((N + kTileN - 1) / kTileN);
     if (p.tiles_m > 16383 || p.tiles_n > (1 << 20)) return DFP4_ERR_SHAPE;
 
     const bool bf16 = out_dtype == DFP4_BF16;
     const bool fast = KB > 0 && KB <= kMaxKB;
     if (fast) {
-        const int64_t rows = (int64_t)p.tiles_m * kTileM + N;
-        dim3 gs((unsigned)((rows + 3) / 4), 1, (unsigned)batch);
-        dim3 ge((unsigned)((KB + kPrepChunk - 1) / kPrepChunk), (unsigned)p.tiles_m, (unsigned)batch);
-        if (mx) {
-            hipLaunchKernelGGL((gemm_rowstat_kernel<true>), gs, dim3(256), 0, stream, p);
-            hipLaunchKernelGGL((gemm_expand_kernel<true>), ge, dim3(256), 0, stream, p);
-        } else {
-            hipLaunchKernelGGL((gemm_rowstat_kernel<false>), gs, dim3(256), 0, stream, p);
-            hipLaunchKernelGGL((gemm_expand_kernel<false>), ge, dim3(256), 0, stream, p);
-        }
+        const int chunks_a = (int)((KB + 7) / 8), n_a = p.tiles_m * chunks_a;
+        int segs = 1;
+        while (segs * 16 < KB) segs <<= 1;
+        const int64_t n_w = (N + 16 * (64 / segs) - 1) / (16 * (64 / segs));
+        if (n_a + n_w > 0x7fffffff) return DFP4_ERR_SHAPE;
+        dim3 gp((unsigned)(n_a + n_w), 1, (unsigned)batch);
+        if (mx)
+            hipLaunchKernelGGL((gemm_prep_kernel<true>), gp, dim3(1024), 0, stream, p, n_a, chunks_a);
+        else
+            hipLaunchKernelGGL((gemm_prep_kernel<false>), gp, dim3(1024), 0, stream, p, n_a, chunks_a);
     }
     // more problems in the batch means more tiles: never split K more than the layout provides for
     p.ksplit = choose_ksplit((int64_t)p.tiles_m * p.tiles_n * batch, KB);
