@@ -76,11 +76,9 @@ constexpr int kGroups = kTileM / 32;        // 32-row groups per tile
 constexpr int kMaxKB = 512;           // fast path: K <= 16384
 constexpr int kMaxClass = 2;          // classes 0..2, i.e. exponent offsets 0..11
 constexpr int kIntBound = 4660;       // n0 + 16 n1 + 256 n2 <= 2^31 / (32 * 120 * 120)
-// one LDS stage of the fast kernel: A fragments of a pair of blocks for 512 rows,
-// the four waves' W codes, the four waves' W table offsets
-constexpr int kStageA = kGroups * 2 * 1024, kStageW = 4 * 1024, kStageM = 4 * 256;
-constexpr int kStageBytes = kStageA + kStageW + kStageM;
-constexpr int kStages = 4;
+constexpr int kBBufBytes = 8 * 1024;  // int8 W operands of one step: 4 column tiles x 2 x 1 KiB
+constexpr int kVisitPad = 12;         // padding visits after the last one (the loop looks 5 steps ahead)
+constexpr int kVisitCap = (kMaxClass + 1) * (kMaxKB + 1) + kVisitPad + 4;
 
 struct GemmParams {
     const uint8_t *a_codes, *a_dial, *a_exp, *w_codes, *w_dial, *w_exp;
@@ -358,17 +356,19 @@ __global__ __launch_bounds__(1024) void gemm_prep_kernel(GemmParams p, int n_a, 
 }
 
 // ---------------------------------------------------------------------------
-// Fast kernel: 512 x 128 outputs per workgroup, one int32 accumulator per output
+// Fast kernel: 512 x 128 outputs per workgroup, one int32 accumulator per output.
+// Wave w owns rows 128w .. 128w+127 and all 128 columns (16 accumulator tiles of
+// 32 x 32: tile i = 4 * gi + n is rows 32 gi .., columns 32 n ..).
 // ---------------------------------------------------------------------------
 template <bool MX, bool BF16>
 __global__ __launch_bounds__(256, 1) void gemm_fast_kernel(GemmParams p) {
-    // per stage: A fragments [group][t][h][r][16] | W codes [wave][lane][16] | W table offsets [wave][lane][4]
-    __shared__ __attribute__((aligned(16))) uint8_t s_stage[kStages][kStageBytes];
+    // int8 W operands of a pair of blocks: [column tile n][t][lane][16 bytes]; three buffers in rotation
+    __shared__ __attribute__((aligned(16))) uint8_t s_b[3][kBBufBytes];
     __shared__ __attribute__((aligned(16))) uint32_t s_tab[kDialects * 4 * 4];
-    __shared__ uint32_t s_va[(kMaxClass + 1) * (kMaxKB + 8) + 8];   // per visit: byte offset of its A fragments
-    __shared__ uint16_t s_vl[(kMaxClass + 1) * (kMaxKB + 8) + 8];   // per visit: block index
-    __shared__ uint8_t s_refa[kTileM], s_refw[kTileN];
-    __shared__ int s_ctl[8];          // group ends (entries), feasibility
+    __shared__ uint16_t s_vl[kVisitCap];     // visits: class << 10 | block, classes from high to low
+    __shared__ __attribute__((aligned(4))) uint8_t s_refa[kTileM];
+    __shared__ uint8_t s_refw[kTileN];
+    __shared__ int s_ctl[8];                 // segment ends (entries), feasibility
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int KB = p.KB;
@@ -406,233 +406,156 @@ __global__ __launch_bounds__(256, 1) void gemm_fast_kernel(GemmParams p) {
                 if (mk & (1u << (kMaxClass + 1))) s_ctl[4] = 1;       // offset beyond the classes kept
                 const bool f = (mk >> c) & 1u;
                 const unsigned long long bal = __ballot(f);
-                if (f) s_vl[pos + __popcll(bal & ((1ull << lane) - 1ull))] = (uint16_t)kb;
+                if (f) s_vl[pos + __popcll(bal & ((1ull << lane) - 1ull))] = (uint16_t)(kb | (c << 10));
                 pos += __popcll(bal);
             }
-            if (pos & 3) {                                            // pad the class to two pairs
-                const int padn = 4 - (pos & 3);
-                if (lane < padn) s_vl[pos + lane] = 0xffffu;
-                pos += padn;
+            if (pos & 1) {                                            // a step takes two visits
+                if (lane == 0) s_vl[pos] = (uint16_t)KB;              // padding: the all-zero block of class 0
+                pos += 1;
             }
             if (lane == 0) s_ctl[kMaxClass - c] = pos;                // s_ctl[0..2]: end of class 2, 1, 0
         }
-        if (lane < 6) s_vl[pos + lane] = 0xffffu;                     // three padding pairs for the prefetch
+        if (lane < kVisitPad) s_vl[pos + lane] = (uint16_t)KB;        // the loop looks five steps ahead
     }
     __syncthreads();
-    const int end2 = s_ctl[0] / 2, end1 = s_ctl[1] / 2, total = s_ctl[2] / 2;   // in pairs
+    const int end2 = s_ctl[0] / 2, end1 = s_ctl[1] / 2, total = s_ctl[2] / 2;   // in steps
     {
         const int n2 = s_ctl[0], n1 = s_ctl[1] - s_ctl[0], n0c = s_ctl[2] - s_ctl[1];
         const int64_t a8_bytes = (int64_t)(kMaxClass + 1) * p.tiles_m * kGroups * (KB + 1) * 1024;
         const bool ok = s_ctl[4] == 0 && (n0c + 16 * n1 + 256 * n2) * S <= kIntBound &&
-                        a8_bytes < ((int64_t)1 << 32) && (int64_t)p.N * KB * 16 < ((int64_t)1 << 32);
+                        a8_bytes < ((int64_t)1 << 31) && (int64_t)p.N * KB * 16 < ((int64_t)1 << 31);
         if (!ok) {
             // decline the tile: the block-flush kernel computes it
             if (tid == 0) *flag = 1;
             return;
         }
     }
-    // byte offset (from the start of the A fragments) of each visit's fragments for this tile's
-    // group 0; padding visits use the all-zero block of class 0 (and block 0 of W)
-    {
-        const uint32_t grp_stride = (uint32_t)(KB + 1) * 1024u;
-        const uint32_t cls_stride = (uint32_t)p.tiles_m * kGroups * grp_stride;
-        const uint32_t tile_off = (uint32_t)blockIdx.y * kGroups * grp_stride;
-        for (int i = tid; i < 2 * total + 6; i += 256) {
-            const uint32_t e = s_vl[i];
-            const uint32_t cls = i < 2 * end2 ? 2u : (i < 2 * end1 ? 1u : 0u);
-            s_va[i] = e == 0xffffu ? tile_off + (uint32_t)KB * 1024u : cls * cls_stride + tile_off + e * 1024u;
-            if (e == 0xffffu) s_vl[i] = 0;
-        }
-    }
-    __syncthreads();
 
-    // ---- main loop over pairs of (block, class) visits
-    const int h = lane >> 5, r = lane & 31;            // MFMA operand: K half h, row / column r
+    const int h = lane >> 5, r = lane & 31;            // MFMA operand: lanes 32.. hold the pair's second block
     const uint32_t wave_u = (uint32_t)__builtin_amdgcn_readfirstlane(wave);
-    const uint32_t lds0 = (uint32_t)__builtin_amdgcn_readfirstlane(
-        (int)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)&s_stage[0][0]);
     const uint32_t lds_tab = (uint32_t)__builtin_amdgcn_readfirstlane(
         (int)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)&s_tab[0]);
-    // Every operand byte goes from global memory straight into LDS (no registers).
-    // A: one wave instruction fills the 1 KiB fragment (group, t): lanes 0..31 take block
-    // h = 0 of the pair, lanes 32..63 block h = 1; wave w fills groups 4w .. 4w+3.
-    // W: each wave fetches the codes of its own 32 rows (lane = (h, row)) and their table offsets.
+    const uint32_t lds_vl = (uint32_t)__builtin_amdgcn_readfirstlane(
+        (int)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)&s_vl[0]);
+    const uint32_t lds_b = (uint32_t)__builtin_amdgcn_readfirstlane(
+        (int)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)&s_b[0][0]);
     const uint32_t grp_stride = (uint32_t)(KB + 1) * 1024u;
-    const uint8_t* a8 = ws + p.off_a8 + (uint64_t)wave_u * 4u * grp_stride;   // uniform per wave
-    const uint8_t* a_base[8];
-#pragma unroll
-    for (int j = 0; j < 8; ++j) a_base[j] = a8 + (uint64_t)(j >> 1) * grp_stride + (j & 1) * 512u;
-    const uint8_t* wcodes = p.w_codes + bz * p.strideW_rows * KB * 16;   // uniform
-    const uint8_t* wmeta = ws + p.off_wmeta;           // uniform
-    const int ncol = min(n0 + wave * 32 + r, p.N - 1);
+    const uint32_t cls_stride = (uint32_t)p.tiles_m * kGroups * grp_stride;
+    const uint32_t tile_off = (uint32_t)blockIdx.y * kGroups * grp_stride;
+    const uint8_t* a8w = ws + p.off_a8 + (uint64_t)wave_u * 4u * grp_stride;   // uniform per wave
+    const uint8_t* wcodes = p.w_codes + bz * p.strideW_rows * KB * 16;        // uniform
+    const uint8_t* wmeta = ws + p.off_wmeta;                                  // uniform
+    const int ncol = min(n0 + wave * 32 + r, p.N - 1);                        // this lane's W row
     const uint32_t w_row_codes = (uint32_t)ncol * (uint32_t)KB * 16u;
     const uint32_t w_row_meta = (uint32_t)ncol * (uint32_t)KB * 4u;
-    const uint32_t a_lane = (uint32_t)r * 16u;
-    // LDS byte addresses inside a stage (add the stage's base)
-    const uint32_t m0a_off = wave_u * 8u * 1024u;
-    const uint32_t m0w_off = kStageA + wave_u * 1024u;
-    const uint32_t m0m_off = kStageA + kStageW + wave_u * 256u;
-    const uint32_t sa_lane = (uint32_t)lane * 16u;
-    const uint32_t swc_lane = kStageA + (uint32_t)wave * 1024u + (uint32_t)lane * 16u;
-    const uint32_t swm_lane = kStageA + kStageW + (uint32_t)wave * 256u + (uint32_t)lane * 4u;
-    const uint32_t sign_sel = 0x090b080au;
 
-    // The accumulators live in a[0:255] and belong to the assembly blocks (gemm_step_asm.inc).
-    asm volatile(DFP4_ACC_ZERO_ASM ::: DFP4_ACC_CLOBBERS);
-
-#define DFP4_LDS_DMA(INSTR, DST, VOFF, SBASE)                                                   \
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\t" INSTR " %1, %2" :: "s"(DST), "v"(VOFF), "s"(SBASE) : "m0", "memory")
-    // prologue loads of pair `vc` into the stage at LDS address `st` (the steady state issues
-    // them from inside the step)
-    auto issue_loads = [&](int vc, uint32_t st) {
-        const uint32_t voff = s_va[2 * vc + h] + a_lane;
-        const uint32_t kb = s_vl[2 * vc + h];
+    // W operands of the first two steps (the loop expands those of step s + 2 during step s)
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const uint32_t dst = st + m0a_off + j * 1024u;
-            DFP4_LDS_DMA("global_load_lds_dwordx4", dst, voff, a_base[j]);
-        }
-        const uint32_t vc_off = w_row_codes + kb * 16u, vm_off = w_row_meta + kb * 4u;
-        const uint32_t dc = st + m0w_off, dm = st + m0m_off;
-        DFP4_LDS_DMA("global_load_lds_dwordx4", dc, vc_off, wcodes);
-        DFP4_LDS_DMA("global_load_lds_dword", dm, vm_off, wmeta);
-    };
-#undef DFP4_LDS_DMA
-
-    // stage rotation (LDS byte addresses): cur holds pair vc, nxt pair vc+1, nx2 pair vc+2
-    // (landing), ld receives pair vc+3
-    uint32_t st_cur = lds0, st_nxt = lds0 + kStageBytes, st_nx2 = lds0 + 2 * kStageBytes,
-             st_ld = lds0 + 3 * kStageBytes;
-    v4i bA0, bA1, bB0, bB1;            // int8 W operands, two sets used alternately (fixed registers)
-    issue_loads(0, st_cur);
-    issue_loads(1, st_nxt);
-    issue_loads(2, st_nx2);
-    asm volatile("s_waitcnt vmcnt(20)" ::: "memory");
-    {
-        const uint8_t* sn = &s_stage[0][0];
-        const uint4 c = *reinterpret_cast<const uint4*>(sn + kStageA + wave * 1024 + lane * 16);
-        const uint32_t meta = *reinterpret_cast<const uint32_t*>(sn + kStageA + kStageW + wave * 256 + lane * 4);
+    for (int s = 0; s < 2; ++s) {
+        const uint32_t kb = min((uint32_t)s_vl[2 * s + h] & 1023u, (uint32_t)KB - 1u);
+        const uint4 c = *reinterpret_cast<const uint4*>(wcodes + w_row_codes + kb * 16u);
+        const uint32_t meta = *reinterpret_cast<const uint32_t*>(wmeta + w_row_meta + kb * 4u);
         const uint4 tab = *reinterpret_cast<const uint4*>(reinterpret_cast<const uint8_t*>(s_tab) + meta);
-        bA0 = unpack16(c.x, c.y, tab);
-        bA1 = unpack16(c.z, c.w, tab);
+        *reinterpret_cast<v4i*>(&s_b[s][(wave * 2 + 0) * 1024 + lane * 16]) = unpack16(c.x, c.y, tab);
+        *reinterpret_cast<v4i*>(&s_b[s][(wave * 2 + 1) * 1024 + lane * 16]) = unpack16(c.z, c.w, tab);
     }
-    asm volatile("s_waitcnt vmcnt(10)" ::: "memory");
     __syncthreads();
 
-    // One step (see gen_gemm_step.py): MFMAs of pair vc from stage cur with the current W
-    // operands; expansion of pair vc+1's W codes (stage nxt) into the other operand set;
-    // loads of pair vc+3 into stage ld; barrier.
-#define DFP4_STEP(ASM, IN0, IN1, OUT0, OUT1, RIN0, RIN1, ROUT0, ROUT1)                               \
-    do {                                                                                             \
-        const uint32_t voff = s_va[2 * (vc + 3) + h] + a_lane;                                       \
-        const uint32_t kb = s_vl[2 * (vc + 3) + h];                                                  \
-        const uint32_t vcoff = w_row_codes + kb * 16u, vmoff = w_row_meta + kb * 4u;                 \
-        const uint32_t sa = st_cur + sa_lane, swc = st_nxt + swc_lane, swm = st_nxt + swm_lane;      \
-        const uint32_t m0a = st_ld + m0a_off, m0w = st_ld + m0w_off, m0m = st_ld + m0m_off;          \
-        asm volatile(ASM                                                                             \
-                     : "=&{" ROUT0 "}"(OUT0), "=&{" ROUT1 "}"(OUT1)                                  \
-                     : "{" RIN0 "}"(IN0), "{" RIN1 "}"(IN1), [sa] "v"(sa), [swc] "v"(swc),           \
-                       [swm] "v"(swm), [voff] "v"(voff), [vcoff] "v"(vcoff), [vmoff] "v"(vmoff),     \
-                       [tabb] "s"(lds_tab), [sel] "s"(sign_sel), [m0a] "s"(m0a), [m0w] "s"(m0w),     \
-                       [m0m] "s"(m0m), [a0] "s"(a_base[0]), [a1] "s"(a_base[1]), [a2] "s"(a_base[2]), \
-                       [a3] "s"(a_base[3]), [a4] "s"(a_base[4]), [a5] "s"(a_base[5]),                \
-                       [a6] "s"(a_base[6]), [a7] "s"(a_base[7]), [wc] "s"(wcodes), [wm] "s"(wmeta)   \
-                     : DFP4_STEP_VGPR_CLOBBERS, DFP4_ACC_CLOBBERS, "m0", "scc", "memory");           \
-        const uint32_t tmp = st_cur;                                                                 \
-        st_cur = st_nxt; st_nxt = st_nx2; st_nx2 = st_ld; st_ld = tmp;                               \
-        ++vc;                                                                                        \
-    } while (0)
-
-    int vc = 0;
-#pragma unroll 1
-    for (int seg = 0; seg < 3; ++seg) {
-        const int seg_end = seg == 0 ? end2 : (seg == 1 ? end1 : total);
-#pragma unroll 1
-        while (vc < seg_end) {                         // every class holds an even number of pairs
-            DFP4_STEP(DFP4_STEP_ASM_X, bA0, bA1, bB0, bB1, "v[128:131]", "v[132:135]", "v[136:139]", "v[140:143]");
-            DFP4_STEP(DFP4_STEP_ASM_Y, bB0, bB1, bA0, bA1, "v[136:139]", "v[140:143]", "v[128:131]", "v[132:135]");
-        }
-        // Horner step: everything summed so far belongs to classes above the next segment's
-        if (seg < 2 && vc > 0)
-            asm volatile(DFP4_ACC_SHIFT4_ASM ::: DFP4_SHIFT_VGPR_CLOBBERS, DFP4_ACC_CLOBBERS);
+    // ---- main loop (gemm_step_asm.inc): accumulators in a[0:255]
+    {
+        const uint64_t a8u = reinterpret_cast<uint64_t>(a8w), wcu = reinterpret_cast<uint64_t>(wcodes),
+                       wmu = reinterpret_cast<uint64_t>(wmeta);
+        const uint32_t a_lane = (uint32_t)r * 16u, l16 = (uint32_t)lane * 16u, h2 = (uint32_t)h * 2u;
+        const uint32_t sign_sel = 0x090b080au, kbm = (uint32_t)KB - 1u;
+        asm volatile(DFP4_MAINLOOP_ASM
+                     :
+                     : [a8lo] "s"((uint32_t)a8u), [a8hi] "s"((uint32_t)(a8u >> 32)), [gstr] "s"(grp_stride),
+                       [wclo] "s"((uint32_t)wcu), [wchi] "s"((uint32_t)(wcu >> 32)),
+                       [wmlo] "s"((uint32_t)wmu), [wmhi] "s"((uint32_t)(wmu >> 32)),
+                       [cstr] "s"(cls_stride), [toff] "s"(tile_off), [kbm] "s"(kbm), [tabb] "s"(lds_tab),
+                       [vlb] "s"(lds_vl), [bb] "s"(lds_b), [sel] "s"(sign_sel),
+                       [e2] "s"((uint32_t)end2), [e1] "s"((uint32_t)end1), [e0] "s"((uint32_t)total),
+                       [wv] "s"(wave_u), [alane] "v"(a_lane), [l16] "v"(l16), [wrc] "v"(w_row_codes),
+                       [wrm] "v"(w_row_meta), [h2] "v"(h2)
+                     : DFP4_LOOP_VGPR_CLOBBERS, DFP4_ACC_CLOBBERS, DFP4_LOOP_SGPR_CLOBBERS, "scc", "memory");
     }
-#undef DFP4_STEP
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the padding pairs' loads
-    asm volatile(DFP4_ACC_DRAIN_ASM);
 
     // ---- epilogue
-#define DFP4_READ_GROUP(G, V)                                                                       \
+#define DFP4_READ_TILE(G, V)                                                                        \
     asm volatile(DFP4_ACC_READ_ASM_##G                                                              \
                  : "=v"(V[0]), "=v"(V[1]), "=v"(V[2]), "=v"(V[3]), "=v"(V[4]), "=v"(V[5]),          \
                    "=v"(V[6]), "=v"(V[7]), "=v"(V[8]), "=v"(V[9]), "=v"(V[10]), "=v"(V[11]),        \
                    "=v"(V[12]), "=v"(V[13]), "=v"(V[14]), "=v"(V[15]))
-#define DFP4_FOR_GROUPS(F)                                                                          \
+#define DFP4_FOR_TILES(F)                                                                           \
     F(0) F(1) F(2) F(3) F(4) F(5) F(6) F(7) F(8) F(9) F(10) F(11) F(12) F(13) F(14) F(15)
-    int* part = reinterpret_cast<int*>(ws + p.off_part) + (int64_t)tile_id * S * (kTileM * kTileN);
     if (S > 1) {
         // K is shared with other workgroups: publish this one's exact int32 sums (the sum of
-        // all ranges is exact and does not depend on their order)
-        int* mine = part + (int64_t)sidx * (kTileM * kTileN);
+        // all ranges is exact and does not depend on their order); gemm_block_kernel adds the
+        // ranges up and stores the tile
+        int* mine = reinterpret_cast<int*>(ws + p.off_part) +
+                    ((int64_t)tile_id * S + sidx) * (kTileM * kTileN);
 #define DFP4_PUBLISH(G)                                                                             \
         {                                                                                           \
             int v[16];                                                                              \
-            DFP4_READ_GROUP(G, v);                                                                  \
+            DFP4_READ_TILE(G, v);                                                                   \
             _Pragma("unroll") for (int x = 0; x < 16; ++x) mine[(G * 16 + x) * 256 + tid] = v[x];   \
         }
-        DFP4_FOR_GROUPS(DFP4_PUBLISH)
+        DFP4_FOR_TILES(DFP4_PUBLISH)
 #undef DFP4_PUBLISH
-        return;                                        // gemm_block_kernel adds the ranges up and stores the tile
+        return;
     }
     {
         // The one rounding of the whole product: int32 -> fp32, scaled by 2^(refA + refW - 2).
-        // Accumulator x of lane (h, r) of group g is output row g*32 + 8*(x>>2) + 4*h + (x&3),
-        // column wave*32 + r.  Row addresses are wave-uniform (scalar registers); the lane adds a
-        // constant byte offset, so a store costs a handful of instructions.
+        // Accumulator x of lane (h, r) of tile (gi, n) is output row 128*wave + 32*gi +
+        // 8*(x>>2) + 4*h + (x&3), column 32*n + r.  Row addresses are wave-uniform (scalar
+        // registers); the lane adds a constant byte offset, so a store costs a handful of
+        // instructions.
         constexpr int kEsz = BF16 ? 2 : 4;
-        const int ew = (int)s_refw[wave * 32 + r] - 256;
-        const int col0 = n0 + (int)wave_u * 32;
-        uint8_t* tile_out = static_cast<uint8_t*>(p.out) +
-                            (bz * p.strideC + (int64_t)m0 * p.ldc + col0) * kEsz;          // uniform
+        const int row0 = m0 + (int)wave_u * 128;
+        uint8_t* wave_out = static_cast<uint8_t*>(p.out) +
+                            (bz * p.strideC + (int64_t)row0 * p.ldc + n0) * kEsz;            // uniform
         const int64_t row_bytes = p.ldc * kEsz;                                              // uniform
-        const bool full = m0 + kTileM <= p.M && col0 + 32 <= p.N;                            // uniform
+        const bool full = row0 + 128 <= p.M && n0 + kTileN <= p.N;                           // uniform
         // bf16: lanes exchange values in pairs so that every lane stores two adjacent columns of
         // one row (even lanes the even row of a row pair, odd lanes the odd row)
         const bool pairs = BF16 && full && (p.ldc & 1) == 0 && ((p.strideC * kEsz) & 3) == 0 &&
                            (reinterpret_cast<uintptr_t>(p.out) & 3) == 0;                    // uniform
         const uint32_t lane_off = pairs ? (uint32_t)((4 * h + (r & 1)) * row_bytes + (r & ~1) * kEsz)
                                         : (uint32_t)(4 * h * row_bytes + r * kEsz);
-        auto store_group = [&](auto full_c, auto pairs_c, int g, int (&v)[16]) {
+        int ew[4];
+#pragma unroll
+        for (int n = 0; n < 4; ++n) ew[n] = (int)s_refw[n * 32 + r] - 256;
+        auto store_tile = [&](auto full_c, auto pairs_c, int i, int (&v)[16]) {
             constexpr bool kFull = decltype(full_c)::value, kPairs = decltype(pairs_c)::value;
-            uint8_t* grp_out = tile_out + (int64_t)g * 32 * row_bytes;
+            const int gi = i >> 2, n = i & 3;
+            uint8_t* tile_out = wave_out + (int64_t)gi * 32 * row_bytes + n * 32 * kEsz;
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                const uint32_t e4 = *reinterpret_cast<const uint32_t*>(&s_refa[g * 32 + 8 * q + 4 * h]);
+                const uint32_t e4 = *reinterpret_cast<const uint32_t*>(&s_refa[wave * 128 + gi * 32 + 8 * q + 4 * h]);
                 float f[4];
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
-                    f[j] = ldexpf((float)v[4 * q + j], (int)((e4 >> (8 * j)) & 0xffu) + ew);
-                uint8_t* rowp = grp_out + (int64_t)(8 * q) * row_bytes;                     // uniform
+                    f[j] = ldexpf((float)v[4 * q + j], (int)((e4 >> (8 * j)) & 0xffu) + ew[n]);
+                uint8_t* rowp = tile_out + (int64_t)(8 * q) * row_bytes;                    // uniform
                 if constexpr (BF16 && kPairs) {
-                    {
 #pragma unroll
-                        for (int j = 0; j < 4; j += 2) {
-                            const uint32_t b0 = f32_to_bf16_rne(f[j]), b1 = f32_to_bf16_rne(f[j + 1]);
-                            const uint32_t send = (r & 1) ? b0 : b1;
-                            const uint32_t recv = (uint32_t)__builtin_amdgcn_mov_dpp((int)send, 0xB1, 0xf, 0xf, true);
-                            const uint32_t word = (r & 1) ? (recv | (b1 << 16)) : (b0 | (recv << 16));
-                            *reinterpret_cast<uint32_t*>(rowp + (int64_t)j * row_bytes + lane_off) = word;
-                        }
-                        continue;
+                    for (int j = 0; j < 4; j += 2) {
+                        const uint32_t b0 = f32_to_bf16_rne(f[j]), b1 = f32_to_bf16_rne(f[j + 1]);
+                        const uint32_t send = (r & 1) ? b0 : b1;
+                        const uint32_t recv = (uint32_t)__builtin_amdgcn_mov_dpp((int)send, 0xB1, 0xf, 0xf, true);
+                        const uint32_t word = (r & 1) ? (recv | (b1 << 16)) : (b0 | (recv << 16));
+                        *reinterpret_cast<uint32_t*>(rowp + (int64_t)j * row_bytes + lane_off) = word;
                     }
-                }
+                } else {
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    if (kFull || (m0 + g * 32 + 8 * q + 4 * h + j < p.M && col0 + r < p.N)) {
-                        uint8_t* dst = rowp + (int64_t)j * row_bytes + lane_off;
-                        if constexpr (BF16)
-                            *reinterpret_cast<uint16_t*>(dst) = f32_to_bf16_rne(f[j]);
-                        else
-                            *reinterpret_cast<float*>(dst) = f[j];
+                    for (int j = 0; j < 4; ++j) {
+                        if (kFull || (row0 + gi * 32 + 8 * q + 4 * h + j < p.M && n0 + n * 32 + r < p.N)) {
+                            uint8_t* dst = rowp + (int64_t)j * row_bytes + lane_off;
+                            if constexpr (BF16)
+                                *reinterpret_cast<uint16_t*>(dst) = f32_to_bf16_rne(f[j]);
+                            else
+                                *reinterpret_cast<float*>(dst) = f[j];
+                        }
                     }
                 }
             }
@@ -640,61 +563,61 @@ __global__ __launch_bounds__(256, 1) void gemm_fast_kernel(GemmParams p) {
 #define DFP4_FINISH(G)                                                                              \
         {                                                                                           \
             int v[16];                                                                              \
-            DFP4_READ_GROUP(G, v);                                                                  \
-            store_group(kFullC, kPairsC, G, v);                                                     \
+            DFP4_READ_TILE(G, v);                                                                   \
+            store_tile(kFullC, kPairsC, G, v);                                                      \
         }
         if (pairs) {
             constexpr std::true_type kFullC{}, kPairsC{};
-            DFP4_FOR_GROUPS(DFP4_FINISH)
+            DFP4_FOR_TILES(DFP4_FINISH)
         } else if (full) {
             constexpr std::true_type kFullC{};
             constexpr std::false_type kPairsC{};
-            DFP4_FOR_GROUPS(DFP4_FINISH)
+            DFP4_FOR_TILES(DFP4_FINISH)
         } else {
             constexpr std::false_type kFullC{}, kPairsC{};
-            DFP4_FOR_GROUPS(DFP4_FINISH)
+            DFP4_FOR_TILES(DFP4_FINISH)
         }
 #undef DFP4_FINISH
     }
-#undef DFP4_FOR_GROUPS
-#undef DFP4_READ_GROUP
+#undef DFP4_FOR_TILES
+#undef DFP4_READ_TILE
 }
 
 // ---------------------------------------------------------------------------
 // Sum of the K ranges of one 128 x 128 piece of a fast-kernel tile (split K):
 // the exact int32 partial sums the ranges published are added, converted once
-// and stored.  Thread t of the fast kernel holds column (t / 64) * 32 + (t % 32);
-// its accumulator x of group g is row g*32 + 8*(x/4) + 4*((t % 64) / 32) + x % 4.
+// and stored.  Wave w of the fast kernel holds rows 128w .. 128w+127 of the tile:
+// accumulator x of its lane (h, r) in tile i = 4*gi + n is row 128w + 32gi +
+// 8*(x/4) + 4h + x%4, column 32n + r, published at [(16i + x) * 256 + 64w + lane].
 // ---------------------------------------------------------------------------
 template <bool BF16>
 __device__ __forceinline__ void reduce_ranges(const GemmParams& p) {
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, n = tid >> 6;
     const int h = lane >> 5, r = lane & 31;
     const int64_t bz = blockIdx.z;
     const uint8_t* ws = p.ws + bz * p.ws_stride;
-    const int tile_m = blockIdx.y >> 2, gq = blockIdx.y & 3, S = p.ksplit;
+    const int tile_m = blockIdx.y >> 2, w = blockIdx.y & 3, S = p.ksplit;
     const int tile_id = tile_m * p.tiles_n + blockIdx.x;
     const int* part = reinterpret_cast<const int*>(ws + p.off_part) + (int64_t)tile_id * S * (kTileM * kTileN);
-    const int n = blockIdx.x * kTileN + wave * 32 + r;
-    const int ew = n < p.N ? (int)ws[p.off_refw + n] - 256 : 0;
+    const int col = blockIdx.x * kTileN + n * 32 + r;
+    const int ew = col < p.N ? (int)ws[p.off_refw + col] - 256 : 0;
 #pragma unroll
     for (int gi = 0; gi < 4; ++gi) {
-        const int g = gq * 4 + gi;
+        const int i = gi * 4 + n;
         int v[16];
 #pragma unroll
-        for (int x = 0; x < 16; ++x) v[x] = part[(g * 16 + x) * 256 + tid];
+        for (int x = 0; x < 16; ++x) v[x] = part[(i * 16 + x) * 256 + w * 64 + lane];
         for (int s = 1; s < S; ++s) {
             const int* other = part + (int64_t)s * (kTileM * kTileN);
 #pragma unroll
-            for (int x = 0; x < 16; ++x) v[x] += other[(g * 16 + x) * 256 + tid];
+            for (int x = 0; x < 16; ++x) v[x] += other[(i * 16 + x) * 256 + w * 64 + lane];
         }
 #pragma unroll
         for (int x = 0; x < 16; ++x) {
-            const int ml = g * 32 + 8 * (x >> 2) + 4 * h + (x & 3);
-            const int m = tile_m * kTileM + ml;
-            if (m < p.M && n < p.N) {
+            const int m = tile_m * kTileM + w * 128 + gi * 32 + 8 * (x >> 2) + 4 * h + (x & 3);
+            if (m < p.M && col < p.N) {
                 const float f = ldexpf((float)v[x], (int)ws[p.off_refa + m] + ew);
-                const int64_t o = bz * p.strideC + (int64_t)m * p.ldc + n;
+                const int64_t o = bz * p.strideC + (int64_t)m * p.ldc + col;
                 if constexpr (BF16)
                     static_cast<uint16_t*>(p.out)[o] = f32_to_bf16_rne(f);
                 else

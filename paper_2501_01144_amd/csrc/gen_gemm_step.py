@@ -1,60 +1,81 @@
 #!/usr/bin/env python3
-"""Generator of gemm_step_asm.inc: the hand-scheduled inner step of gemm_fast_kernel.
+"""Generator of gemm_step_asm.inc: the hand-scheduled main loop of gemm_fast_kernel.
 
-Why assembly.  The fast GEMM kernel runs ONE wavefront per SIMD (its 512 x 32
+Why assembly.  The fast GEMM kernel runs ONE wavefront per SIMD (its 128 x 128
 int32 accumulators fill the 256 accumulation registers), and a lone wavefront
-issues one instruction every 4 cycles.  A v_mfma_i32_32x32x32_i8 occupies the
-matrix core for 8 such slots, so about 5 other instructions fit in the shadow
-of each MFMA -- but only if they are placed between the MFMAs, in program
-order.  The compiler's scheduler does not keep such an order, so the step is
-emitted here, slot by slot:
+issues one instruction every 4 cycles or so.  A v_mfma_i32_32x32x32_i8 occupies
+the matrix core for 8 such slots, so about 5 other instructions fit in the shadow
+of each MFMA -- but only if they are placed between the MFMAs, in program order.
+The compiler's scheduler does not keep such an order, and operands prefetched for
+the next step must stay in fixed registers from one step to the next, so the
+whole loop (with its own loop control) is emitted here.
 
-  slot k (k = 0..31):   s_waitcnt lgkmcnt(n)          A fragment k has arrived from LDS
-                        v_mfma acc[k % 16] += A_frag[k] * B[k / 16]
-                        ds_read_b128  A fragment k + 8 (prefetch distance 8)
-                        one piece (two instructions) of the expansion of the next
-                        pair's W codes to int8          (28 of the 32 slots)
-                        one direct global->LDS load of the pair three steps ahead
-                        (10 of the 32 slots)
+One step = one pair of (block, class) visits = 32 MFMAs per wave:
+  wave w owns rows 128w .. 128w+127 of the 512 x 128 tile (groups gi = 0..3 of 32
+  rows) and all four 32-column tiles n = 0..3; accumulator tile (gi, n) is
+  a[16*(4*gi+n) : +15].  MFMA slot k: t = k / 16 (which half of the pair's
+  operands), gi = (k % 16) / 4, n = k % 4:  acc[gi][n] += A[gi][t] * B[n][t].
 
-Registers are fixed (physical) so that values written asynchronously by LDS
-reads never pass through compiler-chosen copies:
-  a[0:255]      accumulators, group g in a[16g : 16g+15]
-  v[128:135]    B operands (int8) set A: t = 0 in v[128:131], t = 1 in v[132:135]
-  v[136:143]    B operands set B
-  v[144:147]    W codes of the next pair, v[148:151] its table, v152 table offset, v153 table address
-  v[156:191]    9 A-fragment buffers
-  v[192:223]    temporaries of the W expansion (8 per code dword)
-Variant X of the step multiplies by set A and writes set B, variant Y the reverse.
+  A operands (pre-expanded int8 fragments in global memory) are private to the
+  wave: 8 global loads per step straight into registers, two steps ahead, three
+  register sets used in rotation (step s uses set s % 3).
+  B operands: every wave expands the 4-bit codes of ITS 32 rows of W (two steps
+  ahead, v_perm_b32 lookups, 28 two-instruction pieces spread over the slots),
+  writes the int8 result to LDS, and all four waves read the 8 fragments of a
+  step from there (three LDS buffers in rotation, one barrier per step).
+  The codes and table offsets come by global loads four steps ahead (three
+  register sets in rotation).
+  The list of visits sits in LDS (uint16: class << 10 | block); the load offsets
+  of the next step are computed at the end of each step.
+
+The loop is unrolled three times (register sets); after every step the step
+counter is compared with the end of the current class segment and a small
+subroutine (s_call_b64) shifts the accumulators left by 4 between classes
+(Horner's scheme) or leaves the loop after the last one.
+
+Registers (all fixed):
+  a[0:255]                accumulators
+  v[40:135]               A sets 0..2: fragment f = 4*t + gi at set + 4*f
+  v[136:151], v[152:167]  B fragments of phase t = 0 / 1: n at + 4*n
+  v[168:179], v[180:182]  W codes sets 0..2 (4 registers each), table offsets 0..2
+  v[184:187], v188        dialect table of the current expansion, its LDS address
+  v[192:223]              temporaries of the W expansion (8 per code dword)
+  v[224:231]              expanded int8 operands (t = 0: 224..227, t = 1: 228..231)
+  v232 .. v243            visit entries, load offsets, LDS addresses
+  s[60:75]                global base of the wave's A fragments f = 0..7
+  s76 step counter, s77 end of segment, s78 segment, s[80:81] return address,
+  s82..s84 LDS buffers of B (current, next, being written), s85..s87 scratch,
+  s[88:91] W codes / table-offset bases
 
 Run `python gen_gemm_step.py` in this directory to rewrite gemm_step_asm.inc
 (the build does it, and the file is committed).
 """
 import os
 
-B_SETS = {"A": 128, "B": 136}
-C0, TAB0, META, TABADDR = 144, 148, 152, 153
-AF0, NBUF, DEPTH = 156, 9, 8
-TMP0 = 192
-NSLOT, NGROUP = 32, 16
-A_STAGE_FRAG = 1024          # bytes per (group, t) fragment in an LDS stage
+ASET = [40, 72, 104]
+BBUF = [136, 152]
+CODES = [168, 172, 176]
+META = [180, 181, 182]
+TAB0, TABADDR = 184, 188
+TMP0, OUT0 = 192, 224
+EA, EW, VOFF, VCOFF, VMOFF, VLADDR, SB, SBN, SBW, L16W, T0, T1 = range(232, 244)
+S_ABASE, S_VC, S_SEGEND, S_SEG, S_RET, S_BCUR, S_BNXT, S_BW, S_T0, S_T1 = 60, 76, 77, 78, 80, 82, 83, 84, 85, 86
+S_WC, S_WM = 88, 90
+NSLOT = 32
+FRAG = 1024                    # bytes per operand fragment
+B_BUF_BYTES = 8 * FRAG
 
 
 def vr(n, cnt=1):
     return f"v{n}" if cnt == 1 else f"v[{n}:{n + cnt - 1}]"
 
 
-def af(i):
-    return vr(AF0 + 4 * (i % NBUF), 4)
-
-
-def frag_offset(k):
-    g, t = k % NGROUP, k // NGROUP
-    return (g * 2 + t) * A_STAGE_FRAG
+def sr(n, cnt=1):
+    return f"s{n}" if cnt == 1 else f"s[{n}:{n + cnt - 1}]"
 
 
 class Lgkm:
-    """In-order queue of outstanding LDS reads, to compute s_waitcnt lgkmcnt(n)."""
+    """In-order queue of outstanding LDS operations, to compute s_waitcnt lgkmcnt(n)."""
 
     def __init__(self):
         self.q = []
@@ -71,12 +92,13 @@ class Lgkm:
         return f"s_waitcnt lgkmcnt({n})"
 
 
-def expansion_pieces(bn):
-    """The 28 two-instruction pieces that expand the four code dwords (see unpack8 in
-    gemm.hip): 16 that need only the codes, then 12 that need the dialect table."""
+def expansion_pieces(cset):
+    """The 28 two-instruction pieces that expand the four code dwords of code set
+    `cset` (see unpack8 in gemm.hip): 16 that need only the codes, then 12 that
+    need the dialect table."""
     first, second = [], []
     for d in range(4):
-        c = vr(C0 + d)
+        c = vr(CODES[cset] + d)
         t = [vr(TMP0 + 8 * d + i) for i in range(8)]
         ie, io, c4, c8, c12, mo, me, pe = t
         ne, po, no = c4, c8, c12                  # reuse once the masks are built
@@ -90,101 +112,193 @@ def expansion_pieces(bn):
         second += [
             [f"v_perm_b32 {pe}, {phi}, {plo}, {ie}", f"v_perm_b32 {ne}, {nhi}, {nlo}, {ie}"],
             [f"v_perm_b32 {po}, {phi}, {plo}, {io}", f"v_perm_b32 {no}, {nhi}, {nlo}, {io}"],
-            [f"v_bfi_b32 {vr(bn + 2 * d)}, {me}, {ne}, {pe}", f"v_bfi_b32 {vr(bn + 2 * d + 1)}, {mo}, {no}, {po}"],
+            [f"v_bfi_b32 {vr(OUT0 + 2 * d)}, {me}, {ne}, {pe}", f"v_bfi_b32 {vr(OUT0 + 2 * d + 1)}, {mo}, {no}, {po}"],
         ]
     return first, second
 
 
-def dma_ops():
-    """(m0 setup, load) of the 10 direct global->LDS loads of one step."""
-    ops = []
-    for j in range(8):                            # A: fragments (g, t) of this wave's 4 groups
-        ops.append((f"s_add_u32 m0, %[m0a], {j * A_STAGE_FRAG}", f"global_load_lds_dwordx4 %[voff], %[a{j}]"))
-    ops.append(("s_mov_b32 m0, %[m0w]", "global_load_lds_dwordx4 %[vcoff], %[wc]"))
-    ops.append(("s_mov_b32 m0, %[m0m]", "global_load_lds_dword %[vmoff], %[wm]"))
-    return ops
+def a_offset(entry, dst):
+    """byte offset of a visit's A fragments: class * class stride + block * 1 KiB + (tile, lane)"""
+    return [f"v_lshrrev_b32 {vr(T0)}, 10, {vr(entry)}",
+            f"v_mul_lo_u32 {vr(T0)}, {vr(T0)}, %[cstr]",
+            f"v_and_b32 {vr(T1)}, 0x3ff, {vr(entry)}",
+            f"v_lshl_add_u32 {vr(T0)}, {vr(T1)}, 10, {vr(T0)}",
+            f"v_add3_u32 {vr(dst)}, {vr(T0)}, %[toff], %[alane]"]
 
 
-def step(cur, nxt):
-    bc, bn = B_SETS[cur], B_SETS[nxt]
-    out = []
+def w_offsets(entry, dst_codes, dst_meta):
+    """byte offsets of a visit's W codes and table offset (padding visits read the last block)"""
+    return [f"v_and_b32 {vr(T1)}, 0x3ff, {vr(entry)}",
+            f"v_min_u32 {vr(T1)}, %[kbm], {vr(T1)}",
+            f"v_lshl_add_u32 {vr(dst_codes)}, {vr(T1)}, 4, %[wrc]",
+            f"v_lshl_add_u32 {vr(dst_meta)}, {vr(T1)}, 2, %[wrm]"]
+
+
+def a_loads(aset, voff):
+    return [f"global_load_dwordx4 {vr(ASET[aset] + 4 * f, 4)}, {vr(voff)}, {sr(S_ABASE + 2 * f, 2)}" for f in range(8)]
+
+
+def entry_code():
+    o = []
+    # global bases of the wave's 8 A fragments: a8w + gi * group stride + t * 512
+    o.append(f"s_mov_b32 {sr(S_T0)}, 0")
+    for gi in range(4):
+        lo, hi = S_ABASE + 2 * gi, S_ABASE + 2 * gi + 1
+        o += [f"s_add_u32 {sr(lo)}, %[a8lo], {sr(S_T0)}", f"s_addc_u32 {sr(hi)}, %[a8hi], 0"]
+        lo1, hi1 = S_ABASE + 2 * (4 + gi), S_ABASE + 2 * (4 + gi) + 1
+        o += [f"s_add_u32 {sr(lo1)}, {sr(lo)}, 0x200", f"s_addc_u32 {sr(hi1)}, {sr(hi)}, 0"]
+        o.append(f"s_add_u32 {sr(S_T0)}, {sr(S_T0)}, %[gstr]")
+    o += [f"s_mov_b32 {sr(S_WC)}, %[wclo]", f"s_mov_b32 {sr(S_WC + 1)}, %[wchi]",
+          f"s_mov_b32 {sr(S_WM)}, %[wmlo]", f"s_mov_b32 {sr(S_WM + 1)}, %[wmhi]"]
+    o += [f"s_mov_b32 {sr(S_BCUR)}, %[bb]", f"s_add_u32 {sr(S_BNXT)}, %[bb], {B_BUF_BYTES}",
+          f"s_add_u32 {sr(S_BW)}, %[bb], {2 * B_BUF_BYTES}"]
+    o += [f"s_lshl_b32 {sr(S_T0)}, %[wv], 11", f"v_add_u32 {vr(L16W)}, {sr(S_T0)}, %[l16]",
+          f"v_add_u32 {vr(VLADDR)}, %[vlb], %[h2]"]
+    o += [f"s_mov_b32 {sr(S_VC)}, 0", f"s_mov_b32 {sr(S_SEG)}, 0", f"s_mov_b32 {sr(S_SEGEND)}, %[e2]"]
+    # pipeline fill: A of pairs 0, 1; W codes and table offsets of pairs 2, 3
+    for p in range(2):
+        o += [f"ds_read_u16 {vr(EA)}, {vr(VLADDR)} offset:{4 * p}",
+              f"ds_read_u16 {vr(EW)}, {vr(VLADDR)} offset:{4 * (p + 2)}",
+              "s_waitcnt lgkmcnt(0)"]
+        o += a_offset(EA, VOFF) + a_loads(p, VOFF)
+        o += w_offsets(EW, VCOFF, VMOFF)
+        o += [f"global_load_dwordx4 {vr(CODES[p], 4)}, {vr(VCOFF)}, {sr(S_WC, 2)}",
+              f"global_load_dword {vr(META[p])}, {vr(VMOFF)}, {sr(S_WM, 2)}"]
+    # offsets of the loads of step 0 (A of pair 2, W of pair 4)
+    o += [f"ds_read_u16 {vr(EA)}, {vr(VLADDR)} offset:8", f"ds_read_u16 {vr(EW)}, {vr(VLADDR)} offset:16",
+          "s_waitcnt lgkmcnt(0)"]
+    o += a_offset(EA, VOFF) + w_offsets(EW, VCOFF, VMOFF)
+    # B fragments of step 0, phase 0
+    o.append(f"v_add_u32 {vr(SB)}, {sr(S_BCUR)}, %[l16]")
+    for n in range(4):
+        o.append(f"ds_read_b128 {vr(BBUF[0] + 4 * n, 4)}, {vr(SB)} offset:{(2 * n) * FRAG}")
+    o.append("s_waitcnt lgkmcnt(0)")
+    return o
+
+
+def step(v):
+    """One step with A set v, code set v (both step % 3)."""
+    o = []
     lg = Lgkm()
-    # loads complete in order: all but the 10 issued during the previous step (pair vc+2)
-    # have landed, in particular pair vc+1 (fetched two steps ago)
-    out.append("s_waitcnt vmcnt(10)")
-    out.append(f"ds_read_b128 {vr(C0, 4)}, %[swc]")
-    lg.issue("c")
-    out.append(f"ds_read_b32 {vr(META)}, %[swm]")
-    lg.issue("meta")
-    for k in range(DEPTH):
-        out.append(f"ds_read_b128 {af(k)}, %[sa] offset:{frag_offset(k)}")
-        lg.issue(f"af{k}")
-    out.append(lg.need("meta"))
-    out.append(f"v_add_u32 {vr(TABADDR)}, %[tabb], {vr(META)}")
-    out.append(f"ds_read_b128 {vr(TAB0, 4)}, {vr(TABADDR)}")
+    ld = (v + 2) % 3
+    o.append(f"s_cmp_lt_u32 {sr(S_VC)}, {sr(S_SEGEND)}")
+    o.append(f"s_cbranch_scc1 1{v}f")
+    o.append(f"s_call_b64 {sr(S_RET, 2)}, 90f")
+    o.append(f"1{v}:")
+    # everything issued two steps ago has arrived: this step's A fragments and W codes
+    o.append("s_waitcnt vmcnt(10)")
+    o += [f"v_add_u32 {vr(SB)}, {sr(S_BCUR)}, %[l16]", f"v_add_u32 {vr(SBN)}, {sr(S_BNXT)}, %[l16]",
+          f"v_add_u32 {vr(SBW)}, {sr(S_BW)}, {vr(L16W)}"]
+    o += [f"ds_read_u16 {vr(EA)}, {vr(VLADDR)} offset:12", f"ds_read_u16 {vr(EW)}, {vr(VLADDR)} offset:20"]
+    lg.issue("ea"); lg.issue("ew")
+    o += [f"v_add_u32 {vr(TABADDR)}, %[tabb], {vr(META[v])}", f"ds_read_b128 {vr(TAB0, 4)}, {vr(TABADDR)}"]
     lg.issue("tab")
-    first, second = expansion_pieces(bn)
-    dmas = dma_ops()
+    first, second = expansion_pieces(v)
+    loads = a_loads(ld, VOFF)
+    b_reads = {2: (1, 0), 5: (1, 1), 8: (1, 2), 11: (1, 3), 17: (0, 0), 20: (0, 1), 23: (0, 2), 26: (0, 3)}
     for k in range(NSLOT):
-        w = lg.need(f"af{k}")
-        if w:
-            out.append(w)
-        g, t = k % NGROUP, k // NGROUP
-        acc = f"a[{16 * g}:{16 * g + 15}]"
-        out.append(f"v_mfma_i32_32x32x32_i8 {acc}, {af(k)}, {vr(bc + 4 * t, 4)}, {acc}")
-        dma = dmas[k // 2] if (k % 2 == 1 and k // 2 < len(dmas)) else None
-        if dma:
-            out.append(dma[0])
-        if k + DEPTH < NSLOT:
-            out.append(f"ds_read_b128 {af(k + DEPTH)}, %[sa] offset:{frag_offset(k + DEPTH)}")
-            lg.issue(f"af{k + DEPTH}")
+        t, gi, n = k // 16, (k % 16) // 4, k % 4
+        if k >= 16:
+            w = lg.need(f"b1{n}")
+            if w:
+                o.append(w)
+        acc = f"a[{16 * (4 * gi + n)}:{16 * (4 * gi + n) + 15}]"
+        o.append(f"v_mfma_i32_32x32x32_i8 {acc}, {vr(ASET[v] + 4 * (4 * t + gi), 4)}, {vr(BBUF[t] + 4 * n, 4)}, {acc}")
+        if k in b_reads:
+            bt, bn = b_reads[k]
+            src = SB if bt == 1 else SBN
+            o.append(f"ds_read_b128 {vr(BBUF[bt] + 4 * bn, 4)}, {vr(src)} offset:{(2 * bn + bt) * FRAG}")
+            lg.issue(f"b{bt}{bn}")
         piece = first[k] if k < 16 else (second[k - 16] if k - 16 < len(second) else None)
-        if piece and k == 16:
+        if k == 16:
             w = lg.need("tab")
             if w:
-                out.append(w)
+                o.append(w)
         if piece:
-            out.append(piece[0])
-        elif dma:
-            out.append("s_nop 0")
-        if dma:
-            out.append(dma[1])
+            o.append(piece[0])
+        if k % 2 == 1 and k < 16:
+            o.append(loads[k // 2])
+        if k == 17:
+            o.append(f"global_load_dwordx4 {vr(CODES[ld], 4)}, {vr(VCOFF)}, {sr(S_WC, 2)}")
+        if k == 19:
+            o.append(f"global_load_dword {vr(META[ld])}, {vr(VMOFF)}, {sr(S_WM, 2)}")
         if piece:
-            out.append(piece[1])
-    out.append("s_barrier")                      # the next pair's A fragments are visible to all waves
-    return [o for o in out if o]
+            o.append(piece[1])
+        if k == 22:
+            o.append(f"ds_write_b128 {vr(SBW)}, {vr(OUT0, 4)}")
+            lg.issue("w0")
+        if k == 28:
+            o.append(f"ds_write_b128 {vr(SBW)}, {vr(OUT0 + 4, 4)} offset:{FRAG}")
+            lg.issue("w1")
+            w = lg.need("ew")
+            if w:
+                o.append(w)
+            o += a_offset(EA, VOFF)
+        if k == 29:
+            o += w_offsets(EW, VCOFF, VMOFF)
+    # the expanded operands are in LDS and next step's first B fragments have arrived
+    o.append("s_waitcnt lgkmcnt(0)")
+    o.append("s_barrier")
+    o += [f"s_mov_b32 {sr(S_T0)}, {sr(S_BCUR)}", f"s_mov_b32 {sr(S_BCUR)}, {sr(S_BNXT)}",
+          f"s_mov_b32 {sr(S_BNXT)}, {sr(S_BW)}", f"s_mov_b32 {sr(S_BW)}, {sr(S_T0)}",
+          f"s_add_u32 {sr(S_VC)}, {sr(S_VC)}, 1", f"v_add_u32 {vr(VLADDR)}, 4, {vr(VLADDR)}"]
+    return o
+
+
+DRAIN = ["s_nop 15", "s_nop 15", "s_nop 15"]       # all MFMAs have retired before the vector ALU reads accumulators
+
+
+def shift4():
+    o = list(DRAIN)
+    for n0 in range(0, 256, 8):
+        o += [f"v_accvgpr_read_b32 {vr(TMP0 + i)}, a{n0 + i}" for i in range(8)]
+        o += [f"v_lshlrev_b32 {vr(TMP0 + i)}, 4, {vr(TMP0 + i)}" for i in range(8)]
+        o += [f"v_accvgpr_write_b32 a{n0 + i}, {vr(TMP0 + i)}" for i in range(8)]
+    o.append("s_nop 4")
+    return o
+
+
+def handler():
+    """Reached when the step counter equals the end of the segment: shift the accumulators
+    and move to the next class, or leave the loop after the last one."""
+    o = ["90:", f"s_cmp_eq_u32 {sr(S_SEG)}, 2", "s_cbranch_scc1 99f",
+         f"s_cmp_eq_u32 {sr(S_VC)}, 0", "s_cbranch_scc1 91f"]
+    o += shift4()
+    o += ["91:", f"s_add_u32 {sr(S_SEG)}, {sr(S_SEG)}, 1", f"s_cmp_eq_u32 {sr(S_SEG)}, 1",
+          f"s_cselect_b32 {sr(S_SEGEND)}, %[e1], %[e0]", f"s_cmp_lt_u32 {sr(S_VC)}, {sr(S_SEGEND)}",
+          "s_cbranch_scc0 90b", f"s_setpc_b64 {sr(S_RET, 2)}"]
+    return o
+
+
+def main_loop():
+    o = [f"v_accvgpr_write_b32 a{n}, 0" for n in range(256)]
+    o += entry_code()
+    o.append("80:")
+    for v in range(3):
+        o += step(v)
+    o.append("s_branch 80b")
+    o += handler()
+    o += ["99:", "s_waitcnt vmcnt(0) lgkmcnt(0)"] + DRAIN
+    return o
 
 
 def c_string(lines):
-    return "\n".join(f'    "{l}\\n\\t"' for l in lines)
+    return " \\\n".join(f'    "{l}\\n\\t"' for l in lines)
 
 
 def main():
     here = os.path.dirname(os.path.abspath(__file__))
     parts = ["// Generated by gen_gemm_step.py -- do not edit; see that file for the register map.\n"]
-    for name, (cur, nxt) in (("X", ("A", "B")), ("Y", ("B", "A"))):
-        parts.append(f"#define DFP4_STEP_ASM_{name} \\\n" + " \\\n".join(c_string(step(cur, nxt)).split("\n")) + "\n")
-    zero = [f"v_accvgpr_write_b32 a{n}, 0" for n in range(256)]
-    parts.append("#define DFP4_ACC_ZERO_ASM \\\n" + " \\\n".join(c_string(zero).split("\n")) + "\n")
-    # all MFMAs have retired before the accumulators are read by the vector ALU
-    drain = ["s_nop 15", "s_nop 15", "s_nop 15"]
-    parts.append("#define DFP4_ACC_DRAIN_ASM \\\n" + " \\\n".join(c_string(drain).split("\n")) + "\n")
-    shift = list(drain)
-    for n0 in range(0, 256, 8):
-        shift += [f"v_accvgpr_read_b32 {vr(TMP0 + i)}, a{n0 + i}" for i in range(8)]
-        shift += [f"v_lshlrev_b32 {vr(TMP0 + i)}, 4, {vr(TMP0 + i)}" for i in range(8)]
-        shift += [f"v_accvgpr_write_b32 a{n0 + i}, {vr(TMP0 + i)}" for i in range(8)]
-    shift += ["s_nop 4"]
-    parts.append("#define DFP4_ACC_SHIFT4_ASM \\\n" + " \\\n".join(c_string(shift).split("\n")) + "\n")
-    for g in range(NGROUP):
+    parts.append("#define DFP4_MAINLOOP_ASM \\\n" + c_string(main_loop()) + "\n")
+    for g in range(16):
         rd = [f"v_accvgpr_read_b32 %{i}, a{16 * g + i}" for i in range(16)]
-        parts.append(f"#define DFP4_ACC_READ_ASM_{g} \\\n" + " \\\n".join(c_string(rd).split("\n")) + "\n")
-    vclob = ", ".join(f'"v{n}"' for n in range(C0, TMP0 + 32))
+        parts.append(f"#define DFP4_ACC_READ_ASM_{g} \\\n" + c_string(rd) + "\n")
+    vclob = ", ".join(f'"v{n}"' for n in range(ASET[0], 256))
     aclob = ", ".join(f'"a{n}"' for n in range(256))
-    parts.append(f"#define DFP4_STEP_VGPR_CLOBBERS {vclob}\n")
+    sclob = ", ".join(f'"s{n}"' for n in range(S_ABASE, S_WM + 2))
+    parts.append(f"#define DFP4_LOOP_VGPR_CLOBBERS {vclob}\n")
     parts.append(f"#define DFP4_ACC_CLOBBERS {aclob}\n")
-    tclob = ", ".join(f'"v{n}"' for n in range(TMP0, TMP0 + 8))
-    parts.append(f"#define DFP4_SHIFT_VGPR_CLOBBERS {tclob}\n")
+    parts.append(f"#define DFP4_LOOP_SGPR_CLOBBERS {sclob}\n")
     path = os.path.join(here, "gemm_step_asm.inc")
     text = "\n".join(parts)
     if not os.path.exists(path) or open(path).read() != text:
