@@ -177,7 +177,9 @@ def entry_code():
 
 
 def step(v):
-    """One step with A set v, code set v (both step % 3)."""
+    """One step with A set v, code set v (both step % 3).  Everything that is not an MFMA is
+    spread over the MFMA slots, the barrier included, so that the matrix core never waits at
+    the step boundary."""
     o = []
     lg = Lgkm()
     ld = (v + 2) % 3
@@ -187,15 +189,22 @@ def step(v):
     o.append(f"1{v}:")
     # everything issued two steps ago has arrived: this step's A fragments and W codes
     o.append("s_waitcnt vmcnt(10)")
-    o += [f"v_add_u32 {vr(SB)}, {sr(S_BCUR)}, %[l16]", f"v_add_u32 {vr(SBN)}, {sr(S_BNXT)}, %[l16]",
-          f"v_add_u32 {vr(SBW)}, {sr(S_BW)}, {vr(L16W)}"]
-    o += [f"ds_read_u16 {vr(EA)}, {vr(VLADDR)} offset:12", f"ds_read_u16 {vr(EW)}, {vr(VLADDR)} offset:20"]
-    lg.issue("ea"); lg.issue("ew")
-    o += [f"v_add_u32 {vr(TABADDR)}, %[tabb], {vr(META[v])}", f"ds_read_b128 {vr(TAB0, 4)}, {vr(TABADDR)}"]
-    lg.issue("tab")
     first, second = expansion_pieces(v)
     loads = a_loads(ld, VOFF)
-    b_reads = {2: (1, 0), 5: (1, 1), 8: (1, 2), 11: (1, 3), 17: (0, 0), 20: (0, 1), 23: (0, 2), 26: (0, 3)}
+    a_load_slot = {1 + 4 * i: i for i in range(8)}                       # slots 1, 5, ..., 29
+    b_reads = {2: (1, 0), 6: (1, 1), 10: (1, 2), 14: (1, 3), 16: (0, 0), 20: (0, 1), 24: (0, 2), 27: (0, 3)}
+    extra = {
+        0: [f"v_add_u32 {vr(SB)}, {sr(S_BCUR)}, %[l16]", f"v_add_u32 {vr(SBN)}, {sr(S_BNXT)}, %[l16]"],
+        1: [f"v_add_u32 {vr(SBW)}, {sr(S_BW)}, {vr(L16W)}"],
+        3: [f"ds_read_u16 {vr(EA)}, {vr(VLADDR)} offset:12", f"ds_read_u16 {vr(EW)}, {vr(VLADDR)} offset:20",
+            f"v_add_u32 {vr(TABADDR)}, %[tabb], {vr(META[v])}", f"ds_read_b128 {vr(TAB0, 4)}, {vr(TABADDR)}"],
+        4: [f"s_mov_b32 {sr(S_T0)}, {sr(S_BCUR)}", f"s_mov_b32 {sr(S_BCUR)}, {sr(S_BNXT)}",
+            f"s_mov_b32 {sr(S_BNXT)}, {sr(S_BW)}", f"s_mov_b32 {sr(S_BW)}, {sr(S_T0)}"],
+        7: [f"s_add_u32 {sr(S_VC)}, {sr(S_VC)}, 1", f"v_add_u32 {vr(VLADDR)}, 4, {vr(VLADDR)}"],
+        # every wave has written its share of the W operands of the next step (previous step,
+        # waited for at its end) and has finished reading the buffer this step overwrites
+        12: ["s_barrier"],
+    }
     for k in range(NSLOT):
         t, gi, n = k // 16, (k % 16) // 4, k % 4
         if k >= 16:
@@ -216,32 +225,33 @@ def step(v):
                 o.append(w)
         if piece:
             o.append(piece[0])
-        if k % 2 == 1 and k < 16:
-            o.append(loads[k // 2])
-        if k == 17:
+        if k in a_load_slot:
+            o.append(loads[a_load_slot[k]])
+        if k == 11:
             o.append(f"global_load_dwordx4 {vr(CODES[ld], 4)}, {vr(VCOFF)}, {sr(S_WC, 2)}")
-        if k == 19:
+        if k == 15:
             o.append(f"global_load_dword {vr(META[ld])}, {vr(VMOFF)}, {sr(S_WM, 2)}")
         if piece:
             o.append(piece[1])
+        for ins in extra.get(k, []):
+            o.append(ins)
+            if ins.startswith("ds_read_u16") or ins.startswith("ds_read_b128"):
+                lg.issue({"ds_read_u16 " + vr(EA): "ea", "ds_read_u16 " + vr(EW): "ew"}.get(ins.split(",")[0], "tab"))
         if k == 22:
             o.append(f"ds_write_b128 {vr(SBW)}, {vr(OUT0, 4)}")
             lg.issue("w0")
         if k == 28:
             o.append(f"ds_write_b128 {vr(SBW)}, {vr(OUT0 + 4, 4)} offset:{FRAG}")
             lg.issue("w1")
+        if k == 30:                                   # after the last A load of this step
             w = lg.need("ew")
             if w:
                 o.append(w)
             o += a_offset(EA, VOFF)
-        if k == 29:
+        if k == 31:
             o += w_offsets(EW, VCOFF, VMOFF)
     # the expanded operands are in LDS and next step's first B fragments have arrived
     o.append("s_waitcnt lgkmcnt(0)")
-    o.append("s_barrier")
-    o += [f"s_mov_b32 {sr(S_T0)}, {sr(S_BCUR)}", f"s_mov_b32 {sr(S_BCUR)}, {sr(S_BNXT)}",
-          f"s_mov_b32 {sr(S_BNXT)}, {sr(S_BW)}", f"s_mov_b32 {sr(S_BW)}, {sr(S_T0)}",
-          f"s_add_u32 {sr(S_VC)}, {sr(S_VC)}, 1", f"v_add_u32 {vr(VLADDR)}, 4, {vr(VLADDR)}"]
     return o
 
 
