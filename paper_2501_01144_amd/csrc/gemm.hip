@@ -87,13 +87,13 @@ struct GemmParams {
     int64_t ldc, strideA_rows, strideW_rows, strideC;
     // workspace (per batch entry: ws + batch * ws_stride)
     uint8_t* ws;
-    int64_t ws_stride, off_refa, off_refw, off_spreadw, off_wmeta, off_mask, off_flag, off_part, off_a8;
+    int64_t ws_stride, off_refa, off_refw, off_spreadw, off_wmeta, off_mask, off_flag, off_list, off_part, off_a8;
     int tiles_m, tiles_n;             // 512 x 128 output tiles
     int ksplit;                       // workgroups sharing one output tile (each takes a range of K)
 };
 
 struct Layout {
-    int64_t off_refa, off_refw, off_spreadw, off_wmeta, off_mask, off_flag, off_part, off_a8, total;
+    int64_t off_refa, off_refw, off_spreadw, off_wmeta, off_mask, off_flag, off_list, off_part, off_a8, total;
     int ksplit;
 };
 __host__ __device__ inline int64_t align256(int64_t x) { return (x + 255) & ~(int64_t)255; }
@@ -115,7 +115,8 @@ inline Layout make_layout(int64_t M, int64_t N, int64_t KB) {
     l.off_wmeta = align256(l.off_spreadw + tn * kTileN);
     l.off_mask = align256(l.off_wmeta + N * KB * 4);          // one table offset (dword) per W block
     l.off_flag = align256(l.off_mask + tm * KB);
-    l.off_part = align256(l.off_flag + tm * tn);
+    l.off_list = align256(l.off_flag + tm * tn);               // count, then ids of declined tiles
+    l.off_part = align256(l.off_list + (tm * tn + 1) * 4);
     l.off_a8 = align256(l.off_part + (l.ksplit > 1 ? (int64_t)l.ksplit * tm * tn * kTileM * kTileN * 4 : 0));
     // A fragments: [class][tile][group][block 0..KB][1 KiB]; block KB of class 0 is all zeros
     l.total = align256(l.off_a8 + (kMaxClass + 1) * tm * kGroups * (KB + 1) * 1024);
@@ -271,6 +272,7 @@ __global__ __launch_bounds__(1024) void gemm_prep_kernel(GemmParams p, int n_a, 
         // per-tile "declined" flags of the fast kernel
         const int tiles = p.tiles_m * p.tiles_n;
         for (int i = tid; i < tiles; i += 1024) ws[p.off_flag + i] = 0;
+        if (tid == 0) *reinterpret_cast<uint32_t*>(ws + p.off_list) = 0;
     }
     __syncthreads();
 
@@ -426,7 +428,11 @@ __global__ __launch_bounds__(256, 1) void gemm_fast_kernel(GemmParams p) {
                         a8_bytes < ((int64_t)1 << 31) && (int64_t)p.N * KB * 16 < ((int64_t)1 << 31);
         if (!ok) {
             // decline the tile: the block-flush kernel computes it
-            if (tid == 0) *flag = 1;
+            if (tid == 0) {
+                *flag = 1;
+                uint32_t* list = reinterpret_cast<uint32_t*>(ws + p.off_list);
+                if (sidx == 0) list[1 + atomicAdd(list, 1u)] = (uint32_t)tile_id;
+            }
             return;
         }
     }
@@ -633,21 +639,12 @@ __device__ __forceinline__ void reduce_ranges(const GemmParams& p) {
 // When `flags` is set it only computes tiles the fast kernel declined.
 // ---------------------------------------------------------------------------
 template <bool MX, bool BF16>
-__global__ __launch_bounds__(256) void gemm_block_kernel(GemmParams p, int use_flags) {
-    __shared__ uint8_t s_exp[2][256];
+__device__ __forceinline__ void block_flush_tile(const GemmParams& p, int64_t bz, int by, int bx,
+                                                 uint8_t (&s_exp)[2][256]) {
     const int KB = p.KB;
-    const int64_t bz = blockIdx.z;
-    if (use_flags) {
-        const uint8_t* flag = p.ws + bz * p.ws_stride + p.off_flag + (int64_t)(blockIdx.y / 4) * p.tiles_n +
-                              blockIdx.x;
-        if (*flag == 0) {
-            if (p.ksplit > 1) reduce_ranges<BF16>(p);
-            return;
-        }
-    }
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = wave >> 1, wn = wave & 1;
-    const int m0 = blockIdx.y * 128, n0 = blockIdx.x * 128;
+    const int m0 = by * 128, n0 = bx * 128;
     const int64_t a_row0 = bz * p.strideA_rows, w_row0 = bz * p.strideW_rows;
     const int half = lane >> 5, l32 = lane & 31;
 
@@ -718,6 +715,32 @@ __global__ __launch_bounds__(256) void gemm_block_kernel(GemmParams p, int use_f
         }
 }
 
+// mode 0: every 128 x 128 tile of the grid (no fast kernel ran).
+// mode 1: the grid covers all tiles; tiles the fast kernel declined are computed, the others
+//         have their K ranges summed (split K).
+// mode 2: a small grid walks the list of declined tiles (usually empty).
+template <bool MX, bool BF16>
+__global__ __launch_bounds__(256) void gemm_block_kernel(GemmParams p, int mode) {
+    __shared__ uint8_t s_exp[2][256];
+    const int64_t bz = blockIdx.z;
+    const uint8_t* ws = p.ws + bz * p.ws_stride;
+    if (mode == 2) {
+        const uint32_t* list = reinterpret_cast<const uint32_t*>(ws + p.off_list);
+        const uint32_t n = list[0];
+        for (uint32_t i = blockIdx.x; i < n * 4u; i += gridDim.x) {
+            const int tile = (int)list[1 + (i >> 2)], by = (tile / p.tiles_n) * 4 + (int)(i & 3u);
+            if (by * 128 < p.M) block_flush_tile<MX, BF16>(p, bz, by, tile % p.tiles_n, s_exp);
+            __syncthreads();
+        }
+        return;
+    }
+    if (mode == 1 && ws[p.off_flag + (int64_t)(blockIdx.y / 4) * p.tiles_n + blockIdx.x] == 0) {
+        reduce_ranges<BF16>(p);
+        return;
+    }
+    block_flush_tile<MX, BF16>(p, bz, (int)blockIdx.y, (int)blockIdx.x, s_exp);
+}
+
 }  // namespace
 
 size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K) {
@@ -743,7 +766,7 @@ int launch_gemm(bool mx, dfp4_tensor A, dfp4_tensor W, void* out, int out_dtype,
     p.ws = static_cast<uint8_t*>(workspace); p.ws_stride = lay.total;
     p.off_refa = lay.off_refa; p.off_refw = lay.off_refw; p.off_spreadw = lay.off_spreadw;
     p.off_wmeta = lay.off_wmeta; p.off_mask = lay.off_mask; p.off_flag = lay.off_flag;
-    p.off_part = lay.off_part; p.off_a8 = lay.off_a8;
+    p.off_list = lay.off_list; p.off_part = lay.off_part; p.off_a8 = lay.off_a8;
     p.tiles_m = (int)((M + kTileM - 1) / kTileM); p.tiles_n = (int)((N + kTileN - 1) / kTileN);
     if (p.tiles_m > 16383 || p.tiles_n > (1 << 20)) return DFP4_ERR_SHAPE;
 
@@ -768,11 +791,15 @@ int launch_gemm(bool mx, dfp4_tensor A, dfp4_tensor W, void* out, int out_dtype,
     dim3 gf((unsigned)p.tiles_n, (unsigned)p.tiles_m, (unsigned)(batch * p.ksplit));
     dim3 gb((unsigned)((N + 127) / 128), (unsigned)((M + 127) / 128), (unsigned)batch);
     if (gb.y > 65535) return DFP4_ERR_SHAPE;
+    dim3 gl((unsigned)device_cu_count(), 1, (unsigned)batch);     // walks the list of declined tiles
 #define DFP4_LAUNCH(MXV, BV)                                                                     \
     do {                                                                                         \
         if (fast) {                                                                              \
             hipLaunchKernelGGL((gemm_fast_kernel<MXV, BV>), gf, dim3(256), 0, stream, p);        \
-            hipLaunchKernelGGL((gemm_block_kernel<MXV, BV>), gb, dim3(256), 0, stream, p, 1);    \
+            if (p.ksplit > 1)                                                                    \
+                hipLaunchKernelGGL((gemm_block_kernel<MXV, BV>), gb, dim3(256), 0, stream, p, 1); \
+            else                                                                                 \
+                hipLaunchKernelGGL((gemm_block_kernel<MXV, BV>), gl, dim3(256), 0, stream, p, 2); \
         } else {                                                                                 \
             hipLaunchKernelGGL((gemm_block_kernel<MXV, BV>), gb, dim3(256), 0, stream, p, 0);    \
         }                                                                                        \
