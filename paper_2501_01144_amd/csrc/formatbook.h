@@ -82,7 +82,7 @@ constexpr int e2m1_index(int key) {
 
 // Lookup tables over a PAIR of 5-bit magnitudes, key = t0 | t1 << 5.
 //   q[d][key]  = index(t0) | index(t1) << 4 under dialect d   (two code nibbles, no sign)
-//   s[p][key]  = votes for the even dialect of pair p in bits 3:0, for the odd one in 7:4
+//   s[p][key]  = (votes for the even dialect of pair p) - (votes for the odd one), int8 in -2..2
 //   mx[key64]  = E2M1 index for one element with key = 2 t + sticky
 struct QuantTables {
     uint8_t q[kDialects * 1024];
@@ -99,11 +99,12 @@ constexpr QuantTables make_quant_tables() {
             T.q[d * 1024 + k] = (uint8_t)(one[k & 31] | (one[k >> 5] << 4));
     }
     for (int p = 0; p < kPairs; ++p) {
-        uint8_t one[32] = {};
+        // votes of the two magnitudes of a key: +1 for the even dialect's range, -1 for the odd one's
+        int one[32] = {};
         for (int t = 0; t < 32; ++t)
-            one[t] = (uint8_t)((in_range(2 * p, t) ? 1 : 0) | (in_range(2 * p + 1, t) ? 16 : 0));
+            one[t] = (in_range(2 * p, t) ? 1 : 0) - (in_range(2 * p + 1, t) ? 1 : 0);
         for (int k = 0; k < 1024; ++k)
-            T.s[p * 1024 + k] = (uint8_t)(one[k & 31] + one[k >> 5]);
+            T.s[p * 1024 + k] = (uint8_t)(one[k & 31] + one[k >> 5]);      // int8, two's complement
     }
     for (int k = 0; k < 64; ++k) T.mx[k] = (uint8_t)e2m1_index(k);
     return T;

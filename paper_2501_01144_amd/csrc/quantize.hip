@@ -22,11 +22,12 @@ __device__ const QuantTables g_quant_tables = make_quant_tables();
 
 namespace {
 
-constexpr int kThreads = 1024;
+constexpr int kThreads = 512;
 constexpr int kWaves = kThreads / 64;
 constexpr int kPasses = 4;             // 16-byte loads per lane per iteration
 constexpr int kBlocksPerPass = 16;     // 64 lanes / 4 lanes per block
 
+typedef unsigned short us2 __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ float as_f(uint32_t u) { return __builtin_bit_cast(float, u); }
 __device__ __forceinline__ uint32_t as_u(float f) { return __builtin_bit_cast(uint32_t, f); }
 
@@ -37,12 +38,13 @@ __device__ __forceinline__ uint32_t quad(uint32_t v) {
 }
 
 __device__ __forceinline__ uint32_t sign_nibbles(const uint32_t (&w)[4]) {
-    // bf16 sign bits (bit 15 / bit 31 of dword j) -> bit 3 / bit 7 of code byte j
-    uint32_t s = 0;
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-        s |= (((w[j] >> 12) & 0x8u) | ((w[j] >> 24) & 0x80u)) << (8 * j);
-    return s;
+    // bf16 sign bits (bit 15 / bit 31 of dword j) -> bit 3 / bit 7 of code byte j.
+    // v_perm_b32 gathers the high byte of every bf16: p = {w_a.b3, w_b.b3, w_a.b1, w_b.b1}
+    const uint32_t p0 = __builtin_amdgcn_perm(w[1], w[0], 0x05010703u);
+    const uint32_t p1 = __builtin_amdgcn_perm(w[3], w[2], 0x05010703u);
+    const uint32_t hi = __builtin_amdgcn_perm(p1, p0, 0x05040100u);   // odd elements of dwords 0..3
+    const uint32_t lo = __builtin_amdgcn_perm(p1, p0, 0x07060302u);   // even elements of dwords 0..3
+    return (hi & 0x80808080u) | ((lo >> 4) & 0x08080808u);
 }
 
 // Block maximum over the quad's 32 elements, as bf16 bits (sign cleared).
@@ -53,9 +55,11 @@ __device__ __forceinline__ uint32_t block_amax_bits(const uint32_t (&w)[4]) {
         m = __builtin_fmaxf(m, __builtin_fabsf(as_f(w[j] << 16)));
         m = __builtin_fmaxf(m, __builtin_fabsf(as_f(w[j])));
     }
-    m = __builtin_fmaxf(m, as_f(quad<0xB1>(as_u(m))));
-    m = __builtin_fmaxf(m, as_f(quad<0x4E>(as_u(m))));
-    return as_u(m) >> 16;
+    // non-negative floats order like their bit patterns
+    uint32_t u = as_u(m);
+    u = max(u, quad<0xB1>(u));
+    u = max(u, quad<0x4E>(u));
+    return u >> 16;
 }
 
 // One lane's share (8 elements) of one DialectFP4 block.
@@ -78,16 +82,16 @@ __device__ __forceinline__ void dfp4_pass(const uint4& wv, const uint8_t* __rest
         const uint32_t t1 = (uint32_t)ldexpf(__builtin_fabsf(as_f(w[j])), n);
         key[j] = t0 | (t1 << 5);
     }
-    // stage 2: votes of this lane's 8 elements, then of the quad
-    const uint8_t* s = lut_s + pair * 1024u;
-    const uint32_t cnt = (uint32_t)s[key[0]] + s[key[1]] + s[key[2]] + s[key[3]];
-    uint32_t v = (cnt & 0xfu) | ((cnt & 0xf0u) << 12);
+    // stage 2: votes of this lane's 8 elements (even dialect +1, odd dialect -1), then of the
+    // quad; the odd dialect needs strictly more votes
+    const int8_t* s = reinterpret_cast<const int8_t*>(lut_s) + pair * 1024u;
+    uint32_t v = (uint32_t)((int)s[key[0]] + (int)s[key[1]] + (int)s[key[2]] + (int)s[key[3]]);
     v += quad<0xB1>(v);
     v += quad<0x4E>(v);
-    dial = 2u * pair + ((v >> 16) > (v & 0xffffu) ? 1u : 0u);
+    dial = 2u * pair + (v >> 31);
     const uint8_t* q = lut_q + dial * 1024u;
-    code = (uint32_t)q[key[0]] | ((uint32_t)q[key[1]] << 8) | ((uint32_t)q[key[2]] << 16) |
-           ((uint32_t)q[key[3]] << 24) | sign_nibbles(w);
+    const us2 qe = {q[key[0]], q[key[2]]}, qo = {q[key[1]], q[key[3]]};   // bytes 0, 2 and bytes 1, 3
+    code = (__builtin_bit_cast(uint32_t, qe) | (__builtin_bit_cast(uint32_t, qo) << 8)) | sign_nibbles(w);
     ebyte = (uint32_t)byte;
 }
 
@@ -112,46 +116,72 @@ __device__ __forceinline__ void mxfp4_pass(const uint4& wv, const uint8_t* __res
     ebyte = (uint32_t)byte;
 }
 
+// The 4 x 16 bytes of one lane for the 64 blocks of super-chunk `sc` (sc is wave-uniform).
+template <bool CONTIG>
+__device__ __forceinline__ void load_super(const uint16_t* __restrict__ x, int64_t ld, uint32_t blocks_per_row,
+                                           uint32_t nblocks, uint32_t sc, uint32_t lane, uint4 (&w)[kPasses]) {
+    if (CONTIG && sc * 64u + 64u <= nblocks) {
+        // 4 KiB contiguous: scalar base, lane offset, immediate pass offset
+        const uint4* base = reinterpret_cast<const uint4*>(x + (size_t)sc * (64u * kBlock));
+#pragma unroll
+        for (int p = 0; p < kPasses; ++p) w[p] = base[p * 64 + lane];
+        return;
+    }
+    const uint32_t quad_id = lane >> 2, sub = lane & 3u;
+#pragma unroll
+    for (int p = 0; p < kPasses; ++p) {
+        const uint32_t blk = sc * 64u + p * kBlocksPerPass + quad_id;
+        if (blk < nblocks) {
+            int64_t off;
+            if constexpr (CONTIG) {
+                off = (int64_t)blk * kBlock + sub * 8;
+            } else {
+                const uint32_t row = blk / blocks_per_row;
+                off = (int64_t)row * ld + (int64_t)(blk - row * blocks_per_row) * kBlock + sub * 8;
+            }
+            w[p] = *reinterpret_cast<const uint4*>(x + off);
+        } else {
+            w[p] = make_uint4(0, 0, 0, 0);
+        }
+    }
+}
+
 template <bool MX, bool CONTIG>
 __global__ __launch_bounds__(kThreads) void quantize_kernel(
     const uint16_t* __restrict__ x, int64_t ld, uint32_t blocks_per_row, uint32_t nblocks,
     uint32_t* __restrict__ codes, uint8_t* __restrict__ dialect, uint8_t* __restrict__ exponent) {
     __shared__ __attribute__((aligned(16))) uint8_t lds_q[MX ? 64 : kDialects * 1024];
     __shared__ __attribute__((aligned(16))) uint8_t lds_s[MX ? 16 : kPairs * 1024];
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const uint32_t quad_id = lane >> 2, sub = lane & 3u;
+    const uint32_t nsuper = (nblocks + 63u) / 64u;
+    const uint32_t stride = gridDim.x * kWaves;
+    uint32_t sc = blockIdx.x * kWaves + wave;
+
+    // the first loads go out before the lookup tables are copied to LDS
+    uint4 w[kPasses];
+    if (sc < nsuper) load_super<CONTIG>(x, ld, blocks_per_row, nblocks, sc, lane, w);
     if constexpr (MX) {
         if (threadIdx.x < 64) lds_q[threadIdx.x] = g_quant_tables.mx[threadIdx.x];
     } else {
         const uint4* gq = reinterpret_cast<const uint4*>(g_quant_tables.q);
         const uint4* gs = reinterpret_cast<const uint4*>(g_quant_tables.s);
-        reinterpret_cast<uint4*>(lds_q)[threadIdx.x] = gq[threadIdx.x];          // 1024 x 16 B
-        if (threadIdx.x < 512) reinterpret_cast<uint4*>(lds_s)[threadIdx.x] = gs[threadIdx.x];
+        for (uint32_t i = threadIdx.x; i < 1024u; i += kThreads) reinterpret_cast<uint4*>(lds_q)[i] = gq[i];   // 16 KiB
+        for (uint32_t i = threadIdx.x; i < 512u; i += kThreads) reinterpret_cast<uint4*>(lds_s)[i] = gs[i];    // 8 KiB
     }
     __syncthreads();
 
-    const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
-    const uint32_t quad_id = lane >> 2, sub = lane & 3u;
-    const uint32_t nsuper = (nblocks + 63u) / 64u;
-    const uint32_t stride = gridDim.x * kWaves;
-    for (uint32_t sc = blockIdx.x * kWaves + wave; sc < nsuper; sc += stride) {
-        uint4 w[kPasses];
-        uint32_t blk[kPasses];
-#pragma unroll
-        for (int p = 0; p < kPasses; ++p) {
-            blk[p] = sc * 64u + p * kBlocksPerPass + quad_id;
-            if (blk[p] < nblocks) {
-                int64_t off;
-                if constexpr (CONTIG) {
-                    off = (int64_t)blk[p] * kBlock + sub * 8;
-                } else {
-                    const uint32_t row = blk[p] / blocks_per_row;
-                    off = (int64_t)row * ld + (int64_t)(blk[p] - row * blocks_per_row) * kBlock + sub * 8;
-                }
-                w[p] = *reinterpret_cast<const uint4*>(x + off);
-            } else {
-                w[p] = make_uint4(0, 0, 0, 0);
-            }
-        }
+    while (sc < nsuper) {
+        // Rolling loads: as soon as pass p of this super-chunk has been computed, its registers
+        // receive pass p of the wave's next super-chunk, so that three or four loads per lane
+        // are in flight all the time and memory traffic never pauses for the arithmetic.
+        const uint32_t nsc = sc + stride;
+        const bool full = sc * 64u + 64u <= nblocks;                      // wave-uniform
+        const bool next_fast = CONTIG && nsc < nsuper && nsc * 64u + 64u <= nblocks;   // wave-uniform
+        const uint4* nbase = reinterpret_cast<const uint4*>(x + (size_t)nsc * (64u * kBlock));
         uint32_t eb[kPasses], dl[kPasses];
+        uint32_t* cdst = codes + (size_t)sc * 256u;           // code dword of (pass p, lane): p * 64 + lane
 #pragma unroll
         for (int p = 0; p < kPasses; ++p) {
             uint32_t code;
@@ -161,19 +191,22 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(
             } else {
                 dfp4_pass(w[p], lds_s, lds_q, code, eb[p], dl[p]);
             }
-            if (blk[p] < nblocks) codes[(size_t)blk[p] * 4u + sub] = code;
+            if (full || sc * 64u + p * kBlocksPerPass + quad_id < nblocks) cdst[p * 64 + lane] = code;
+            if (next_fast) w[p] = nbase[p * 64 + lane];
         }
+        if (!next_fast && nsc < nsuper) load_super<CONTIG>(x, ld, blocks_per_row, nblocks, nsc, lane, w);
         // lane (quad_id, sub) stores the per-block bytes of pass `sub`:
         // one byte-store instruction covers the wave's 64 consecutive blocks
         const uint32_t e_sel = sub == 0 ? eb[0] : sub == 1 ? eb[1] : sub == 2 ? eb[2] : eb[3];
         const uint32_t bm = sc * 64u + sub * kBlocksPerPass + quad_id;
-        if (bm < nblocks) {
+        if (full || bm < nblocks) {
             exponent[bm] = (uint8_t)e_sel;
             if constexpr (!MX) {
                 const uint32_t d_sel = sub == 0 ? dl[0] : sub == 1 ? dl[1] : sub == 2 ? dl[2] : dl[3];
                 dialect[bm] = (uint8_t)d_sel;
             }
         }
+        sc = nsc;
     }
 }
 
@@ -187,7 +220,7 @@ int launch_quantize(bool mx, const void* x, int64_t rows, int64_t K, int64_t ld,
     const uint32_t nblocks = (uint32_t)nblocks64;
     const uint32_t nsuper = (nblocks + 63u) / 64u;
     const uint32_t want = (nsuper + kWaves - 1) / kWaves;
-    const uint32_t cap = (uint32_t)device_cu_count() * 2u;
+    const uint32_t cap = (uint32_t)device_cu_count() * 4u;
     const uint32_t grid = want < cap ? want : cap;
     const bool contig = (ld == K);
     const uint16_t* xp = static_cast<const uint16_t*>(x);
