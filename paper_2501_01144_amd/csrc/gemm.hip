@@ -178,8 +178,12 @@ __device__ __forceinline__ int max_bytes(uint32_t x) {
     return max(max((int)(x & 0xffu), (int)((x >> 8) & 0xffu)), max((int)((x >> 16) & 0xffu), (int)(x >> 24)));
 }
 // up to 8 bytes starting at q (the first n are read), little-endian in a 64-bit word
-__device__ __forceinline__ uint64_t load_bytes8(const uint8_t* q, int n, bool vec) {
-    if (vec && n == 8) return *reinterpret_cast<const uint64_t*>(q);
+__device__ __forceinline__ uint64_t load_bytes8(const uint8_t* q, int n) {
+    if (n == 8) {
+        uint64_t v;
+        __builtin_memcpy(&v, q, 8);                   // no alignment assumed: the compiler picks the access
+        return v;
+    }
     uint64_t v = 0;
     for (int i = 0; i < n; ++i) v |= (uint64_t)q[i] << (8 * i);
     return v;
@@ -206,16 +210,10 @@ __global__ __launch_bounds__(1024) void gemm_prep_kernel(GemmParams p, int n_a, 
         const bool valid = row < p.N;
         const int64_t base = (bz * p.strideW_rows + min(row, p.N - 1)) * KB;
         const int k0 = seg * 16, nb = max(0, min(16, KB - k0));
-        const bool vec = (KB & 15) == 0 && ((reinterpret_cast<uintptr_t>(p.w_exp) |
-                         (MX ? 0 : reinterpret_cast<uintptr_t>(p.w_dial))) & 15) == 0;
         uint32_t e[4] = {0, 0, 0, 0}, d[4] = {0x07070707u, 0x07070707u, 0x07070707u, 0x07070707u};
-        if (vec && nb == 16) {
-            const uint4 ev = *reinterpret_cast<const uint4*>(p.w_exp + base + k0);
-            e[0] = ev.x; e[1] = ev.y; e[2] = ev.z; e[3] = ev.w;
-            if (!MX) {
-                const uint4 dv = *reinterpret_cast<const uint4*>(p.w_dial + base + k0);
-                d[0] = dv.x; d[1] = dv.y; d[2] = dv.z; d[3] = dv.w;
-            }
+        if (nb == 16) {
+            __builtin_memcpy(e, p.w_exp + base + k0, 16);     // no alignment assumed
+            if (!MX) __builtin_memcpy(d, p.w_dial + base + k0, 16);
         } else {
             for (int j = 0; j < nb; ++j) {
                 e[j >> 2] |= (uint32_t)p.w_exp[base + k0 + j] << (8 * (j & 3));
@@ -252,7 +250,7 @@ __global__ __launch_bounds__(1024) void gemm_prep_kernel(GemmParams p, int n_a, 
                     const uint32_t ee = (e[i] >> (8 * j)) & 0xffu, dd = (d[i] >> (8 * j)) & 15u;
                     o[j] = (dd * 4u + ((ee - (uint32_t)mn) & 3u)) * 16u;
                 }
-                *reinterpret_cast<uint4*>(wmeta + 4 * i) = make_uint4(o[0], o[1], o[2], o[3]);
+                __builtin_memcpy(wmeta + 4 * i, o, 16);       // 4-byte aligned only when KB is odd
             }
         } else {
             for (int j = 0; j < nb; ++j) {
@@ -279,8 +277,6 @@ __global__ __launch_bounds__(1024) void gemm_prep_kernel(GemmParams p, int n_a, 
     const int r = lane & 31, t = lane >> 5;
     const int row0 = tile * kTileM + wave * 32;
     const bool group_valid = row0 < p.M;              // wave-uniform
-    const bool vec = (KB & 15) == 0 && ((reinterpret_cast<uintptr_t>(p.a_exp) |
-                     (MX ? 0 : reinterpret_cast<uintptr_t>(p.a_dial))) & 15) == 0;
     int cls[8], sh[8];
     uint64_t d8 = 0x0707070707070707ull;
     if (group_valid) {
@@ -294,25 +290,22 @@ __global__ __launch_bounds__(1024) void gemm_prep_kernel(GemmParams p, int n_a, 
                               : make_uint4(0, 0, 0, 0);
         }
         const int64_t arow = bz * p.strideA_rows + min(row0 + r, p.M - 1);
-        const uint64_t e8 = load_bytes8(p.a_exp + arow * KB + kc, nk, vec);
-        if (!MX) d8 = load_bytes8(p.a_dial + arow * KB + kc, nk, vec);
+        const uint64_t e8 = load_bytes8(p.a_exp + arow * KB + kc, nk);
+        if (!MX) d8 = load_bytes8(p.a_dial + arow * KB + kc, nk);
         // reference exponent of the row: lane (t, r) scans every other 16-byte piece
         int mn = 255;
         const uint8_t* erow = p.a_exp + arow * KB;
-        if (vec) {
-            const int n16 = KB >> 4;
-            for (int i0 = 0; i0 < n16; i0 += 8) {
-                uint4 v[4];
+        const int n16 = KB >> 4;
+        for (int i0 = 0; i0 < n16; i0 += 8) {
+            uint4 v[4];
 #pragma unroll
-                for (int u = 0; u < 4; ++u)
-                    v[u] = *reinterpret_cast<const uint4*>(erow + 16 * min(i0 + 2 * u + t, n16 - 1));
+            for (int u = 0; u < 4; ++u)
+                __builtin_memcpy(&v[u], erow + 16 * min(i0 + 2 * u + t, n16 - 1), 16);   // no alignment assumed
 #pragma unroll
-                for (int u = 0; u < 4; ++u)
-                    mn = min(mn, min(min(min_bytes(v[u].x), min_bytes(v[u].y)), min(min_bytes(v[u].z), min_bytes(v[u].w))));
-            }
-        } else {
-            for (int i = t; i < KB; i += 2) mn = min(mn, (int)erow[i]);
+            for (int u = 0; u < 4; ++u)
+                mn = min(mn, min(min(min_bytes(v[u].x), min_bytes(v[u].y)), min(min_bytes(v[u].z), min_bytes(v[u].w))));
         }
+        for (int i = n16 * 16 + t; i < KB; i += 2) mn = min(mn, (int)erow[i]);
         mn = min(mn, __shfl_xor(mn, 32));
         const bool row_valid = row0 + r < p.M;
         if (chunk == 0 && t == 0) ws[p.off_refa + row0 + r] = row_valid ? (uint8_t)mn : (uint8_t)0;
@@ -486,7 +479,8 @@ __global__ __launch_bounds__(256, 1) void gemm_fast_kernel(GemmParams p) {
                      : DFP4_LOOP_VGPR_CLOBBERS, DFP4_ACC_CLOBBERS, DFP4_LOOP_SGPR_CLOBBERS, "scc", "memory");
     }
 
-    // ---- epilogue
+    // ---- epilogue (nothing to store or publish for a wave whose 128 rows lie beyond M)
+    if (m0 + (int)wave_u * 128 >= p.M) return;
 #define DFP4_READ_TILE(G, V)                                                                        \
     asm volatile(DFP4_ACC_READ_ASM_##G                                                              \
                  : "=v"(V[0]), "=v"(V[1]), "=v"(V[2]), "=v"(V[3]), "=v"(V[4]), "=v"(V[5]),          \

@@ -261,3 +261,72 @@ def test_gemm_mlp_prefill_sampled_outputs():
     cols = np.sort(rng.choice(wd.shape[0], 64, replace=False))
     ref, absdot = _gemm_ref(synth.to_f64(h[rows]), synth.to_f64(wd[cols]))
     _assert_gemm_close(out[rows][:, cols], ref, absdot, "mlp down sampled")
+
+
+def test_gemm_mlp_prefill_bf16_sampled_outputs():
+    # bf16 output of a full-size GEMM (full tiles store two adjacent columns per lane)
+    ops = synth.llama3_8b_mlp(seed=2)
+    x, w = ops["x"], ops["w_up"]
+    print("gemm parity: 2048x14336x4096 bf16 sampled", flush=True)
+    out = dfp4.gemm(dfp4.quantize(_dev(x)), dfp4.quantize(_dev(w)), dtype=torch.bfloat16)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(2)
+    rows = np.sort(rng.choice(x.shape[0], 24, replace=False))
+    cols = np.sort(rng.choice(w.shape[0], 192, replace=False))
+    ref, absdot = _gemm_ref(synth.to_f64(x[rows]), synth.to_f64(w[cols]))
+    _assert_gemm_close(out[rows][:, cols], ref, absdot, "mlp up bf16 sampled", bf16=True)
+
+
+def test_gemm_some_tiles_declined():
+    # rows 520..539 carry block exponents spread over tens of binades, so the second 512-row
+    # tile goes to the per-block-flush fallback while the first one takes the fast path
+    g = torch.Generator().manual_seed(9)
+    M, N, K = 600, 300, 512
+    a = torch.randn(M, K, generator=g)
+    scale = torch.exp2(torch.randint(-25, 25, (20, K // 32), generator=g).repeat_interleave(32, dim=1).float())
+    a[520:540] *= scale
+    a = a.to(torch.bfloat16)
+    w = (torch.randn(N, K, generator=g) * 0.02).to(torch.bfloat16)
+    print("gemm parity: 600x300x512 with declined tiles", flush=True)
+    out = dfp4.gemm(dfp4.quantize(_dev(a)), dfp4.quantize(_dev(w)))
+    torch.cuda.synchronize()
+    ref, absdot = _gemm_ref(synth.to_f64(a), synth.to_f64(w))
+    _assert_gemm_close(out, ref, absdot, "mixed fast and declined tiles")
+
+
+def test_gemm_llama2_down_projection_sampled_outputs():
+    # LLaMA-2-7B down projection at M = 4096: K = 11008 is 344 blocks (not a multiple of 16)
+    g = synth.llama2_7b_linears(seed=4)
+    h, w = g["h"], g["w_down"]
+    print("gemm parity: 4096x4096x11008 sampled", flush=True)
+    out = dfp4.gemm(dfp4.quantize(_dev(h)), dfp4.quantize(_dev(w)))
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(4)
+    rows = np.sort(rng.choice(h.shape[0], 16, replace=False))
+    cols = np.sort(rng.choice(w.shape[0], 96, replace=False))
+    ref, absdot = _gemm_ref(synth.to_f64(h[rows]), synth.to_f64(w[cols]))
+    _assert_gemm_close(out[rows][:, cols], ref, absdot, "llama2 down sampled")
+
+
+def test_gemm_attention_shapes_batched_sampled():
+    # attention matmuls at the real sequence length and head size, 4 of the 128 heads:
+    # Q K^T (K = 128, blocks along the head dimension) and P V (K = 2048, blocks along the sequence)
+    B, H, S, D = 1, 4, 2048, 128
+    ops = synth.attention_operands(seed=5, B=B, H=H, S=S, D=D)
+    q, k, vt = ops["q"], ops["k"], ops["vt"]
+    print("gemm parity: attention 4 heads Q K^T", flush=True)
+    out = dfp4.gemm_batched(dfp4.quantize(_dev(q.reshape(H * S, D))), dfp4.quantize(_dev(k.reshape(H * S, D))), H, S, S)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(5)
+    rows = np.sort(rng.choice(S, 16, replace=False))
+    cols = np.sort(rng.choice(S, 128, replace=False))
+    for hd in (0, 3):
+        ref, absdot = _gemm_ref(synth.to_f64(q[hd][rows]), synth.to_f64(k[hd][cols]))
+        _assert_gemm_close(out[hd][rows][:, cols], ref, absdot, f"QK^T head {hd}")
+    print("gemm parity: attention 4 heads P V", flush=True)
+    p = synth.softmax_rows(H * S, S, seed=55)
+    out = dfp4.gemm_batched(dfp4.quantize(_dev(p)), dfp4.quantize(_dev(vt.reshape(H * D, S))), H, S, D)
+    torch.cuda.synchronize()
+    for hd in (1, 2):
+        ref, absdot = _gemm_ref(synth.to_f64(p[hd * S:(hd + 1) * S][rows]), synth.to_f64(vt[hd]))
+        _assert_gemm_close(out[hd][rows], ref, absdot, f"PV head {hd}")
