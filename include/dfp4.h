@@ -97,8 +97,11 @@ int dfp4_dequantize(dfp4_tensor in, void* y, int y_dtype, int64_t ld_elems, void
  *   out[m, n] = sum over blocks kb of 2^(ea[m,kb] + ew[n,kb] - 2) *
  *               sum over k in kb of (+-ua[m,k]) * (+-uw[n,k])
  * with u the 4-bit unsigned integers (half-units) the codes index.  The inner
- * sums run on the int8 matrix cores with int32 accumulation and are exact;
- * the outer sum is accumulated in fp32.
+ * sums run on the int8 matrix cores with int32 accumulation and are exact.
+ * Where the block exponents of a tile span at most 12 binades per row the
+ * outer sum is exact as well (exponent offsets folded into the int8 operands,
+ * one conversion to fp32 at the end); otherwise it is accumulated in fp32,
+ * one addition per block.
  *   A        quantized [M, K]; W quantized [N, K] (both blocked along K)
  *   out      device, [M, N] row-major, leading dimension ldc (elements, N <= ldc < 2^27);
  *            out_dtype DFP4_F32 or DFP4_BF16 (round to nearest even)

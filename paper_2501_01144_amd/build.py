@@ -1,4 +1,4 @@
-"""Build libdfp4.so (HIP kernels + C ABI) in-tree with hipcc for gfx950.
+"""Build libdfp4.so (HIP kernels + C ABI) and the mfma_peak measurement helper in-tree with hipcc for gfx950.
 
     python -m paper_2501_01144_amd.build
 
@@ -12,6 +12,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdfp4.so")
+PEAK = os.path.join(HERE, "mfma_peak")
 SOURCES = ["api.hip", "quantize.hip", "dequantize.hip", "gemm.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
@@ -50,6 +51,11 @@ def build_library(verbose=True):
     if failed:
         raise RuntimeError("libdfp4 build failed")
     cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.run(cmd, check=True)
+    # measurement helper used by bench.py: register-only int8 MFMA loop
+    cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", os.path.join(CSRC, "mfma_peak.hip"), "-o", PEAK]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)

@@ -21,26 +21,26 @@
 //   the tile (its other rows contribute zeros).  With activations that have
 //   outlier channels, that is a second visit for the few outlier blocks.
 //
-// Four kernels per call:
-//   gemm_rowstat_kernel  per-row reference exponents; for W also the spread and
+// Three kernels per call:
+//   gemm_prep_kernel     per-row reference exponents; for W also the spread and
 //                        one dword per block naming its table (dialect, shift);
-//   gemm_expand_kernel   per-(512 rows, block) class masks and A expanded to
+//                        per-(512 rows, block) class masks and A expanded to
 //                        pre-shifted int8 in MFMA fragment order (A is the
 //                        small operand; W stays 4-bit in HBM);
 //   gemm_fast_kernel     512 x 128 outputs per workgroup, 4 waves, each wave
-//                        512 x 32 with 256 accumulator registers (one wave per
-//                        SIMD); every operand byte moves global -> LDS without
-//                        passing through registers; each wave expands its own
-//                        32 rows of W from 4-bit codes (v_perm_b32 lookups);
-//                        three LDS stages: loads two steps ahead, W expansion
-//                        one step ahead of the MFMAs.  A lone wave issues one
-//                        instruction per 4 cycles, so the step is laid out to
-//                        keep the non-MFMA instruction count per MFMA below
-//                        what fits in the MFMA's shadow;
-//   gemm_block_kernel    always-correct per-block-flush kernel; it only runs
-//                        for tiles the fast kernel declined (exponent spread
-//                        above 3 classes, W rows spreading over more than one
-//                        class, K too long for the int32 bound).
+//                        128 x 128 with 256 accumulator registers (one wave per
+//                        SIMD).  A fragments are private to a wave and come by
+//                        global loads straight into registers, two steps ahead;
+//                        each wave expands its own 32 rows of W from 4-bit codes
+//                        (v_perm_b32 lookups) and shares the int8 result through
+//                        LDS.  A lone wave issues one instruction per 4 cycles or
+//                        so; the whole main loop is generated assembly that places
+//                        the few non-MFMA instructions per MFMA in its shadow;
+//   gemm_block_kernel    always-correct per-block-flush kernel for tiles the
+//                        fast kernel declined (exponent spread above 3 classes,
+//                        W rows spreading over more than one class, K too long
+//                        for the int32 bound); with split K it also adds up the
+//                        K ranges of the other tiles.
 //
 // The order of the elements inside an MFMA operand does not matter as long
 // as A and W use the same order; both sides go through unpack8() below.
@@ -210,26 +210,17 @@ __global__ __launch_bounds__(1024) void gemm_prep_kernel(GemmParams p, int n_a, 
         const bool valid = row < p.N;
         const int64_t base = (bz * p.strideW_rows + min(row, p.N - 1)) * KB;
         const int k0 = seg * 16, nb = max(0, min(16, KB - k0));
+        const uint8_t* we = p.w_exp + base + k0;
+        const uint8_t* wd = MX ? nullptr : p.w_dial + base + k0;
         uint32_t e[4] = {0, 0, 0, 0}, d[4] = {0x07070707u, 0x07070707u, 0x07070707u, 0x07070707u};
-        if (nb == 16) {
-            __builtin_memcpy(e, p.w_exp + base + k0, 16);     // no alignment assumed
-            if (!MX) __builtin_memcpy(d, p.w_dial + base + k0, 16);
-        } else {
-            for (int j = 0; j < nb; ++j) {
-                e[j >> 2] |= (uint32_t)p.w_exp[base + k0 + j] << (8 * (j & 3));
-                if (!MX) d[j >> 2] = (d[j >> 2] & ~(0xffu << (8 * (j & 3)))) |
-                                     ((uint32_t)p.w_dial[base + k0 + j] << (8 * (j & 3)));
-            }
-        }
         int mn = 255, mx = 0;
         if (nb == 16) {
+            __builtin_memcpy(e, we, 16);              // no alignment assumed: the compiler picks the access
+            if (!MX) __builtin_memcpy(d, wd, 16);
 #pragma unroll
             for (int i = 0; i < 4; ++i) { mn = min(mn, min_bytes(e[i])); mx = max(mx, max_bytes(e[i])); }
         } else {
-            for (int j = 0; j < nb; ++j) {
-                const int v = (e[j >> 2] >> (8 * (j & 3))) & 0xff;
-                mn = min(mn, v); mx = max(mx, v);
-            }
+            for (int j = 0; j < nb; ++j) { mn = min(mn, (int)we[j]); mx = max(mx, (int)we[j]); }
         }
         for (int s = 1; s < segs; s <<= 1) {
             mn = min(mn, __shfl_xor(mn, s));
@@ -254,7 +245,7 @@ __global__ __launch_bounds__(1024) void gemm_prep_kernel(GemmParams p, int n_a, 
             }
         } else {
             for (int j = 0; j < nb; ++j) {
-                const uint32_t ee = (e[j >> 2] >> (8 * (j & 3))) & 0xffu, dd = (d[j >> 2] >> (8 * (j & 3))) & 15u;
+                const uint32_t ee = we[j], dd = MX ? 7u : ((uint32_t)wd[j] & 15u);
                 wmeta[j] = (dd * 4u + ((ee - (uint32_t)mn) & 3u)) * 16u;
             }
         }
