@@ -700,6 +700,107 @@ __device__ __forceinline__ void block_flush_tile(const GemmParams& p, int64_t bz
         }
 }
 
+// ---------------------------------------------------------------------------
+// Few rows of A (decode shapes, M <= 64): W is streamed once per 32 rows of A and
+// the time goes into expanding W, so the tile is 32 (A rows) x 32 (W rows) per
+// workgroup and the workgroup's 16 waves share K: wave w takes a contiguous range
+// of blocks, multiplies block by block (one MFMA each) and applies the exponent
+// pair per block in fp32 as the paper does; the 16 partial tiles are added in a
+// fixed order through LDS.  No prepass and no workspace.
+// ---------------------------------------------------------------------------
+constexpr int kSmallWaves = 16;
+constexpr int kSmallMaxKB = 512;      // LDS holds the 32 rows' exponent bytes of all blocks
+constexpr int kSmallMaxM = 64;
+
+template <bool MX, bool BF16>
+__global__ __launch_bounds__(kSmallWaves * 64) void gemm_small_kernel(GemmParams p) {
+    __shared__ __attribute__((aligned(16))) uint32_t s_tab[kDialects * 4];   // shift-0 tables
+    __shared__ __attribute__((aligned(4))) uint8_t s_ea[kSmallMaxKB * 32];   // [block][row] exponent bytes of A
+    __shared__ float s_red[kSmallWaves / 2][16][64];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int h = lane >> 5, r = lane & 31;
+    const int KB = p.KB;
+    const int64_t bz = blockIdx.z;
+    const int m0 = blockIdx.y * 32, n0 = blockIdx.x * 32;
+    const int64_t a_row0 = bz * p.strideA_rows, w_row0 = bz * p.strideW_rows;
+
+    const int64_t arow = a_row0 + min(m0 + r, p.M - 1), wrow = w_row0 + min(n0 + r, p.N - 1);
+    const uint8_t* ac = p.a_codes + arow * KB * 16 + h * 8;
+    const uint8_t* wc = p.w_codes + wrow * KB * 16 + h * 8;
+    const uint8_t* ad = MX ? nullptr : p.a_dial + arow * KB;
+    const uint8_t* wd = MX ? nullptr : p.w_dial + wrow * KB;
+    const uint8_t* we = p.w_exp + wrow * KB;
+    const int per = (KB + kSmallWaves - 1) / kSmallWaves;
+    const int kb_lo = wave * per, kb_hi = min(KB, kb_lo + per);
+
+    for (int i = tid; i < kDialects * 4; i += kSmallWaves * 64) s_tab[i] = g_shifted_book.w[i >> 2][0][i & 3];
+    for (int i = tid; i < 32 * KB; i += kSmallWaves * 64) {
+        const int row = i / KB, kb = i - row * KB;
+        s_ea[kb * 32 + row] = p.a_exp[(a_row0 + min(m0 + row, p.M - 1)) * KB + kb];
+    }
+    __syncthreads();
+
+    float acc[16];
+#pragma unroll
+    for (int x = 0; x < 16; ++x) acc[x] = 0.0f;
+    constexpr int kU = 4;              // blocks whose loads are issued together
+    for (int kb0 = kb_lo; kb0 < kb_hi; kb0 += kU) {
+        uint2 ca[kU], cw[kU];
+        uint32_t da[kU], dw[kU], ew[kU];
+#pragma unroll
+        for (int u = 0; u < kU; ++u) {
+            const int kb = min(kb0 + u, kb_hi - 1);            // the tail repeats the last block (not used)
+            ca[u] = *reinterpret_cast<const uint2*>(ac + (int64_t)kb * 16);
+            cw[u] = *reinterpret_cast<const uint2*>(wc + (int64_t)kb * 16);
+            da[u] = MX ? 7u : ((uint32_t)ad[kb] & 15u);
+            dw[u] = MX ? 7u : ((uint32_t)wd[kb] & 15u);
+            ew[u] = we[kb];
+        }
+#pragma unroll
+        for (int u = 0; u < kU; ++u) {
+            const int kb = kb0 + u;
+            if (kb >= kb_hi) break;                            // wave-uniform
+            const v4i a = unpack16(ca[u].x, ca[u].y, *reinterpret_cast<const uint4*>(&s_tab[da[u] * 4]));
+            const v4i b = unpack16(cw[u].x, cw[u].y, *reinterpret_cast<const uint4*>(&s_tab[dw[u] * 4]));
+            v16i pr = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+            pr = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, pr, 0, 0, 0);
+            const int ewc = (int)ew[u] - 256;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const uint32_t e4 = *reinterpret_cast<const uint32_t*>(&s_ea[kb * 32 + 8 * q + 4 * h]);
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    acc[4 * q + j] += ldexpf((float)pr[4 * q + j], (int)((e4 >> (8 * j)) & 0xffu) + ewc);
+            }
+        }
+    }
+    // the 16 partial tiles, added in a fixed order: waves 8..15 hand theirs to waves 0..7
+    if (wave >= kSmallWaves / 2) {
+#pragma unroll
+        for (int x = 0; x < 16; ++x) s_red[wave - kSmallWaves / 2][x][lane] = acc[x];
+    }
+    __syncthreads();
+    if (wave < kSmallWaves / 2) {
+#pragma unroll
+        for (int x = 0; x < 16; ++x) s_red[wave][x][lane] += acc[x];
+    }
+    __syncthreads();
+    {
+        const int x = wave;                                    // thread (x, lane) finishes one output
+        float sum = 0.0f;
+#pragma unroll
+        for (int w = 0; w < kSmallWaves / 2; ++w) sum += s_red[w][x][lane];
+        const int m = m0 + 8 * (x >> 2) + 4 * h + (x & 3), n = n0 + r;
+        if (m < p.M && n < p.N) {
+            const int64_t o = bz * p.strideC + (int64_t)m * p.ldc + n;
+            if constexpr (BF16)
+                static_cast<uint16_t*>(p.out)[o] = f32_to_bf16_rne(sum);
+            else
+                static_cast<float*>(p.out)[o] = sum;
+        }
+    }
+}
+
 // mode 0: every 128 x 128 tile of the grid (no fast kernel ran).
 // mode 1: the grid covers all tiles; tiles the fast kernel declined are computed, the others
 //         have their K ranges summed (split K).
@@ -756,6 +857,17 @@ int launch_gemm(bool mx, dfp4_tensor A, dfp4_tensor W, void* out, int out_dtype,
     if (p.tiles_m > 16383 || p.tiles_n > (1 << 20)) return DFP4_ERR_SHAPE;
 
     const bool bf16 = out_dtype == DFP4_BF16;
+    if (M <= kSmallMaxM && KB > 0 && KB <= kSmallMaxKB) {
+        dim3 gs((unsigned)((N + 31) / 32), (unsigned)((M + 31) / 32), (unsigned)batch);
+        if (mx) {
+            if (bf16) hipLaunchKernelGGL((gemm_small_kernel<true, true>), gs, dim3(kSmallWaves * 64), 0, stream, p);
+            else hipLaunchKernelGGL((gemm_small_kernel<true, false>), gs, dim3(kSmallWaves * 64), 0, stream, p);
+        } else {
+            if (bf16) hipLaunchKernelGGL((gemm_small_kernel<false, true>), gs, dim3(kSmallWaves * 64), 0, stream, p);
+            else hipLaunchKernelGGL((gemm_small_kernel<false, false>), gs, dim3(kSmallWaves * 64), 0, stream, p);
+        }
+        return check_launch();
+    }
     const bool fast = KB > 0 && KB <= kMaxKB;
     if (fast) {
         const int chunks_a = (int)((KB + 7) / 8), n_a = p.tiles_m * chunks_a;

@@ -330,3 +330,22 @@ def test_gemm_attention_shapes_batched_sampled():
     for hd in (1, 2):
         ref, absdot = _gemm_ref(synth.to_f64(p[hd * S:(hd + 1) * S][rows]), synth.to_f64(vt[hd]))
         _assert_gemm_close(out[hd][rows], ref, absdot, f"PV head {hd}")
+
+
+@pytest.mark.parametrize("M,N,K", [(5, 40, 64), (33, 100, 4096), (64, 96, 256), (16, 4096, 14336)])
+def test_gemm_few_rows(M, N, K):
+    # decode shapes (M <= 64) take the W-streaming kernel: per-block exponent pairs in fp32
+    print(f"gemm parity: few rows {M}x{N}x{K}", flush=True)
+    a = synth.gaussian_outlier_channels(M, K, max(1, K // 200), 50.0, 1.0, seed=100 + M)
+    w = synth.gaussian(N, K, 0.02, seed=200 + N)
+    ref, absdot = _gemm_ref(synth.to_f64(a), synth.to_f64(w))
+    out = dfp4.gemm(dfp4.quantize(_dev(a)), dfp4.quantize(_dev(w)))
+    torch.cuda.synchronize()
+    _assert_gemm_close(out, ref, absdot, "few rows f32")
+    outb = dfp4.gemm(dfp4.quantize(_dev(a)), dfp4.quantize(_dev(w)), dtype=torch.bfloat16)
+    torch.cuda.synchronize()
+    _assert_gemm_close(outb, ref, absdot, "few rows bf16", bf16=True)
+    refm, absm = _gemm_ref(synth.to_f64(a), synth.to_f64(w), mx=True)
+    outm = dfp4.mxfp4_gemm(dfp4.mxfp4_quantize(_dev(a)), dfp4.mxfp4_quantize(_dev(w)))
+    torch.cuda.synchronize()
+    _assert_gemm_close(outm, refm, absm, "few rows mxfp4")
