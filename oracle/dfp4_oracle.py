@@ -163,6 +163,52 @@ def dfp4_quantize(x, chunk_blocks=1 << 15):
     return codes, dialect.reshape(rows, K // BLOCK), exponent.reshape(rows, K // BLOCK)
 
 
+def select_dialect_mse(s):
+    """Dialect with the smallest squared error (Section 3.2: for weights, known in
+    advance, the best dialect of a block can be found by computing the exact mean
+    squared error of every dialect).  s [nblocks, 32] scaled magnitudes; returns ids.
+
+    Every dialect rounds a magnitude below 0.25 to 0, so those elements add the same
+    amount to all 16 errors and are left out of the comparison; the remaining terms
+    (s - v)^2 are multiples of 2^-18 below 2^6, and their sums are exact in float64.
+    Equal errors: the lowest dialect id (the paper does not say).
+    """
+    big = s >= 0.25
+    err = np.empty((s.shape[0], 16), dtype=np.float64)
+    for d in range(16):
+        idx = nearest_index(s, np.full(s.shape[0], d, dtype=np.int64))
+        v = np.take_along_axis(np.broadcast_to(FORMATBOOK[d], (s.shape[0], 8)), idx, axis=1)
+        err[:, d] = (np.where(big, s - v, 0.0) ** 2).sum(axis=1)
+    return np.argmin(err, axis=1)          # first minimum = lowest id
+
+
+def dfp4_quantize_mse(x, chunk_blocks=1 << 13):
+    """DialectFP4 quantization with MSE-based dialect selection (offline, for
+    weights): same shared exponent, element rounding and layouts as dfp4_quantize;
+    only the choice of the block's dialect differs."""
+    x = np.asarray(x, dtype=np.float64)
+    assert x.ndim == 2 and x.shape[1] % BLOCK == 0
+    assert np.isfinite(x).all()
+    rows, K = x.shape
+    nb = rows * (K // BLOCK)
+    xb = x.reshape(nb, BLOCK)
+    index = np.empty((nb, BLOCK), dtype=np.uint8)
+    dialect = np.empty(nb, dtype=np.uint8)
+    exponent = np.empty(nb, dtype=np.uint8)
+    for b0 in range(0, nb, chunk_blocks):
+        blk = xb[b0:b0 + chunk_blocks]
+        mag = np.abs(blk)
+        e = shared_exponent(mag.max(axis=1))
+        s = np.ldexp(mag, (-e)[:, None].astype(np.int32))
+        d = select_dialect_mse(s)
+        index[b0:b0 + chunk_blocks] = nearest_index(s, d)
+        dialect[b0:b0 + chunk_blocks] = d
+        exponent[b0:b0 + chunk_blocks] = e + EXP_BIAS
+    sign = np.signbit(xb)
+    codes = pack_codes(sign, index).reshape(rows, K // 2)
+    return codes, dialect.reshape(rows, K // BLOCK), exponent.reshape(rows, K // BLOCK)
+
+
 def dfp4_dequantize(codes, dialect, exponent):
     """Section 3.3 dequantization: index -> 4-bit unsigned integer u through the
     dialect's table, value = (-1)**sign * 0.5 * u * 2**e.  Returns float64 [rows, K]."""

@@ -349,3 +349,29 @@ def test_gemm_few_rows(M, N, K):
     outm = dfp4.mxfp4_gemm(dfp4.mxfp4_quantize(_dev(a)), dfp4.mxfp4_quantize(_dev(w)))
     torch.cuda.synchronize()
     _assert_gemm_close(outm, refm, absm, "few rows mxfp4")
+
+
+def test_gemm_very_long_k_takes_block_flush_kernel():
+    # K beyond the single-accumulator kernel's range (more than 512 blocks): every tile is
+    # computed block by block with fp32 accumulation
+    M, N, K = 70, 64, 32 * 520
+    print(f"gemm parity: long K {M}x{N}x{K}", flush=True)
+    a = synth.gaussian(M, K, 1.0, seed=71)
+    w = synth.gaussian(N, K, 0.02, seed=72)
+    out = dfp4.gemm(dfp4.quantize(_dev(a)), dfp4.quantize(_dev(w)))
+    torch.cuda.synchronize()
+    ref, absdot = _gemm_ref(synth.to_f64(a), synth.to_f64(w))
+    _assert_gemm_close(out, ref, absdot, "long K")
+
+
+def test_gemm_batched_with_split_k():
+    # few tiles per problem and a long K: the K ranges of every batch entry are summed separately
+    B, M, N, K = 2, 100, 200, 2048
+    print(f"gemm parity: batched split K {B}x{M}x{N}x{K}", flush=True)
+    a = synth.gaussian_outlier_channels(B * M, K, 8, 50.0, 1.0, seed=81)
+    w = synth.gaussian(B * N, K, 0.02, seed=82)
+    out = dfp4.gemm_batched(dfp4.quantize(_dev(a)), dfp4.quantize(_dev(w)), B, M, N)
+    torch.cuda.synchronize()
+    for b in range(B):
+        ref, absdot = _gemm_ref(synth.to_f64(a[b * M:(b + 1) * M]), synth.to_f64(w[b * N:(b + 1) * N]))
+        _assert_gemm_close(out[b], ref, absdot, f"batch {b}")

@@ -431,3 +431,50 @@ def test_planted_mistakes_are_caught(monkeypatch, golden_dir):
         test_formatbook_rows_printed_in_the_paper(golden_dir)
     monkeypatch.undo()
     assert handworked_ok() and g
+
+
+# --------------------------------------------------------------------------
+# MSE-based dialect selection (Section 3.2: offline choice for weights)
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("kind", ["gauss", "t3", "outlier", "wide", "grid"])
+def test_mse_selection_vs_exact_brute_force(kind):
+    # exhaustive search over the 16 dialects in exact rationals, all 32 terms included;
+    # among equal errors the lowest id
+    rng = np.random.default_rng({"gauss": 21, "t3": 22, "outlier": 23, "wide": 24, "grid": 25}[kind])
+    x = _random_blocks(rng, 64, kind)
+    codes, dialect, expo = O.dfp4_quantize_mse(x)
+    nib = _nibbles(codes)
+    for b in range(x.shape[0]):
+        xs = [Fraction(v) for v in x[b]]
+        best, _ = BF.mse_best_dialects(xs, BOOK_FR)
+        d = int(dialect[b, 0])
+        assert d == best[0], (kind, b, d, best)
+        e = BF.exponent_by_search(max(abs(v) for v in xs))
+        assert int(expo[b, 0]) - 127 == e
+        s = [abs(v) / Fraction(2) ** e for v in xs]
+        assert list(nib[b] & 7) == [BF.nearest_ties_up(v, BOOK_FR[d]) for v in s], (kind, b)
+
+
+def test_mse_selection_never_worse_than_two_stage():
+    rng = np.random.default_rng(26)
+    for kind in ("gauss", "t3", "outlier"):
+        x = _random_blocks(rng, 300, kind)
+        err_mse = ((O.dfp4_dequantize(*O.dfp4_quantize_mse(x)) - x) ** 2).sum(axis=1)
+        err_two = ((O.dfp4_dequantize(*O.dfp4_quantize(x)) - x) ** 2).sum(axis=1)
+        assert (err_mse <= err_two * (1 + 1e-12)).all(), kind
+        assert err_mse.sum() < err_two.sum(), kind
+
+
+def test_mse_selection_on_grid_block_is_lossless():
+    # a block made of dialect 11's own values (scaled by 2^3) is reproduced exactly, and
+    # dialect 11 is the lowest id that holds all of them (3.5 occurs only in d11, d13, d14)
+    vals = O.FORMATBOOK[11]
+    x = np.tile(np.concatenate([vals, -vals]), 2).reshape(1, 32) * 8.0
+    codes, dialect, expo = O.dfp4_quantize_mse(x)
+    assert int(dialect[0, 0]) == 11 and int(expo[0, 0]) == 127 + 3
+    assert np.array_equal(O.dfp4_dequantize(codes, dialect, expo), x)
+
+
+def test_mse_selection_all_zero_block():
+    codes, dialect, expo = O.dfp4_quantize_mse(np.zeros((1, 32)))
+    assert int(dialect[0, 0]) == 0 and int(expo[0, 0]) == 0 and not codes.any()
