@@ -86,6 +86,18 @@ int dfp4_quantize(const void* x_bf16, int64_t rows, int64_t K, int64_t ld_elems,
                   dfp4_tensor out, void* stream);
 
 /*
+ * Offline DialectFP4 quantization with MSE-based dialect selection (Section 3.2:
+ * for tensors known in advance, such as weights, the best dialect of a block is
+ * found by computing the squared error of every dialect).  Arguments, layouts,
+ * shared exponent and element rounding as dfp4_quantize; the block's dialect is
+ * the one whose 32 rounded values have the smallest sum of squared errors, the
+ * lowest id among equal sums.  Not meant for the online path: it does 16 rounds
+ * of quantization per block.
+ */
+int dfp4_quantize_mse(const void* x_bf16, int64_t rows, int64_t K, int64_t ld_elems,
+                      dfp4_tensor out, void* stream);
+
+/*
  * Dequantization (Section 3.3): y[r, k] = (-1)^sign * 0.5 * u[dialect][index] * 2^e.
  *   y        device, [rows, K] with leading dimension ld_elems (>= K, multiple of 8),
  *            16-byte aligned; y_dtype selects DFP4_F32 or DFP4_BF16 (both exact).

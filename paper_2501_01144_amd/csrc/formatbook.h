@@ -84,10 +84,13 @@ constexpr int e2m1_index(int key) {
 //   q[d][key]  = index(t0) | index(t1) << 4 under dialect d   (two code nibbles, no sign)
 //   s[p][key]  = (votes for the even dialect of pair p) - (votes for the odd one), int8 in -2..2
 //   mx[key64]  = E2M1 index for one element with key = 2 t + sticky
+//   near_i[d][t], near_u[d][t] = index / half-unit value of dialect d nearest to a single magnitude t
 struct QuantTables {
     uint8_t q[kDialects * 1024];
     uint8_t s[kPairs * 1024];
     uint8_t mx[64];
+    uint8_t near_i[kDialects * 32];
+    uint8_t near_u[kDialects * 32];
 };
 
 constexpr QuantTables make_quant_tables() {
@@ -107,6 +110,11 @@ constexpr QuantTables make_quant_tables() {
             T.s[p * 1024 + k] = (uint8_t)(one[k & 31] + one[k >> 5]);      // int8, two's complement
     }
     for (int k = 0; k < 64; ++k) T.mx[k] = (uint8_t)e2m1_index(k);
+    for (int d = 0; d < kDialects; ++d)
+        for (int t = 0; t < 32; ++t) {
+            T.near_i[d * 32 + t] = (uint8_t)nearest_index(d, t);
+            T.near_u[d * 32 + t] = kBook[d][nearest_index(d, t)];
+        }
     return T;
 }
 

@@ -210,6 +210,81 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(
     }
 }
 
+// ---------------------------------------------------------------------------
+// Offline quantizer with MSE-based dialect selection (Section 3.2: for weights,
+// known in advance, the best dialect of a block is the one with the smallest
+// squared error).  Same mapping as above (4 lanes per block, 8 elements per lane),
+// one block per quad, no persistence: it runs once per weight matrix.
+// Errors are exact integers: magnitudes below 0.25 round to 0 in every dialect and
+// are left out of the comparison; every other scaled magnitude is a multiple of
+// 2^-9 below 8, so with s9 = 512 s and v9 = 256 u the error sum of a block stays
+// below 2^30.  Equal errors: the lowest dialect id.
+// ---------------------------------------------------------------------------
+template <bool CONTIG>
+__global__ __launch_bounds__(256) void quantize_mse_kernel(
+    const uint16_t* __restrict__ x, int64_t ld, uint32_t blocks_per_row, uint32_t nblocks,
+    uint32_t* __restrict__ codes, uint8_t* __restrict__ dialect, uint8_t* __restrict__ exponent) {
+    __shared__ uint8_t s_i[kDialects * 32], s_u[kDialects * 32];
+    for (uint32_t i = threadIdx.x; i < kDialects * 32u; i += 256u) {
+        s_i[i] = g_quant_tables.near_i[i];
+        s_u[i] = g_quant_tables.near_u[i];
+    }
+    __syncthreads();
+    const uint32_t gid = blockIdx.x * 256u + threadIdx.x;
+    const uint32_t blk = gid >> 2, sub = gid & 3u;
+    const bool valid = blk < nblocks;             // whole quads are valid or not
+    uint4 wv = make_uint4(0, 0, 0, 0);
+    if (valid) {
+        int64_t off;
+        if constexpr (CONTIG) {
+            off = (int64_t)blk * kBlock + sub * 8;
+        } else {
+            const uint32_t row = blk / blocks_per_row;
+            off = (int64_t)row * ld + (int64_t)(blk - row * blocks_per_row) * kBlock + sub * 8;
+        }
+        wv = *reinterpret_cast<const uint4*>(x + off);
+    }
+    const uint32_t w[4] = {wv.x, wv.y, wv.z, wv.w};
+    const uint32_t ab = block_amax_bits(w);
+    const int byte = max((int)(ab >> 7) - 2, 0);
+    const int n = 129 - byte;                       // 4 |x| / 2^e = |x| * 2^n
+    uint32_t s9[8], t[8];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        s9[2 * j] = (uint32_t)ldexpf(__builtin_fabsf(as_f(w[j] << 16)), n + 7);
+        s9[2 * j + 1] = (uint32_t)ldexpf(__builtin_fabsf(as_f(w[j] & 0xffff0000u)), n + 7);
+        t[2 * j] = s9[2 * j] >> 7;
+        t[2 * j + 1] = s9[2 * j + 1] >> 7;
+    }
+    uint32_t best_err = 0xffffffffu, best_d = 0;
+    for (uint32_t d = 0; d < (uint32_t)kDialects; ++d) {
+        uint32_t err = 0;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int diff = t[i] ? (int)s9[i] - 256 * (int)s_u[d * 32 + t[i]] : 0;
+            err += (uint32_t)(diff * diff);
+        }
+        err += quad<0xB1>(err);
+        err += quad<0x4E>(err);
+        if (err < best_err) {
+            best_err = err;
+            best_d = d;
+        }
+    }
+    uint32_t code = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        code |= ((uint32_t)s_i[best_d * 32 + t[2 * j]] | ((uint32_t)s_i[best_d * 32 + t[2 * j + 1]] << 4)) << (8 * j);
+    code |= sign_nibbles(w);
+    if (valid) {
+        codes[(size_t)blk * 4u + sub] = code;
+        if (sub == 0) {
+            exponent[blk] = (uint8_t)byte;
+            dialect[blk] = (uint8_t)best_d;
+        }
+    }
+}
+
 }  // namespace
 
 int launch_quantize(bool mx, const void* x, int64_t rows, int64_t K, int64_t ld, dfp4_tensor out,
@@ -235,6 +310,24 @@ int launch_quantize(bool mx, const void* x, int64_t rows, int64_t K, int64_t ld,
         if (contig) DFP4_LAUNCH(false, true); else DFP4_LAUNCH(false, false);
     }
 #undef DFP4_LAUNCH
+    return check_launch();
+}
+
+int launch_quantize_mse(const void* x, int64_t rows, int64_t K, int64_t ld, dfp4_tensor out, hipStream_t stream) {
+    const int64_t nblocks64 = rows * (K / kBlock);
+    if (nblocks64 == 0) return DFP4_OK;
+    if (nblocks64 >= (int64_t)1 << 29) return DFP4_ERR_SHAPE;
+    const uint32_t nblocks = (uint32_t)nblocks64;
+    const uint32_t grid = (nblocks * 4u + 255u) / 256u;
+    const uint16_t* xp = static_cast<const uint16_t*>(x);
+    uint32_t* cp = reinterpret_cast<uint32_t*>(out.codes);
+    const uint32_t kb = (uint32_t)(K / kBlock);
+    if (ld == K)
+        hipLaunchKernelGGL((quantize_mse_kernel<true>), dim3(grid), dim3(256), 0, stream, xp, ld, kb, nblocks, cp,
+                           out.dialect, out.exponent);
+    else
+        hipLaunchKernelGGL((quantize_mse_kernel<false>), dim3(grid), dim3(256), 0, stream, xp, ld, kb, nblocks, cp,
+                           out.dialect, out.exponent);
     return check_launch();
 }
 

@@ -25,7 +25,7 @@ class _CTensor(ctypes.Structure):
 
 
 SYMBOLS = [
-    "dfp4_quantize", "dfp4_dequantize", "dfp4_gemm", "dfp4_gemm_batched", "dfp4_gemm_workspace_bytes",
+    "dfp4_quantize", "dfp4_quantize_mse", "dfp4_dequantize", "dfp4_gemm", "dfp4_gemm_batched", "dfp4_gemm_workspace_bytes",
     "mxfp4_quantize", "mxfp4_dequantize", "mxfp4_gemm", "dfp4_formatbook", "dfp4_strerror",
 ]
 
@@ -45,6 +45,7 @@ def load():
     i64, vp, ci = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
     lib.dfp4_quantize.argtypes = [vp, i64, i64, i64, _CTensor, vp]
     lib.mxfp4_quantize.argtypes = [vp, i64, i64, i64, _CTensor, vp]
+    lib.dfp4_quantize_mse.argtypes = [vp, i64, i64, i64, _CTensor, vp]
     lib.dfp4_dequantize.argtypes = [_CTensor, vp, ci, i64, vp]
     lib.mxfp4_dequantize.argtypes = [_CTensor, vp, ci, i64, vp]
     lib.dfp4_gemm.argtypes = [_CTensor, _CTensor, vp, ci, i64, vp, ctypes.c_size_t, vp]
@@ -56,7 +57,7 @@ def load():
     lib.dfp4_formatbook.argtypes = [vp]
     lib.dfp4_strerror.argtypes = [ci]
     lib.dfp4_strerror.restype = ctypes.c_char_p
-    for name in ("dfp4_quantize", "mxfp4_quantize", "dfp4_dequantize", "mxfp4_dequantize", "dfp4_gemm",
+    for name in ("dfp4_quantize", "dfp4_quantize_mse", "mxfp4_quantize", "dfp4_dequantize", "mxfp4_dequantize", "dfp4_gemm",
                  "mxfp4_gemm", "dfp4_gemm_batched", "dfp4_formatbook"):
         getattr(lib, name).restype = ci
     _lib = lib
@@ -114,6 +115,11 @@ def _quantize(fn, what, x, out, mx):
 def quantize(x, out=None):
     """dfp4_quantize: bf16 [rows, K] (row stride allowed) -> QTensor."""
     return _quantize(load().dfp4_quantize, "dfp4_quantize", x, out, False)
+
+
+def quantize_mse(x, out=None):
+    """dfp4_quantize_mse: offline quantization, the dialect of each block chosen by squared error."""
+    return _quantize(load().dfp4_quantize_mse, "dfp4_quantize_mse", x, out, False)
 
 
 def mxfp4_quantize(x, out=None):

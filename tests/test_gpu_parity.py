@@ -375,3 +375,41 @@ def test_gemm_batched_with_split_k():
     for b in range(B):
         ref, absdot = _gemm_ref(synth.to_f64(a[b * M:(b + 1) * M]), synth.to_f64(w[b * N:(b + 1) * N]))
         _assert_gemm_close(out[b], ref, absdot, f"batch {b}")
+
+
+# --------------------------------------------------------------------------
+# offline quantizer with MSE-based dialect selection
+# --------------------------------------------------------------------------
+def _check_quantize_mse(x_bf16, what):
+    print(f"quantize_mse parity: {what} shape={tuple(x_bf16.shape)}", flush=True)
+    q = dfp4.quantize_mse(_dev(x_bf16))
+    torch.cuda.synchronize()
+    _assert_quant_equal(q, O.dfp4_quantize_mse(synth.to_f64(x_bf16)), what)
+    return q
+
+
+@pytest.mark.parametrize("rows,K", [(1, 32), (7, 96), (33, 4096), (257, 1056)])
+def test_quantize_mse_shapes(rows, K):
+    _check_quantize_mse(synth.student_t(rows, K, 3.0, seed=rows + K), "student-t")
+    _check_quantize_mse(synth.gaussian(rows, K, 0.02, seed=rows), "weights")
+
+
+def test_quantize_mse_every_bf16_value_and_ties():
+    _check_quantize_mse(synth.all_bf16_bit_patterns(), "all finite bf16 values")
+    g = torch.Generator().manual_seed(12)
+    grid = (torch.randint(-64, 64, (64, 256), generator=g).float() / 8.0).to(torch.bfloat16)   # many equal errors
+    _check_quantize_mse(grid, "multiples of 1/8")
+    scale = torch.exp2(torch.randint(-120, 120, (64, 8), generator=g).repeat_interleave(32, dim=1).float())
+    _check_quantize_mse((torch.randn(64, 256, generator=g) * scale).to(torch.bfloat16), "wide range")
+    _check_quantize_mse(torch.zeros(4, 64, dtype=torch.bfloat16), "zeros")
+
+
+def test_gemm_with_mse_quantized_weights():
+    M, N, K = 96, 160, 512
+    a = synth.gaussian_outlier_channels(M, K, 4, 50.0, 1.0, seed=91)
+    w = synth.gaussian(N, K, 0.02, seed=92)
+    out = dfp4.gemm(dfp4.quantize(_dev(a)), dfp4.quantize_mse(_dev(w)))
+    torch.cuda.synchronize()
+    ad = O.dfp4_dequantize(*O.dfp4_quantize(synth.to_f64(a)))
+    wd = O.dfp4_dequantize(*O.dfp4_quantize_mse(synth.to_f64(w)))
+    _assert_gemm_close(out, ad @ wd.T, np.abs(ad) @ np.abs(wd).T, "mse weights")
