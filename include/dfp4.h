@@ -86,6 +86,20 @@ int dfp4_quantize(const void* x_bf16, int64_t rows, int64_t K, int64_t ld_elems,
                   dfp4_tensor out, void* stream);
 
 /*
+ * Transposing quantizers (Appendix C: every operand is blocked along the dimension
+ * it is multiplied over): x [rows, cols] row-major (leading dimension ld_elems) is
+ * quantized in blocks of 32 along its ROWS; `out` is the quantized transpose,
+ * out.rows = cols, out.K = rows, bit-identical to dfp4_quantize / mxfp4_quantize
+ * applied to x^T.  For V of the attention product P V: stored [sequence, head
+ * dim], contracted over the sequence.  rows must be a multiple of 32, cols and
+ * ld_elems multiples of 8, x 16-byte aligned.
+ */
+int dfp4_quantize_t(const void* x_bf16, int64_t rows, int64_t cols, int64_t ld_elems,
+                    dfp4_tensor out, void* stream);
+int mxfp4_quantize_t(const void* x_bf16, int64_t rows, int64_t cols, int64_t ld_elems,
+                     dfp4_tensor out, void* stream);
+
+/*
  * Offline DialectFP4 quantization with MSE-based dialect selection (Section 3.2:
  * for tensors known in advance, such as weights, the best dialect of a block is
  * found by computing the squared error of every dialect).  Arguments, layouts,

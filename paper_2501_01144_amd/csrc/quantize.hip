@@ -211,6 +211,71 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(
 }
 
 // ---------------------------------------------------------------------------
+// Transposing quantizer: x [rows, cols] row-major is quantized along its ROWS, i.e.
+// the result is the quantized x^T [cols, rows] with blocks of 32 along the original
+// row index.  Appendix C: an operand must be blocked along the dimension it is
+// multiplied over; V of the attention product P V is stored [sequence, head dim]
+// but contracted over the sequence.  A workgroup loads a 128 x 64 tile (whole
+// 128-byte lines), transposes it through LDS and runs the same per-block
+// arithmetic as quantize_kernel: thread (column c, quarter sub) handles rows
+// 32 p + 8 sub .. + 7 of column c for p = 0..3.
+// ---------------------------------------------------------------------------
+constexpr int kTRows = 128, kTCols = 64, kTPitch = 66;     // LDS row pitch in bf16 (33 dwords: no bank conflicts)
+
+template <bool MX>
+__global__ __launch_bounds__(256) void quantize_t_kernel(
+    const uint16_t* __restrict__ x, int64_t ld, uint32_t rows, uint32_t cols,
+    uint32_t* __restrict__ codes, uint8_t* __restrict__ dialect, uint8_t* __restrict__ exponent) {
+    __shared__ __attribute__((aligned(16))) uint8_t lds_q[MX ? 64 : kDialects * 1024];
+    __shared__ __attribute__((aligned(16))) uint8_t lds_s[MX ? 16 : kPairs * 1024];
+    __shared__ __attribute__((aligned(4))) uint16_t s_x[kTRows * kTPitch];
+    const uint32_t tid = threadIdx.x;
+    if constexpr (MX) {
+        if (tid < 64) lds_q[tid] = g_quant_tables.mx[tid];
+    } else {
+        const uint4* gq = reinterpret_cast<const uint4*>(g_quant_tables.q);
+        const uint4* gs = reinterpret_cast<const uint4*>(g_quant_tables.s);
+        for (uint32_t i = tid; i < 1024u; i += 256u) reinterpret_cast<uint4*>(lds_q)[i] = gq[i];
+        for (uint32_t i = tid; i < 512u; i += 256u) reinterpret_cast<uint4*>(lds_s)[i] = gs[i];
+    }
+    const uint32_t r0 = blockIdx.y * kTRows, c0 = blockIdx.x * kTCols;
+    // load: 8 threads per row (8 bf16 = 16 bytes each), 32 rows per sweep
+    for (uint32_t i = tid; i < kTRows * 8u; i += 256u) {
+        const uint32_t rr = i >> 3, cc = (i & 7u) * 8u;
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (r0 + rr < rows && c0 + cc < cols)                  // cols is a multiple of 8
+            v = *reinterpret_cast<const uint4*>(x + (int64_t)(r0 + rr) * ld + c0 + cc);
+        uint32_t* dst = reinterpret_cast<uint32_t*>(&s_x[rr * kTPitch + cc]);
+        dst[0] = v.x; dst[1] = v.y; dst[2] = v.z; dst[3] = v.w;
+    }
+    __syncthreads();
+    const uint32_t c = tid >> 2, sub = tid & 3u;
+    const uint32_t kb_per_col = rows / kBlock;                 // blocks of x^T's row `c0 + c`
+    const bool col_ok = c0 + c < cols;
+#pragma unroll
+    for (uint32_t p = 0; p < kTRows / kBlock; ++p) {
+        const uint32_t rb = p * kBlock + sub * 8u;             // first of this lane's 8 rows
+        uint32_t w[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            w[j] = (uint32_t)s_x[(rb + 2 * j) * kTPitch + c] | ((uint32_t)s_x[(rb + 2 * j + 1) * kTPitch + c] << 16);
+        const uint4 wv = make_uint4(w[0], w[1], w[2], w[3]);
+        uint32_t code, eb, dl = 0;
+        if constexpr (MX) mxfp4_pass(wv, lds_q, code, eb);
+        else dfp4_pass(wv, lds_s, lds_q, code, eb, dl);
+        const uint32_t blk_row = (r0 >> 5) + p;                // block index along the original rows
+        if (col_ok && blk_row < kb_per_col) {
+            const size_t blk = (size_t)(c0 + c) * kb_per_col + blk_row;
+            codes[blk * 4u + sub] = code;
+            if (sub == 0) {
+                exponent[blk] = (uint8_t)eb;
+                if constexpr (!MX) dialect[blk] = (uint8_t)dl;
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
 // Offline quantizer with MSE-based dialect selection (Section 3.2: for weights,
 // known in advance, the best dialect of a block is the one with the smallest
 // squared error).  Same mapping as above (4 lanes per block, 8 elements per lane),
@@ -310,6 +375,24 @@ int launch_quantize(bool mx, const void* x, int64_t rows, int64_t K, int64_t ld,
         if (contig) DFP4_LAUNCH(false, true); else DFP4_LAUNCH(false, false);
     }
 #undef DFP4_LAUNCH
+    return check_launch();
+}
+
+int launch_quantize_t(bool mx, const void* x, int64_t rows, int64_t cols, int64_t ld, dfp4_tensor out,
+                      hipStream_t stream) {
+    if (rows == 0 || cols == 0) return DFP4_OK;
+    if (rows * (cols / 1) >= ((int64_t)1 << 34) || rows >= ((int64_t)1 << 31) || cols >= ((int64_t)1 << 31))
+        return DFP4_ERR_SHAPE;
+    dim3 grid((unsigned)((cols + kTCols - 1) / kTCols), (unsigned)((rows + kTRows - 1) / kTRows));
+    if (grid.y > 65535) return DFP4_ERR_SHAPE;
+    const uint16_t* xp = static_cast<const uint16_t*>(x);
+    uint32_t* cp = reinterpret_cast<uint32_t*>(out.codes);
+    if (mx)
+        hipLaunchKernelGGL((quantize_t_kernel<true>), grid, dim3(256), 0, stream, xp, ld, (uint32_t)rows,
+                           (uint32_t)cols, cp, out.dialect, out.exponent);
+    else
+        hipLaunchKernelGGL((quantize_t_kernel<false>), grid, dim3(256), 0, stream, xp, ld, (uint32_t)rows,
+                           (uint32_t)cols, cp, out.dialect, out.exponent);
     return check_launch();
 }
 

@@ -25,7 +25,7 @@ class _CTensor(ctypes.Structure):
 
 
 SYMBOLS = [
-    "dfp4_quantize", "dfp4_quantize_mse", "dfp4_dequantize", "dfp4_gemm", "dfp4_gemm_batched", "dfp4_gemm_workspace_bytes",
+    "dfp4_quantize", "dfp4_quantize_mse", "dfp4_quantize_t", "mxfp4_quantize_t", "dfp4_dequantize", "dfp4_gemm", "dfp4_gemm_batched", "dfp4_gemm_workspace_bytes",
     "mxfp4_quantize", "mxfp4_dequantize", "mxfp4_gemm", "dfp4_formatbook", "dfp4_strerror",
 ]
 
@@ -46,6 +46,8 @@ def load():
     lib.dfp4_quantize.argtypes = [vp, i64, i64, i64, _CTensor, vp]
     lib.mxfp4_quantize.argtypes = [vp, i64, i64, i64, _CTensor, vp]
     lib.dfp4_quantize_mse.argtypes = [vp, i64, i64, i64, _CTensor, vp]
+    lib.dfp4_quantize_t.argtypes = [vp, i64, i64, i64, _CTensor, vp]
+    lib.mxfp4_quantize_t.argtypes = [vp, i64, i64, i64, _CTensor, vp]
     lib.dfp4_dequantize.argtypes = [_CTensor, vp, ci, i64, vp]
     lib.mxfp4_dequantize.argtypes = [_CTensor, vp, ci, i64, vp]
     lib.dfp4_gemm.argtypes = [_CTensor, _CTensor, vp, ci, i64, vp, ctypes.c_size_t, vp]
@@ -57,7 +59,7 @@ def load():
     lib.dfp4_formatbook.argtypes = [vp]
     lib.dfp4_strerror.argtypes = [ci]
     lib.dfp4_strerror.restype = ctypes.c_char_p
-    for name in ("dfp4_quantize", "dfp4_quantize_mse", "mxfp4_quantize", "dfp4_dequantize", "mxfp4_dequantize", "dfp4_gemm",
+    for name in ("dfp4_quantize", "dfp4_quantize_mse", "dfp4_quantize_t", "mxfp4_quantize_t", "mxfp4_quantize", "dfp4_dequantize", "mxfp4_dequantize", "dfp4_gemm",
                  "mxfp4_gemm", "dfp4_gemm_batched", "dfp4_formatbook"):
         getattr(lib, name).restype = ci
     _lib = lib
@@ -120,6 +122,25 @@ def quantize(x, out=None):
 def quantize_mse(x, out=None):
     """dfp4_quantize_mse: offline quantization, the dialect of each block chosen by squared error."""
     return _quantize(load().dfp4_quantize_mse, "dfp4_quantize_mse", x, out, False)
+
+
+def _quantize_t(fn, what, x, out, mx):
+    assert x.dtype == torch.bfloat16 and x.dim() == 2 and x.is_cuda and x.stride(1) == 1
+    rows, cols = x.shape
+    if out is None:
+        out = empty_qtensor(cols, rows, x.device, mx)
+    ld = x.stride(0) if rows > 1 else cols
+    _check(fn(_ptr(x), rows, cols, ld, out.c(), _stream()), what)
+    return out
+
+
+def quantize_t(x, out=None):
+    """dfp4_quantize_t: bf16 [rows, cols] -> QTensor of x^T (blocks of 32 along the rows of x)."""
+    return _quantize_t(load().dfp4_quantize_t, "dfp4_quantize_t", x, out, False)
+
+
+def mxfp4_quantize_t(x, out=None):
+    return _quantize_t(load().mxfp4_quantize_t, "mxfp4_quantize_t", x, out, True)
 
 
 def mxfp4_quantize(x, out=None):

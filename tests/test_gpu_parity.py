@@ -413,3 +413,38 @@ def test_gemm_with_mse_quantized_weights():
     ad = O.dfp4_dequantize(*O.dfp4_quantize(synth.to_f64(a)))
     wd = O.dfp4_dequantize(*O.dfp4_quantize_mse(synth.to_f64(w)))
     _assert_gemm_close(out, ad @ wd.T, np.abs(ad) @ np.abs(wd).T, "mse weights")
+
+
+# --------------------------------------------------------------------------
+# transposing quantizer (blocks along the rows of the input)
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("rows,cols", [(32, 8), (96, 72), (2048, 128), (160, 264), (4096, 64)])
+def test_quantize_transposed(rows, cols):
+    print(f"quantize_t parity: {rows}x{cols}", flush=True)
+    x = synth.gaussian_outlier_channels(rows, cols, max(1, cols // 64), 30.0, 1.0, seed=rows + cols)
+    xt = synth.to_f64(x).T.copy()
+    q = dfp4.quantize_t(_dev(x))
+    torch.cuda.synchronize()
+    assert (q.rows, q.K) == (cols, rows)
+    _assert_quant_equal(q, O.dfp4_quantize(xt), "transposed")
+    qm = dfp4.mxfp4_quantize_t(_dev(x))
+    torch.cuda.synchronize()
+    codes, expo = MX.mxfp4_quantize(xt)
+    assert np.array_equal(_np(qm.exponent), expo) and np.array_equal(_np(qm.codes), codes)
+
+
+def test_quantize_transposed_strided_input_and_pv_product():
+    # V stored [S, D] inside a wider buffer; P V with V quantized along the sequence by the
+    # transposing quantizer equals the product with an explicitly transposed V
+    S, D = 256, 64
+    buf = synth.gaussian(S, D + 16, 1.0, seed=77).cuda()
+    v = buf[:, 8:8 + D]
+    qv = dfp4.quantize_t(v)
+    torch.cuda.synchronize()
+    vt = synth.to_f64(v.cpu()).T.copy()
+    _assert_quant_equal(qv, O.dfp4_quantize(vt), "strided transposed")
+    p = synth.softmax_rows(96, S, seed=78)
+    out = dfp4.gemm(dfp4.quantize(_dev(p)), qv)
+    torch.cuda.synchronize()
+    ref, absdot = _gemm_ref(synth.to_f64(p), vt)
+    _assert_gemm_close(out, ref, absdot, "P V")
