@@ -234,6 +234,20 @@ def dfp4_gemm(a_q, w_q):
     return a @ w.T
 
 
+def round_to_bf16(x):
+    """Round float64 values to float32 and then to bf16, both to nearest even (the
+    precision chain of a bf16 result computed from an exact sum); returns float64."""
+    u = np.asarray(x, dtype=np.float64).astype(np.float32).view(np.uint32).astype(np.uint64)
+    u = (u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000
+    return u.astype(np.uint32).view(np.float32).astype(np.float64)
+
+
+def dfp4_gemm_requant(a_q, w_q):
+    """Section 3.3: the result of a multiplication that feeds another one is quantized
+    again.  out = quantize(bf16(A W^T)), blocks of 32 along N."""
+    return dfp4_quantize(round_to_bf16(dfp4_gemm(a_q, w_q)))
+
+
 def effective_bits(block, exponent_bits=5, dialect_bits=4):
     """Appendix I: element bits plus per-block overhead spread over the block."""
     return 4.0 + (exponent_bits + dialect_bits) / block

@@ -478,3 +478,30 @@ def test_mse_selection_on_grid_block_is_lossless():
 def test_mse_selection_all_zero_block():
     codes, dialect, expo = O.dfp4_quantize_mse(np.zeros((1, 32)))
     assert int(dialect[0, 0]) == 0 and int(expo[0, 0]) == 0 and not codes.any()
+
+
+# --------------------------------------------------------------------------
+# requantized product
+# --------------------------------------------------------------------------
+def test_round_to_bf16_matches_library_rounding():
+    import torch
+    rng = np.random.default_rng(31)
+    x = np.concatenate([rng.standard_normal(5000) * np.exp2(rng.integers(-60, 60, 5000)),
+                        np.array([0.0, -0.0, 1.0, 1.00390625, 1.01171875, -3.0e38, 2.0 ** -130])])
+    want = torch.from_numpy(x.astype(np.float32)).to(torch.bfloat16).to(torch.float64).numpy()
+    got = O.round_to_bf16(x)
+    assert np.array_equal(got, want) and np.array_equal(np.signbit(got), np.signbit(want))
+
+
+def test_gemm_requant_is_quantized_rounded_product():
+    rng = np.random.default_rng(32)
+    a = _random_blocks(rng, 3 * 2, "outlier").reshape(3, 64)
+    w = _bf16(rng.standard_normal((32, 64)) * 0.02)
+    aq, wq = O.dfp4_quantize(a), O.dfp4_quantize(w)
+    codes, dialect, expo = O.dfp4_gemm_requant(aq, wq)
+    prod = O.dfp4_dequantize(*aq) @ O.dfp4_dequantize(*wq).T
+    deq = O.dfp4_dequantize(codes, dialect, expo)
+    # one block of 32 per row; error bounded by the largest half-gap of any dialect (1.5 units)
+    amax = np.abs(prod).max(axis=1, keepdims=True)
+    assert (np.abs(deq - prod) <= amax * (1.5 / 4.0) + 1e-30).all()
+    assert codes.shape == (3, 16) and dialect.shape == (3, 1)
