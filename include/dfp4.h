@@ -153,6 +153,24 @@ int dfp4_gemm_batched(dfp4_tensor A, dfp4_tensor W, void* out, int out_dtype, in
 size_t dfp4_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
 
 /*
+ * Matrix multiply with requantizing epilogue (Section 3.3: the result of a
+ * multiplication is quantized again when it feeds the next one):
+ *   out = quantize(bf16(A * W^T))   in blocks of 32 along N,
+ * bit-identical to dfp4_gemm with DFP4_BF16 output followed by dfp4_quantize
+ * (mxfp4_gemm / mxfp4_quantize for the MXFP4 variant), without the bf16 [M, N]
+ * round trip through memory for tiles the single-accumulator kernel computes.
+ *   out      quantized [M, N]: out.rows = A.rows, out.K = W.rows (a multiple of 32)
+ *   workspace   at least dfp4_gemm_requant_workspace_bytes(M, N, K) bytes, 256-byte
+ *            aligned (it includes a bf16 [M, N] temporary used by the paths that
+ *            are not fused: few rows, split K, declined tiles)
+ */
+int dfp4_gemm_requant(dfp4_tensor A, dfp4_tensor W, dfp4_tensor out, void* workspace,
+                      size_t workspace_bytes, void* stream);
+int mxfp4_gemm_requant(dfp4_tensor A, dfp4_tensor W, dfp4_tensor out, void* workspace,
+                       size_t workspace_bytes, void* stream);
+size_t dfp4_gemm_requant_workspace_bytes(int64_t M, int64_t N, int64_t K);
+
+/*
  * MXFP4 comparison path (Section 4.1, baseline): FP4 E2M1 elements
  * {0, 0.5, 1, 1.5, 2, 3, 4, 6} with the same shared exponent; elements are
  * rounded to nearest, ties to the even code, magnitudes above 6 saturate.

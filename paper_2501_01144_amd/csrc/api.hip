@@ -145,6 +145,40 @@ size_t dfp4_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K) {
     return gemm_workspace_bytes(M, N, K);
 }
 
+static int gemm_requant_common(bool mx, dfp4_tensor A, dfp4_tensor W, dfp4_tensor out, void* workspace,
+                               size_t workspace_bytes, void* stream) {
+    if (A.rows < 0 || W.rows < 0 || A.K < 0 || A.K != W.K || A.K % kBlock != 0 || W.rows % kBlock != 0 ||
+        out.rows != A.rows || out.K != W.rows)
+        return DFP4_ERR_SHAPE;
+    if (A.rows == 0 || W.rows == 0) return DFP4_OK;
+    if (!out.codes || !out.exponent || (!mx && !out.dialect)) return DFP4_ERR_NULL;
+    if (!aligned(out.codes, 4)) return DFP4_ERR_ALIGN;
+    const size_t need = gemm_requant_workspace_bytes(A.rows, W.rows, A.K);
+    if (!workspace || workspace_bytes < need) return DFP4_ERR_WORKSPACE;
+    // the bf16 [M, N] temporary sits behind the plain GEMM's workspace
+    const size_t gemm_ws = need - (size_t)(((A.rows * W.rows * 2) + 255) & ~(int64_t)255);
+    void* temp = static_cast<uint8_t*>(workspace) + gemm_ws;
+    const int rc = check_gemm_args(A, W, temp, DFP4_BF16, W.rows, !mx, workspace, gemm_ws);
+    if (rc != DFP4_OK) return rc;
+    return launch_gemm(mx, A, W, temp, DFP4_BF16, W.rows, 1, 0, 0, A.rows * W.rows, workspace, gemm_ws,
+                       static_cast<hipStream_t>(stream), &out);
+}
+
+int dfp4_gemm_requant(dfp4_tensor A, dfp4_tensor W, dfp4_tensor out, void* workspace, size_t workspace_bytes,
+                      void* stream) {
+    return gemm_requant_common(false, A, W, out, workspace, workspace_bytes, stream);
+}
+
+int mxfp4_gemm_requant(dfp4_tensor A, dfp4_tensor W, dfp4_tensor out, void* workspace, size_t workspace_bytes,
+                       void* stream) {
+    return gemm_requant_common(true, A, W, out, workspace, workspace_bytes, stream);
+}
+
+size_t dfp4_gemm_requant_workspace_bytes(int64_t M, int64_t N, int64_t K) {
+    if (M < 0 || N < 0 || K < 0) return 0;
+    return gemm_requant_workspace_bytes(M, N, K);
+}
+
 int dfp4_formatbook(uint8_t* out) {
     if (!out) return DFP4_ERR_NULL;
     for (int d = 0; d < kDialects; ++d)

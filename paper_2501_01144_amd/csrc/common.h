@@ -29,7 +29,8 @@ int launch_quantize_mse(const void* x, int64_t rows, int64_t K, int64_t ld, dfp4
 int launch_dequantize(bool mx, dfp4_tensor in, void* y, int y_dtype, int64_t ld, hipStream_t stream);
 int launch_gemm(bool mx, dfp4_tensor A, dfp4_tensor W, void* out, int out_dtype, int64_t ldc,
                 int64_t batch, int64_t strideA_rows, int64_t strideW_rows, int64_t strideC,
-                void* workspace, size_t workspace_bytes, hipStream_t stream);
+                void* workspace, size_t workspace_bytes, hipStream_t stream, const dfp4_tensor* rq = nullptr);
 size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
+size_t gemm_requant_workspace_bytes(int64_t M, int64_t N, int64_t K);
 
 }  // namespace dfp4

@@ -47,6 +47,7 @@
 #include <type_traits>
 #include "common.h"
 #include "formatbook.h"
+#include "quant_pass.h"
 #include "gemm_step_asm.inc"
 
 namespace dfp4 {
@@ -77,6 +78,7 @@ constexpr int kMaxKB = 512;           // fast path: K <= 16384
 constexpr int kMaxClass = 2;          // classes 0..2, i.e. exponent offsets 0..11
 constexpr int kIntBound = 4660;       // n0 + 16 n1 + 256 n2 <= 2^31 / (32 * 120 * 120)
 constexpr int kBBufBytes = 8 * 1024;  // int8 W operands of one step: 4 column tiles x 2 x 1 KiB
+constexpr int kRqPitch = 136;         // bf16 per staged output row (128 + 8: rows stay 16-byte aligned)
 constexpr int kVisitPad = 12;         // padding visits after the last one (the loop looks 5 steps ahead)
 constexpr int kVisitCap = (kMaxClass + 1) * (kMaxKB + 1) + kVisitPad + 4;
 
@@ -90,6 +92,9 @@ struct GemmParams {
     int64_t ws_stride, off_refa, off_refw, off_spreadw, off_wmeta, off_mask, off_flag, off_list, off_part, off_a8;
     int tiles_m, tiles_n;             // 512 x 128 output tiles
     int ksplit;                       // workgroups sharing one output tile (each takes a range of K)
+    // requantizing epilogue: the quantized [M, N] output (blocks of 32 along N)
+    uint32_t* q_codes;
+    uint8_t *q_dial, *q_exp;
 };
 
 struct Layout {
@@ -346,10 +351,14 @@ __global__ __launch_bounds__(1024) void gemm_prep_kernel(GemmParams p, int n_a, 
 // Wave w owns rows 128w .. 128w+127 and all 128 columns (16 accumulator tiles of
 // 32 x 32: tile i = 4 * gi + n is rows 32 gi .., columns 32 n ..).
 // ---------------------------------------------------------------------------
-template <bool MX, bool BF16>
+template <bool MX, bool BF16, bool RQ>
 __global__ __launch_bounds__(256, 1) void gemm_fast_kernel(GemmParams p) {
     // int8 W operands of a pair of blocks: [column tile n][t][lane][16 bytes]; three buffers in rotation
     __shared__ __attribute__((aligned(16))) uint8_t s_b[3][kBBufBytes];
+    // requantizing epilogue only: quantizer tables and, per wave, 64 rows x 128 columns of bf16 results
+    __shared__ __attribute__((aligned(16))) uint8_t s_rq_q[RQ ? (MX ? 64 : kDialects * 1024) : 16];
+    __shared__ __attribute__((aligned(16))) uint8_t s_rq_s[RQ ? (MX ? 16 : kPairs * 1024) : 16];
+    __shared__ __attribute__((aligned(16))) uint16_t s_rq[RQ ? 4 * 64 * kRqPitch : 8];
     __shared__ __attribute__((aligned(16))) uint32_t s_tab[kDialects * 4 * 4];
     __shared__ uint16_t s_vl[kVisitCap];     // visits: class << 10 | block, classes from high to low
     __shared__ __attribute__((aligned(4))) uint8_t s_refa[kTileM];
@@ -471,6 +480,17 @@ __global__ __launch_bounds__(256, 1) void gemm_fast_kernel(GemmParams p) {
     }
 
     // ---- epilogue (nothing to store or publish for a wave whose 128 rows lie beyond M)
+    if constexpr (RQ) {
+        if constexpr (MX) {
+            if (tid < 64) s_rq_q[tid] = g_quant_tables.mx[tid];
+        } else {
+            const uint4* gq = reinterpret_cast<const uint4*>(g_quant_tables.q);
+            const uint4* gs = reinterpret_cast<const uint4*>(g_quant_tables.s);
+            for (int i = tid; i < 1024; i += 256) reinterpret_cast<uint4*>(s_rq_q)[i] = gq[i];
+            for (int i = tid; i < 512; i += 256) reinterpret_cast<uint4*>(s_rq_s)[i] = gs[i];
+        }
+        __syncthreads();
+    }
     if (m0 + (int)wave_u * 128 >= p.M) return;
 #define DFP4_READ_TILE(G, V)                                                                        \
     asm volatile(DFP4_ACC_READ_ASM_##G                                                              \
@@ -493,6 +513,55 @@ __global__ __launch_bounds__(256, 1) void gemm_fast_kernel(GemmParams p) {
         }
         DFP4_FOR_TILES(DFP4_PUBLISH)
 #undef DFP4_PUBLISH
+        return;
+    }
+    if constexpr (RQ) {
+        // Requantizing epilogue (Section 3.3: results are quantized again for the next
+        // multiplication).  Each value is converted and rounded to bf16 exactly as the bf16
+        // output would be; the wave stages 64 rows x 128 columns in LDS and re-reads them in
+        // the quantizer's layout (4 lanes per block of 32 consecutive columns), then stores
+        // codes, dialect ids and exponent bytes of the [M, N] result blocked along N.
+        const int row0 = m0 + (int)wave_u * 128;
+        uint16_t* st = &s_rq[wave * 64 * kRqPitch];
+        const int nb_row = p.N / kBlock;
+        int ew[4];
+#pragma unroll
+        for (int n = 0; n < 4; ++n) ew[n] = (int)s_refw[n * 32 + r] - 256;
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+#define DFP4_STAGE(G)                                                                               \
+            if ((G >> 3) == half) {                                                                 \
+                int v[16];                                                                          \
+                DFP4_READ_TILE(G, v);                                                               \
+                const int gi = G >> 2, n = G & 3;                                                   \
+                _Pragma("unroll") for (int q = 0; q < 4; ++q) {                                     \
+                    const uint32_t e4 = *reinterpret_cast<const uint32_t*>(                         \
+                        &s_refa[wave * 128 + gi * 32 + 8 * q + 4 * h]);                             \
+                    _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                 \
+                        const float f = ldexpf((float)v[4 * q + j], (int)((e4 >> (8 * j)) & 0xffu) + ew[n]); \
+                        st[((gi & 1) * 32 + 8 * q + 4 * h + j) * kRqPitch + n * 32 + r] = f32_to_bf16_rne(f); \
+                    }                                                                               \
+                }                                                                                   \
+            }
+            DFP4_FOR_TILES(DFP4_STAGE)
+#undef DFP4_STAGE
+            for (int pass = 0; pass < 16; ++pass) {
+                const int b = pass * 16 + (lane >> 2), row = b >> 2, cb = b & 3, sub = lane & 3;
+                const uint4 wv = *reinterpret_cast<const uint4*>(&st[row * kRqPitch + cb * 32 + sub * 8]);
+                uint32_t code, eb, dl = 0;
+                if constexpr (MX) mxfp4_pass(wv, s_rq_q, code, eb);
+                else dfp4_pass(wv, s_rq_s, s_rq_q, code, eb, dl);
+                const int m = row0 + half * 64 + row, nb = (n0 >> 5) + cb;
+                if (m < p.M && nb < nb_row) {
+                    const size_t blk = (size_t)(bz * p.M + m) * nb_row + nb;
+                    p.q_codes[blk * 4 + sub] = code;
+                    if (sub == 0) {
+                        p.q_exp[blk] = (uint8_t)eb;
+                        if constexpr (!MX) p.q_dial[blk] = (uint8_t)dl;
+                    }
+                }
+            }
+        }
         return;
     }
     {
@@ -808,15 +877,64 @@ __global__ __launch_bounds__(kSmallWaves * 64) void gemm_small_kernel(GemmParams
 template <bool MX, bool BF16>
 __global__ __launch_bounds__(256) void gemm_block_kernel(GemmParams p, int mode) {
     __shared__ uint8_t s_exp[2][256];
+    // requantizing GEMM only (mode 2 with a quantized output): quantizer tables
+    __shared__ __attribute__((aligned(16))) uint8_t lds_q[BF16 ? (MX ? 64 : kDialects * 1024) : 16];
+    __shared__ __attribute__((aligned(16))) uint8_t lds_s[BF16 ? (MX ? 16 : kPairs * 1024) : 16];
     const int64_t bz = blockIdx.z;
     const uint8_t* ws = p.ws + bz * p.ws_stride;
     if (mode == 2) {
         const uint32_t* list = reinterpret_cast<const uint32_t*>(ws + p.off_list);
         const uint32_t n = list[0];
+        if (n == 0) return;
+        const int tid = threadIdx.x;
+        const bool rq = BF16 && p.q_codes != nullptr;
+        if constexpr (BF16) {
+            if (rq) {
+                if constexpr (MX) {
+                    if (tid < 64) lds_q[tid] = g_quant_tables.mx[tid];
+                } else {
+                    const uint4* gq = reinterpret_cast<const uint4*>(g_quant_tables.q);
+                    const uint4* gs = reinterpret_cast<const uint4*>(g_quant_tables.s);
+                    for (int i = tid; i < 1024; i += 256) reinterpret_cast<uint4*>(lds_q)[i] = gq[i];
+                    for (int i = tid; i < 512; i += 256) reinterpret_cast<uint4*>(lds_s)[i] = gs[i];
+                }
+            }
+        }
+        __syncthreads();
         for (uint32_t i = blockIdx.x; i < n * 4u; i += gridDim.x) {
             const int tile = (int)list[1 + (i >> 2)], by = (tile / p.tiles_n) * 4 + (int)(i & 3u);
-            if (by * 128 < p.M) block_flush_tile<MX, BF16>(p, bz, by, tile % p.tiles_n, s_exp);
+            const int bx = tile % p.tiles_n;
+            if (by * 128 < p.M) block_flush_tile<MX, BF16>(p, bz, by, bx, s_exp);
             __syncthreads();
+            if constexpr (BF16) {
+                if (rq && by * 128 < p.M) {
+                    // requantizing GEMM: quantize the 128 x 128 bf16 results this workgroup has
+                    // just written to the temporary (16 rows x 4 blocks per sweep, 4 lanes per block)
+                    __threadfence_block();
+                    const int nb_row = p.N / kBlock;
+                    const uint16_t* src = static_cast<const uint16_t*>(p.out) + bz * p.strideC;
+                    for (int sweep = 0; sweep < 8; ++sweep) {
+                        const int q = tid >> 2, sub = tid & 3;
+                        const int m = by * 128 + sweep * 16 + (q >> 2), nb = bx * 4 + (q & 3);
+                        const bool valid = m < p.M && nb < nb_row;      // the same for the 4 lanes of a block
+                        uint4 wv = make_uint4(0, 0, 0, 0);
+                        if (valid)
+                            wv = *reinterpret_cast<const uint4*>(src + (int64_t)m * p.ldc + nb * kBlock + sub * 8);
+                        uint32_t code, eb, dl = 0;
+                        if constexpr (MX) mxfp4_pass(wv, lds_q, code, eb);
+                        else dfp4_pass(wv, lds_s, lds_q, code, eb, dl);
+                        if (valid) {
+                            const size_t blk = (size_t)(bz * p.M + m) * nb_row + nb;
+                            p.q_codes[blk * 4 + sub] = code;
+                            if (sub == 0) {
+                                p.q_exp[blk] = (uint8_t)eb;
+                                if constexpr (!MX) p.q_dial[blk] = (uint8_t)dl;
+                            }
+                        }
+                    }
+                    __syncthreads();
+                }
+            }
         }
         return;
     }
@@ -834,9 +952,16 @@ size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K) {
     return (size_t)make_layout(M, N, K / kBlock).total;
 }
 
+size_t gemm_requant_workspace_bytes(int64_t M, int64_t N, int64_t K) {
+    if (M == 0 || N == 0) return 0;
+    return (size_t)align256(make_layout(M, N, K / kBlock).total) + (size_t)align256(M * N * 2);
+}
+
+// `rq` (optional): quantize the result along N into *rq.  `out` must then be a bf16 [M, N]
+// temporary (ldc = N, batch 1): it receives the results of every path that is not fused.
 int launch_gemm(bool mx, dfp4_tensor A, dfp4_tensor W, void* out, int out_dtype, int64_t ldc,
                 int64_t batch, int64_t strideA_rows, int64_t strideW_rows, int64_t strideC,
-                void* workspace, size_t workspace_bytes, hipStream_t stream) {
+                void* workspace, size_t workspace_bytes, hipStream_t stream, const dfp4_tensor* rq) {
     const int64_t M = A.rows, N = W.rows, KB = A.K / kBlock;
     if (M == 0 || N == 0 || batch == 0) return DFP4_OK;
     if (M >= (1 << 30) || N >= (1 << 30) || KB >= (1 << 26) || batch > 65535 || ldc >= (1 << 27))
@@ -857,6 +982,9 @@ int launch_gemm(bool mx, dfp4_tensor A, dfp4_tensor W, void* out, int out_dtype,
     if (p.tiles_m > 16383 || p.tiles_n > (1 << 20)) return DFP4_ERR_SHAPE;
 
     const bool bf16 = out_dtype == DFP4_BF16;
+    if (rq) {
+        p.q_codes = reinterpret_cast<uint32_t*>(rq->codes); p.q_dial = rq->dialect; p.q_exp = rq->exponent;
+    }
     if (M <= kSmallMaxM && KB > 0 && KB <= kSmallMaxKB) {
         dim3 gs((unsigned)((N + 31) / 32), (unsigned)((M + 31) / 32), (unsigned)batch);
         if (mx) {
@@ -866,7 +994,9 @@ int launch_gemm(bool mx, dfp4_tensor A, dfp4_tensor W, void* out, int out_dtype,
             if (bf16) hipLaunchKernelGGL((gemm_small_kernel<false, true>), gs, dim3(kSmallWaves * 64), 0, stream, p);
             else hipLaunchKernelGGL((gemm_small_kernel<false, false>), gs, dim3(kSmallWaves * 64), 0, stream, p);
         }
-        return check_launch();
+        const int rc = check_launch();
+        if (rc != DFP4_OK || !rq) return rc;
+        return launch_quantize(mx, out, M, N, ldc, *rq, stream);
     }
     const bool fast = KB > 0 && KB <= kMaxKB;
     if (fast) {
@@ -889,10 +1019,21 @@ int launch_gemm(bool mx, dfp4_tensor A, dfp4_tensor W, void* out, int out_dtype,
     dim3 gb((unsigned)((N + 127) / 128), (unsigned)((M + 127) / 128), (unsigned)batch);
     if (gb.y > 65535) return DFP4_ERR_SHAPE;
     dim3 gl((unsigned)device_cu_count(), 1, (unsigned)batch);     // walks the list of declined tiles
+    const bool fuse = rq && fast && p.ksplit == 1;       // the fast kernel quantizes its own tiles
+    if (fuse) {
+        if (mx) {
+            hipLaunchKernelGGL((gemm_fast_kernel<true, true, true>), gf, dim3(256), 0, stream, p);
+            hipLaunchKernelGGL((gemm_block_kernel<true, true>), gl, dim3(256), 0, stream, p, 2);
+        } else {
+            hipLaunchKernelGGL((gemm_fast_kernel<false, true, true>), gf, dim3(256), 0, stream, p);
+            hipLaunchKernelGGL((gemm_block_kernel<false, true>), gl, dim3(256), 0, stream, p, 2);
+        }
+        return check_launch();
+    }
 #define DFP4_LAUNCH(MXV, BV)                                                                     \
     do {                                                                                         \
         if (fast) {                                                                              \
-            hipLaunchKernelGGL((gemm_fast_kernel<MXV, BV>), gf, dim3(256), 0, stream, p);        \
+            hipLaunchKernelGGL((gemm_fast_kernel<MXV, BV, false>), gf, dim3(256), 0, stream, p); \
             if (p.ksplit > 1)                                                                    \
                 hipLaunchKernelGGL((gemm_block_kernel<MXV, BV>), gb, dim3(256), 0, stream, p, 1); \
             else                                                                                 \
@@ -907,7 +1048,9 @@ int launch_gemm(bool mx, dfp4_tensor A, dfp4_tensor W, void* out, int out_dtype,
         if (bf16) DFP4_LAUNCH(false, true); else DFP4_LAUNCH(false, false);
     }
 #undef DFP4_LAUNCH
-    return check_launch();
+    const int rc = check_launch();
+    if (rc != DFP4_OK || !rq) return rc;
+    return launch_quantize(mx, out, M, N, ldc, *rq, stream);
 }
 
 }  // namespace dfp4

@@ -26,6 +26,7 @@ class _CTensor(ctypes.Structure):
 
 SYMBOLS = [
     "dfp4_quantize", "dfp4_quantize_mse", "dfp4_quantize_t", "mxfp4_quantize_t", "dfp4_dequantize", "dfp4_gemm", "dfp4_gemm_batched", "dfp4_gemm_workspace_bytes",
+    "dfp4_gemm_requant", "mxfp4_gemm_requant", "dfp4_gemm_requant_workspace_bytes",
     "mxfp4_quantize", "mxfp4_dequantize", "mxfp4_gemm", "dfp4_formatbook", "dfp4_strerror",
 ]
 
@@ -56,6 +57,12 @@ def load():
                                       ctypes.c_size_t, vp]
     lib.dfp4_gemm_workspace_bytes.argtypes = [i64, i64, i64]
     lib.dfp4_gemm_workspace_bytes.restype = ctypes.c_size_t
+    lib.dfp4_gemm_requant.argtypes = [_CTensor, _CTensor, _CTensor, vp, ctypes.c_size_t, vp]
+    lib.mxfp4_gemm_requant.argtypes = [_CTensor, _CTensor, _CTensor, vp, ctypes.c_size_t, vp]
+    lib.dfp4_gemm_requant.restype = ci
+    lib.mxfp4_gemm_requant.restype = ci
+    lib.dfp4_gemm_requant_workspace_bytes.argtypes = [i64, i64, i64]
+    lib.dfp4_gemm_requant_workspace_bytes.restype = ctypes.c_size_t
     lib.dfp4_formatbook.argtypes = [vp]
     lib.dfp4_strerror.argtypes = [ci]
     lib.dfp4_strerror.restype = ctypes.c_char_p
@@ -193,6 +200,26 @@ def gemm(a, w, dtype=torch.float32, out=None, workspace=None):
 
 def mxfp4_gemm(a, w, dtype=torch.float32, out=None, workspace=None):
     return _gemm(load().mxfp4_gemm, "mxfp4_gemm", a, w, dtype, out, workspace)
+
+
+def _gemm_requant(fn, what, a, w, out, workspace, mx):
+    if out is None:
+        out = empty_qtensor(a.rows, w.rows, a.codes.device, mx)
+    need = int(load().dfp4_gemm_requant_workspace_bytes(a.rows, w.rows, a.K))
+    if workspace is None and need > 0:
+        workspace = torch.empty(need, dtype=torch.uint8, device=a.codes.device)
+    _check(fn(a.c(), w.c(), out.c(), _ptr(workspace), workspace.numel() if workspace is not None else 0, _stream()),
+           what)
+    return out
+
+
+def gemm_requant(a, w, out=None, workspace=None):
+    """dfp4_gemm_requant: quantize(bf16(A W^T)) in blocks of 32 along N -> QTensor [M, N]."""
+    return _gemm_requant(load().dfp4_gemm_requant, "dfp4_gemm_requant", a, w, out, workspace, False)
+
+
+def mxfp4_gemm_requant(a, w, out=None, workspace=None):
+    return _gemm_requant(load().mxfp4_gemm_requant, "mxfp4_gemm_requant", a, w, out, workspace, True)
 
 
 def gemm_batched(a, w, batch, M, N, dtype=torch.float32, out=None, workspace=None):

@@ -448,3 +448,70 @@ def test_quantize_transposed_strided_input_and_pv_product():
     torch.cuda.synchronize()
     ref, absdot = _gemm_ref(synth.to_f64(p), vt)
     _assert_gemm_close(out, ref, absdot, "P V")
+
+
+# --------------------------------------------------------------------------
+# GEMM with requantizing epilogue
+# --------------------------------------------------------------------------
+def _requant_ref(a_bf16, w_bf16, mx=False):
+    a64, w64 = synth.to_f64(a_bf16), synth.to_f64(w_bf16)
+    if mx:
+        prod = MX.mxfp4_dequantize(*MX.mxfp4_quantize(a64)) @ MX.mxfp4_dequantize(*MX.mxfp4_quantize(w64)).T
+        return MX.mxfp4_quantize(O.round_to_bf16(prod))
+    return O.dfp4_gemm_requant(O.dfp4_quantize(a64), O.dfp4_quantize(w64))
+
+
+@pytest.mark.parametrize("M,N,K", [(600, 352, 512), (512, 128, 64), (130, 96, 1024)])
+def test_gemm_requant_fused_tiles_bit_exact(M, N, K):
+    # enough tiles that K is not split and moderate exponent spreads: every tile takes the
+    # single-accumulator kernel, whose sums are exact, so the quantized result must equal the
+    # oracle's bit for bit
+    print(f"gemm_requant parity: {M}x{N}x{K}", flush=True)
+    a = synth.gaussian_outlier_channels(M, K, max(1, K // 128), 50.0, 1.0, seed=300 + M)
+    w = synth.gaussian(N, K, 0.02, seed=400 + N)
+    qa, qw = dfp4.quantize(_dev(a)), dfp4.quantize(_dev(w))
+    q = dfp4.gemm_requant(qa, qw)
+    torch.cuda.synchronize()
+    _assert_quant_equal(q, _requant_ref(a, w), "requant")
+    qm = dfp4.mxfp4_gemm_requant(dfp4.mxfp4_quantize(_dev(a)), dfp4.mxfp4_quantize(_dev(w)))
+    torch.cuda.synchronize()
+    codes, expo = _requant_ref(a, w, mx=True)
+    assert np.array_equal(_np(qm.exponent), expo) and np.array_equal(_np(qm.codes), codes)
+
+
+def test_gemm_requant_full_size_sampled_rows():
+    ops = synth.llama3_8b_mlp(seed=2)
+    x, w = ops["x"], ops["w_gate"]
+    print("gemm_requant parity: 2048x14336x4096 sampled rows", flush=True)
+    q = dfp4.gemm_requant(dfp4.quantize(_dev(x)), dfp4.quantize(_dev(w)))
+    torch.cuda.synchronize()
+    rows = np.sort(np.random.default_rng(6).choice(x.shape[0], 6, replace=False))
+    codes, dialect, expo = _requant_ref(x[rows], w)
+    assert np.array_equal(_np(q.exponent)[rows], expo)
+    assert np.array_equal(_np(q.dialect)[rows], dialect)
+    assert np.array_equal(_np(q.codes)[rows], codes)
+
+
+@pytest.mark.parametrize("M,N,K,why", [(16, 256, 512, "few rows"), (100, 256, 4096, "split K"),
+                                       (96, 160, 256, "declined tiles")])
+def test_gemm_requant_unfused_paths_equal_gemm_then_quantize(M, N, K, why):
+    # paths that accumulate in fp32 (or go through the bf16 temporary): the result must be
+    # what dfp4_gemm (bf16) followed by dfp4_quantize gives, and those two are tested above
+    print(f"gemm_requant consistency: {why} {M}x{N}x{K}", flush=True)
+    g = torch.Generator().manual_seed(M)
+    a = torch.randn(M, K, generator=g)
+    if why == "declined tiles":
+        a = a * torch.exp2(torch.randint(-30, 30, (M, K // 32), generator=g).repeat_interleave(32, dim=1).float())
+    a = a.to(torch.bfloat16)
+    w = (torch.randn(N, K, generator=g) * 0.02).to(torch.bfloat16)
+    qa, qw = dfp4.quantize(_dev(a)), dfp4.quantize(_dev(w))
+    q = dfp4.gemm_requant(qa, qw)
+    want = dfp4.quantize(dfp4.gemm(qa, qw, dtype=torch.bfloat16))
+    torch.cuda.synchronize()
+    assert torch.equal(q.codes, want.codes) and torch.equal(q.dialect, want.dialect)
+    assert torch.equal(q.exponent, want.exponent)
+    # and close to the oracle's product: dequantized error within the coarsest dialect step
+    ref, _ = _gemm_ref(synth.to_f64(a), synth.to_f64(w))
+    deq = dfp4.dequantize(q).cpu().double().numpy()
+    blockmax = np.abs(ref).reshape(M, N // 32, 32).max(axis=2).repeat(32, axis=1)
+    assert (np.abs(deq - ref) <= blockmax * 0.4 + 1e-30).all()
