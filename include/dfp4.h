@@ -153,6 +153,24 @@ int dfp4_gemm_batched(dfp4_tensor A, dfp4_tensor W, void* out, int out_dtype, in
 size_t dfp4_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
 
 /*
+ * Matrix multiply on the block-scaled matrix instruction of the GPU
+ * (v_mfma_scale_f32_32x32x64_f8f6f4): out = A * W^T as dfp4_gemm / mxfp4_gemm, but
+ * with the power-of-two block scales applied and the sum accumulated in fp32 by
+ * the hardware.  dfp4_gemm_native repacks the DialectFP4 operands to FP6 E2M3,
+ * in which every DialectFP4 value is exact; mxfp4_gemm_native uses the MXFP4
+ * codes as they are (FP4 E2M1).  The exponent bytes are the scales (E8M0).
+ * Results agree with dfp4_gemm / mxfp4_gemm within the rounding of fp32
+ * accumulation (the tolerance of the parity tests), not bit for bit.
+ *   workspace   at least dfp4_gemm_native_workspace_bytes(M, N, K) bytes, 256-byte
+ *            aligned: both operands in the instruction's register order
+ */
+int dfp4_gemm_native(dfp4_tensor A, dfp4_tensor W, void* out, int out_dtype, int64_t ldc,
+                     void* workspace, size_t workspace_bytes, void* stream);
+int mxfp4_gemm_native(dfp4_tensor A, dfp4_tensor W, void* out, int out_dtype, int64_t ldc,
+                      void* workspace, size_t workspace_bytes, void* stream);
+size_t dfp4_gemm_native_workspace_bytes(int64_t M, int64_t N, int64_t K);
+
+/*
  * Matrix multiply with requantizing epilogue (Section 3.3: the result of a
  * multiplication is quantized again when it feeds the next one):
  *   out = quantize(bf16(A * W^T))   in blocks of 32 along N,

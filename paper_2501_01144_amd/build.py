@@ -13,7 +13,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdfp4.so")
 PEAK = os.path.join(HERE, "mfma_peak")
-SOURCES = ["api.hip", "quantize.hip", "dequantize.hip", "gemm.hip"]
+SOURCES = ["api.hip", "quantize.hip", "dequantize.hip", "gemm.hip", "gemm_native.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     "-fconstexpr-steps=200000000",

@@ -145,6 +145,37 @@ size_t dfp4_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K) {
     return gemm_workspace_bytes(M, N, K);
 }
 
+static int gemm_native_common(bool fp6, dfp4_tensor A, dfp4_tensor W, void* out, int out_dtype, int64_t ldc,
+                              void* workspace, size_t workspace_bytes, void* stream) {
+    if (A.rows < 0 || W.rows < 0 || A.K < 0 || A.K != W.K || A.K % kBlock != 0) return DFP4_ERR_SHAPE;
+    if (out_dtype != DFP4_F32 && out_dtype != DFP4_BF16) return DFP4_ERR_DTYPE;
+    if (A.rows == 0 || W.rows == 0) return DFP4_OK;
+    if (ldc < W.rows || A.K == 0) return DFP4_ERR_SHAPE;
+    if (!out || !A.codes || !A.exponent || !W.codes || !W.exponent) return DFP4_ERR_NULL;
+    if (fp6 && (!A.dialect || !W.dialect)) return DFP4_ERR_NULL;
+    if (!aligned(A.codes, 16) || !aligned(W.codes, 16)) return DFP4_ERR_ALIGN;
+    const size_t need = gemm_native_workspace_bytes(A.rows, W.rows, A.K, fp6);
+    if (!workspace || workspace_bytes < need) return DFP4_ERR_WORKSPACE;
+    if (!aligned(workspace, 256)) return DFP4_ERR_ALIGN;
+    return launch_gemm_native(fp6, A, W, out, out_dtype, ldc, workspace, workspace_bytes,
+                              static_cast<hipStream_t>(stream));
+}
+
+int mxfp4_gemm_native(dfp4_tensor A, dfp4_tensor W, void* out, int out_dtype, int64_t ldc, void* workspace,
+                      size_t workspace_bytes, void* stream) {
+    return gemm_native_common(false, A, W, out, out_dtype, ldc, workspace, workspace_bytes, stream);
+}
+
+int dfp4_gemm_native(dfp4_tensor A, dfp4_tensor W, void* out, int out_dtype, int64_t ldc, void* workspace,
+                     size_t workspace_bytes, void* stream) {
+    return gemm_native_common(true, A, W, out, out_dtype, ldc, workspace, workspace_bytes, stream);
+}
+
+size_t dfp4_gemm_native_workspace_bytes(int64_t M, int64_t N, int64_t K) {
+    if (M < 0 || N < 0 || K < 0) return 0;
+    return gemm_native_workspace_bytes(M, N, K, true);      // covers the FP4 form as well
+}
+
 static int gemm_requant_common(bool mx, dfp4_tensor A, dfp4_tensor W, dfp4_tensor out, void* workspace,
                                size_t workspace_bytes, void* stream) {
     if (A.rows < 0 || W.rows < 0 || A.K < 0 || A.K != W.K || A.K % kBlock != 0 || W.rows % kBlock != 0 ||

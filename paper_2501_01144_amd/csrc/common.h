@@ -32,5 +32,8 @@ int launch_gemm(bool mx, dfp4_tensor A, dfp4_tensor W, void* out, int out_dtype,
                 void* workspace, size_t workspace_bytes, hipStream_t stream, const dfp4_tensor* rq = nullptr);
 size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
 size_t gemm_requant_workspace_bytes(int64_t M, int64_t N, int64_t K);
+int launch_gemm_native(bool fp6, dfp4_tensor A, dfp4_tensor W, void* out, int out_dtype, int64_t ldc,
+                       void* workspace, size_t workspace_bytes, hipStream_t stream);
+size_t gemm_native_workspace_bytes(int64_t M, int64_t N, int64_t K, bool fp6);
 
 }  // namespace dfp4

@@ -26,7 +26,7 @@ class _CTensor(ctypes.Structure):
 
 SYMBOLS = [
     "dfp4_quantize", "dfp4_quantize_mse", "dfp4_quantize_t", "mxfp4_quantize_t", "dfp4_dequantize", "dfp4_gemm", "dfp4_gemm_batched", "dfp4_gemm_workspace_bytes",
-    "dfp4_gemm_requant", "mxfp4_gemm_requant", "dfp4_gemm_requant_workspace_bytes",
+    "mxfp4_gemm_native", "dfp4_gemm_native", "dfp4_gemm_native_workspace_bytes", "dfp4_gemm_requant", "mxfp4_gemm_requant", "dfp4_gemm_requant_workspace_bytes",
     "mxfp4_quantize", "mxfp4_dequantize", "mxfp4_gemm", "dfp4_formatbook", "dfp4_strerror",
 ]
 
@@ -57,6 +57,12 @@ def load():
                                       ctypes.c_size_t, vp]
     lib.dfp4_gemm_workspace_bytes.argtypes = [i64, i64, i64]
     lib.dfp4_gemm_workspace_bytes.restype = ctypes.c_size_t
+    lib.mxfp4_gemm_native.argtypes = [_CTensor, _CTensor, vp, ci, i64, vp, ctypes.c_size_t, vp]
+    lib.mxfp4_gemm_native.restype = ci
+    lib.dfp4_gemm_native.argtypes = [_CTensor, _CTensor, vp, ci, i64, vp, ctypes.c_size_t, vp]
+    lib.dfp4_gemm_native.restype = ci
+    lib.dfp4_gemm_native_workspace_bytes.argtypes = [i64, i64, i64]
+    lib.dfp4_gemm_native_workspace_bytes.restype = ctypes.c_size_t
     lib.dfp4_gemm_requant.argtypes = [_CTensor, _CTensor, _CTensor, vp, ctypes.c_size_t, vp]
     lib.mxfp4_gemm_requant.argtypes = [_CTensor, _CTensor, _CTensor, vp, ctypes.c_size_t, vp]
     lib.dfp4_gemm_requant.restype = ci
@@ -220,6 +226,29 @@ def gemm_requant(a, w, out=None, workspace=None):
 
 def mxfp4_gemm_requant(a, w, out=None, workspace=None):
     return _gemm_requant(load().mxfp4_gemm_requant, "mxfp4_gemm_requant", a, w, out, workspace, True)
+
+
+def _gemm_native(fn, what, a, w, dtype, out, workspace):
+    if out is None:
+        out = torch.empty((a.rows, w.rows), dtype=dtype, device=a.codes.device)
+    assert out.dtype in (torch.float32, torch.bfloat16) and out.stride(1) == 1
+    need = int(load().dfp4_gemm_native_workspace_bytes(a.rows, w.rows, a.K))
+    if workspace is None and need > 0:
+        workspace = torch.empty(need, dtype=torch.uint8, device=out.device)
+    ldc = out.stride(0) if a.rows > 1 else w.rows
+    _check(fn(a.c(), w.c(), _ptr(out), F32 if out.dtype == torch.float32 else BF16, ldc, _ptr(workspace),
+              workspace.numel() if workspace is not None else 0, _stream()), what)
+    return out
+
+
+def gemm_native(a, w, dtype=torch.float32, out=None, workspace=None):
+    """dfp4_gemm_native: DialectFP4 product on the block-scaled matrix instruction (FP6 E2M3 operands)."""
+    return _gemm_native(load().dfp4_gemm_native, "dfp4_gemm_native", a, w, dtype, out, workspace)
+
+
+def mxfp4_gemm_native(a, w, dtype=torch.float32, out=None, workspace=None):
+    """mxfp4_gemm_native: the MXFP4 product on the block-scaled matrix instruction (FP4 operands)."""
+    return _gemm_native(load().mxfp4_gemm_native, "mxfp4_gemm_native", a, w, dtype, out, workspace)
 
 
 def gemm_batched(a, w, batch, M, N, dtype=torch.float32, out=None, workspace=None):

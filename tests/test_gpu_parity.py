@@ -515,3 +515,81 @@ def test_gemm_requant_unfused_paths_equal_gemm_then_quantize(M, N, K, why):
     deq = dfp4.dequantize(q).cpu().double().numpy()
     blockmax = np.abs(ref).reshape(M, N // 32, 32).max(axis=2).repeat(32, axis=1)
     assert (np.abs(deq - ref) <= blockmax * 0.4 + 1e-30).all()
+
+
+# --------------------------------------------------------------------------
+# MXFP4 on the block-scaled matrix instruction
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("M,N,K", [(1, 1, 32), (70, 200, 160), (300, 130, 1056), (512, 512, 4096)])
+def test_mxfp4_gemm_native(M, N, K):
+    print(f"mxfp4_gemm_native parity: {M}x{N}x{K}", flush=True)
+    a = synth.gaussian_outlier_channels(M, K, max(1, K // 100), 50.0, 1.0, seed=500 + M)
+    w = synth.student_t(N, K, 3.0, seed=600 + N)
+    qa, qw = dfp4.mxfp4_quantize(_dev(a)), dfp4.mxfp4_quantize(_dev(w))
+    ref, absdot = _gemm_ref(synth.to_f64(a), synth.to_f64(w), mx=True)
+    out = dfp4.mxfp4_gemm_native(qa, qw)
+    torch.cuda.synchronize()
+    _assert_gemm_close(out, ref, absdot, "native f32")
+    outb = dfp4.mxfp4_gemm_native(qa, qw, dtype=torch.bfloat16)
+    torch.cuda.synchronize()
+    _assert_gemm_close(outb, ref, absdot, "native bf16", bf16=True)
+
+
+def test_mxfp4_gemm_native_wide_exponents_and_full_size_sample():
+    g = torch.Generator().manual_seed(16)
+    scale = torch.exp2(torch.randint(-40, 40, (96, 8), generator=g).repeat_interleave(32, dim=1).float())
+    a = (torch.randn(96, 256, generator=g) * scale).to(torch.bfloat16)
+    w = (torch.randn(160, 256, generator=g) * scale[:1]).to(torch.bfloat16)
+    out = dfp4.mxfp4_gemm_native(dfp4.mxfp4_quantize(_dev(a)), dfp4.mxfp4_quantize(_dev(w)))
+    torch.cuda.synchronize()
+    ref, absdot = _gemm_ref(synth.to_f64(a), synth.to_f64(w), mx=True)
+    _assert_gemm_close(out, ref, absdot, "native wide")
+    ops = synth.llama3_8b_mlp(seed=2)
+    x, wg = ops["x"], ops["w_gate"]
+    out = dfp4.mxfp4_gemm_native(dfp4.mxfp4_quantize(_dev(x)), dfp4.mxfp4_quantize(_dev(wg)))
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(17)
+    rows = np.sort(rng.choice(x.shape[0], 16, replace=False))
+    cols = np.sort(rng.choice(wg.shape[0], 128, replace=False))
+    ref, absdot = _gemm_ref(synth.to_f64(x[rows]), synth.to_f64(wg[cols]), mx=True)
+    _assert_gemm_close(out[rows][:, cols], ref, absdot, "native full size sampled")
+
+
+@pytest.mark.parametrize("M,N,K", [(1, 1, 32), (70, 200, 160), (300, 130, 1056), (512, 512, 4096)])
+def test_dfp4_gemm_native(M, N, K):
+    # DialectFP4 operands repacked to FP6 E2M3 (exact) on the block-scaled matrix instruction
+    print(f"dfp4_gemm_native parity: {M}x{N}x{K}", flush=True)
+    a = synth.gaussian_outlier_channels(M, K, max(1, K // 100), 50.0, 1.0, seed=700 + M)
+    w = synth.student_t(N, K, 3.0, seed=800 + N)
+    qa, qw = dfp4.quantize(_dev(a)), dfp4.quantize(_dev(w))
+    ref, absdot = _gemm_ref(synth.to_f64(a), synth.to_f64(w))
+    out = dfp4.gemm_native(qa, qw)
+    torch.cuda.synchronize()
+    _assert_gemm_close(out, ref, absdot, "native fp6 f32")
+    outb = dfp4.gemm_native(qa, qw, dtype=torch.bfloat16)
+    torch.cuda.synchronize()
+    _assert_gemm_close(outb, ref, absdot, "native fp6 bf16", bf16=True)
+
+
+def test_dfp4_gemm_native_all_dialects_wide_exponents_and_full_size_sample():
+    # every dialect and every index occurs; block exponents spread over tens of binades
+    g = torch.Generator().manual_seed(18)
+    scale = torch.exp2(torch.randint(-40, 40, (128, 16), generator=g).repeat_interleave(32, dim=1).float())
+    a = (torch.randn(128, 512, generator=g) * scale).to(torch.bfloat16)
+    w = (torch.randn(160, 512, generator=g) * scale[:1]).to(torch.bfloat16)
+    qa, qw = dfp4.quantize(_dev(a)), dfp4.quantize_mse(_dev(w))
+    assert len(torch.unique(qa.dialect)) == 16
+    out = dfp4.gemm_native(qa, qw)
+    torch.cuda.synchronize()
+    ad = O.dfp4_dequantize(*O.dfp4_quantize(synth.to_f64(a)))
+    wd = O.dfp4_dequantize(*O.dfp4_quantize_mse(synth.to_f64(w)))
+    _assert_gemm_close(out, ad @ wd.T, np.abs(ad) @ np.abs(wd).T, "native fp6 wide")
+    ops = synth.llama3_8b_mlp(seed=2)
+    x, wg = ops["x"], ops["w_gate"]
+    out = dfp4.gemm_native(dfp4.quantize(_dev(x)), dfp4.quantize(_dev(wg)))
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(19)
+    rows = np.sort(rng.choice(x.shape[0], 16, replace=False))
+    cols = np.sort(rng.choice(wg.shape[0], 128, replace=False))
+    ref, absdot = _gemm_ref(synth.to_f64(x[rows]), synth.to_f64(wg[cols]))
+    _assert_gemm_close(out[rows][:, cols], ref, absdot, "native fp6 full size sampled")
