@@ -27,6 +27,8 @@ def build_library(verbose=True):
     # the hand-scheduled GEMM step is generated text (see csrc/gen_gemm_step.py)
     subprocess.run([sys.executable, os.path.join(CSRC, "gen_gemm_step.py")], check=True,
                    stdout=subprocess.DEVNULL)
+    subprocess.run([sys.executable, os.path.join(CSRC, "gen_native_loop.py")], check=True,
+                   stdout=subprocess.DEVNULL)
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     objdir = os.path.join(HERE, "_build")
     os.makedirs(objdir, exist_ok=True)

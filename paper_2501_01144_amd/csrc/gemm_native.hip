@@ -21,12 +21,14 @@
 // Two kernels.  native_pack_kernel rewrites an operand in the order the matrix instruction
 // wants it (per 32-row tile and step, 64 lanes x 16 or 24 bytes, plus one dword of four
 // scale bytes per lane and group of four tiles), so that the multiply kernel's loads are
-// whole 1 KiB lines.  gemm_native_kernel: 256 x 256 outputs per workgroup, four waves as
-// 2 x 2, each 128 x 128 (16 accumulator tiles = 256 registers, one wave per SIMD); operands
-// go from global memory straight to registers, one step (a pair of blocks) ahead; no LDS,
-// no barrier.  For weights the packing could be done once, offline.
+// whole lines.  gemm_native_kernel: 256 x 256 outputs per workgroup, four waves as 2 x 2,
+// each 128 x 128 (16 accumulator tiles = 256 registers, one wave per SIMD); operands go
+// global -> LDS by direct loads three steps ahead (four stages), LDS -> registers one step
+// ahead, one barrier per step; the main loop is generated assembly (gen_native_loop.py).
+// For weights the packing could be done once, offline.
 #include "common.h"
 #include "formatbook.h"
+#include "gemm_native_asm.inc"
 
 namespace dfp4 {
 namespace {
@@ -42,14 +44,14 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne_n(float f) {
     return (uint16_t)(u >> 16);
 }
 
-// Packed operands (written by native_pack_kernel): rows padded to a multiple of 128,
+// Packed operands (written by native_pack_kernel): rows padded to a multiple of 256,
 // S = ceil(KB / 2) steps, a missing second block is all zeros.
-//   lo  [row tile of 32][step][lane][16 bytes]   registers 0..3 of the lane
-//   hi  [row tile of 32][step][lane][ 8 bytes]   registers 4..5 (FP6 only)
-//   sc  [group of 4 row tiles][step][lane] dword: byte t = scale byte of row tile 4 g + t
+//   bits [row tile of 32][step][64 lanes x 16 bytes]                    FP4: registers 0..3 of the lane
+//        [row tile of 32][step][64 lanes x 16 bytes | 64 lanes x 12 bytes]   FP6: registers 0..3 | 4, 5, pad
+//   sc   [group of 4 row tiles][step][lane] dword: byte t = scale byte of row tile 4 g + t
+// Both arrays end with three steps of slack: the loop loads three steps ahead.
 struct PackedOperand {
-    uint4* lo;
-    uint2* hi;
+    uint8_t* bits;
     uint32_t* sc;
 };
 
@@ -63,7 +65,7 @@ struct NativeParams {
 struct PackParams {
     const uint8_t *codes, *dial, *expo;
     PackedOperand dst;
-    int rows, KB, S, tiles;        // tiles = padded rows / 32
+    int rows, KB, S;
 };
 
 // E2M3 bit pattern of the magnitude 0.5 u, u = 0..15 (all exact: step 1/8 below 1, 1/4 below 4, 1/2 below 8)
@@ -107,113 +109,109 @@ __global__ __launch_bounds__(256) void native_pack_kernel(PackParams p) {
         eb = p.expo[blk];
         if constexpr (FMT == kFmtFp6) dl = p.dial ? ((uint32_t)p.dial[blk] & 15u) : 7u;
     }
-    const int64_t slot = ((int64_t)tile * p.S + s) * 64 + lane;
+    const int64_t chunk = (int64_t)tile * p.S + s;
     if constexpr (FMT == kFmtFp4) {
-        p.dst.lo[slot] = codes;                 // the MXFP4 code is the E2M1 bit pattern
+        reinterpret_cast<uint4*>(p.dst.bits)[chunk * 64 + lane] = codes;     // the MXFP4 code is the E2M1 bit pattern
     } else {
         const uint32_t tlo = g_fp6_book.w[dl][0], thi = g_fp6_book.w[dl][1];
         const uint64_t p0 = pack6(codes.x, tlo, thi), p1 = pack6(codes.y, tlo, thi);
         const uint64_t p2 = pack6(codes.z, tlo, thi), p3 = pack6(codes.w, tlo, thi);
-        uint4 lo;
-        lo.x = (uint32_t)p0;
-        lo.y = (uint32_t)(p0 >> 32) | ((uint32_t)p1 << 16);
-        lo.z = (uint32_t)(p1 >> 16);
-        lo.w = (uint32_t)p2;
-        p.dst.lo[slot] = lo;
-        p.dst.hi[slot] = make_uint2((uint32_t)(p2 >> 32) | ((uint32_t)p3 << 16), (uint32_t)(p3 >> 16));
+        uint32_t* d0 = reinterpret_cast<uint32_t*>(p.dst.bits + chunk * 1792 + lane * 16);
+        d0[0] = (uint32_t)p0;
+        d0[1] = (uint32_t)(p0 >> 32) | ((uint32_t)p1 << 16);
+        d0[2] = (uint32_t)(p1 >> 16);
+        d0[3] = (uint32_t)p2;
+        uint32_t* d1 = reinterpret_cast<uint32_t*>(p.dst.bits + chunk * 1792 + 1024 + lane * 12);
+        d1[0] = (uint32_t)(p2 >> 32) | ((uint32_t)p3 << 16);
+        d1[1] = (uint32_t)(p3 >> 16);
+        d1[2] = 0;
     }
     reinterpret_cast<uint8_t*>(p.dst.sc)[(((int64_t)(tile >> 2) * p.S + s) * 64 + lane) * 4 + (tile & 3)] = (uint8_t)eb;
 }
 
-template <int FMT>
-struct Operand {
-    v8i v[4];        // four 32-row (or 32-column) tiles
-    int s;           // their four scale bytes
-};
-
-template <int FMT>
-__device__ __forceinline__ void load_operand(const PackedOperand& src, int tile0, int S, int s, int lane,
-                                             Operand<FMT>& o) {
-#pragma unroll
-    for (int t = 0; t < 4; ++t) {
-        const int64_t slot = ((int64_t)(tile0 + t) * S + s) * 64 + lane;
-        const uint4 lo = src.lo[slot];
-        o.v[t] = v8i{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, 0, 0, 0, 0};
-        if constexpr (FMT == kFmtFp6) {
-            const uint2 hi = src.hi[slot];
-            o.v[t][4] = (int)hi.x;
-            o.v[t][5] = (int)hi.y;
-        }
-    }
-    o.s = (int)src.sc[((int64_t)(tile0 >> 2) * S + s) * 64 + lane];
-}
-
 template <int FMT, bool BF16>
 __global__ __launch_bounds__(256, 1) void gemm_native_kernel(NativeParams p) {
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    constexpr bool kFp6 = FMT == kFmtFp6;
+    constexpr int kTileLds = kFp6 ? 2048 : 1024, kStage = 16 * kTileLds + 1024, kStages = 4;
+    constexpr int kGStride = kFp6 ? 1792 : 1024;             // global bytes per (tile, step)
+    __shared__ __attribute__((aligned(16))) uint8_t s_stage[kStages * kStage];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane(tid >> 6);
     const int kh = lane >> 5, c = lane & 31;
-    const int wm = wave >> 1, wn = wave & 1;
-    const int m0 = blockIdx.y * 256 + wm * 128, n0 = blockIdx.x * 256 + wn * 128;
-    if (m0 >= p.M || n0 >= p.N) return;        // wave-uniform; the kernel has no barrier
+    const int wm = (int)wave >> 1, wn = (int)wave & 1;
     const int S = p.S;
-    v16f acc[4][4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-            for (int x = 0; x < 16; ++x) acc[i][j][x] = 0.0f;
-
-    Operand<FMT> a, b, an, bn;
-    load_operand<FMT>(p.a, m0 >> 5, S, 0, lane, a);
-    load_operand<FMT>(p.w, n0 >> 5, S, 0, lane, b);
-    for (int s = 0; s < S; ++s) {
-        const int sn = min(s + 1, S - 1);       // the last step reloads itself (unused)
-        load_operand<FMT>(p.a, m0 >> 5, S, sn, lane, an);
-        load_operand<FMT>(p.w, n0 >> 5, S, sn, lane, bn);
-#define DFP4_NATIVE_ROW(I)                                                                                    \
-        acc[I][0] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a.v[I], b.v[0], acc[I][0], FMT, FMT, I, a.s, 0, b.s); \
-        acc[I][1] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a.v[I], b.v[1], acc[I][1], FMT, FMT, I, a.s, 1, b.s); \
-        acc[I][2] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a.v[I], b.v[2], acc[I][2], FMT, FMT, I, a.s, 2, b.s); \
-        acc[I][3] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a.v[I], b.v[3], acc[I][3], FMT, FMT, I, a.s, 3, b.s);
-        DFP4_NATIVE_ROW(0) DFP4_NATIVE_ROW(1) DFP4_NATIVE_ROW(2) DFP4_NATIVE_ROW(3)
-#undef DFP4_NATIVE_ROW
-        a = an;
-        b = bn;
+    {
+        const uint32_t lds = (uint32_t)__builtin_amdgcn_readfirstlane(
+            (int)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)&s_stage[0]);
+        const uint32_t tstride = (uint32_t)S * (uint32_t)kGStride;        // bytes per tile
+        // this wave fetches A tiles 2w, 2w+1 and B tiles 2w, 2w+1 of the workgroup's 8 + 8, and scale chunk w
+        const uint64_t ab = reinterpret_cast<uint64_t>(p.a.bits) + ((uint64_t)blockIdx.y * 8 + 2 * wave) * tstride;
+        const uint64_t bb = reinterpret_cast<uint64_t>(p.w.bits) + ((uint64_t)blockIdx.x * 8 + 2 * wave) * tstride;
+        const uint64_t sb = wave < 2
+            ? reinterpret_cast<uint64_t>(p.a.sc) + ((uint64_t)blockIdx.y * 2 + wave) * (uint64_t)S * 256
+            : reinterpret_cast<uint64_t>(p.w.sc) + ((uint64_t)blockIdx.x * 2 + (wave - 2)) * (uint64_t)S * 256;
+        const uint32_t l16 = (uint32_t)lane * 16u, l4 = (uint32_t)lane * 4u, lg = (uint32_t)lane * 12u + 1024u;
+        if constexpr (kFp6)
+            asm volatile(DFP4_NATIVE_LOOP_FP6
+                         :
+                         : [alo] "s"((uint32_t)ab), [ahi] "s"((uint32_t)(ab >> 32)), [blo] "s"((uint32_t)bb),
+                           [bhi] "s"((uint32_t)(bb >> 32)), [slo] "s"((uint32_t)sb), [shi] "s"((uint32_t)(sb >> 32)),
+                           [tstride] "s"(tstride), [wv] "s"(wave), [lds] "s"(lds),
+                           [ldsend] "s"(lds + (uint32_t)(kStages * kStage)), [steps] "s"((uint32_t)S),
+                           [l16] "v"(l16), [l4] "v"(l4), [lg] "v"(lg)
+                         : DFP4_NATIVE_VGPR_CLOBBERS, DFP4_NATIVE_ACC_CLOBBERS, DFP4_NATIVE_SGPR_CLOBBERS, "m0", "scc",
+                           "memory");
+        else
+            asm volatile(DFP4_NATIVE_LOOP_FP4
+                         :
+                         : [alo] "s"((uint32_t)ab), [ahi] "s"((uint32_t)(ab >> 32)), [blo] "s"((uint32_t)bb),
+                           [bhi] "s"((uint32_t)(bb >> 32)), [slo] "s"((uint32_t)sb), [shi] "s"((uint32_t)(sb >> 32)),
+                           [tstride] "s"(tstride), [wv] "s"(wave), [lds] "s"(lds),
+                           [ldsend] "s"(lds + (uint32_t)(kStages * kStage)), [steps] "s"((uint32_t)S),
+                           [l16] "v"(l16), [l4] "v"(l4), [lg] "v"(lg)
+                         : DFP4_NATIVE_VGPR_CLOBBERS, DFP4_NATIVE_ACC_CLOBBERS, DFP4_NATIVE_SGPR_CLOBBERS, "m0", "scc",
+                           "memory");
     }
 
-    // epilogue: fp32 (or bf16, round to nearest even) [M, N]
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int n = n0 + j * 32 + c;
-#pragma unroll
-            for (int x = 0; x < 16; ++x) {
-                const int m = m0 + i * 32 + 8 * (x >> 2) + 4 * kh + (x & 3);
-                if (m < p.M && n < p.N) {
-                    const int64_t o = (int64_t)m * p.ldc + n;
-                    if constexpr (BF16)
-                        static_cast<uint16_t*>(p.out)[o] = f32_to_bf16_rne_n(acc[i][j][x]);
-                    else
-                        static_cast<float*>(p.out)[o] = acc[i][j][x];
-                }
-            }
-        }
+    // epilogue: fp32 (or bf16, round to nearest even) [M, N]; accumulator tile (i, j) = 4 i + j
+    const int m0 = blockIdx.y * 256 + wm * 128, n0 = blockIdx.x * 256 + wn * 128;
+    if (m0 >= p.M || n0 >= p.N) return;
+#define DFP4_NATIVE_STORE(G)                                                                        \
+    {                                                                                               \
+        int v[16];                                                                                  \
+        asm volatile(DFP4_NATIVE_ACC_READ_##G                                                       \
+                     : "=v"(v[0]), "=v"(v[1]), "=v"(v[2]), "=v"(v[3]), "=v"(v[4]), "=v"(v[5]),      \
+                       "=v"(v[6]), "=v"(v[7]), "=v"(v[8]), "=v"(v[9]), "=v"(v[10]), "=v"(v[11]),    \
+                       "=v"(v[12]), "=v"(v[13]), "=v"(v[14]), "=v"(v[15]));                         \
+        const int n = n0 + (G & 3) * 32 + c;                                                        \
+        _Pragma("unroll") for (int x = 0; x < 16; ++x) {                                            \
+            const int m = m0 + (G >> 2) * 32 + 8 * (x >> 2) + 4 * kh + (x & 3);                     \
+            if (m < p.M && n < p.N) {                                                               \
+                const float f = __builtin_bit_cast(float, v[x]);                                    \
+                const int64_t o = (int64_t)m * p.ldc + n;                                           \
+                if constexpr (BF16) static_cast<uint16_t*>(p.out)[o] = f32_to_bf16_rne_n(f);        \
+                else static_cast<float*>(p.out)[o] = f;                                             \
+            }                                                                                       \
+        }                                                                                           \
+    }
+    DFP4_NATIVE_STORE(0) DFP4_NATIVE_STORE(1) DFP4_NATIVE_STORE(2) DFP4_NATIVE_STORE(3)
+    DFP4_NATIVE_STORE(4) DFP4_NATIVE_STORE(5) DFP4_NATIVE_STORE(6) DFP4_NATIVE_STORE(7)
+    DFP4_NATIVE_STORE(8) DFP4_NATIVE_STORE(9) DFP4_NATIVE_STORE(10) DFP4_NATIVE_STORE(11)
+    DFP4_NATIVE_STORE(12) DFP4_NATIVE_STORE(13) DFP4_NATIVE_STORE(14) DFP4_NATIVE_STORE(15)
+#undef DFP4_NATIVE_STORE
 }
 
-struct NativeLayout { int64_t a_lo, a_hi, a_sc, w_lo, w_hi, w_sc, total; };
+struct NativeLayout { int64_t a_bits, a_sc, w_bits, w_sc, total; };
 inline int64_t up256(int64_t x) { return (x + 255) & ~(int64_t)255; }
 inline NativeLayout native_layout(int64_t M, int64_t N, int64_t KB, bool fp6) {
-    const int64_t S = (KB + 1) / 2, tm = (M + 127) / 128 * 4, tn = (N + 127) / 128 * 4;
+    const int64_t S = (KB + 1) / 2, tm = (M + 255) / 256 * 8, tn = (N + 255) / 256 * 8;
+    const int64_t gstride = fp6 ? 1792 : 1024;
     NativeLayout l{};
-    l.a_lo = 0;
-    l.a_hi = up256(l.a_lo + tm * S * 1024);
-    l.a_sc = up256(l.a_hi + (fp6 ? tm * S * 512 : 0));
-    l.w_lo = up256(l.a_sc + (tm / 4) * S * 256);
-    l.w_hi = up256(l.w_lo + tn * S * 1024);
-    l.w_sc = up256(l.w_hi + (fp6 ? tn * S * 512 : 0));
-    l.total = up256(l.w_sc + (tn / 4) * S * 256);
+    l.a_bits = 0;
+    l.a_sc = up256(l.a_bits + (tm * S + 3) * gstride);
+    l.w_bits = up256(l.a_sc + ((tm / 4) * S + 3) * 256);
+    l.w_sc = up256(l.w_bits + (tn * S + 3) * gstride);
+    l.total = up256(l.w_sc + ((tn / 4) * S + 3) * 256);
     return l;
 }
 
@@ -236,18 +234,16 @@ int launch_gemm_native(bool fp6, dfp4_tensor A, dfp4_tensor W, void* out, int ou
     uint8_t* ws = static_cast<uint8_t*>(workspace);
     const int S = (int)((KB + 1) / 2);
     NativeParams p{};
-    p.a = PackedOperand{reinterpret_cast<uint4*>(ws + lay.a_lo), reinterpret_cast<uint2*>(ws + lay.a_hi),
-                        reinterpret_cast<uint32_t*>(ws + lay.a_sc)};
-    p.w = PackedOperand{reinterpret_cast<uint4*>(ws + lay.w_lo), reinterpret_cast<uint2*>(ws + lay.w_hi),
-                        reinterpret_cast<uint32_t*>(ws + lay.w_sc)};
+    p.a = PackedOperand{ws + lay.a_bits, reinterpret_cast<uint32_t*>(ws + lay.a_sc)};
+    p.w = PackedOperand{ws + lay.w_bits, reinterpret_cast<uint32_t*>(ws + lay.w_sc)};
     p.out = out; p.M = (int)M; p.N = (int)N; p.S = S; p.ldc = ldc;
     for (int side = 0; side < 2; ++side) {
         const dfp4_tensor& T = side ? W : A;
         PackParams q{};
         q.codes = T.codes; q.dial = T.dialect; q.expo = T.exponent;
         q.dst = side ? p.w : p.a;
-        q.rows = (int)T.rows; q.KB = (int)KB; q.S = S; q.tiles = (int)((T.rows + 127) / 128 * 4);
-        dim3 gp((unsigned)((S + 3) / 4), (unsigned)q.tiles);
+        q.rows = (int)T.rows; q.KB = (int)KB; q.S = S;
+        dim3 gp((unsigned)((S + 3) / 4), (unsigned)((T.rows + 255) / 256 * 8));
         if (gp.y > 65535) return DFP4_ERR_SHAPE;
         if (fp6) hipLaunchKernelGGL((native_pack_kernel<kFmtFp6>), gp, dim3(256), 0, stream, q);
         else hipLaunchKernelGGL((native_pack_kernel<kFmtFp4>), gp, dim3(256), 0, stream, q);
