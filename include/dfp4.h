@@ -171,6 +171,22 @@ int mxfp4_gemm_native(dfp4_tensor A, dfp4_tensor W, void* out, int out_dtype, in
 size_t dfp4_gemm_native_workspace_bytes(int64_t M, int64_t N, int64_t K);
 
 /*
+ * The same with W arranged in the instruction's register order beforehand (weights:
+ * once, offline).  dfp4_native_pack / mxfp4_native_pack write the packed form of a
+ * quantized [rows, K] tensor into `packed` (device, 256-byte aligned, at least
+ * dfp4_native_packed_bytes(rows, K) bytes; the layout is private to the library).
+ * The *_packed_w calls take A quantized and W packed (N = number of rows of W); their
+ * workspace holds only the packed A: dfp4_native_packed_bytes(M, K) bytes.
+ */
+size_t dfp4_native_packed_bytes(int64_t rows, int64_t K);
+int dfp4_native_pack(dfp4_tensor T, void* packed, size_t bytes, void* stream);
+int mxfp4_native_pack(dfp4_tensor T, void* packed, size_t bytes, void* stream);
+int dfp4_gemm_native_packed_w(dfp4_tensor A, const void* w_packed, int64_t N, void* out, int out_dtype,
+                              int64_t ldc, void* workspace, size_t workspace_bytes, void* stream);
+int mxfp4_gemm_native_packed_w(dfp4_tensor A, const void* w_packed, int64_t N, void* out, int out_dtype,
+                               int64_t ldc, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Matrix multiply with requantizing epilogue (Section 3.3: the result of a
  * multiplication is quantized again when it feeds the next one):
  *   out = quantize(bf16(A * W^T))   in blocks of 32 along N,

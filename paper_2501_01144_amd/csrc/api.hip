@@ -145,35 +145,83 @@ size_t dfp4_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K) {
     return gemm_workspace_bytes(M, N, K);
 }
 
-static int gemm_native_common(bool fp6, dfp4_tensor A, dfp4_tensor W, void* out, int out_dtype, int64_t ldc,
-                              void* workspace, size_t workspace_bytes, void* stream) {
-    if (A.rows < 0 || W.rows < 0 || A.K < 0 || A.K != W.K || A.K % kBlock != 0) return DFP4_ERR_SHAPE;
+// Native block-scaled GEMM.  w_packed == nullptr: both operands are packed into the workspace
+// (A first, then W); otherwise only A is, and W comes packed (dfp4_native_pack / mxfp4_native_pack).
+static int gemm_native_common(bool fp6, dfp4_tensor A, const dfp4_tensor* W, const void* w_packed, int64_t N,
+                              void* out, int out_dtype, int64_t ldc, void* workspace, size_t workspace_bytes,
+                              void* stream) {
+    if (A.rows < 0 || N < 0 || A.K < 0 || A.K % kBlock != 0) return DFP4_ERR_SHAPE;
+    if (W && (W->K != A.K || W->rows != N)) return DFP4_ERR_SHAPE;
     if (out_dtype != DFP4_F32 && out_dtype != DFP4_BF16) return DFP4_ERR_DTYPE;
-    if (A.rows == 0 || W.rows == 0) return DFP4_OK;
-    if (ldc < W.rows || A.K == 0) return DFP4_ERR_SHAPE;
-    if (!out || !A.codes || !A.exponent || !W.codes || !W.exponent) return DFP4_ERR_NULL;
-    if (fp6 && (!A.dialect || !W.dialect)) return DFP4_ERR_NULL;
-    if (!aligned(A.codes, 16) || !aligned(W.codes, 16)) return DFP4_ERR_ALIGN;
-    const size_t need = gemm_native_workspace_bytes(A.rows, W.rows, A.K, fp6);
+    if (A.rows == 0 || N == 0) return DFP4_OK;
+    if (ldc < N || A.K == 0) return DFP4_ERR_SHAPE;
+    if (!out || !A.codes || !A.exponent || (fp6 && !A.dialect)) return DFP4_ERR_NULL;
+    if (W && (!W->codes || !W->exponent || (fp6 && !W->dialect))) return DFP4_ERR_NULL;
+    if (!W && !w_packed) return DFP4_ERR_NULL;
+    if (!aligned(A.codes, 16) || (W && !aligned(W->codes, 16)) || (w_packed && !aligned(w_packed, 256)))
+        return DFP4_ERR_ALIGN;
+    const size_t a_bytes = native_packed_bytes(A.rows, A.K, fp6);
+    const size_t need = a_bytes + (W ? native_packed_bytes(N, A.K, fp6) : 0);
     if (!workspace || workspace_bytes < need) return DFP4_ERR_WORKSPACE;
     if (!aligned(workspace, 256)) return DFP4_ERR_ALIGN;
-    return launch_gemm_native(fp6, A, W, out, out_dtype, ldc, workspace, workspace_bytes,
-                              static_cast<hipStream_t>(stream));
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    int rc = launch_native_pack(fp6, A, workspace, a_bytes, st);
+    if (rc != DFP4_OK) return rc;
+    const void* wp = w_packed;
+    if (W) {
+        void* dst = static_cast<uint8_t*>(workspace) + a_bytes;
+        rc = launch_native_pack(fp6, *W, dst, need - a_bytes, st);
+        if (rc != DFP4_OK) return rc;
+        wp = dst;
+    }
+    return launch_gemm_native_packed(fp6, workspace, wp, A.rows, N, A.K, out, out_dtype, ldc, st);
 }
 
 int mxfp4_gemm_native(dfp4_tensor A, dfp4_tensor W, void* out, int out_dtype, int64_t ldc, void* workspace,
                       size_t workspace_bytes, void* stream) {
-    return gemm_native_common(false, A, W, out, out_dtype, ldc, workspace, workspace_bytes, stream);
+    return gemm_native_common(false, A, &W, nullptr, W.rows, out, out_dtype, ldc, workspace, workspace_bytes, stream);
 }
 
 int dfp4_gemm_native(dfp4_tensor A, dfp4_tensor W, void* out, int out_dtype, int64_t ldc, void* workspace,
                      size_t workspace_bytes, void* stream) {
-    return gemm_native_common(true, A, W, out, out_dtype, ldc, workspace, workspace_bytes, stream);
+    return gemm_native_common(true, A, &W, nullptr, W.rows, out, out_dtype, ldc, workspace, workspace_bytes, stream);
+}
+
+int mxfp4_gemm_native_packed_w(dfp4_tensor A, const void* w_packed, int64_t N, void* out, int out_dtype,
+                               int64_t ldc, void* workspace, size_t workspace_bytes, void* stream) {
+    return gemm_native_common(false, A, nullptr, w_packed, N, out, out_dtype, ldc, workspace, workspace_bytes, stream);
+}
+
+int dfp4_gemm_native_packed_w(dfp4_tensor A, const void* w_packed, int64_t N, void* out, int out_dtype,
+                              int64_t ldc, void* workspace, size_t workspace_bytes, void* stream) {
+    return gemm_native_common(true, A, nullptr, w_packed, N, out, out_dtype, ldc, workspace, workspace_bytes, stream);
+}
+
+static int native_pack_common(bool fp6, dfp4_tensor T, void* packed, size_t bytes, void* stream) {
+    if (T.rows < 0 || T.K < 0 || T.K % kBlock != 0) return DFP4_ERR_SHAPE;
+    if (T.rows == 0 || T.K == 0) return DFP4_OK;
+    if (!packed || !T.codes || !T.exponent || (fp6 && !T.dialect)) return DFP4_ERR_NULL;
+    if (!aligned(T.codes, 16) || !aligned(packed, 256)) return DFP4_ERR_ALIGN;
+    if (bytes < native_packed_bytes(T.rows, T.K, fp6)) return DFP4_ERR_WORKSPACE;
+    return launch_native_pack(fp6, T, packed, bytes, static_cast<hipStream_t>(stream));
+}
+
+int dfp4_native_pack(dfp4_tensor T, void* packed, size_t bytes, void* stream) {
+    return native_pack_common(true, T, packed, bytes, stream);
+}
+
+int mxfp4_native_pack(dfp4_tensor T, void* packed, size_t bytes, void* stream) {
+    return native_pack_common(false, T, packed, bytes, stream);
+}
+
+size_t dfp4_native_packed_bytes(int64_t rows, int64_t K) {
+    if (rows < 0 || K < 0) return 0;
+    return native_packed_bytes(rows, K, true);               // covers the FP4 form as well
 }
 
 size_t dfp4_gemm_native_workspace_bytes(int64_t M, int64_t N, int64_t K) {
     if (M < 0 || N < 0 || K < 0) return 0;
-    return gemm_native_workspace_bytes(M, N, K, true);      // covers the FP4 form as well
+    return gemm_native_workspace_bytes(M, N, K, true);       // covers the FP4 form as well
 }
 
 static int gemm_requant_common(bool mx, dfp4_tensor A, dfp4_tensor W, dfp4_tensor out, void* workspace,

@@ -32,8 +32,10 @@ int launch_gemm(bool mx, dfp4_tensor A, dfp4_tensor W, void* out, int out_dtype,
                 void* workspace, size_t workspace_bytes, hipStream_t stream, const dfp4_tensor* rq = nullptr);
 size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
 size_t gemm_requant_workspace_bytes(int64_t M, int64_t N, int64_t K);
-int launch_gemm_native(bool fp6, dfp4_tensor A, dfp4_tensor W, void* out, int out_dtype, int64_t ldc,
-                       void* workspace, size_t workspace_bytes, hipStream_t stream);
+size_t native_packed_bytes(int64_t rows, int64_t K, bool fp6);
 size_t gemm_native_workspace_bytes(int64_t M, int64_t N, int64_t K, bool fp6);
+int launch_native_pack(bool fp6, dfp4_tensor T, void* packed, size_t bytes, hipStream_t stream);
+int launch_gemm_native_packed(bool fp6, const void* a_packed, const void* w_packed, int64_t M, int64_t N, int64_t K,
+                              void* out, int out_dtype, int64_t ldc, hipStream_t stream);
 
 }  // namespace dfp4

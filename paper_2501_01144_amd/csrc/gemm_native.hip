@@ -26,6 +26,7 @@
 // global -> LDS by direct loads three steps ahead (four stages), LDS -> registers one step
 // ahead, one barrier per step; the main loop is generated assembly (gen_native_loop.py).
 // For weights the packing could be done once, offline.
+#include <type_traits>
 #include "common.h"
 #include "formatbook.h"
 #include "gemm_native_asm.inc"
@@ -49,7 +50,7 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne_n(float f) {
 //   bits [row tile of 32][step][64 lanes x 16 bytes]                    FP4: registers 0..3 of the lane
 //        [row tile of 32][step][64 lanes x 16 bytes | 64 lanes x 12 bytes]   FP6: registers 0..3 | 4, 5, pad
 //   sc   [group of 4 row tiles][step][lane] dword: byte t = scale byte of row tile 4 g + t
-// Both arrays end with three steps of slack: the loop loads three steps ahead.
+// Both arrays end with eight steps of slack: the loop loads up to seven steps ahead.
 struct PackedOperand {
     uint8_t* bits;
     uint32_t* sc;
@@ -132,7 +133,7 @@ __global__ __launch_bounds__(256) void native_pack_kernel(PackParams p) {
 template <int FMT, bool BF16>
 __global__ __launch_bounds__(256, 1) void gemm_native_kernel(NativeParams p) {
     constexpr bool kFp6 = FMT == kFmtFp6;
-    constexpr int kTileLds = kFp6 ? 2048 : 1024, kStage = 16 * kTileLds + 1024, kStages = 4;
+    constexpr int kTileLds = kFp6 ? 2048 : 1024, kStage = 16 * kTileLds + 1024, kStages = kFp6 ? 4 : 8;
     constexpr int kGStride = kFp6 ? 1792 : 1024;             // global bytes per (tile, step)
     __shared__ __attribute__((aligned(16))) uint8_t s_stage[kStages * kStage];
     const int tid = threadIdx.x, lane = tid & 63;
@@ -173,9 +174,51 @@ __global__ __launch_bounds__(256, 1) void gemm_native_kernel(NativeParams p) {
                            "memory");
     }
 
-    // epilogue: fp32 (or bf16, round to nearest even) [M, N]; accumulator tile (i, j) = 4 i + j
+    // epilogue: fp32 (or bf16, round to nearest even) [M, N]; accumulator tile (i, j) = 4 i + j.
+    // Register x of lane (kh, c) is row 32 i + 8 (x / 4) + 4 kh + x % 4, column 32 j + c.  Row
+    // addresses are wave-uniform (scalar registers); the lane adds a constant byte offset.
     const int m0 = blockIdx.y * 256 + wm * 128, n0 = blockIdx.x * 256 + wn * 128;
     if (m0 >= p.M || n0 >= p.N) return;
+    constexpr int kEsz = BF16 ? 2 : 4;
+    uint8_t* wave_out = static_cast<uint8_t*>(p.out) + ((int64_t)m0 * p.ldc + n0) * kEsz;     // uniform
+    const int64_t row_bytes = p.ldc * kEsz;                                                    // uniform
+    const bool full = m0 + 128 <= p.M && n0 + 128 <= p.N;                                      // uniform
+    // bf16: lanes exchange values in pairs so that every lane stores two adjacent columns of one
+    // row (even lanes the even row of a row pair, odd lanes the odd row)
+    const bool pairs = BF16 && full && (p.ldc & 1) == 0 && (reinterpret_cast<uintptr_t>(p.out) & 3) == 0;
+    const uint32_t lane_off = pairs ? (uint32_t)((4 * kh + (c & 1)) * row_bytes + (c & ~1) * kEsz)
+                                    : (uint32_t)(4 * kh * row_bytes + c * kEsz);
+    auto store_tile = [&](auto full_c, auto pairs_c, int t, int (&v)[16]) {
+        constexpr bool kFull = decltype(full_c)::value, kPairs = decltype(pairs_c)::value;
+        const int i = t >> 2, j = t & 3;
+        uint8_t* tile_out = wave_out + (int64_t)i * 32 * row_bytes + j * 32 * kEsz;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            uint8_t* rowp = tile_out + (int64_t)(8 * q) * row_bytes;                           // uniform
+            if constexpr (BF16 && kPairs) {
+#pragma unroll
+                for (int jj = 0; jj < 4; jj += 2) {
+                    const uint32_t b0 = f32_to_bf16_rne_n(__builtin_bit_cast(float, v[4 * q + jj]));
+                    const uint32_t b1 = f32_to_bf16_rne_n(__builtin_bit_cast(float, v[4 * q + jj + 1]));
+                    const uint32_t send = (c & 1) ? b0 : b1;
+                    const uint32_t recv = (uint32_t)__builtin_amdgcn_mov_dpp((int)send, 0xB1, 0xf, 0xf, true);
+                    const uint32_t word = (c & 1) ? (recv | (b1 << 16)) : (b0 | (recv << 16));
+                    *reinterpret_cast<uint32_t*>(rowp + (int64_t)jj * row_bytes + lane_off) = word;
+                }
+            } else {
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj) {
+                    if (kFull || (m0 + i * 32 + 8 * q + 4 * kh + jj < p.M && n0 + j * 32 + c < p.N)) {
+                        uint8_t* dst = rowp + (int64_t)jj * row_bytes + lane_off;
+                        if constexpr (BF16)
+                            *reinterpret_cast<uint16_t*>(dst) = f32_to_bf16_rne_n(__builtin_bit_cast(float, v[4 * q + jj]));
+                        else
+                            *reinterpret_cast<int*>(dst) = v[4 * q + jj];
+                    }
+                }
+            }
+        }
+    };
 #define DFP4_NATIVE_STORE(G)                                                                        \
     {                                                                                               \
         int v[16];                                                                                  \
@@ -183,71 +226,81 @@ __global__ __launch_bounds__(256, 1) void gemm_native_kernel(NativeParams p) {
                      : "=v"(v[0]), "=v"(v[1]), "=v"(v[2]), "=v"(v[3]), "=v"(v[4]), "=v"(v[5]),      \
                        "=v"(v[6]), "=v"(v[7]), "=v"(v[8]), "=v"(v[9]), "=v"(v[10]), "=v"(v[11]),    \
                        "=v"(v[12]), "=v"(v[13]), "=v"(v[14]), "=v"(v[15]));                         \
-        const int n = n0 + (G & 3) * 32 + c;                                                        \
-        _Pragma("unroll") for (int x = 0; x < 16; ++x) {                                            \
-            const int m = m0 + (G >> 2) * 32 + 8 * (x >> 2) + 4 * kh + (x & 3);                     \
-            if (m < p.M && n < p.N) {                                                               \
-                const float f = __builtin_bit_cast(float, v[x]);                                    \
-                const int64_t o = (int64_t)m * p.ldc + n;                                           \
-                if constexpr (BF16) static_cast<uint16_t*>(p.out)[o] = f32_to_bf16_rne_n(f);        \
-                else static_cast<float*>(p.out)[o] = f;                                             \
-            }                                                                                       \
-        }                                                                                           \
+        store_tile(kFullC, kPairsC, G, v);                                                          \
     }
-    DFP4_NATIVE_STORE(0) DFP4_NATIVE_STORE(1) DFP4_NATIVE_STORE(2) DFP4_NATIVE_STORE(3)
-    DFP4_NATIVE_STORE(4) DFP4_NATIVE_STORE(5) DFP4_NATIVE_STORE(6) DFP4_NATIVE_STORE(7)
-    DFP4_NATIVE_STORE(8) DFP4_NATIVE_STORE(9) DFP4_NATIVE_STORE(10) DFP4_NATIVE_STORE(11)
+#define DFP4_NATIVE_ALL                                                                             \
+    DFP4_NATIVE_STORE(0) DFP4_NATIVE_STORE(1) DFP4_NATIVE_STORE(2) DFP4_NATIVE_STORE(3)             \
+    DFP4_NATIVE_STORE(4) DFP4_NATIVE_STORE(5) DFP4_NATIVE_STORE(6) DFP4_NATIVE_STORE(7)             \
+    DFP4_NATIVE_STORE(8) DFP4_NATIVE_STORE(9) DFP4_NATIVE_STORE(10) DFP4_NATIVE_STORE(11)           \
     DFP4_NATIVE_STORE(12) DFP4_NATIVE_STORE(13) DFP4_NATIVE_STORE(14) DFP4_NATIVE_STORE(15)
+    if (pairs) {
+        constexpr std::true_type kFullC{}, kPairsC{};
+        DFP4_NATIVE_ALL
+    } else if (full) {
+        constexpr std::true_type kFullC{};
+        constexpr std::false_type kPairsC{};
+        DFP4_NATIVE_ALL
+    } else {
+        constexpr std::false_type kFullC{}, kPairsC{};
+        DFP4_NATIVE_ALL
+    }
+#undef DFP4_NATIVE_ALL
 #undef DFP4_NATIVE_STORE
 }
 
-struct NativeLayout { int64_t a_bits, a_sc, w_bits, w_sc, total; };
 inline int64_t up256(int64_t x) { return (x + 255) & ~(int64_t)255; }
-inline NativeLayout native_layout(int64_t M, int64_t N, int64_t KB, bool fp6) {
-    const int64_t S = (KB + 1) / 2, tm = (M + 255) / 256 * 8, tn = (N + 255) / 256 * 8;
-    const int64_t gstride = fp6 ? 1792 : 1024;
-    NativeLayout l{};
-    l.a_bits = 0;
-    l.a_sc = up256(l.a_bits + (tm * S + 3) * gstride);
-    l.w_bits = up256(l.a_sc + ((tm / 4) * S + 3) * 256);
-    l.w_sc = up256(l.w_bits + (tn * S + 3) * gstride);
-    l.total = up256(l.w_sc + ((tn / 4) * S + 3) * 256);
+// One packed operand: [bits | scales], rows padded to 256, eight steps of slack behind each array.
+struct OperandLayout { int64_t sc, total; };
+inline OperandLayout operand_layout(int64_t rows, int64_t KB, bool fp6) {
+    const int64_t S = (KB + 1) / 2, tiles = (rows + 255) / 256 * 8;
+    OperandLayout l{};
+    l.sc = up256((tiles * S + 8) * (fp6 ? 1792 : 1024));
+    l.total = up256(l.sc + ((tiles / 4) * S + 8) * 256);
     return l;
 }
 
 }  // namespace
 
-size_t gemm_native_workspace_bytes(int64_t M, int64_t N, int64_t K, bool fp6) {
-    if (M == 0 || N == 0) return 0;
-    return (size_t)native_layout(M, N, K / kBlock, fp6).total;
+size_t native_packed_bytes(int64_t rows, int64_t K, bool fp6) {
+    if (rows == 0 || K == 0) return 0;
+    return (size_t)operand_layout(rows, K / kBlock, fp6).total;
 }
 
-// fp6 = false: MXFP4 operands on the FP4 form of the instruction; true: DialectFP4 (or MXFP4,
-// dialect pointer null) operands repacked to FP6 E2M3.
-int launch_gemm_native(bool fp6, dfp4_tensor A, dfp4_tensor W, void* out, int out_dtype, int64_t ldc,
-                       void* workspace, size_t workspace_bytes, hipStream_t stream) {
-    const int64_t M = A.rows, N = W.rows, KB = A.K / kBlock;
-    if (M == 0 || N == 0) return DFP4_OK;
-    if (M >= (1 << 30) || N >= (1 << 30) || KB >= (1 << 26) || KB == 0) return KB == 0 ? DFP4_ERR_SHAPE : DFP4_ERR_SHAPE;
-    const NativeLayout lay = native_layout(M, N, KB, fp6);
-    if ((size_t)lay.total > workspace_bytes) return DFP4_ERR_WORKSPACE;
-    uint8_t* ws = static_cast<uint8_t*>(workspace);
+size_t gemm_native_workspace_bytes(int64_t M, int64_t N, int64_t K, bool fp6) {
+    return native_packed_bytes(M, K, fp6) + native_packed_bytes(N, K, fp6);
+}
+
+// Rewrite a quantized tensor in the matrix instruction's register order (see the file header).
+int launch_native_pack(bool fp6, dfp4_tensor T, void* packed, size_t bytes, hipStream_t stream) {
+    const int64_t KB = T.K / kBlock;
+    if (T.rows == 0 || KB == 0) return DFP4_OK;
+    if (T.rows >= (1 << 30) || KB >= (1 << 20)) return DFP4_ERR_SHAPE;
+    const OperandLayout lay = operand_layout(T.rows, KB, fp6);
+    if ((size_t)lay.total > bytes) return DFP4_ERR_WORKSPACE;
     const int S = (int)((KB + 1) / 2);
+    PackParams q{};
+    q.codes = T.codes; q.dial = T.dialect; q.expo = T.exponent;
+    q.dst = PackedOperand{static_cast<uint8_t*>(packed), reinterpret_cast<uint32_t*>(static_cast<uint8_t*>(packed) + lay.sc)};
+    q.rows = (int)T.rows; q.KB = (int)KB; q.S = S;
+    dim3 gp((unsigned)((S + 3) / 4), (unsigned)((T.rows + 255) / 256 * 8));
+    if (gp.y > 65535) return DFP4_ERR_SHAPE;
+    if (fp6) hipLaunchKernelGGL((native_pack_kernel<kFmtFp6>), gp, dim3(256), 0, stream, q);
+    else hipLaunchKernelGGL((native_pack_kernel<kFmtFp4>), gp, dim3(256), 0, stream, q);
+    return check_launch();
+}
+
+// out = A * W^T from two packed operands ([M, K] and [N, K] before packing)
+int launch_gemm_native_packed(bool fp6, const void* a_packed, const void* w_packed, int64_t M, int64_t N, int64_t K,
+                              void* out, int out_dtype, int64_t ldc, hipStream_t stream) {
+    const int64_t KB = K / kBlock;
+    if (M == 0 || N == 0) return DFP4_OK;
+    if (M >= (1 << 30) || N >= (1 << 30) || KB >= (1 << 20) || KB == 0 || ldc >= (1 << 27)) return DFP4_ERR_SHAPE;
     NativeParams p{};
-    p.a = PackedOperand{ws + lay.a_bits, reinterpret_cast<uint32_t*>(ws + lay.a_sc)};
-    p.w = PackedOperand{ws + lay.w_bits, reinterpret_cast<uint32_t*>(ws + lay.w_sc)};
-    p.out = out; p.M = (int)M; p.N = (int)N; p.S = S; p.ldc = ldc;
-    for (int side = 0; side < 2; ++side) {
-        const dfp4_tensor& T = side ? W : A;
-        PackParams q{};
-        q.codes = T.codes; q.dial = T.dialect; q.expo = T.exponent;
-        q.dst = side ? p.w : p.a;
-        q.rows = (int)T.rows; q.KB = (int)KB; q.S = S;
-        dim3 gp((unsigned)((S + 3) / 4), (unsigned)((T.rows + 255) / 256 * 8));
-        if (gp.y > 65535) return DFP4_ERR_SHAPE;
-        if (fp6) hipLaunchKernelGGL((native_pack_kernel<kFmtFp6>), gp, dim3(256), 0, stream, q);
-        else hipLaunchKernelGGL((native_pack_kernel<kFmtFp4>), gp, dim3(256), 0, stream, q);
-    }
+    uint8_t* ap = static_cast<uint8_t*>(const_cast<void*>(a_packed));
+    uint8_t* wp = static_cast<uint8_t*>(const_cast<void*>(w_packed));
+    p.a = PackedOperand{ap, reinterpret_cast<uint32_t*>(ap + operand_layout(M, KB, fp6).sc)};
+    p.w = PackedOperand{wp, reinterpret_cast<uint32_t*>(wp + operand_layout(N, KB, fp6).sc)};
+    p.out = out; p.M = (int)M; p.N = (int)N; p.S = (int)((KB + 1) / 2); p.ldc = ldc;
     dim3 grid((unsigned)((N + 255) / 256), (unsigned)((M + 255) / 256));
     if (grid.y > 65535) return DFP4_ERR_SHAPE;
     const bool bf16 = out_dtype == DFP4_BF16;

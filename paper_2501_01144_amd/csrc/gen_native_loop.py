@@ -9,12 +9,13 @@ instruction's register order (native_pack_kernel), so a (tile, step) chunk is 64
 16 bytes (FP4), followed for FP6 by 64 lanes x 12 bytes (8 used: registers 4 and 5), and the loop only moves data:
 
   global -> LDS  direct loads (global_load_lds_dwordx4 / dwordx3; a lane's 12 bytes land
-                 at a 16-byte lane stride), three steps ahead, four LDS stages in rotation;
+                 at a 16-byte lane stride), three (FP6) or seven (FP4) steps ahead, four or eight LDS
+                 stages in rotation;
                  wave w fetches A tiles 2w, 2w+1, B tiles 2w, 2w+1 and scale chunk w;
   LDS -> regs    the wave's 4 A and 4 B tiles and two scale dwords of step s + 1 are read
                  during step s (two register sets used alternately);
   one barrier per step, in the middle of the MFMA stream: after it every wave's loads of
-  step s + 1 have landed and nobody reads the stage that the loads of step s + 3 overwrite.
+  step s + 1 have landed and nobody reads the stage that this step's loads overwrite.
 
 LDS stage: 16 tiles x TILE bytes (A tiles 0..7, B tiles 0..7; TILE = 1 KiB for FP4, 2 KiB
 for FP6: two 1 KiB halves) + 4 x 256 bytes of scales (A groups 0, 1, B groups 0, 1).
@@ -34,7 +35,6 @@ SB = [137, 139]
 VA, VB, VSA, VSB, VOFF, VSOFF, VOFF2 = 140, 141, 142, 143, 144, 145, 146
 S_BASE, S_VC, S_RD, S_LD, S_T0, S_T1, S_T2 = 60, 70, 72, 73, 74, 75, 76
 S_RA, S_RB, S_RSA, S_RSB, S_DA, S_DB, S_DS = 77, 78, 79, 80, 81, 82, 83
-NST, DIST = 4, 3
 
 
 def vr(n, cnt=1):
@@ -54,6 +54,8 @@ class Fmt:
         self.gstride = 1792 if fp6 else 1024         # global bytes per (tile, step): 1024 + 768
         self.code = 2 if fp6 else 4                  # cbsz / blgp
         self.per_step = 9 if fp6 else 5              # direct loads per wave and step
+        self.nst = 4 if fp6 else 8                   # LDS stages (FP6: 4 x 33 KiB, FP4: 8 x 17 KiB)
+        self.dist = self.nst - 1                     # loads run this many steps ahead
 
 
 def frag_reads(f, p):
@@ -128,8 +130,8 @@ def step(f, p):
     for k in range(16):
         o.append(mfma(f, p, k))
         if k == 2:
-            # the loads of step s + 1 (issued two steps ago) have landed; only the last step's may be pending
-            o += [f"s_waitcnt vmcnt({f.per_step})", "s_barrier"] + dst_setup()
+            # the loads of step s + 1 have landed; those of the steps after it may be pending
+            o += [f"s_waitcnt vmcnt({(f.dist - 2) * f.per_step})", "s_barrier"] + dst_setup()
         if k >= 3:
             n_r = (len(reads) + 12) // 13
             o += reads[(k - 3) * n_r:(k - 2) * n_r]
@@ -160,14 +162,14 @@ def entry(f):
     o += [f"s_mov_b32 {sr(S_VC)}, 0", f"s_mov_b32 {sr(S_LD)}, %[lds]",
           f"v_mov_b32 {vr(VOFF)}, %[l16]", f"v_mov_b32 {vr(VSOFF)}, %[l4]", f"v_mov_b32 {vr(VOFF2)}, %[lg]"]
     # pipeline fill: steps 0, 1, 2 into stages 0, 1, 2
-    for _ in range(DIST):
+    for _ in range(f.dist):
         o += dst_setup()
         for m0, ld in dma_ops(f):
             o += [m0, "s_nop 0", ld]
         o += advance_load_stage(f)
     # step 0's operands into set 0 (S_RD is advanced before use: start one stage "before" stage 0)
-    o += [f"s_waitcnt vmcnt({(DIST - 1) * f.per_step})", "s_barrier",
-          f"s_add_u32 {sr(S_RD)}, %[lds], {(NST - 1) * f.stage}"]
+    o += [f"s_waitcnt vmcnt({(f.dist - 1) * f.per_step})", "s_barrier",
+          f"s_add_u32 {sr(S_RD)}, %[lds], {(f.nst - 1) * f.stage}"]
     o += read_addr(f) + frag_reads(f, 0) + ["s_waitcnt lgkmcnt(0)"]
     return o
 

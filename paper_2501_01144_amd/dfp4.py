@@ -26,7 +26,9 @@ class _CTensor(ctypes.Structure):
 
 SYMBOLS = [
     "dfp4_quantize", "dfp4_quantize_mse", "dfp4_quantize_t", "mxfp4_quantize_t", "dfp4_dequantize", "dfp4_gemm", "dfp4_gemm_batched", "dfp4_gemm_workspace_bytes",
-    "mxfp4_gemm_native", "dfp4_gemm_native", "dfp4_gemm_native_workspace_bytes", "dfp4_gemm_requant", "mxfp4_gemm_requant", "dfp4_gemm_requant_workspace_bytes",
+    "mxfp4_gemm_native", "dfp4_gemm_native", "dfp4_gemm_native_workspace_bytes", "dfp4_native_packed_bytes",
+    "dfp4_native_pack", "mxfp4_native_pack", "dfp4_gemm_native_packed_w", "mxfp4_gemm_native_packed_w",
+    "dfp4_gemm_requant", "mxfp4_gemm_requant", "dfp4_gemm_requant_workspace_bytes",
     "mxfp4_quantize", "mxfp4_dequantize", "mxfp4_gemm", "dfp4_formatbook", "dfp4_strerror",
 ]
 
@@ -63,6 +65,14 @@ def load():
     lib.dfp4_gemm_native.restype = ci
     lib.dfp4_gemm_native_workspace_bytes.argtypes = [i64, i64, i64]
     lib.dfp4_gemm_native_workspace_bytes.restype = ctypes.c_size_t
+    lib.dfp4_native_packed_bytes.argtypes = [i64, i64]
+    lib.dfp4_native_packed_bytes.restype = ctypes.c_size_t
+    for name in ("dfp4_native_pack", "mxfp4_native_pack"):
+        getattr(lib, name).argtypes = [_CTensor, vp, ctypes.c_size_t, vp]
+        getattr(lib, name).restype = ci
+    for name in ("dfp4_gemm_native_packed_w", "mxfp4_gemm_native_packed_w"):
+        getattr(lib, name).argtypes = [_CTensor, vp, i64, vp, ci, i64, vp, ctypes.c_size_t, vp]
+        getattr(lib, name).restype = ci
     lib.dfp4_gemm_requant.argtypes = [_CTensor, _CTensor, _CTensor, vp, ctypes.c_size_t, vp]
     lib.mxfp4_gemm_requant.argtypes = [_CTensor, _CTensor, _CTensor, vp, ctypes.c_size_t, vp]
     lib.dfp4_gemm_requant.restype = ci
@@ -249,6 +259,39 @@ def gemm_native(a, w, dtype=torch.float32, out=None, workspace=None):
 def mxfp4_gemm_native(a, w, dtype=torch.float32, out=None, workspace=None):
     """mxfp4_gemm_native: the MXFP4 product on the block-scaled matrix instruction (FP4 operands)."""
     return _gemm_native(load().mxfp4_gemm_native, "mxfp4_gemm_native", a, w, dtype, out, workspace)
+
+
+@dataclass
+class PackedWeights:
+    """A quantized [rows, K] tensor in the matrix instruction's register order (dfp4_native_pack)."""
+    buf: torch.Tensor
+    rows: int
+    K: int
+    mx: bool
+
+
+def native_pack(w, mx=False):
+    """dfp4_native_pack / mxfp4_native_pack: pack a quantized tensor once (weights)."""
+    n = int(load().dfp4_native_packed_bytes(w.rows, w.K))
+    buf = torch.empty(max(n, 256), dtype=torch.uint8, device=w.codes.device)
+    fn = load().mxfp4_native_pack if mx else load().dfp4_native_pack
+    _check(fn(w.c(), _ptr(buf), buf.numel(), _stream()), "native_pack")
+    return PackedWeights(buf, w.rows, w.K, mx)
+
+
+def gemm_native_packed_w(a, wp, dtype=torch.float32, out=None, workspace=None):
+    """dfp4_gemm_native_packed_w / mxfp4_gemm_native_packed_w: A quantized, W packed beforehand."""
+    if out is None:
+        out = torch.empty((a.rows, wp.rows), dtype=dtype, device=a.codes.device)
+    assert out.dtype in (torch.float32, torch.bfloat16) and out.stride(1) == 1 and a.K == wp.K
+    need = int(load().dfp4_native_packed_bytes(a.rows, a.K))
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=out.device)
+    fn = load().mxfp4_gemm_native_packed_w if wp.mx else load().dfp4_gemm_native_packed_w
+    ldc = out.stride(0) if a.rows > 1 else wp.rows
+    _check(fn(a.c(), _ptr(wp.buf), wp.rows, _ptr(out), F32 if out.dtype == torch.float32 else BF16, ldc,
+              _ptr(workspace), workspace.numel(), _stream()), "gemm_native_packed_w")
+    return out
 
 
 def gemm_batched(a, w, batch, M, N, dtype=torch.float32, out=None, workspace=None):

@@ -593,3 +593,24 @@ def test_dfp4_gemm_native_all_dialects_wide_exponents_and_full_size_sample():
     cols = np.sort(rng.choice(wg.shape[0], 128, replace=False))
     ref, absdot = _gemm_ref(synth.to_f64(x[rows]), synth.to_f64(wg[cols]))
     _assert_gemm_close(out[rows][:, cols], ref, absdot, "native fp6 full size sampled")
+
+
+def test_gemm_native_with_prepacked_weights():
+    # weights arranged once in the instruction's register order; results identical to the call
+    # that packs both operands
+    M, N, K = 300, 520, 1056
+    a = synth.gaussian_outlier_channels(M, K, 8, 50.0, 1.0, seed=901)
+    w = synth.gaussian(N, K, 0.02, seed=902)
+    qa, qw = dfp4.quantize(_dev(a)), dfp4.quantize(_dev(w))
+    wp = dfp4.native_pack(qw)
+    out = dfp4.gemm_native_packed_w(qa, wp)
+    both = dfp4.gemm_native(qa, qw)
+    torch.cuda.synchronize()
+    assert torch.equal(out, both)
+    ref, absdot = _gemm_ref(synth.to_f64(a), synth.to_f64(w))
+    _assert_gemm_close(out, ref, absdot, "prepacked fp6")
+    qam, qwm = dfp4.mxfp4_quantize(_dev(a)), dfp4.mxfp4_quantize(_dev(w))
+    outm = dfp4.gemm_native_packed_w(qam, dfp4.native_pack(qwm, mx=True), dtype=torch.bfloat16)
+    torch.cuda.synchronize()
+    refm, absm = _gemm_ref(synth.to_f64(a), synth.to_f64(w), mx=True)
+    _assert_gemm_close(outm, refm, absm, "prepacked fp4 bf16", bf16=True)
