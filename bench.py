@@ -26,6 +26,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0
 INT8_PEAK_TOPS = 5000.0
+FP6_PEAK_TOPS = 10100.0
 
 
 def _events(n, torch):
@@ -256,6 +257,51 @@ def main():
     out["mxfp4_step"] = {"ms_per_step": round(ms_mx, 4), "TOPs": round(total_ops / (ms_mx * 1e-3) / 1e12, 1),
                          "steps": nmx}
     del wqm
+
+    # the same step on the block-scaled matrix instruction: DialectFP4 operands repacked (exactly) to
+    # FP6 E2M3, weights packed once beforehand like they are quantized once beforehand
+    wpk = {k: dfp4.native_pack(wq[k]) for k in ("w_gate", "w_up", "w_down")}
+    ws_n = torch.empty(max(int(dfp4.load().dfp4_native_packed_bytes(M, max(H, I))), 256), dtype=torch.uint8, device=dev)
+    nnames = ["quantize_x", "gemm_gate", "gemm_up", "quantize_h", "gemm_down"]
+
+    def step_native(ev=None):
+        calls = [
+            lambda: dfp4.quantize(x, out=qx),
+            lambda: dfp4.gemm_native_packed_w(qx, wpk["w_gate"], out=gate, workspace=ws_n),
+            lambda: dfp4.gemm_native_packed_w(qx, wpk["w_up"], out=up, workspace=ws_n),
+            lambda: dfp4.quantize(h, out=qh),
+            lambda: dfp4.gemm_native_packed_w(qh, wpk["w_down"], out=down, workspace=ws_n),
+        ]
+        for i, c in enumerate(calls):
+            if ev is not None:
+                ev[i][0].record()
+            c()
+            if ev is not None:
+                ev[i][1].record()
+
+    nn = max(10, args.steps // 2)
+    for _ in range(max(3, args.warmup // 2)):
+        step_native()
+    torch.cuda.synchronize()
+    nev = [_events(len(nnames), torch) for _ in range(nn)]
+    t0 = time.perf_counter()
+    for s in range(nn):
+        step_native(nev[s])
+    torch.cuda.synchronize()
+    ms_n = (time.perf_counter() - t0) / nn * 1e3
+    nk = {n: sum(e[i][0].elapsed_time(e[i][1]) for e in nev) / nn for i, n in enumerate(nnames)}
+    n_gemm_ms = sum(nk[n] for n in gemm_ops)
+    n_tops = total_ops / (n_gemm_ms * 1e-3) / 1e12
+    out["native_fp6_step"] = {
+        "what": "same step with dfp4_gemm_native_packed_w (v_mfma_scale_f32_32x32x64_f8f6f4, FP6 E2M3 operands, "
+                "fp32 accumulation in the matrix core); weights packed beforehand, A packed inside each call",
+        "ms_per_step": round(ms_n, 4), "TOPs": round(total_ops / (ms_n * 1e-3) / 1e12, 1), "steps": nn,
+        "kernel_ms": {k: round(v, 4) for k, v in nk.items()},
+        "roofline": {"bound": "mfma", "kernel": "dfp4_gemm_native_packed_w call = native_pack_kernel (A) + "
+                                                 "gemm_native_kernel", "achieved": round(n_tops, 1),
+                     "peak": FP6_PEAK_TOPS, "unit": "TOP/s", "frac": round(n_tops / FP6_PEAK_TOPS, 4),
+                     "traffic": None}}
+    del wpk
 
     if not args.no_stream_quant:
         # quantizer-only streaming tensors (Student-t, df=3): DialectFP4 and MXFP4,
