@@ -176,7 +176,9 @@ size_t dfp4_gemm_native_workspace_bytes(int64_t M, int64_t N, int64_t K);
  * quantized [rows, K] tensor into `packed` (device, 256-byte aligned, at least
  * dfp4_native_packed_bytes(rows, K) bytes; the layout is private to the library).
  * The *_packed_w calls take A quantized and W packed (N = number of rows of W); their
- * workspace holds only the packed A: dfp4_native_packed_bytes(M, K) bytes.
+ * workspace holds the packed A and, where K is split between workgroups (few output
+ * tiles), their fp32 partial tiles: dfp4_native_packed_bytes(M, K) +
+ * dfp4_gemm_native_splitk_bytes(M, N, K) bytes.
  */
 size_t dfp4_native_packed_bytes(int64_t rows, int64_t K);
 int dfp4_native_pack(dfp4_tensor T, void* packed, size_t bytes, void* stream);
@@ -185,6 +187,17 @@ int dfp4_gemm_native_packed_w(dfp4_tensor A, const void* w_packed, int64_t N, vo
                               int64_t ldc, void* workspace, size_t workspace_bytes, void* stream);
 int mxfp4_gemm_native_packed_w(dfp4_tensor A, const void* w_packed, int64_t N, void* out, int out_dtype,
                                int64_t ldc, void* workspace, size_t workspace_bytes, void* stream);
+/* Both operands packed beforehand ([M, K] and [N, K] before packing).  An activation that
+ * feeds several products (gate and up projections) is packed once.  workspace: at least
+ * dfp4_gemm_native_splitk_bytes(M, N, K) bytes (0 for most shapes), or NULL: then K is never
+ * split, whatever the number of tiles. */
+int dfp4_gemm_native_packed(const void* a_packed, int64_t M, const void* w_packed, int64_t N, int64_t K,
+                            void* out, int out_dtype, int64_t ldc, void* workspace,
+                            size_t workspace_bytes, void* stream);
+int mxfp4_gemm_native_packed(const void* a_packed, int64_t M, const void* w_packed, int64_t N, int64_t K,
+                             void* out, int out_dtype, int64_t ldc, void* workspace,
+                             size_t workspace_bytes, void* stream);
+size_t dfp4_gemm_native_splitk_bytes(int64_t M, int64_t N, int64_t K);
 
 /*
  * Matrix multiply with requantizing epilogue (Section 3.3: the result of a

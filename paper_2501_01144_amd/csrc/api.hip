@@ -161,7 +161,8 @@ static int gemm_native_common(bool fp6, dfp4_tensor A, const dfp4_tensor* W, con
     if (!aligned(A.codes, 16) || (W && !aligned(W->codes, 16)) || (w_packed && !aligned(w_packed, 256)))
         return DFP4_ERR_ALIGN;
     const size_t a_bytes = native_packed_bytes(A.rows, A.K, fp6);
-    const size_t need = a_bytes + (W ? native_packed_bytes(N, A.K, fp6) : 0);
+    const size_t w_bytes = W ? native_packed_bytes(N, A.K, fp6) : 0;
+    const size_t need = a_bytes + w_bytes + native_splitk_bytes(A.rows, N, A.K);
     if (!workspace || workspace_bytes < need) return DFP4_ERR_WORKSPACE;
     if (!aligned(workspace, 256)) return DFP4_ERR_ALIGN;
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -170,11 +171,12 @@ static int gemm_native_common(bool fp6, dfp4_tensor A, const dfp4_tensor* W, con
     const void* wp = w_packed;
     if (W) {
         void* dst = static_cast<uint8_t*>(workspace) + a_bytes;
-        rc = launch_native_pack(fp6, *W, dst, need - a_bytes, st);
+        rc = launch_native_pack(fp6, *W, dst, w_bytes, st);
         if (rc != DFP4_OK) return rc;
         wp = dst;
     }
-    return launch_gemm_native_packed(fp6, workspace, wp, A.rows, N, A.K, out, out_dtype, ldc, st);
+    return launch_gemm_native_packed(fp6, workspace, wp, A.rows, N, A.K, out, out_dtype, ldc,
+                                     static_cast<uint8_t*>(workspace) + a_bytes + w_bytes, need - a_bytes - w_bytes, st);
 }
 
 int mxfp4_gemm_native(dfp4_tensor A, dfp4_tensor W, void* out, int out_dtype, int64_t ldc, void* workspace,
@@ -195,6 +197,37 @@ int mxfp4_gemm_native_packed_w(dfp4_tensor A, const void* w_packed, int64_t N, v
 int dfp4_gemm_native_packed_w(dfp4_tensor A, const void* w_packed, int64_t N, void* out, int out_dtype,
                               int64_t ldc, void* workspace, size_t workspace_bytes, void* stream) {
     return gemm_native_common(true, A, nullptr, w_packed, N, out, out_dtype, ldc, workspace, workspace_bytes, stream);
+}
+
+static int gemm_native_packed_common(bool fp6, const void* a_packed, int64_t M, const void* w_packed, int64_t N,
+                                     int64_t K, void* out, int out_dtype, int64_t ldc, void* workspace,
+                                     size_t workspace_bytes, void* stream) {
+    if (M < 0 || N < 0 || K <= 0 || K % kBlock != 0) return DFP4_ERR_SHAPE;
+    if (out_dtype != DFP4_F32 && out_dtype != DFP4_BF16) return DFP4_ERR_DTYPE;
+    if (M == 0 || N == 0) return DFP4_OK;
+    if (ldc < N) return DFP4_ERR_SHAPE;
+    if (!out || !a_packed || !w_packed) return DFP4_ERR_NULL;
+    if (!aligned(a_packed, 256) || !aligned(w_packed, 256)) return DFP4_ERR_ALIGN;
+    if (workspace && !aligned(workspace, 256)) return DFP4_ERR_ALIGN;
+    return launch_gemm_native_packed(fp6, a_packed, w_packed, M, N, K, out, out_dtype, ldc, workspace,
+                                     workspace ? workspace_bytes : 0, static_cast<hipStream_t>(stream));
+}
+
+int dfp4_gemm_native_packed(const void* a_packed, int64_t M, const void* w_packed, int64_t N, int64_t K, void* out,
+                            int out_dtype, int64_t ldc, void* workspace, size_t workspace_bytes, void* stream) {
+    return gemm_native_packed_common(true, a_packed, M, w_packed, N, K, out, out_dtype, ldc, workspace,
+                                     workspace_bytes, stream);
+}
+
+int mxfp4_gemm_native_packed(const void* a_packed, int64_t M, const void* w_packed, int64_t N, int64_t K, void* out,
+                             int out_dtype, int64_t ldc, void* workspace, size_t workspace_bytes, void* stream) {
+    return gemm_native_packed_common(false, a_packed, M, w_packed, N, K, out, out_dtype, ldc, workspace,
+                                     workspace_bytes, stream);
+}
+
+size_t dfp4_gemm_native_splitk_bytes(int64_t M, int64_t N, int64_t K) {
+    if (M < 0 || N < 0 || K < 0) return 0;
+    return native_splitk_bytes(M, N, K);
 }
 
 static int native_pack_common(bool fp6, dfp4_tensor T, void* packed, size_t bytes, void* stream) {

@@ -36,6 +36,8 @@ size_t native_packed_bytes(int64_t rows, int64_t K, bool fp6);
 size_t gemm_native_workspace_bytes(int64_t M, int64_t N, int64_t K, bool fp6);
 int launch_native_pack(bool fp6, dfp4_tensor T, void* packed, size_t bytes, hipStream_t stream);
 int launch_gemm_native_packed(bool fp6, const void* a_packed, const void* w_packed, int64_t M, int64_t N, int64_t K,
-                              void* out, int out_dtype, int64_t ldc, hipStream_t stream);
+                              void* out, int out_dtype, int64_t ldc, void* splitk, size_t splitk_bytes,
+                              hipStream_t stream);
+size_t native_splitk_bytes(int64_t M, int64_t N, int64_t K);
 
 }  // namespace dfp4

@@ -61,6 +61,8 @@ struct NativeParams {
     void* out;
     int M, N, S;
     int64_t ldc;
+    int ksplit;              // workgroups sharing a tile (each a range of steps); partial tiles go to `part`
+    float* part;             // [ksplit][M][N] fp32
 };
 
 struct PackParams {
@@ -140,18 +142,22 @@ __global__ __launch_bounds__(256, 1) void gemm_native_kernel(NativeParams p) {
     const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane(tid >> 6);
     const int kh = lane >> 5, c = lane & 31;
     const int wm = (int)wave >> 1, wn = (int)wave & 1;
-    const int S = p.S;
+    // this workgroup's range of steps (split K: blockIdx.z)
+    const int per = (p.S + p.ksplit - 1) / p.ksplit;
+    const int s_lo = (int)blockIdx.z * per, S = min(p.S, s_lo + per) - s_lo;
     {
         const uint32_t lds = (uint32_t)__builtin_amdgcn_readfirstlane(
             (int)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)&s_stage[0]);
-        const uint32_t tstride = (uint32_t)S * (uint32_t)kGStride;        // bytes per tile
+        const uint32_t tstride = (uint32_t)p.S * (uint32_t)kGStride;      // bytes per tile
         // this wave fetches A tiles 2w, 2w+1 and B tiles 2w, 2w+1 of the workgroup's 8 + 8, and scale chunk w
         const uint64_t ab = reinterpret_cast<uint64_t>(p.a.bits) + ((uint64_t)blockIdx.y * 8 + 2 * wave) * tstride;
         const uint64_t bb = reinterpret_cast<uint64_t>(p.w.bits) + ((uint64_t)blockIdx.x * 8 + 2 * wave) * tstride;
         const uint64_t sb = wave < 2
-            ? reinterpret_cast<uint64_t>(p.a.sc) + ((uint64_t)blockIdx.y * 2 + wave) * (uint64_t)S * 256
-            : reinterpret_cast<uint64_t>(p.w.sc) + ((uint64_t)blockIdx.x * 2 + (wave - 2)) * (uint64_t)S * 256;
-        const uint32_t l16 = (uint32_t)lane * 16u, l4 = (uint32_t)lane * 4u, lg = (uint32_t)lane * 12u + 1024u;
+            ? reinterpret_cast<uint64_t>(p.a.sc) + ((uint64_t)blockIdx.y * 2 + wave) * (uint64_t)p.S * 256
+            : reinterpret_cast<uint64_t>(p.w.sc) + ((uint64_t)blockIdx.x * 2 + (wave - 2)) * (uint64_t)p.S * 256;
+        const uint32_t l16 = (uint32_t)lane * 16u, l4 = (uint32_t)lane * 4u;
+        const uint32_t g16 = l16 + (uint32_t)s_lo * kGStride, g12 = (uint32_t)lane * 12u + 1024u + (uint32_t)s_lo * kGStride;
+        const uint32_t g4 = l4 + (uint32_t)s_lo * 256u;
         if constexpr (kFp6)
             asm volatile(DFP4_NATIVE_LOOP_FP6
                          :
@@ -159,7 +165,7 @@ __global__ __launch_bounds__(256, 1) void gemm_native_kernel(NativeParams p) {
                            [bhi] "s"((uint32_t)(bb >> 32)), [slo] "s"((uint32_t)sb), [shi] "s"((uint32_t)(sb >> 32)),
                            [tstride] "s"(tstride), [wv] "s"(wave), [lds] "s"(lds),
                            [ldsend] "s"(lds + (uint32_t)(kStages * kStage)), [steps] "s"((uint32_t)S),
-                           [l16] "v"(l16), [l4] "v"(l4), [lg] "v"(lg)
+                           [l16] "v"(l16), [l4] "v"(l4), [g16] "v"(g16), [g12] "v"(g12), [g4] "v"(g4)
                          : DFP4_NATIVE_VGPR_CLOBBERS, DFP4_NATIVE_ACC_CLOBBERS, DFP4_NATIVE_SGPR_CLOBBERS, "m0", "scc",
                            "memory");
         else
@@ -169,7 +175,7 @@ __global__ __launch_bounds__(256, 1) void gemm_native_kernel(NativeParams p) {
                            [bhi] "s"((uint32_t)(bb >> 32)), [slo] "s"((uint32_t)sb), [shi] "s"((uint32_t)(sb >> 32)),
                            [tstride] "s"(tstride), [wv] "s"(wave), [lds] "s"(lds),
                            [ldsend] "s"(lds + (uint32_t)(kStages * kStage)), [steps] "s"((uint32_t)S),
-                           [l16] "v"(l16), [l4] "v"(l4), [lg] "v"(lg)
+                           [l16] "v"(l16), [l4] "v"(l4), [g16] "v"(g16), [g12] "v"(g12), [g4] "v"(g4)
                          : DFP4_NATIVE_VGPR_CLOBBERS, DFP4_NATIVE_ACC_CLOBBERS, DFP4_NATIVE_SGPR_CLOBBERS, "m0", "scc",
                            "memory");
     }
@@ -180,12 +186,17 @@ __global__ __launch_bounds__(256, 1) void gemm_native_kernel(NativeParams p) {
     const int m0 = blockIdx.y * 256 + wm * 128, n0 = blockIdx.x * 256 + wn * 128;
     if (m0 >= p.M || n0 >= p.N) return;
     constexpr int kEsz = BF16 ? 2 : 4;
-    uint8_t* wave_out = static_cast<uint8_t*>(p.out) + ((int64_t)m0 * p.ldc + n0) * kEsz;     // uniform
-    const int64_t row_bytes = p.ldc * kEsz;                                                    // uniform
+    // split K: the fp32 partial tile of this range goes to part[blockIdx.z] (the kernel is then the fp32 one)
+    const bool partial = p.ksplit > 1;
+    const int64_t ld = partial ? p.N : p.ldc;
+    uint8_t* base = partial ? reinterpret_cast<uint8_t*>(p.part + (int64_t)blockIdx.z * p.M * p.N)
+                            : static_cast<uint8_t*>(p.out);
+    uint8_t* wave_out = base + ((int64_t)m0 * ld + n0) * kEsz;                                 // uniform
+    const int64_t row_bytes = ld * kEsz;                                                       // uniform
     const bool full = m0 + 128 <= p.M && n0 + 128 <= p.N;                                      // uniform
     // bf16: lanes exchange values in pairs so that every lane stores two adjacent columns of one
     // row (even lanes the even row of a row pair, odd lanes the odd row)
-    const bool pairs = BF16 && full && (p.ldc & 1) == 0 && (reinterpret_cast<uintptr_t>(p.out) & 3) == 0;
+    const bool pairs = BF16 && full && (ld & 1) == 0 && (reinterpret_cast<uintptr_t>(base) & 3) == 0;
     const uint32_t lane_off = pairs ? (uint32_t)((4 * kh + (c & 1)) * row_bytes + (c & ~1) * kEsz)
                                     : (uint32_t)(4 * kh * row_bytes + c * kEsz);
     auto store_tile = [&](auto full_c, auto pairs_c, int t, int (&v)[16]) {
@@ -248,7 +259,27 @@ __global__ __launch_bounds__(256, 1) void gemm_native_kernel(NativeParams p) {
 #undef DFP4_NATIVE_STORE
 }
 
+// Split K: out = sum of the ranges' fp32 partial tiles, added in range order, converted once.
+template <bool BF16>
+__global__ __launch_bounds__(256) void native_reduce_kernel(const float* __restrict__ part, void* out, int M, int N,
+                                                            int64_t ldc, int ksplit) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x, total = (int64_t)M * N;
+    if (i >= total) return;
+    float s = part[i];
+    for (int z = 1; z < ksplit; ++z) s += part[(int64_t)z * total + i];
+    const int64_t m = i / N, o = m * ldc + (i - m * N);
+    if constexpr (BF16) static_cast<uint16_t*>(out)[o] = f32_to_bf16_rne_n(s);
+    else static_cast<float*>(out)[o] = s;
+}
+
 inline int64_t up256(int64_t x) { return (x + 255) & ~(int64_t)255; }
+// Workgroups per output tile: with fewer tiles than compute units K is split in 2 or 4 ranges
+inline int native_ksplit(int64_t M, int64_t N, int64_t KB) {
+    const int64_t tiles = ((M + 255) / 256) * ((N + 255) / 256), S = (KB + 1) / 2, cu = device_cu_count();
+    int s = 1;
+    while (s < 4 && tiles * s * 2 <= cu && S / (2 * s) >= 8) s *= 2;
+    return s;
+}
 // One packed operand: [bits | scales], rows padded to 256, eight steps of slack behind each array.
 struct OperandLayout { int64_t sc, total; };
 inline OperandLayout operand_layout(int64_t rows, int64_t KB, bool fp6) {
@@ -266,8 +297,14 @@ size_t native_packed_bytes(int64_t rows, int64_t K, bool fp6) {
     return (size_t)operand_layout(rows, K / kBlock, fp6).total;
 }
 
+size_t native_splitk_bytes(int64_t M, int64_t N, int64_t K) {
+    if (M == 0 || N == 0) return 0;
+    const int s = native_ksplit(M, N, K / kBlock);
+    return s > 1 ? (size_t)up256((int64_t)s * M * N * 4) : 0;
+}
+
 size_t gemm_native_workspace_bytes(int64_t M, int64_t N, int64_t K, bool fp6) {
-    return native_packed_bytes(M, K, fp6) + native_packed_bytes(N, K, fp6);
+    return native_packed_bytes(M, K, fp6) + native_packed_bytes(N, K, fp6) + native_splitk_bytes(M, N, K);
 }
 
 // Rewrite a quantized tensor in the matrix instruction's register order (see the file header).
@@ -290,8 +327,10 @@ int launch_native_pack(bool fp6, dfp4_tensor T, void* packed, size_t bytes, hipS
 }
 
 // out = A * W^T from two packed operands ([M, K] and [N, K] before packing)
+// `splitk` (may be null): native_splitk_bytes(M, N, K) bytes; without it K is never split
 int launch_gemm_native_packed(bool fp6, const void* a_packed, const void* w_packed, int64_t M, int64_t N, int64_t K,
-                              void* out, int out_dtype, int64_t ldc, hipStream_t stream) {
+                              void* out, int out_dtype, int64_t ldc, void* splitk, size_t splitk_bytes,
+                              hipStream_t stream) {
     const int64_t KB = K / kBlock;
     if (M == 0 || N == 0) return DFP4_OK;
     if (M >= (1 << 30) || N >= (1 << 30) || KB >= (1 << 20) || KB == 0 || ldc >= (1 << 27)) return DFP4_ERR_SHAPE;
@@ -301,15 +340,25 @@ int launch_gemm_native_packed(bool fp6, const void* a_packed, const void* w_pack
     p.a = PackedOperand{ap, reinterpret_cast<uint32_t*>(ap + operand_layout(M, KB, fp6).sc)};
     p.w = PackedOperand{wp, reinterpret_cast<uint32_t*>(wp + operand_layout(N, KB, fp6).sc)};
     p.out = out; p.M = (int)M; p.N = (int)N; p.S = (int)((KB + 1) / 2); p.ldc = ldc;
-    dim3 grid((unsigned)((N + 255) / 256), (unsigned)((M + 255) / 256));
+    p.ksplit = native_ksplit(M, N, KB);
+    if (p.ksplit > 1 && (!splitk || splitk_bytes < native_splitk_bytes(M, N, K))) p.ksplit = 1;
+    p.part = static_cast<float*>(splitk);
+    dim3 grid((unsigned)((N + 255) / 256), (unsigned)((M + 255) / 256), (unsigned)p.ksplit);
     if (grid.y > 65535) return DFP4_ERR_SHAPE;
-    const bool bf16 = out_dtype == DFP4_BF16;
+    const bool bf16 = out_dtype == DFP4_BF16 && p.ksplit == 1;     // partial tiles are fp32
     if (fp6) {
         if (bf16) hipLaunchKernelGGL((gemm_native_kernel<kFmtFp6, true>), grid, dim3(256), 0, stream, p);
         else hipLaunchKernelGGL((gemm_native_kernel<kFmtFp6, false>), grid, dim3(256), 0, stream, p);
     } else {
         if (bf16) hipLaunchKernelGGL((gemm_native_kernel<kFmtFp4, true>), grid, dim3(256), 0, stream, p);
         else hipLaunchKernelGGL((gemm_native_kernel<kFmtFp4, false>), grid, dim3(256), 0, stream, p);
+    }
+    if (p.ksplit > 1) {
+        const unsigned gr = (unsigned)((M * N + 255) / 256);
+        if (out_dtype == DFP4_BF16)
+            hipLaunchKernelGGL((native_reduce_kernel<true>), dim3(gr), dim3(256), 0, stream, p.part, out, p.M, p.N, ldc, p.ksplit);
+        else
+            hipLaunchKernelGGL((native_reduce_kernel<false>), dim3(gr), dim3(256), 0, stream, p.part, out, p.M, p.N, ldc, p.ksplit);
     }
     return check_launch();
 }

@@ -160,7 +160,7 @@ def entry(f):
           f"s_mul_i32 {sr(S_DA)}, %[wv], {2 * f.tile}", f"s_add_u32 {sr(S_DB)}, {sr(S_DA)}, {8 * f.tile}",
           f"s_lshl_b32 {sr(S_DS)}, %[wv], 8", f"s_add_u32 {sr(S_DS)}, {sr(S_DS)}, {16 * f.tile}"]
     o += [f"s_mov_b32 {sr(S_VC)}, 0", f"s_mov_b32 {sr(S_LD)}, %[lds]",
-          f"v_mov_b32 {vr(VOFF)}, %[l16]", f"v_mov_b32 {vr(VSOFF)}, %[l4]", f"v_mov_b32 {vr(VOFF2)}, %[lg]"]
+          f"v_mov_b32 {vr(VOFF)}, %[g16]", f"v_mov_b32 {vr(VSOFF)}, %[g4]", f"v_mov_b32 {vr(VOFF2)}, %[g12]"]
     # pipeline fill: steps 0, 1, 2 into stages 0, 1, 2
     for _ in range(f.dist):
         o += dst_setup()

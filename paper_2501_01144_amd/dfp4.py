@@ -28,6 +28,7 @@ SYMBOLS = [
     "dfp4_quantize", "dfp4_quantize_mse", "dfp4_quantize_t", "mxfp4_quantize_t", "dfp4_dequantize", "dfp4_gemm", "dfp4_gemm_batched", "dfp4_gemm_workspace_bytes",
     "mxfp4_gemm_native", "dfp4_gemm_native", "dfp4_gemm_native_workspace_bytes", "dfp4_native_packed_bytes",
     "dfp4_native_pack", "mxfp4_native_pack", "dfp4_gemm_native_packed_w", "mxfp4_gemm_native_packed_w",
+    "dfp4_gemm_native_packed", "mxfp4_gemm_native_packed", "dfp4_gemm_native_splitk_bytes",
     "dfp4_gemm_requant", "mxfp4_gemm_requant", "dfp4_gemm_requant_workspace_bytes",
     "mxfp4_quantize", "mxfp4_dequantize", "mxfp4_gemm", "dfp4_formatbook", "dfp4_strerror",
 ]
@@ -70,6 +71,11 @@ def load():
     for name in ("dfp4_native_pack", "mxfp4_native_pack"):
         getattr(lib, name).argtypes = [_CTensor, vp, ctypes.c_size_t, vp]
         getattr(lib, name).restype = ci
+    for name in ("dfp4_gemm_native_packed", "mxfp4_gemm_native_packed"):
+        getattr(lib, name).argtypes = [vp, i64, vp, i64, i64, vp, ci, i64, vp, ctypes.c_size_t, vp]
+        getattr(lib, name).restype = ci
+    lib.dfp4_gemm_native_splitk_bytes.argtypes = [i64, i64, i64]
+    lib.dfp4_gemm_native_splitk_bytes.restype = ctypes.c_size_t
     for name in ("dfp4_gemm_native_packed_w", "mxfp4_gemm_native_packed_w"):
         getattr(lib, name).argtypes = [_CTensor, vp, i64, vp, ci, i64, vp, ctypes.c_size_t, vp]
         getattr(lib, name).restype = ci
@@ -270,10 +276,11 @@ class PackedWeights:
     mx: bool
 
 
-def native_pack(w, mx=False):
-    """dfp4_native_pack / mxfp4_native_pack: pack a quantized tensor once (weights)."""
+def native_pack(w, mx=False, buf=None):
+    """dfp4_native_pack / mxfp4_native_pack: pack a quantized tensor (weights: once)."""
     n = int(load().dfp4_native_packed_bytes(w.rows, w.K))
-    buf = torch.empty(max(n, 256), dtype=torch.uint8, device=w.codes.device)
+    if buf is None:
+        buf = torch.empty(max(n, 256), dtype=torch.uint8, device=w.codes.device)
     fn = load().mxfp4_native_pack if mx else load().dfp4_native_pack
     _check(fn(w.c(), _ptr(buf), buf.numel(), _stream()), "native_pack")
     return PackedWeights(buf, w.rows, w.K, mx)
@@ -284,13 +291,30 @@ def gemm_native_packed_w(a, wp, dtype=torch.float32, out=None, workspace=None):
     if out is None:
         out = torch.empty((a.rows, wp.rows), dtype=dtype, device=a.codes.device)
     assert out.dtype in (torch.float32, torch.bfloat16) and out.stride(1) == 1 and a.K == wp.K
-    need = int(load().dfp4_native_packed_bytes(a.rows, a.K))
+    need = int(load().dfp4_native_packed_bytes(a.rows, a.K)) + \
+        int(load().dfp4_gemm_native_splitk_bytes(a.rows, wp.rows, a.K))
     if workspace is None:
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=out.device)
     fn = load().mxfp4_gemm_native_packed_w if wp.mx else load().dfp4_gemm_native_packed_w
     ldc = out.stride(0) if a.rows > 1 else wp.rows
     _check(fn(a.c(), _ptr(wp.buf), wp.rows, _ptr(out), F32 if out.dtype == torch.float32 else BF16, ldc,
               _ptr(workspace), workspace.numel(), _stream()), "gemm_native_packed_w")
+    return out
+
+
+def gemm_native_packed(ap, wp, dtype=torch.float32, out=None, workspace=None):
+    """dfp4_gemm_native_packed / mxfp4_gemm_native_packed: both operands packed beforehand."""
+    if out is None:
+        out = torch.empty((ap.rows, wp.rows), dtype=dtype, device=ap.buf.device)
+    need = int(load().dfp4_gemm_native_splitk_bytes(ap.rows, wp.rows, ap.K))
+    if workspace is None and need > 0:
+        workspace = torch.empty(need, dtype=torch.uint8, device=out.device)
+    assert out.dtype in (torch.float32, torch.bfloat16) and out.stride(1) == 1 and ap.K == wp.K and ap.mx == wp.mx
+    fn = load().mxfp4_gemm_native_packed if wp.mx else load().dfp4_gemm_native_packed
+    ldc = out.stride(0) if ap.rows > 1 else wp.rows
+    _check(fn(_ptr(ap.buf), ap.rows, _ptr(wp.buf), wp.rows, ap.K, _ptr(out),
+              F32 if out.dtype == torch.float32 else BF16, ldc, _ptr(workspace),
+              workspace.numel() if workspace is not None else 0, _stream()), "gemm_native_packed")
     return out
 
 

@@ -605,8 +605,9 @@ def test_gemm_native_with_prepacked_weights():
     wp = dfp4.native_pack(qw)
     out = dfp4.gemm_native_packed_w(qa, wp)
     both = dfp4.gemm_native(qa, qw)
+    both_packed = dfp4.gemm_native_packed(dfp4.native_pack(qa), wp)
     torch.cuda.synchronize()
-    assert torch.equal(out, both)
+    assert torch.equal(out, both) and torch.equal(both_packed, both)
     ref, absdot = _gemm_ref(synth.to_f64(a), synth.to_f64(w))
     _assert_gemm_close(out, ref, absdot, "prepacked fp6")
     qam, qwm = dfp4.mxfp4_quantize(_dev(a)), dfp4.mxfp4_quantize(_dev(w))
