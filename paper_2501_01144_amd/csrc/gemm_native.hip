@@ -156,7 +156,7 @@ __global__ __launch_bounds__(256, 1) void gemm_native_kernel(NativeParams p) {
             ? reinterpret_cast<uint64_t>(p.a.sc) + ((uint64_t)blockIdx.y * 2 + wave) * (uint64_t)p.S * 256
             : reinterpret_cast<uint64_t>(p.w.sc) + ((uint64_t)blockIdx.x * 2 + (wave - 2)) * (uint64_t)p.S * 256;
         const uint32_t l16 = (uint32_t)lane * 16u, l4 = (uint32_t)lane * 4u;
-        const uint32_t g16 = l16 + (uint32_t)s_lo * kGStride, g12 = (uint32_t)lane * 12u + 1024u + (uint32_t)s_lo * kGStride;
+        const uint32_t g16 = l16 + (uint32_t)s_lo * kGStride, g12 = (uint32_t)lane * 12u + (uint32_t)s_lo * kGStride;
         const uint32_t g4 = l4 + (uint32_t)s_lo * 256u;
         if constexpr (kFp6)
             asm volatile(DFP4_NATIVE_LOOP_FP6

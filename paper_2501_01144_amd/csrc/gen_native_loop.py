@@ -22,18 +22,20 @@ for FP6: two 1 KiB halves) + 4 x 256 bytes of scales (A groups 0, 1, B groups 0,
 
 Registers (fixed): a[0:255] accumulators; v[40:87] / v[88:135] operand sets (A tile i at
 +6 i, B tile j at +24 + 6 j); v136..v139 scale dwords (A, B of set 0; A, B of set 1);
-v140..v143 LDS read addresses (A, B, scales A, B), v144 / v145 / v146 global offsets (operands, scales, second
-halves); s[60:69] global bases of the wave's five chunks, s70 step, s72 / s73 LDS address
-of the stage read next / loaded next, s74..s76 scratch, s77..s83 the wave's offsets inside
-a stage.
+v144 / v145 / v146 global offsets (operands, scales, second halves), v150.. LDS read bases
+(the loop is unrolled over the stages, so a stage is a base register plus an immediate);
+s[60:69] global bases of the wave's five chunks, s70 step, s74 / s75 scratch, s77..s83 the
+wave's LDS addresses inside stage 0 (reads: A, B, scales A, B; loads: A, B, scales).
 """
 import os
 
 FR = [40, 88]
 SA = [136, 138]
 SB = [137, 139]
-VA, VB, VSA, VSB, VOFF, VSOFF, VOFF2 = 140, 141, 142, 143, 144, 145, 146
-S_BASE, S_VC, S_RD, S_LD, S_T0, S_T1, S_T2 = 60, 70, 72, 73, 74, 75, 76
+VOFF, VSOFF, VOFF2 = 144, 145, 146
+VBASE = 150                      # LDS read bases: group q at VBASE + 4 q: operands A, B, scales A, B
+S_BASE, S_VC = 60, 70
+S_T0, S_T1 = 74, 75
 S_RA, S_RB, S_RSA, S_RSB, S_DA, S_DB, S_DS = 77, 78, 79, 80, 81, 82, 83
 
 
@@ -56,61 +58,46 @@ class Fmt:
         self.per_step = 9 if fp6 else 5              # direct loads per wave and step
         self.nst = 4 if fp6 else 8                   # LDS stages (FP6: 4 x 33 KiB, FP4: 8 x 17 KiB)
         self.dist = self.nst - 1                     # loads run this many steps ahead
+        # LDS reads address a stage as (base register of its group) + immediate (< 64 KiB)
+        self.per_group = max(1, (65535 - (3 * self.tile + 1024 + 16)) // self.stage)
+        self.groups = (self.nst + self.per_group - 1) // self.per_group
 
 
-def frag_reads(f, p):
-    """LDS reads of a step's operands into register set p (addresses VA, VB, VSA, VSB)."""
+def frag_reads(f, p, stage):
+    """LDS reads of the operands held in `stage` into register set p."""
+    q, off = stage // f.per_group, (stage % f.per_group) * f.stage
+    va, vb, vsa, vsb = (VBASE + 4 * q + i for i in range(4))
     o = []
-    for side, va in ((0, VA), (1, VB)):
+    for side, v in ((0, va), (1, vb)):
         for t in range(4):
             r = FR[p] + 24 * side + 6 * t
+            o.append(f"ds_read_b128 {vr(r, 4)}, {vr(v)} offset:{off + t * f.tile}")
             if f.fp6:
-                o.append(f"ds_read_b128 {vr(r, 4)}, {vr(va)} offset:{t * f.tile}")
-                o.append(f"ds_read_b64 {vr(r + 4, 2)}, {vr(va)} offset:{t * f.tile + 1024}")
-            else:
-                o.append(f"ds_read_b128 {vr(r, 4)}, {vr(va)} offset:{t * f.tile}")
-    o.append(f"ds_read_b32 {vr(SA[p])}, {vr(VSA)}")
-    o.append(f"ds_read_b32 {vr(SB[p])}, {vr(VSB)}")
+                o.append(f"ds_read_b64 {vr(r + 4, 2)}, {vr(v)} offset:{off + t * f.tile + 1024}")
+    o.append(f"ds_read_b32 {vr(SA[p])}, {vr(vsa)} offset:{off}")
+    o.append(f"ds_read_b32 {vr(SB[p])}, {vr(vsb)} offset:{off}")
     return o
 
 
-def dma_ops(f):
-    """(m0 setup, load) pairs of one step's direct loads of this wave; S_T0 / S_T1 / S_T2 hold
-    the LDS addresses of its A, B and scale destinations in the stage being loaded."""
+def dma_groups(f, stage):
+    """Direct loads of one step of this wave into `stage`, as groups (m0 setup, [loads that use it]).
+    An instruction offset applies to the global and to the LDS address alike, and the second half of an
+    FP6 chunk sits 1024 bytes behind the first in both, so the two halves share one m0."""
     o = []
-    for side, dst in ((0, S_T0), (1, S_T1)):
+    for side, dst in ((0, S_DA), (1, S_DB)):
         for k in range(2):
             base = sr(S_BASE + 4 * side + 2 * k, 2)
+            loads = [f"global_load_lds_dwordx4 {vr(VOFF)}, {base}"]
             if f.fp6:
-                o.append((f"s_add_u32 m0, {sr(dst)}, {k * f.tile}", f"global_load_lds_dwordx4 {vr(VOFF)}, {base}"))
-                o.append((f"s_add_u32 m0, {sr(dst)}, {k * f.tile + 1024}",
-                          f"global_load_lds_dwordx3 {vr(VOFF2)}, {base}"))
-            else:
-                o.append((f"s_add_u32 m0, {sr(dst)}, {k * f.tile}", f"global_load_lds_dwordx4 {vr(VOFF)}, {base}"))
-    o.append((f"s_mov_b32 m0, {sr(S_T2)}", f"global_load_lds_dword {vr(VSOFF)}, {sr(S_BASE + 8, 2)}"))
+                loads.append(f"global_load_lds_dwordx3 {vr(VOFF2)}, {base} offset:1024")
+            o.append((f"s_add_u32 m0, {sr(dst)}, {stage * f.stage + k * f.tile}", loads))
+    o.append((f"s_add_u32 m0, {sr(S_DS)}, {stage * f.stage}", [f"global_load_lds_dword {vr(VSOFF)}, {sr(S_BASE + 8, 2)}"]))
     return o
 
 
-def dst_setup():
-    return [f"s_add_u32 {sr(S_T0)}, {sr(S_LD)}, {sr(S_DA)}", f"s_add_u32 {sr(S_T1)}, {sr(S_LD)}, {sr(S_DB)}",
-            f"s_add_u32 {sr(S_T2)}, {sr(S_LD)}, {sr(S_DS)}"]
-
-
-def advance_load_stage(f):
-    """next LDS stage to load (wraps), next global step"""
-    return [f"s_add_u32 {sr(S_LD)}, {sr(S_LD)}, {f.stage}", f"s_cmp_lt_u32 {sr(S_LD)}, %[ldsend]",
-            f"s_cselect_b32 {sr(S_LD)}, {sr(S_LD)}, %[lds]",
-            f"v_add_u32 {vr(VOFF)}, {f.gstride}, {vr(VOFF)}", f"v_add_u32 {vr(VSOFF)}, 0x100, {vr(VSOFF)}"] + (
-                [f"v_add_u32 {vr(VOFF2)}, {f.gstride}, {vr(VOFF2)}"] if f.fp6 else [])
-
-
-def read_addr(f):
-    return [f"s_add_u32 {sr(S_RD)}, {sr(S_RD)}, {f.stage}", f"s_cmp_lt_u32 {sr(S_RD)}, %[ldsend]",
-            f"s_cselect_b32 {sr(S_RD)}, {sr(S_RD)}, %[lds]",
-            f"s_add_u32 {sr(S_T0)}, {sr(S_RD)}, {sr(S_RA)}", f"v_add_u32 {vr(VA)}, {sr(S_T0)}, %[l16]",
-            f"s_add_u32 {sr(S_T0)}, {sr(S_RD)}, {sr(S_RB)}", f"v_add_u32 {vr(VB)}, {sr(S_T0)}, %[l16]",
-            f"s_add_u32 {sr(S_T0)}, {sr(S_RD)}, {sr(S_RSA)}", f"v_add_u32 {vr(VSA)}, {sr(S_T0)}, %[l4]",
-            f"s_add_u32 {sr(S_T0)}, {sr(S_RD)}, {sr(S_RSB)}", f"v_add_u32 {vr(VSB)}, {sr(S_T0)}, %[l4]"]
+def advance_global(f):
+    return [f"v_add_u32 {vr(VOFF)}, {f.gstride}, {vr(VOFF)}", f"v_add_u32 {vr(VSOFF)}, 0x100, {vr(VSOFF)}"] + (
+        [f"v_add_u32 {vr(VOFF2)}, {f.gstride}, {vr(VOFF2)}"] if f.fp6 else [])
 
 
 def mfma(f, p, k):
@@ -122,23 +109,30 @@ def mfma(f, p, k):
             f"op_sel:[{i & 1},{j & 1},0] op_sel_hi:[{i >> 1},{j >> 1},0] cbsz:{f.code} blgp:{f.code}")
 
 
-def step(f, p):
+def step(f, u):
+    """Step number u (mod the number of stages): multiplies register set u % 2, reads the operands of
+    the next step from stage (u + 1) % nst, loads stage (u + dist) % nst = (u - 1) % nst."""
+    p = u % 2
     o = [f"s_cmp_lt_u32 {sr(S_VC)}, %[steps]", "s_cbranch_scc0 99f"]
-    o += read_addr(f)                                       # LDS addresses of step s + 1's operands
-    reads = frag_reads(f, 1 - p)
-    dmas = dma_ops(f)
+    reads = frag_reads(f, 1 - p, (u + 1) % f.nst)
+    dmas = dma_groups(f, (u + f.dist) % f.nst)
+    # after the barrier: every m0 setup is followed by an LDS read (m0 needs one instruction before its use)
+    tail = []
+    for m0, loads in dmas:
+        tail.append([m0] + ([reads.pop(0)] if reads else ["s_nop 0"]) + loads)
+    while reads:
+        tail.append([reads.pop(0)] + ([reads.pop(0)] if reads else []))
+    per = (len(tail) + 11) // 12      # spread evenly: bunching the memory instructions is slower
     for k in range(16):
         o.append(mfma(f, p, k))
         if k == 2:
             # the loads of step s + 1 have landed; those of the steps after it may be pending
-            o += [f"s_waitcnt vmcnt({(f.dist - 2) * f.per_step})", "s_barrier"] + dst_setup()
+            o += [f"s_waitcnt vmcnt({(f.dist - 2) * f.per_step})", "s_barrier"]
         if k >= 3:
-            n_r = (len(reads) + 12) // 13
-            o += reads[(k - 3) * n_r:(k - 2) * n_r]
-            n_d = (len(dmas) + 12) // 13
-            for m0, ld in dmas[(k - 3) * n_d:(k - 2) * n_d]:
-                o += [m0, "s_nop 0", ld]
-    o += advance_load_stage(f)
+            for grp in tail[(k - 3) * per:(k - 2) * per]:
+                o += grp
+        if k == 15:
+            o += advance_global(f)
     o += [f"s_add_u32 {sr(S_VC)}, {sr(S_VC)}, 1", "s_waitcnt lgkmcnt(0)"]
     return o
 
@@ -151,34 +145,41 @@ def entry(f):
           f"s_mov_b32 {sr(S_BASE + 4)}, %[blo]", f"s_mov_b32 {sr(S_BASE + 5)}, %[bhi]",
           f"s_add_u32 {sr(S_BASE + 6)}, %[blo], %[tstride]", f"s_addc_u32 {sr(S_BASE + 7)}, %[bhi], 0",
           f"s_mov_b32 {sr(S_BASE + 8)}, %[slo]", f"s_mov_b32 {sr(S_BASE + 9)}, %[shi]"]
-    # the wave's offsets inside a stage: wm = wv >> 1, wn = wv & 1
+    # the wave's LDS addresses inside stage 0: wm = wv >> 1, wn = wv & 1
     o += [f"s_lshr_b32 {sr(S_T0)}, %[wv], 1", f"s_and_b32 {sr(S_T1)}, %[wv], 1",
-          f"s_mul_i32 {sr(S_RA)}, {sr(S_T0)}, {4 * f.tile}",
+          f"s_mul_i32 {sr(S_RA)}, {sr(S_T0)}, {4 * f.tile}", f"s_add_u32 {sr(S_RA)}, {sr(S_RA)}, %[lds]",
           f"s_mul_i32 {sr(S_RB)}, {sr(S_T1)}, {4 * f.tile}", f"s_add_u32 {sr(S_RB)}, {sr(S_RB)}, {8 * f.tile}",
+          f"s_add_u32 {sr(S_RB)}, {sr(S_RB)}, %[lds]",
           f"s_lshl_b32 {sr(S_RSA)}, {sr(S_T0)}, 8", f"s_add_u32 {sr(S_RSA)}, {sr(S_RSA)}, {16 * f.tile}",
+          f"s_add_u32 {sr(S_RSA)}, {sr(S_RSA)}, %[lds]",
           f"s_lshl_b32 {sr(S_RSB)}, {sr(S_T1)}, 8", f"s_add_u32 {sr(S_RSB)}, {sr(S_RSB)}, {16 * f.tile + 512}",
-          f"s_mul_i32 {sr(S_DA)}, %[wv], {2 * f.tile}", f"s_add_u32 {sr(S_DB)}, {sr(S_DA)}, {8 * f.tile}",
-          f"s_lshl_b32 {sr(S_DS)}, %[wv], 8", f"s_add_u32 {sr(S_DS)}, {sr(S_DS)}, {16 * f.tile}"]
-    o += [f"s_mov_b32 {sr(S_VC)}, 0", f"s_mov_b32 {sr(S_LD)}, %[lds]",
+          f"s_add_u32 {sr(S_RSB)}, {sr(S_RSB)}, %[lds]",
+          f"s_mul_i32 {sr(S_DA)}, %[wv], {2 * f.tile}", f"s_add_u32 {sr(S_DA)}, {sr(S_DA)}, %[lds]",
+          f"s_add_u32 {sr(S_DB)}, {sr(S_DA)}, {8 * f.tile}",
+          f"s_lshl_b32 {sr(S_DS)}, %[wv], 8", f"s_add_u32 {sr(S_DS)}, {sr(S_DS)}, {16 * f.tile}",
+          f"s_add_u32 {sr(S_DS)}, {sr(S_DS)}, %[lds]"]
+    for q in range(f.groups):
+        goff = q * f.per_group * f.stage
+        for i, (s, lane) in enumerate(((S_RA, "%[l16]"), (S_RB, "%[l16]"), (S_RSA, "%[l4]"), (S_RSB, "%[l4]"))):
+            o += [f"s_add_u32 {sr(S_T0)}, {sr(s)}, {goff}", f"v_add_u32 {vr(VBASE + 4 * q + i)}, {sr(S_T0)}, {lane}"]
+    o += [f"s_mov_b32 {sr(S_VC)}, 0",
           f"v_mov_b32 {vr(VOFF)}, %[g16]", f"v_mov_b32 {vr(VSOFF)}, %[g4]", f"v_mov_b32 {vr(VOFF2)}, %[g12]"]
-    # pipeline fill: steps 0, 1, 2 into stages 0, 1, 2
-    for _ in range(f.dist):
-        o += dst_setup()
-        for m0, ld in dma_ops(f):
-            o += [m0, "s_nop 0", ld]
-        o += advance_load_stage(f)
-    # step 0's operands into set 0 (S_RD is advanced before use: start one stage "before" stage 0)
-    o += [f"s_waitcnt vmcnt({(f.dist - 1) * f.per_step})", "s_barrier",
-          f"s_add_u32 {sr(S_RD)}, %[lds], {(f.nst - 1) * f.stage}"]
-    o += read_addr(f) + frag_reads(f, 0) + ["s_waitcnt lgkmcnt(0)"]
+    # pipeline fill: steps 0 .. dist-1 into stages 0 .. dist-1
+    for st in range(f.dist):
+        for m0, loads in dma_groups(f, st):
+            o += [m0, "s_nop 0"] + loads
+        o += advance_global(f)
+    # step 0's operands into set 0
+    o += [f"s_waitcnt vmcnt({(f.dist - 1) * f.per_step})", "s_barrier"]
+    o += frag_reads(f, 0, 0) + ["s_waitcnt lgkmcnt(0)"]
     return o
 
 
 def main_loop(f):
     o = entry(f)
     o.append("80:")
-    for p in range(2):
-        o += step(f, p)
+    for u in range(f.nst):
+        o += step(f, u)
     o.append("s_branch 80b")
     o += ["99:", "s_waitcnt vmcnt(0) lgkmcnt(0)", "s_nop 15", "s_nop 15", "s_nop 15", "s_nop 15"]
     return o
@@ -196,7 +197,7 @@ def main():
     for g in range(16):
         rd = [f"v_accvgpr_read_b32 %{i}, a{16 * g + i}" for i in range(16)]
         parts.append(f"#define DFP4_NATIVE_ACC_READ_{g} \\\n" + c_string(rd) + "\n")
-    vclob = ", ".join(f'"v{n}"' for n in range(40, 148))
+    vclob = ", ".join(f'"v{n}"' for n in range(40, 170))
     aclob = ", ".join(f'"a{n}"' for n in range(256))
     sclob = ", ".join(f'"s{n}"' for n in range(S_BASE, S_DS + 1))
     parts.append(f"#define DFP4_NATIVE_VGPR_CLOBBERS {vclob}\n")
