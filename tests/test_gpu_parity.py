@@ -615,3 +615,37 @@ def test_gemm_native_with_prepacked_weights():
     torch.cuda.synchronize()
     refm, absm = _gemm_ref(synth.to_f64(a), synth.to_f64(w), mx=True)
     _assert_gemm_close(outm, refm, absm, "prepacked fp4 bf16", bf16=True)
+
+
+def test_gemm_random_edge_shapes_all_paths():
+    # seeded sweep over awkward shapes (sizes around the tile boundaries, odd block counts) and three
+    # input recipes; every GEMM path against the oracle, the requantizing one against its composition
+    rng = np.random.default_rng(2024)
+    for it in range(14):
+        M = int(rng.choice([1, 31, 33, 65, 127, 129, 257, 300, 513, 700]))
+        N = int(rng.choice([1, 7, 33, 96, 130, 256, 257, 520]))
+        KB = int(rng.choice([1, 3, 8, 15, 17, 33, 65]))
+        K, kind = KB * 32, int(rng.integers(0, 3))
+        print(f"gemm sweep {it}: {M}x{N}x{K} recipe {kind}", flush=True)
+        g = torch.Generator().manual_seed(int(rng.integers(1 << 30)))
+        a = torch.randn(M, K, generator=g)
+        if kind == 1:
+            a[:, rng.integers(0, K, max(1, K // 100))] *= 50
+        if kind == 2:
+            a = a * torch.exp2(torch.randint(-12, 12, (M, KB), generator=g).repeat_interleave(32, dim=1).float())
+        a = a.to(torch.bfloat16)
+        w = (torch.randn(N, K, generator=g) * 0.02).to(torch.bfloat16)
+        ref, absdot = _gemm_ref(synth.to_f64(a), synth.to_f64(w))
+        qa, qw = dfp4.quantize(_dev(a)), dfp4.quantize(_dev(w))
+        _assert_gemm_close(dfp4.gemm(qa, qw), ref, absdot, f"int8 path {M}x{N}x{K}")
+        _assert_gemm_close(dfp4.gemm_native(qa, qw), ref, absdot, f"native path {M}x{N}x{K}")
+        if N % 32 == 0:
+            rq = dfp4.gemm_requant(qa, qw)
+            want = dfp4.quantize(dfp4.gemm(qa, qw, dtype=torch.bfloat16))
+            torch.cuda.synchronize()
+            assert torch.equal(rq.codes, want.codes) and torch.equal(rq.dialect, want.dialect)
+            assert torch.equal(rq.exponent, want.exponent)
+        refm, absm = _gemm_ref(synth.to_f64(a), synth.to_f64(w), mx=True)
+        qam, qwm = dfp4.mxfp4_quantize(_dev(a)), dfp4.mxfp4_quantize(_dev(w))
+        _assert_gemm_close(dfp4.mxfp4_gemm(qam, qwm), refm, absm, f"mx int8 path {M}x{N}x{K}")
+        _assert_gemm_close(dfp4.mxfp4_gemm_native(qam, qwm), refm, absm, f"mx native path {M}x{N}x{K}")
