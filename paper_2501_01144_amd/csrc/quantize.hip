@@ -82,38 +82,51 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(
     }
     __syncthreads();
 
+    // Rolling loads: as soon as pass p of a super-chunk has been computed, its registers receive
+    // pass p of the wave's next super-chunk, so that three or four loads per lane are in flight
+    // all the time and memory traffic never pauses for the arithmetic.
     while (sc < nsuper) {
-        // Rolling loads: as soon as pass p of this super-chunk has been computed, its registers
-        // receive pass p of the wave's next super-chunk, so that three or four loads per lane
-        // are in flight all the time and memory traffic never pauses for the arithmetic.
         const uint32_t nsc = sc + stride;
-        const bool full = sc * 64u + 64u <= nblocks;                      // wave-uniform
-        const bool next_fast = CONTIG && nsc < nsuper && nsc * 64u + 64u <= nblocks;   // wave-uniform
-        const uint4* nbase = reinterpret_cast<const uint4*>(x + (size_t)nsc * (64u * kBlock));
         uint32_t eb[kPasses], dl[kPasses];
         uint32_t* cdst = codes + (size_t)sc * 256u;           // code dword of (pass p, lane): p * 64 + lane
-#pragma unroll
-        for (int p = 0; p < kPasses; ++p) {
-            uint32_t code;
-            if constexpr (MX) {
-                mxfp4_pass(w[p], lds_q, code, eb[p]);
-                dl[p] = 0;
-            } else {
-                dfp4_pass(w[p], lds_s, lds_q, code, eb[p], dl[p]);
-            }
-            if (full || sc * 64u + p * kBlocksPerPass + quad_id < nblocks) cdst[p * 64 + lane] = code;
-            if (next_fast) w[p] = nbase[p * 64 + lane];
-        }
-        if (!next_fast && nsc < nsuper) load_super<CONTIG>(x, ld, blocks_per_row, nblocks, nsc, lane, w);
-        // lane (quad_id, sub) stores the per-block bytes of pass `sub`:
-        // one byte-store instruction covers the wave's 64 consecutive blocks
-        const uint32_t e_sel = sub == 0 ? eb[0] : sub == 1 ? eb[1] : sub == 2 ? eb[2] : eb[3];
         const uint32_t bm = sc * 64u + sub * kBlocksPerPass + quad_id;
-        if (full || bm < nblocks) {
-            exponent[bm] = (uint8_t)e_sel;
-            if constexpr (!MX) {
-                const uint32_t d_sel = sub == 0 ? dl[0] : sub == 1 ? dl[1] : sub == 2 ? dl[2] : dl[3];
-                dialect[bm] = (uint8_t)d_sel;
+        if (CONTIG && nsc < nsuper && nsc * 64u + 64u <= nblocks) {
+            // this super-chunk and the next are complete: no bounds checks at all (wave-uniform branch)
+            const uint4* nbase = reinterpret_cast<const uint4*>(x + (size_t)nsc * (64u * kBlock));
+#pragma unroll
+            for (int p = 0; p < kPasses; ++p) {
+                uint32_t code;
+                if constexpr (MX) {
+                    mxfp4_pass(w[p], lds_q, code, eb[p]);
+                    dl[p] = 0;
+                } else {
+                    dfp4_pass(w[p], lds_s, lds_q, code, eb[p], dl[p]);
+                }
+                cdst[p * 64 + lane] = code;
+                w[p] = nbase[p * 64 + lane];
+            }
+            // lane (quad_id, sub) stores the per-block bytes of pass `sub`:
+            // one byte-store instruction covers the wave's 64 consecutive blocks
+            exponent[bm] = (uint8_t)(sub == 0 ? eb[0] : sub == 1 ? eb[1] : sub == 2 ? eb[2] : eb[3]);
+            if constexpr (!MX) dialect[bm] = (uint8_t)(sub == 0 ? dl[0] : sub == 1 ? dl[1] : sub == 2 ? dl[2] : dl[3]);
+        } else {
+            const bool full = sc * 64u + 64u <= nblocks;          // wave-uniform
+#pragma unroll
+            for (int p = 0; p < kPasses; ++p) {
+                uint32_t code;
+                if constexpr (MX) {
+                    mxfp4_pass(w[p], lds_q, code, eb[p]);
+                    dl[p] = 0;
+                } else {
+                    dfp4_pass(w[p], lds_s, lds_q, code, eb[p], dl[p]);
+                }
+                if (full || sc * 64u + p * kBlocksPerPass + quad_id < nblocks) cdst[p * 64 + lane] = code;
+            }
+            if (nsc < nsuper) load_super<CONTIG>(x, ld, blocks_per_row, nblocks, nsc, lane, w);
+            if (full || bm < nblocks) {
+                exponent[bm] = (uint8_t)(sub == 0 ? eb[0] : sub == 1 ? eb[1] : sub == 2 ? eb[2] : eb[3]);
+                if constexpr (!MX)
+                    dialect[bm] = (uint8_t)(sub == 0 ? dl[0] : sub == 1 ? dl[1] : sub == 2 ? dl[2] : dl[3]);
             }
         }
         sc = nsc;
