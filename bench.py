@@ -266,17 +266,16 @@ def main():
     hbuf = torch.empty(max(int(lib.dfp4_native_packed_bytes(M, I)), 256), dtype=torch.uint8, device=dev)
     ws_n = torch.empty(max(int(lib.dfp4_gemm_native_splitk_bytes(M, H, I)),
                            int(lib.dfp4_gemm_native_splitk_bytes(M, I, H)), 256), dtype=torch.uint8, device=dev)
-    nnames = ["quantize_x", "pack_x", "gemm_gate", "gemm_up", "quantize_h", "pack_h", "gemm_down"]
+    nnames = ["quantize_native_x", "gemm_gate", "gemm_up", "quantize_native_h", "gemm_down"]
     packed = {}
 
     def step_native(ev=None):
         calls = [
-            lambda: dfp4.quantize(x, out=qx),
-            lambda: packed.__setitem__("x", dfp4.native_pack(qx, buf=xbuf)),      # once for gate and up
+            # online quantization straight into the matrix instruction's operand order, once for gate and up
+            lambda: packed.__setitem__("x", dfp4.quantize_native(x, buf=xbuf)),
             lambda: dfp4.gemm_native_packed(packed["x"], wpk["w_gate"], out=gate, workspace=ws_n),
             lambda: dfp4.gemm_native_packed(packed["x"], wpk["w_up"], out=up, workspace=ws_n),
-            lambda: dfp4.quantize(h, out=qh),
-            lambda: packed.__setitem__("h", dfp4.native_pack(qh, buf=hbuf)),
+            lambda: packed.__setitem__("h", dfp4.quantize_native(h, buf=hbuf)),
             lambda: dfp4.gemm_native_packed(packed["h"], wpk["w_down"], out=down, workspace=ws_n),
         ]
         for i, c in enumerate(calls):
@@ -300,9 +299,9 @@ def main():
     n_gemm_ms = sum(nk[n] for n in gemm_ops)
     n_tops = total_ops / (n_gemm_ms * 1e-3) / 1e12
     out["native_fp6_step"] = {
-        "what": "same step with dfp4_native_pack + dfp4_gemm_native_packed (v_mfma_scale_f32_32x32x64_f8f6f4, "
+        "what": "same step with dfp4_quantize_native + dfp4_gemm_native_packed (v_mfma_scale_f32_32x32x64_f8f6f4, "
                 "FP6 E2M3 operands, fp32 accumulation in the matrix core); weights packed beforehand, each "
-                "activation packed once inside the step",
+                "activation quantized online straight into the packed form",
         "ms_per_step": round(ms_n, 4), "TOPs": round(total_ops / (ms_n * 1e-3) / 1e12, 1), "steps": nn,
         "kernel_ms": {k: round(v, 4) for k, v in nk.items()},
         "roofline": {"bound": "mfma", "kernel": "dfp4_gemm_native_packed call = gemm_native_kernel "

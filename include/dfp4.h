@@ -181,6 +181,11 @@ size_t dfp4_gemm_native_workspace_bytes(int64_t M, int64_t N, int64_t K);
  * dfp4_gemm_native_splitk_bytes(M, N, K) bytes.
  */
 size_t dfp4_native_packed_bytes(int64_t rows, int64_t K);
+/* Online DialectFP4 quantization (as dfp4_quantize) straight into the packed form: equal to
+ * dfp4_quantize followed by dfp4_native_pack, except that the layout's padding rows are left
+ * untouched (they only reach outputs that are never stored).  x as for dfp4_quantize. */
+int dfp4_quantize_native(const void* x_bf16, int64_t rows, int64_t K, int64_t ld_elems, void* packed,
+                         size_t bytes, void* stream);
 int dfp4_native_pack(dfp4_tensor T, void* packed, size_t bytes, void* stream);
 int mxfp4_native_pack(dfp4_tensor T, void* packed, size_t bytes, void* stream);
 int dfp4_gemm_native_packed_w(dfp4_tensor A, const void* w_packed, int64_t N, void* out, int out_dtype,

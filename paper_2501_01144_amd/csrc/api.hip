@@ -239,6 +239,17 @@ static int native_pack_common(bool fp6, dfp4_tensor T, void* packed, size_t byte
     return launch_native_pack(fp6, T, packed, bytes, static_cast<hipStream_t>(stream));
 }
 
+int dfp4_quantize_native(const void* x_bf16, int64_t rows, int64_t K, int64_t ld_elems, void* packed, size_t bytes,
+                         void* stream) {
+    if (rows < 0 || K < 0 || K % kBlock != 0 || ld_elems < K) return DFP4_ERR_SHAPE;
+    if (rows == 0 || K == 0) return DFP4_OK;
+    if (!x_bf16 || !packed) return DFP4_ERR_NULL;
+    if (ld_elems % 8 != 0 || !aligned(x_bf16, 16) || !aligned(packed, 256)) return DFP4_ERR_ALIGN;
+    if (bytes < native_packed_bytes(rows, K, true)) return DFP4_ERR_WORKSPACE;
+    return launch_quantize_native(x_bf16, rows, K, ld_elems, packed, native_scale_offset(rows, K, true),
+                                  static_cast<hipStream_t>(stream));
+}
+
 int dfp4_native_pack(dfp4_tensor T, void* packed, size_t bytes, void* stream) {
     return native_pack_common(true, T, packed, bytes, stream);
 }

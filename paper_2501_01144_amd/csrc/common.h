@@ -25,6 +25,9 @@ int launch_quantize(bool mx, const void* x, int64_t rows, int64_t K, int64_t ld,
                     hipStream_t stream);
 int launch_quantize_t(bool mx, const void* x, int64_t rows, int64_t cols, int64_t ld, dfp4_tensor out,
                       hipStream_t stream);
+int launch_quantize_native(const void* x, int64_t rows, int64_t K, int64_t ld, void* packed, size_t sc_offset,
+                           hipStream_t stream);
+size_t native_scale_offset(int64_t rows, int64_t K, bool fp6);
 int launch_quantize_mse(const void* x, int64_t rows, int64_t K, int64_t ld, dfp4_tensor out, hipStream_t stream);
 int launch_dequantize(bool mx, dfp4_tensor in, void* y, int y_dtype, int64_t ld, hipStream_t stream);
 int launch_gemm(bool mx, dfp4_tensor A, dfp4_tensor W, void* out, int out_dtype, int64_t ldc,

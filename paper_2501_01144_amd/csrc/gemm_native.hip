@@ -29,6 +29,7 @@
 #include <type_traits>
 #include "common.h"
 #include "formatbook.h"
+#include "fp6_pack.h"
 #include "gemm_native_asm.inc"
 
 namespace dfp4 {
@@ -70,30 +71,6 @@ struct PackParams {
     PackedOperand dst;
     int rows, KB, S;
 };
-
-// E2M3 bit pattern of the magnitude 0.5 u, u = 0..15 (all exact: step 1/8 below 1, 1/4 below 4, 1/2 below 8)
-constexpr uint8_t e2m3_of_half_units(int u) {
-    return u < 2 ? (uint8_t)(4 * u) : u < 4 ? (uint8_t)(8 + 4 * (u - 2)) : u < 8 ? (uint8_t)(16 + 2 * (u - 4))
-                                                                                 : (uint8_t)(24 + (u - 8));
-}
-struct Fp6Book { uint32_t w[kDialects][2]; };   // [dialect] -> 8 six-bit magnitudes, one per byte
-constexpr Fp6Book make_fp6_book() {
-    Fp6Book b{};
-    for (int d = 0; d < kDialects; ++d)
-        for (int j = 0; j < 8; ++j) b.w[d][j / 4] |= (uint32_t)e2m3_of_half_units(kBook[d][j]) << (8 * (j % 4));
-    return b;
-}
-__device__ const Fp6Book g_fp6_book = make_fp6_book();
-
-// 8 codes (one dword) -> 48 bits: 8 six-bit values, element j in bits [6 j, 6 j + 6)
-__device__ __forceinline__ uint64_t pack6(uint32_t c, uint32_t tlo, uint32_t thi) {
-    const uint32_t ie = c & 0x07070707u, io = (c >> 4) & 0x07070707u;
-    const uint32_t e = __builtin_amdgcn_perm(thi, tlo, ie) | ((c << 2) & 0x20202020u);   // elements 0, 2, 4, 6
-    const uint32_t o = __builtin_amdgcn_perm(thi, tlo, io) | ((c >> 2) & 0x20202020u);   // elements 1, 3, 5, 7
-    const uint32_t lo24 = (e & 0x3fu) | ((o & 0x3fu) << 6) | (((e >> 8) & 0x3fu) << 12) | (((o >> 8) & 0x3fu) << 18);
-    const uint32_t hi24 = ((e >> 16) & 0x3fu) | (((o >> 16) & 0x3fu) << 6) | ((e >> 24) << 12) | ((o >> 24) << 18);
-    return (uint64_t)lo24 | ((uint64_t)hi24 << 24);
-}
 
 // One wave per (row tile, step); lane (kh, c) takes row 32 tile + c, block 2 step + kh.
 template <int FMT>
@@ -295,6 +272,10 @@ inline OperandLayout operand_layout(int64_t rows, int64_t KB, bool fp6) {
 size_t native_packed_bytes(int64_t rows, int64_t K, bool fp6) {
     if (rows == 0 || K == 0) return 0;
     return (size_t)operand_layout(rows, K / kBlock, fp6).total;
+}
+
+size_t native_scale_offset(int64_t rows, int64_t K, bool fp6) {
+    return (size_t)operand_layout(rows, K / kBlock, fp6).sc;
 }
 
 size_t native_splitk_bytes(int64_t M, int64_t N, int64_t K) {

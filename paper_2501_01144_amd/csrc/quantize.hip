@@ -16,6 +16,7 @@
 #include "common.h"
 #include "formatbook.h"
 #include "quant_pass.h"
+#include "fp6_pack.h"
 
 namespace dfp4 {
 
@@ -130,6 +131,82 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(
             }
         }
         sc = nsc;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Online quantizer that writes the FP6 operand of the block-scaled matrix instruction
+// directly (see gemm_native.hip and fp6_pack.h for the layout): same arithmetic as
+// quantize_kernel, but instead of codes, dialect ids and exponent bytes a block leaves as
+// six dwords of 6-bit E2M3 values in the instruction's register order plus its scale byte.
+// Work unit of a wave: 8 rows x 4 steps (8 blocks = 512 bytes per row); pass p is step 4 j + p,
+// quad q is (row q / 2, block q % 2 of the step), so that a pass writes, for each of the two
+// blocks of the step, the 16-byte register groups of 8 consecutive rows = 128 contiguous bytes.
+// Lane `sub` of a quad holds elements 8 sub .. 8 sub + 7 = bits [48 sub, 48 sub + 48) of the
+// block's 192; quad permutes gather them so that lane 0 stores registers 0..3 and lane 2
+// registers 4, 5.  Rows beyond `rows` (padding of the packed layout) are not written.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void quantize_native_kernel(
+    const uint16_t* __restrict__ x, int64_t ld, uint32_t rows, uint32_t KB, uint32_t S,
+    uint8_t* __restrict__ bits, uint8_t* __restrict__ scales) {
+    __shared__ __attribute__((aligned(16))) uint8_t lds_q[kDialects * 1024];
+    __shared__ __attribute__((aligned(16))) uint8_t lds_s[kPairs * 1024];
+    __shared__ uint32_t s_fp6[kDialects * 2];
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const uint32_t quad_id = lane >> 2, sub = lane & 3u;
+    const uint32_t sgroups = (S + 3u) / 4u, rgroups = (rows + 7u) / 8u, nunits = sgroups * rgroups;
+    const uint32_t stride = gridDim.x * kWaves;
+    {
+        const uint4* gq = reinterpret_cast<const uint4*>(g_quant_tables.q);
+        const uint4* gs = reinterpret_cast<const uint4*>(g_quant_tables.s);
+        for (uint32_t i = threadIdx.x; i < 1024u; i += kThreads) reinterpret_cast<uint4*>(lds_q)[i] = gq[i];
+        for (uint32_t i = threadIdx.x; i < 512u; i += kThreads) reinterpret_cast<uint4*>(lds_s)[i] = gs[i];
+        if (threadIdx.x < kDialects * 2) s_fp6[threadIdx.x] = (&g_fp6_book.w[0][0])[threadIdx.x];
+    }
+    __syncthreads();
+    const uint32_t rq = quad_id >> 1, kh = quad_id & 1u;
+    for (uint32_t u = blockIdx.x * kWaves + wave; u < nunits; u += stride) {
+        // consecutive units walk along K first: a row group's steps are handled by neighbouring waves
+        const uint32_t rg = u / sgroups, sg = u - rg * sgroups;
+        const uint32_t row = rg * 8u + rq;
+        const bool row_ok = row < rows;
+        const uint16_t* xr = x + (int64_t)min(row, rows - 1u) * ld;
+        uint4 w[kPasses];
+        bool on[kPasses];
+#pragma unroll
+        for (int p = 0; p < kPasses; ++p) {
+            const uint32_t kb = (sg * 4u + p) * 2u + kh;
+            on[p] = row_ok && kb < KB;
+            w[p] = on[p] ? *reinterpret_cast<const uint4*>(xr + (size_t)kb * kBlock + sub * 8u) : make_uint4(0, 0, 0, 0);
+        }
+#pragma unroll
+        for (int p = 0; p < kPasses; ++p) {
+            uint32_t code, eb, dl;
+            dfp4_pass(w[p], lds_s, lds_q, code, eb, dl);
+            const uint32_t step = sg * 4u + p;
+            const uint64_t p48 = pack6(code, s_fp6[dl * 2], s_fp6[dl * 2 + 1]);
+            const uint32_t lo32 = (uint32_t)p48, mid32 = (uint32_t)(p48 >> 16), hi16 = (uint32_t)(p48 >> 32);
+            // lane 0: {p0 lo, p0 hi16 | p1 lo16 << 16, p1 mid, p2 lo};  lane 2: {p2 hi16 | p3 lo16 << 16, p3 mid}
+            const uint32_t next_lo = quad<0x39>(lo32);                 // low dword of the lane after this one
+            const uint32_t next_mid = quad<0x39>(mid32);
+            const uint32_t lo_of_2 = quad<0xAA>(lo32);                 // lane 2's low dword
+            const uint32_t tile = row >> 5, slot = kh * 32u + (row & 31u);
+            uint8_t* chunk = bits + ((size_t)tile * S + step) * kFp6ChunkBytes;
+            // a step past the last one of an odd-length group does not exist; a missing second block
+            // (odd KB) is written as zeros with a finite scale so that it multiplies to zero
+            const bool step_ok = row_ok && step < S;
+            if (step_ok && sub == 0) {
+                const uint4 v = on[p] ? make_uint4(lo32, hi16 | (next_lo << 16), next_mid, lo_of_2) : make_uint4(0, 0, 0, 0);
+                *reinterpret_cast<uint4*>(chunk + slot * 16u) = v;
+                scales[(((size_t)(tile >> 2) * S + step) * 64u + slot) * 4u + (tile & 3u)] = on[p] ? (uint8_t)eb : (uint8_t)0;
+            }
+            if (step_ok && sub == 2) {
+                uint32_t* d = reinterpret_cast<uint32_t*>(chunk + 1024u + slot * 12u);       // 4-byte aligned only
+                d[0] = on[p] ? (hi16 | (next_lo << 16)) : 0u;
+                d[1] = on[p] ? next_mid : 0u;
+            }
+        }
     }
 }
 
@@ -298,6 +375,21 @@ int launch_quantize(bool mx, const void* x, int64_t rows, int64_t K, int64_t ld,
         if (contig) DFP4_LAUNCH(false, true); else DFP4_LAUNCH(false, false);
     }
 #undef DFP4_LAUNCH
+    return check_launch();
+}
+
+int launch_quantize_native(const void* x, int64_t rows, int64_t K, int64_t ld, void* packed, size_t sc_offset,
+                           hipStream_t stream) {
+    const int64_t KB = K / kBlock;
+    if (rows == 0 || KB == 0) return DFP4_OK;
+    if (rows >= ((int64_t)1 << 30) || KB >= (1 << 20)) return DFP4_ERR_SHAPE;
+    const int64_t S = (KB + 1) / 2, units = ((S + 3) / 4) * ((rows + 7) / 8);
+    if (units >= ((int64_t)1 << 31)) return DFP4_ERR_SHAPE;
+    const int64_t want = (units + kWaves - 1) / kWaves, cap = (int64_t)device_cu_count() * 4;
+    const uint32_t grid = (uint32_t)(want < cap ? want : cap);
+    uint8_t* bits = static_cast<uint8_t*>(packed);
+    hipLaunchKernelGGL(quantize_native_kernel, dim3(grid), dim3(kThreads), 0, stream, static_cast<const uint16_t*>(x),
+                       ld, (uint32_t)rows, (uint32_t)KB, (uint32_t)S, bits, bits + sc_offset);
     return check_launch();
 }
 

@@ -27,7 +27,7 @@ class _CTensor(ctypes.Structure):
 SYMBOLS = [
     "dfp4_quantize", "dfp4_quantize_mse", "dfp4_quantize_t", "mxfp4_quantize_t", "dfp4_dequantize", "dfp4_gemm", "dfp4_gemm_batched", "dfp4_gemm_workspace_bytes",
     "mxfp4_gemm_native", "dfp4_gemm_native", "dfp4_gemm_native_workspace_bytes", "dfp4_native_packed_bytes",
-    "dfp4_native_pack", "mxfp4_native_pack", "dfp4_gemm_native_packed_w", "mxfp4_gemm_native_packed_w",
+    "dfp4_quantize_native", "dfp4_native_pack", "mxfp4_native_pack", "dfp4_gemm_native_packed_w", "mxfp4_gemm_native_packed_w",
     "dfp4_gemm_native_packed", "mxfp4_gemm_native_packed", "dfp4_gemm_native_splitk_bytes",
     "dfp4_gemm_requant", "mxfp4_gemm_requant", "dfp4_gemm_requant_workspace_bytes",
     "mxfp4_quantize", "mxfp4_dequantize", "mxfp4_gemm", "dfp4_formatbook", "dfp4_strerror",
@@ -68,6 +68,8 @@ def load():
     lib.dfp4_gemm_native_workspace_bytes.restype = ctypes.c_size_t
     lib.dfp4_native_packed_bytes.argtypes = [i64, i64]
     lib.dfp4_native_packed_bytes.restype = ctypes.c_size_t
+    lib.dfp4_quantize_native.argtypes = [vp, i64, i64, i64, vp, ctypes.c_size_t, vp]
+    lib.dfp4_quantize_native.restype = ci
     for name in ("dfp4_native_pack", "mxfp4_native_pack"):
         getattr(lib, name).argtypes = [_CTensor, vp, ctypes.c_size_t, vp]
         getattr(lib, name).restype = ci
@@ -284,6 +286,18 @@ def native_pack(w, mx=False, buf=None):
     fn = load().mxfp4_native_pack if mx else load().dfp4_native_pack
     _check(fn(w.c(), _ptr(buf), buf.numel(), _stream()), "native_pack")
     return PackedWeights(buf, w.rows, w.K, mx)
+
+
+def quantize_native(x, buf=None):
+    """dfp4_quantize_native: bf16 [rows, K] -> packed FP6 operand of the block-scaled matrix instruction."""
+    assert x.dtype == torch.bfloat16 and x.dim() == 2 and x.is_cuda and x.stride(1) == 1
+    rows, K = x.shape
+    n = int(load().dfp4_native_packed_bytes(rows, K))
+    if buf is None:
+        buf = torch.zeros(max(n, 256), dtype=torch.uint8, device=x.device)
+    ld = x.stride(0) if rows > 1 else K
+    _check(load().dfp4_quantize_native(_ptr(x), rows, K, ld, _ptr(buf), buf.numel(), _stream()), "dfp4_quantize_native")
+    return PackedWeights(buf, rows, K, False)
 
 
 def gemm_native_packed_w(a, wp, dtype=torch.float32, out=None, workspace=None):

@@ -649,3 +649,28 @@ def test_gemm_random_edge_shapes_all_paths():
         qam, qwm = dfp4.mxfp4_quantize(_dev(a)), dfp4.mxfp4_quantize(_dev(w))
         _assert_gemm_close(dfp4.mxfp4_gemm(qam, qwm), refm, absm, f"mx int8 path {M}x{N}x{K}")
         _assert_gemm_close(dfp4.mxfp4_gemm_native(qam, qwm), refm, absm, f"mx native path {M}x{N}x{K}")
+
+
+@pytest.mark.parametrize("rows,K", [(1, 32), (70, 160), (300, 1056), (513, 4096), (64, 14336)])
+def test_quantize_native_equals_quantize_then_pack(rows, K):
+    # the quantizer that writes the matrix instruction's FP6 operand directly: byte-identical to
+    # dfp4_quantize + dfp4_native_pack (both buffers start as zeros: the fused kernel leaves the
+    # layout's padding rows untouched), also from a strided input
+    print(f"quantize_native parity: {rows}x{K}", flush=True)
+    x = synth.gaussian_outlier_channels(rows, K, max(1, K // 100), 50.0, 1.0, seed=rows + K).cuda()
+    n = int(dfp4.load().dfp4_native_packed_bytes(rows, K))
+    want = dfp4.native_pack(dfp4.quantize(x), buf=torch.zeros(n, dtype=torch.uint8, device="cuda"))
+    got = dfp4.quantize_native(x)
+    torch.cuda.synchronize()
+    assert torch.equal(got.buf, want.buf), int((got.buf != want.buf).sum())
+    wide = torch.zeros(rows, K + 64, dtype=torch.bfloat16, device="cuda")
+    wide[:, 32:32 + K] = x
+    got2 = dfp4.quantize_native(wide[:, 32:32 + K])
+    torch.cuda.synchronize()
+    assert torch.equal(got2.buf, want.buf)
+    # and it multiplies to the oracle's product
+    w = synth.gaussian(96, K, 0.02, seed=K)
+    out = dfp4.gemm_native_packed(got, dfp4.native_pack(dfp4.quantize(_dev(w))))
+    torch.cuda.synchronize()
+    ref, absdot = _gemm_ref(synth.to_f64(x.cpu()), synth.to_f64(w))
+    _assert_gemm_close(out, ref, absdot, "quantize_native product")
