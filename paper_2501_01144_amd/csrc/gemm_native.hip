@@ -250,11 +250,12 @@ __global__ __launch_bounds__(256) void native_reduce_kernel(const float* __restr
 }
 
 inline int64_t up256(int64_t x) { return (x + 255) & ~(int64_t)255; }
-// Workgroups per output tile: with fewer tiles than compute units K is split in 2 or 4 ranges
+// Workgroups per output tile: with at most a quarter as many tiles as compute units K is split in 2
+// or 4 ranges (at half as many the partial tiles and the extra kernel cost what the split gains)
 inline int native_ksplit(int64_t M, int64_t N, int64_t KB) {
     const int64_t tiles = ((M + 255) / 256) * ((N + 255) / 256), S = (KB + 1) / 2, cu = device_cu_count();
     int s = 1;
-    while (s < 4 && tiles * s * 2 <= cu && S / (2 * s) >= 8) s *= 2;
+    while (s < 4 && tiles * s * 4 <= cu && S / (2 * s) >= 8) s *= 2;
     return s;
 }
 // One packed operand: [bits | scales], rows padded to 256, eight steps of slack behind each array.
