@@ -109,10 +109,12 @@ __global__ __launch_bounds__(256) void native_pack_kernel(PackParams p) {
     reinterpret_cast<uint8_t*>(p.dst.sc)[(((int64_t)(tile >> 2) * p.S + s) * 64 + lane) * 4 + (tile & 3)] = (uint8_t)eb;
 }
 
-template <int FMT, bool BF16>
+// TA = 32-row tiles per wave: 4 (256 x 256 per workgroup) or 2 (128 x 256, for products with few tiles)
+template <int FMT, bool BF16, int TA>
 __global__ __launch_bounds__(256, 1) void gemm_native_kernel(NativeParams p) {
     constexpr bool kFp6 = FMT == kFmtFp6;
-    constexpr int kTileLds = kFp6 ? 2048 : 1024, kStage = 16 * kTileLds + 1024, kStages = kFp6 ? 4 : 8;
+    constexpr int kTileLds = kFp6 ? 2048 : 1024, kStage = (2 * TA + 8) * kTileLds + 1024, kStages = kFp6 ? 4 : 8;
+    constexpr int kRowsWg = 64 * TA, kRowsWave = 32 * TA;
     constexpr int kGStride = kFp6 ? 1792 : 1024;             // global bytes per (tile, step)
     __shared__ __attribute__((aligned(16))) uint8_t s_stage[kStages * kStage];
     const int tid = threadIdx.x, lane = tid & 63;
@@ -127,40 +129,36 @@ __global__ __launch_bounds__(256, 1) void gemm_native_kernel(NativeParams p) {
             (int)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)&s_stage[0]);
         const uint32_t tstride = (uint32_t)p.S * (uint32_t)kGStride;      // bytes per tile
         // this wave fetches A tiles 2w, 2w+1 and B tiles 2w, 2w+1 of the workgroup's 8 + 8, and scale chunk w
-        const uint64_t ab = reinterpret_cast<uint64_t>(p.a.bits) + ((uint64_t)blockIdx.y * 8 + 2 * wave) * tstride;
+        const uint64_t ab = reinterpret_cast<uint64_t>(p.a.bits) +
+                            ((uint64_t)blockIdx.y * (2 * TA) + (TA == 4 ? 2 * wave : wave)) * tstride;
         const uint64_t bb = reinterpret_cast<uint64_t>(p.w.bits) + ((uint64_t)blockIdx.x * 8 + 2 * wave) * tstride;
         const uint64_t sb = wave < 2
-            ? reinterpret_cast<uint64_t>(p.a.sc) + ((uint64_t)blockIdx.y * 2 + wave) * (uint64_t)p.S * 256
+            ? reinterpret_cast<uint64_t>(p.a.sc) + (TA == 4 ? (uint64_t)blockIdx.y * 2 + wave : (uint64_t)blockIdx.y) * (uint64_t)p.S * 256
             : reinterpret_cast<uint64_t>(p.w.sc) + ((uint64_t)blockIdx.x * 2 + (wave - 2)) * (uint64_t)p.S * 256;
         const uint32_t l16 = (uint32_t)lane * 16u, l4 = (uint32_t)lane * 4u;
         const uint32_t g16 = l16 + (uint32_t)s_lo * kGStride, g12 = (uint32_t)lane * 12u + (uint32_t)s_lo * kGStride;
         const uint32_t g4 = l4 + (uint32_t)s_lo * 256u;
-        if constexpr (kFp6)
-            asm volatile(DFP4_NATIVE_LOOP_FP6
-                         :
-                         : [alo] "s"((uint32_t)ab), [ahi] "s"((uint32_t)(ab >> 32)), [blo] "s"((uint32_t)bb),
-                           [bhi] "s"((uint32_t)(bb >> 32)), [slo] "s"((uint32_t)sb), [shi] "s"((uint32_t)(sb >> 32)),
-                           [tstride] "s"(tstride), [wv] "s"(wave), [lds] "s"(lds),
-                           [ldsend] "s"(lds + (uint32_t)(kStages * kStage)), [steps] "s"((uint32_t)S),
-                           [l16] "v"(l16), [l4] "v"(l4), [g16] "v"(g16), [g12] "v"(g12), [g4] "v"(g4)
-                         : DFP4_NATIVE_VGPR_CLOBBERS, DFP4_NATIVE_ACC_CLOBBERS, DFP4_NATIVE_SGPR_CLOBBERS, "m0", "scc",
-                           "memory");
-        else
-            asm volatile(DFP4_NATIVE_LOOP_FP4
-                         :
-                         : [alo] "s"((uint32_t)ab), [ahi] "s"((uint32_t)(ab >> 32)), [blo] "s"((uint32_t)bb),
-                           [bhi] "s"((uint32_t)(bb >> 32)), [slo] "s"((uint32_t)sb), [shi] "s"((uint32_t)(sb >> 32)),
-                           [tstride] "s"(tstride), [wv] "s"(wave), [lds] "s"(lds),
-                           [ldsend] "s"(lds + (uint32_t)(kStages * kStage)), [steps] "s"((uint32_t)S),
-                           [l16] "v"(l16), [l4] "v"(l4), [g16] "v"(g16), [g12] "v"(g12), [g4] "v"(g4)
-                         : DFP4_NATIVE_VGPR_CLOBBERS, DFP4_NATIVE_ACC_CLOBBERS, DFP4_NATIVE_SGPR_CLOBBERS, "m0", "scc",
-                           "memory");
+#define DFP4_NATIVE_RUN(LOOP)                                                                                     \
+        asm volatile(LOOP                                                                                           \
+                     :                                                                                              \
+                     : [alo] "s"((uint32_t)ab), [ahi] "s"((uint32_t)(ab >> 32)), [blo] "s"((uint32_t)bb),        \
+                       [bhi] "s"((uint32_t)(bb >> 32)), [slo] "s"((uint32_t)sb), [shi] "s"((uint32_t)(sb >> 32)), \
+                       [tstride] "s"(tstride), [wv] "s"(wave), [lds] "s"(lds),                                      \
+                       [ldsend] "s"(lds + (uint32_t)(kStages * kStage)), [steps] "s"((uint32_t)S),                  \
+                       [l16] "v"(l16), [l4] "v"(l4), [g16] "v"(g16), [g12] "v"(g12), [g4] "v"(g4)                   \
+                     : DFP4_NATIVE_VGPR_CLOBBERS, DFP4_NATIVE_ACC_CLOBBERS, DFP4_NATIVE_SGPR_CLOBBERS, "m0", "scc", \
+                       "memory")
+        if constexpr (kFp6 && TA == 4) DFP4_NATIVE_RUN(DFP4_NATIVE_LOOP_FP6);
+        else if constexpr (kFp6) DFP4_NATIVE_RUN(DFP4_NATIVE_LOOP_FP6_H);
+        else if constexpr (TA == 4) DFP4_NATIVE_RUN(DFP4_NATIVE_LOOP_FP4);
+        else DFP4_NATIVE_RUN(DFP4_NATIVE_LOOP_FP4_H);
+#undef DFP4_NATIVE_RUN
     }
 
     // epilogue: fp32 (or bf16, round to nearest even) [M, N]; accumulator tile (i, j) = 4 i + j.
     // Register x of lane (kh, c) is row 32 i + 8 (x / 4) + 4 kh + x % 4, column 32 j + c.  Row
     // addresses are wave-uniform (scalar registers); the lane adds a constant byte offset.
-    const int m0 = blockIdx.y * 256 + wm * 128, n0 = blockIdx.x * 256 + wn * 128;
+    const int m0 = blockIdx.y * kRowsWg + wm * kRowsWave, n0 = blockIdx.x * 256 + wn * 128;
     if (m0 >= p.M || n0 >= p.N) return;
     constexpr int kEsz = BF16 ? 2 : 4;
     // split K: the fp32 partial tile of this range goes to part[blockIdx.z] (the kernel is then the fp32 one)
@@ -170,7 +168,7 @@ __global__ __launch_bounds__(256, 1) void gemm_native_kernel(NativeParams p) {
                             : static_cast<uint8_t*>(p.out);
     uint8_t* wave_out = base + ((int64_t)m0 * ld + n0) * kEsz;                                 // uniform
     const int64_t row_bytes = ld * kEsz;                                                       // uniform
-    const bool full = m0 + 128 <= p.M && n0 + 128 <= p.N;                                      // uniform
+    const bool full = m0 + kRowsWave <= p.M && n0 + 128 <= p.N;                                // uniform
     // bf16: lanes exchange values in pairs so that every lane stores two adjacent columns of one
     // row (even lanes the even row of a row pair, odd lanes the odd row)
     const bool pairs = BF16 && full && (ld & 1) == 0 && (reinterpret_cast<uintptr_t>(base) & 3) == 0;
@@ -219,8 +217,10 @@ __global__ __launch_bounds__(256, 1) void gemm_native_kernel(NativeParams p) {
 #define DFP4_NATIVE_ALL                                                                             \
     DFP4_NATIVE_STORE(0) DFP4_NATIVE_STORE(1) DFP4_NATIVE_STORE(2) DFP4_NATIVE_STORE(3)             \
     DFP4_NATIVE_STORE(4) DFP4_NATIVE_STORE(5) DFP4_NATIVE_STORE(6) DFP4_NATIVE_STORE(7)             \
-    DFP4_NATIVE_STORE(8) DFP4_NATIVE_STORE(9) DFP4_NATIVE_STORE(10) DFP4_NATIVE_STORE(11)           \
-    DFP4_NATIVE_STORE(12) DFP4_NATIVE_STORE(13) DFP4_NATIVE_STORE(14) DFP4_NATIVE_STORE(15)
+    if constexpr (TA == 4) {                                                                        \
+        DFP4_NATIVE_STORE(8) DFP4_NATIVE_STORE(9) DFP4_NATIVE_STORE(10) DFP4_NATIVE_STORE(11)       \
+        DFP4_NATIVE_STORE(12) DFP4_NATIVE_STORE(13) DFP4_NATIVE_STORE(14) DFP4_NATIVE_STORE(15)     \
+    }
     if (pairs) {
         constexpr std::true_type kFullC{}, kPairsC{};
         DFP4_NATIVE_ALL
@@ -325,16 +325,23 @@ int launch_gemm_native_packed(bool fp6, const void* a_packed, const void* w_pack
     p.ksplit = native_ksplit(M, N, KB);
     if (p.ksplit > 1 && (!splitk || splitk_bytes < native_splitk_bytes(M, N, K))) p.ksplit = 1;
     p.part = static_cast<float*>(splitk);
-    dim3 grid((unsigned)((N + 255) / 256), (unsigned)((M + 255) / 256), (unsigned)p.ksplit);
+    // 256-row workgroups unless they would leave half of the compute units idle
+    const int64_t tiles256 = ((M + 255) / 256) * ((N + 255) / 256);
+    const bool half = tiles256 * p.ksplit * 2 <= device_cu_count() && M > 128;
+    dim3 grid((unsigned)((N + 255) / 256), (unsigned)((M + (half ? 127 : 255)) / (half ? 128 : 256)), (unsigned)p.ksplit);
     if (grid.y > 65535) return DFP4_ERR_SHAPE;
     const bool bf16 = out_dtype == DFP4_BF16 && p.ksplit == 1;     // partial tiles are fp32
+#define DFP4_NATIVE_LAUNCH(F, B)                                                                         \
+    do {                                                                                                 \
+        if (half) hipLaunchKernelGGL((gemm_native_kernel<F, B, 2>), grid, dim3(256), 0, stream, p);      \
+        else hipLaunchKernelGGL((gemm_native_kernel<F, B, 4>), grid, dim3(256), 0, stream, p);           \
+    } while (0)
     if (fp6) {
-        if (bf16) hipLaunchKernelGGL((gemm_native_kernel<kFmtFp6, true>), grid, dim3(256), 0, stream, p);
-        else hipLaunchKernelGGL((gemm_native_kernel<kFmtFp6, false>), grid, dim3(256), 0, stream, p);
+        if (bf16) DFP4_NATIVE_LAUNCH(kFmtFp6, true); else DFP4_NATIVE_LAUNCH(kFmtFp6, false);
     } else {
-        if (bf16) hipLaunchKernelGGL((gemm_native_kernel<kFmtFp4, true>), grid, dim3(256), 0, stream, p);
-        else hipLaunchKernelGGL((gemm_native_kernel<kFmtFp4, false>), grid, dim3(256), 0, stream, p);
+        if (bf16) DFP4_NATIVE_LAUNCH(kFmtFp4, true); else DFP4_NATIVE_LAUNCH(kFmtFp4, false);
     }
+#undef DFP4_NATIVE_LAUNCH
     if (p.ksplit > 1) {
         const unsigned gr = (unsigned)((M * N + 255) / 256);
         if (out_dtype == DFP4_BF16)

@@ -4,7 +4,8 @@ v_mfma_scale_f32_32x32x64_f8f6f4 on FP4 or FP6 operands, see gemm_native.hip).
 
 A workgroup computes 256 x 256 outputs with four waves as 2 x 2, each wave 128 x 128
 (4 x 4 tiles of 32 x 32, accumulator tile (i, j) in a[16 (4 i + j) : +15]).  One step =
-one pair of blocks (K = 64) = 16 MFMAs per wave.  Both operands arrive pre-arranged in the
+one pair of blocks (K = 64) = 16 MFMAs per wave.  A second form (suffix _H) halves the rows:
+128 x 256 per workgroup, 64 x 128 per wave, 8 MFMAs per step, for products with few tiles.  Both operands arrive pre-arranged in the
 instruction's register order (native_pack_kernel), so a (tile, step) chunk is 64 lanes x
 16 bytes (FP4), followed for FP6 by 64 lanes x 12 bytes (8 used: registers 4 and 5), and the loop only moves data:
 
@@ -48,14 +49,16 @@ def sr(n, cnt=1):
 
 
 class Fmt:
-    def __init__(self, fp6):
+    def __init__(self, fp6, ta=4):
         self.fp6 = fp6
+        self.ta = ta                                 # A tiles (of 32 rows) per wave: 4 (256-row workgroup) or 2 (128)
         self.regs = 6 if fp6 else 4
         self.tile = 2048 if fp6 else 1024            # LDS bytes per tile and stage
-        self.stage = 16 * self.tile + 1024
+        self.stage = (2 * ta + 8) * self.tile + 1024
         self.gstride = 1792 if fp6 else 1024         # global bytes per (tile, step): 1024 + 768
         self.code = 2 if fp6 else 4                  # cbsz / blgp
-        self.per_step = 9 if fp6 else 5              # direct loads per wave and step
+        a_tiles = ta // 2                            # A tiles this wave fetches per step (B: always 2)
+        self.per_step = (a_tiles + 2) * (2 if fp6 else 1) + 1     # direct loads per wave and step
         self.nst = 4 if fp6 else 8                   # LDS stages (FP6: 4 x 33 KiB, FP4: 8 x 17 KiB)
         self.dist = self.nst - 1                     # loads run this many steps ahead
         # LDS reads address a stage as (base register of its group) + immediate (< 64 KiB)
@@ -69,7 +72,7 @@ def frag_reads(f, p, stage):
     va, vb, vsa, vsb = (VBASE + 4 * q + i for i in range(4))
     o = []
     for side, v in ((0, va), (1, vb)):
-        for t in range(4):
+        for t in range(f.ta if side == 0 else 4):
             r = FR[p] + 24 * side + 6 * t
             o.append(f"ds_read_b128 {vr(r, 4)}, {vr(v)} offset:{off + t * f.tile}")
             if f.fp6:
@@ -85,7 +88,7 @@ def dma_groups(f, stage):
     FP6 chunk sits 1024 bytes behind the first in both, so the two halves share one m0."""
     o = []
     for side, dst in ((0, S_DA), (1, S_DB)):
-        for k in range(2):
+        for k in range(f.ta // 2 if side == 0 else 2):
             base = sr(S_BASE + 4 * side + 2 * k, 2)
             loads = [f"global_load_lds_dwordx4 {vr(VOFF)}, {base}"]
             if f.fp6:
@@ -122,8 +125,9 @@ def step(f, u):
         tail.append([m0] + ([reads.pop(0)] if reads else ["s_nop 0"]) + loads)
     while reads:
         tail.append([reads.pop(0)] + ([reads.pop(0)] if reads else []))
-    per = (len(tail) + 11) // 12      # spread evenly: bunching the memory instructions is slower
-    for k in range(16):
+    nm = 4 * f.ta                     # MFMAs per step
+    per = (len(tail) + nm - 5) // (nm - 4)      # spread evenly: bunching the memory instructions is slower
+    for k in range(nm):
         o.append(mfma(f, p, k))
         if k == 2:
             # the loads of step s + 1 have landed; those of the steps after it may be pending
@@ -131,9 +135,11 @@ def step(f, u):
         if k >= 3:
             for grp in tail[(k - 3) * per:(k - 2) * per]:
                 o += grp
-        if k == 15:
+        if k == nm - 1:
             o += advance_global(f)
     o += [f"s_add_u32 {sr(S_VC)}, {sr(S_VC)}, 1", "s_waitcnt lgkmcnt(0)"]
+    if f.ta == 2:                     # both row halves of the workgroup share one scale dword: bytes 2 wm, 2 wm + 1
+        o.append(f"v_lshrrev_b32 {vr(SA[1 - p])}, {sr(S_T1)}, {vr(SA[1 - p])}")
     return o
 
 
@@ -146,18 +152,27 @@ def entry(f):
           f"s_add_u32 {sr(S_BASE + 6)}, %[blo], %[tstride]", f"s_addc_u32 {sr(S_BASE + 7)}, %[bhi], 0",
           f"s_mov_b32 {sr(S_BASE + 8)}, %[slo]", f"s_mov_b32 {sr(S_BASE + 9)}, %[shi]"]
     # the wave's LDS addresses inside stage 0: wm = wv >> 1, wn = wv & 1
+    offb, offs = 2 * f.ta * f.tile, (2 * f.ta + 8) * f.tile
     o += [f"s_lshr_b32 {sr(S_T0)}, %[wv], 1", f"s_and_b32 {sr(S_T1)}, %[wv], 1",
-          f"s_mul_i32 {sr(S_RA)}, {sr(S_T0)}, {4 * f.tile}", f"s_add_u32 {sr(S_RA)}, {sr(S_RA)}, %[lds]",
-          f"s_mul_i32 {sr(S_RB)}, {sr(S_T1)}, {4 * f.tile}", f"s_add_u32 {sr(S_RB)}, {sr(S_RB)}, {8 * f.tile}",
-          f"s_add_u32 {sr(S_RB)}, {sr(S_RB)}, %[lds]",
-          f"s_lshl_b32 {sr(S_RSA)}, {sr(S_T0)}, 8", f"s_add_u32 {sr(S_RSA)}, {sr(S_RSA)}, {16 * f.tile}",
-          f"s_add_u32 {sr(S_RSA)}, {sr(S_RSA)}, %[lds]",
-          f"s_lshl_b32 {sr(S_RSB)}, {sr(S_T1)}, 8", f"s_add_u32 {sr(S_RSB)}, {sr(S_RSB)}, {16 * f.tile + 512}",
+          f"s_mul_i32 {sr(S_RA)}, {sr(S_T0)}, {f.ta * f.tile}", f"s_add_u32 {sr(S_RA)}, {sr(S_RA)}, %[lds]",
+          f"s_mul_i32 {sr(S_RB)}, {sr(S_T1)}, {4 * f.tile}", f"s_add_u32 {sr(S_RB)}, {sr(S_RB)}, {offb}",
+          f"s_add_u32 {sr(S_RB)}, {sr(S_RB)}, %[lds]"]
+    if f.ta == 4:
+        o += [f"s_lshl_b32 {sr(S_RSA)}, {sr(S_T0)}, 8", f"s_add_u32 {sr(S_RSA)}, {sr(S_RSA)}, {offs}"]
+    else:
+        o += [f"s_mov_b32 {sr(S_RSA)}, {offs}"]
+    o += [f"s_add_u32 {sr(S_RSA)}, {sr(S_RSA)}, %[lds]",
+          f"s_lshl_b32 {sr(S_RSB)}, {sr(S_T1)}, 8", f"s_add_u32 {sr(S_RSB)}, {sr(S_RSB)}, {offs + 512}",
           f"s_add_u32 {sr(S_RSB)}, {sr(S_RSB)}, %[lds]",
-          f"s_mul_i32 {sr(S_DA)}, %[wv], {2 * f.tile}", f"s_add_u32 {sr(S_DA)}, {sr(S_DA)}, %[lds]",
-          f"s_add_u32 {sr(S_DB)}, {sr(S_DA)}, {8 * f.tile}",
-          f"s_lshl_b32 {sr(S_DS)}, %[wv], 8", f"s_add_u32 {sr(S_DS)}, {sr(S_DS)}, {16 * f.tile}",
-          f"s_add_u32 {sr(S_DS)}, {sr(S_DS)}, %[lds]"]
+          f"s_mul_i32 {sr(S_DA)}, %[wv], {(f.ta // 2) * f.tile}", f"s_add_u32 {sr(S_DA)}, {sr(S_DA)}, %[lds]",
+          f"s_mul_i32 {sr(S_DB)}, %[wv], {2 * f.tile}", f"s_add_u32 {sr(S_DB)}, {sr(S_DB)}, {offb}",
+          f"s_add_u32 {sr(S_DB)}, {sr(S_DB)}, %[lds]"]
+    if f.ta == 4:
+        o += [f"s_lshl_b32 {sr(S_DS)}, %[wv], 8"]
+    else:                             # scale chunks: wave 0 and 1 -> the A group (slot 0), waves 2, 3 -> B groups (slots 2, 3)
+        o += [f"s_cmp_lt_u32 %[wv], 2", f"s_cselect_b32 {sr(S_DS)}, 0, %[wv]", f"s_lshl_b32 {sr(S_DS)}, {sr(S_DS)}, 8"]
+    o += [f"s_add_u32 {sr(S_DS)}, {sr(S_DS)}, {offs}", f"s_add_u32 {sr(S_DS)}, {sr(S_DS)}, %[lds]",
+          f"s_lshl_b32 {sr(S_T1)}, {sr(S_T0)}, 4"]              # S_T1 = 16 wm: shift of the A scale dword (128-row form)
     for q in range(f.groups):
         goff = q * f.per_group * f.stage
         for i, (s, lane) in enumerate(((S_RA, "%[l16]"), (S_RB, "%[l16]"), (S_RSA, "%[l4]"), (S_RSB, "%[l4]"))):
@@ -172,6 +187,8 @@ def entry(f):
     # step 0's operands into set 0
     o += [f"s_waitcnt vmcnt({(f.dist - 1) * f.per_step})", "s_barrier"]
     o += frag_reads(f, 0, 0) + ["s_waitcnt lgkmcnt(0)"]
+    if f.ta == 2:
+        o.append(f"v_lshrrev_b32 {vr(SA[0])}, {sr(S_T1)}, {vr(SA[0])}")
     return o
 
 
@@ -194,6 +211,8 @@ def main():
     parts = ["// Generated by gen_native_loop.py -- do not edit; see that file for the register map.\n"]
     parts.append("#define DFP4_NATIVE_LOOP_FP4 \\\n" + c_string(main_loop(Fmt(False))) + "\n")
     parts.append("#define DFP4_NATIVE_LOOP_FP6 \\\n" + c_string(main_loop(Fmt(True))) + "\n")
+    parts.append("#define DFP4_NATIVE_LOOP_FP4_H \\\n" + c_string(main_loop(Fmt(False, 2))) + "\n")
+    parts.append("#define DFP4_NATIVE_LOOP_FP6_H \\\n" + c_string(main_loop(Fmt(True, 2))) + "\n")
     for g in range(16):
         rd = [f"v_accvgpr_read_b32 %{i}, a{16 * g + i}" for i in range(16)]
         parts.append(f"#define DFP4_NATIVE_ACC_READ_{g} \\\n" + c_string(rd) + "\n")
