@@ -18,14 +18,17 @@
 // the scale register that op_sel names, 2^(byte - 127).  Output as the other 32x32 MFMAs:
 // register x of lane (h, c) is row 8 (x / 4) + 4 h + x % 4, column c.
 //
-// Two kernels.  native_pack_kernel rewrites an operand in the order the matrix instruction
-// wants it (per 32-row tile and step, 64 lanes x 16 or 24 bytes, plus one dword of four
-// scale bytes per lane and group of four tiles), so that the multiply kernel's loads are
-// whole lines.  gemm_native_kernel: 256 x 256 outputs per workgroup, four waves as 2 x 2,
-// each 128 x 128 (16 accumulator tiles = 256 registers, one wave per SIMD); operands go
-// global -> LDS by direct loads three steps ahead (four stages), LDS -> registers one step
-// ahead, one barrier per step; the main loop is generated assembly (gen_native_loop.py).
-// For weights the packing could be done once, offline.
+// Kernels.  native_pack_kernel rewrites an operand in the order the matrix instruction
+// wants it (per 32-row tile and step, 64 lanes x 16 bytes, for FP6 followed by 64 lanes x 12
+// bytes of which 8 are used, plus one dword of four scale bytes per lane and group of four
+// tiles), so that the multiply kernel's loads are whole lines; weights are packed once,
+// offline, and quantize_native_kernel (quantize.hip) writes an activation in this form
+// directly.  gemm_native_kernel: 256 x 256 outputs per workgroup, four waves as 2 x 2, each
+// 128 x 128 (16 accumulator tiles = 256 registers, one wave per SIMD), or 128 x 256 per
+// workgroup when there are few tiles; operands go global -> LDS by direct loads three (FP6)
+// or seven (FP4) steps ahead, LDS -> registers one step ahead, one barrier per step; the
+// main loop is generated assembly (gen_native_loop.py).  With very few tiles K is split
+// between workgroups and native_reduce_kernel adds their fp32 partial tiles in a fixed order.
 #include <type_traits>
 #include "common.h"
 #include "formatbook.h"
