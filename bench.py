@@ -310,6 +310,33 @@ def main():
                      "traffic": None}}
     del wpk
 
+    # and the MXFP4 comparison on the same instruction (FP4 E2M1 operands are the codes themselves)
+    wqm = {k: dfp4.mxfp4_quantize(ops[k].to(dev)) for k in ("w_gate", "w_up", "w_down")}
+    wpm = {k: dfp4.native_pack(wqm[k], mx=True) for k in wqm}
+    del wqm
+
+    def step_native_mx():
+        dfp4.mxfp4_quantize(x, out=qxm)
+        px = dfp4.native_pack(qxm, mx=True, buf=xbuf)
+        dfp4.gemm_native_packed(px, wpm["w_gate"], out=gate, workspace=ws_n)
+        dfp4.gemm_native_packed(px, wpm["w_up"], out=up, workspace=ws_n)
+        dfp4.mxfp4_quantize(h, out=qhm)
+        ph = dfp4.native_pack(qhm, mx=True, buf=hbuf)
+        dfp4.gemm_native_packed(ph, wpm["w_down"], out=down, workspace=ws_n)
+
+    for _ in range(max(3, args.warmup // 4)):
+        step_native_mx()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(nmx):
+        step_native_mx()
+    torch.cuda.synchronize()
+    ms_nmx = (time.perf_counter() - t0) / nmx * 1e3
+    out["native_fp4_mxfp4_step"] = {
+        "what": "MXFP4 step on the same instruction: mxfp4_quantize + mxfp4_native_pack + mxfp4_gemm_native_packed",
+        "ms_per_step": round(ms_nmx, 4), "TOPs": round(total_ops / (ms_nmx * 1e-3) / 1e12, 1), "steps": nmx}
+    del wpm
+
     if not args.no_stream_quant:
         # quantizer-only streaming tensors (Student-t, df=3): DialectFP4 and MXFP4,
         # warm (same buffer, fits the memory-side cache) and cold (rotating buffers)
