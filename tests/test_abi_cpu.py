@@ -82,3 +82,17 @@ def test_binding_refuses_to_run_without_the_library(monkeypatch):
     monkeypatch.setattr(dfp4, "_LIB_PATH", "/nonexistent/libdfp4.so")
     with pytest.raises(dfp4.Dfp4Error):
         dfp4.load()
+
+
+def test_header_compiles_as_c99(tmp_path):
+    # the boundary is a C ABI: the public header must be plain C
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler")
+    header = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include", "dfp4.h")
+    src = tmp_path / "t.c"
+    src.write_text('#include "%s"\nint main(void) { return dfp4_strerror(0) == 0; }\n' % header)
+    subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-c", str(src), "-o",
+                    str(tmp_path / "t.o")], check=True)
