@@ -112,6 +112,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--out-dtype", choices=["f32", "bf16"], default="f32", help="GEMM output type")
     ap.add_argument("--no-mfma-peak", action="store_true", help="skip the register-only MFMA loop")
+    ap.add_argument("--gemm", choices=["int8", "native"], default="int8",
+                    help="which GEMM path the headline fields describe: the int8 matrix-core path "
+                         "(dfp4_gemm) or the block-scaled FP6 one (dfp4_gemm_native_packed); both are "
+                         "always measured and reported")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-stream-quant", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -382,6 +386,16 @@ def main():
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(ops)
+    if args.gemm == "native":
+        n = out["native_fp6_step"]
+        out["int8_step"] = {"ms_per_step": out["ms_per_step"], "TOPs": out["value"], "kernel_ms": out["kernel_ms"],
+                            "roofline": out["roofline"]}
+        out.update({"value": n["TOPs"], "ms_per_step": n["ms_per_step"], "kernel_ms": n["kernel_ms"], "dtype": "fp6",
+                    "roofline": n["roofline"], "steps": n["steps"],
+                    "pct_int8_peak_step": round(100.0 * n["TOPs"] / INT8_PEAK_TOPS, 2)})
+        out["config"]["gemm"] = "native (v_mfma_scale_f32_32x32x64_f8f6f4, FP6 E2M3 operands)"
+    else:
+        out["config"]["gemm"] = "int8 (v_mfma_i32_32x32x32_i8, exact int32 accumulation)"
     print(json.dumps(out))
 
 
