@@ -341,6 +341,25 @@ def main():
         "ms_per_step": round(ms_nmx, 4), "TOPs": round(total_ops / (ms_nmx * 1e-3) / 1e12, 1), "steps": nmx}
     del wpm
 
+    # the small single-linear case (few rows: bound by the weight stream, reported in GB/s)
+    a1, w1 = synth.single_linear(seed=0)
+    qa1, qw1 = dfp4.quantize(a1.to(dev)), dfp4.quantize(w1.to(dev))
+    o1 = torch.empty((a1.shape[0], w1.shape[0]), dtype=torch.float32, device=dev)
+    ws1 = torch.empty(max(dfp4.gemm_workspace_bytes(a1.shape[0], w1.shape[0], a1.shape[1]), 256), dtype=torch.uint8,
+                      device=dev)
+    for _ in range(5):
+        dfp4.gemm(qa1, qw1, out=o1, workspace=ws1)
+    ev1 = _events(30, torch)
+    for i in range(30):
+        ev1[i][0].record()
+        dfp4.gemm(qa1, qw1, out=o1, workspace=ws1)
+        ev1[i][1].record()
+    torch.cuda.synchronize()
+    ms1 = sorted(e[0].elapsed_time(e[1]) for e in ev1)[15]
+    b1 = gemm_bytes(a1.shape[0], w1.shape[0], a1.shape[1])
+    out["single_linear_32x4096x4096"] = {"ms": round(ms1, 4), "GBps": round(b1 / (ms1 * 1e-3) / 1e9, 1),
+                                         "algorithmic_bytes": int(b1), "kernel": "gemm_small_kernel"}
+
     if not args.no_stream_quant:
         # quantizer-only streaming tensors (Student-t, df=3): DialectFP4 and MXFP4,
         # warm (same buffer, fits the memory-side cache) and cold (rotating buffers)
