@@ -96,3 +96,39 @@ def test_header_compiles_as_c99(tmp_path):
     src.write_text('#include "%s"\nint main(void) { return dfp4_strerror(0) == 0; }\n' % header)
     subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-c", str(src), "-o",
                     str(tmp_path / "t.o")], check=True)
+
+
+def test_argument_errors_of_the_later_entry_points(lib):
+    vp, sz = ctypes.c_void_p, ctypes.c_size_t
+    q = _t(16, 16, 16, 64, 64)
+    # MSE and transposing quantizers: same checks as dfp4_quantize; the transposing one needs rows % 32 == 0
+    assert lib.dfp4_quantize_mse(vp(16), 4, 48, 48, _t(16, 16, 16, 4, 48), vp(0)) == -2
+    assert lib.dfp4_quantize_mse(vp(0), 4, 64, 64, _t(16, 16, 16, 4, 64), vp(0)) == -1
+    assert lib.dfp4_quantize_t(vp(16), 48, 64, 64, _t(16, 16, 16, 64, 48), vp(0)) == -2
+    assert lib.dfp4_quantize_t(vp(16), 64, 64, 64, _t(16, 16, 16, 64, 32), vp(0)) == -2
+    assert lib.dfp4_quantize_t(vp(8), 64, 64, 64, q, vp(0)) == -3
+    assert lib.mxfp4_quantize_t(vp(16), 64, 64, 64, _t(0, 0, 16, 64, 64), vp(0)) == -1
+    # requantizing GEMM: N must be a multiple of 32, the output shape [M, N], a workspace is required
+    a, w = _t(16, 16, 16, 64, 64), _t(16, 16, 16, 48, 64)
+    assert lib.dfp4_gemm_requant(a, w, _t(16, 16, 16, 64, 48), vp(256), sz(1 << 30), vp(0)) == -2
+    w = _t(16, 16, 16, 64, 64)
+    assert lib.dfp4_gemm_requant(a, w, _t(16, 16, 16, 64, 32), vp(256), sz(1 << 30), vp(0)) == -2
+    assert lib.dfp4_gemm_requant(a, w, _t(0, 16, 16, 64, 64), vp(256), sz(1 << 30), vp(0)) == -1
+    assert lib.dfp4_gemm_requant(a, w, q, vp(0), sz(0), vp(0)) == -5
+    assert lib.dfp4_gemm_requant_workspace_bytes(64, 64, 64) > lib.dfp4_gemm_workspace_bytes(64, 64, 64)
+    # native family: packed sizes, workspace and alignment checks
+    need = lib.dfp4_native_packed_bytes(64, 64)
+    assert need > 0 and lib.dfp4_native_packed_bytes(0, 64) == 0
+    assert lib.dfp4_native_pack(a, vp(256), sz(need - 1), vp(0)) == -5
+    assert lib.dfp4_native_pack(a, vp(128), sz(need), vp(0)) == -3
+    assert lib.dfp4_native_pack(_t(16, 0, 16, 64, 64), vp(256), sz(need), vp(0)) == -1
+    assert lib.mxfp4_native_pack(_t(16, 0, 16, 64, 48), vp(256), sz(need), vp(0)) == -2
+    assert lib.dfp4_quantize_native(vp(16), 64, 64, 64, vp(256), sz(need - 1), vp(0)) == -5
+    assert lib.dfp4_quantize_native(vp(16), 64, 64, 32, vp(256), sz(need), vp(0)) == -2
+    assert lib.dfp4_gemm_native(a, w, vp(16), 0, 64, vp(256), sz(need), vp(0)) == -5          # two operands do not fit
+    assert lib.dfp4_gemm_native(a, _t(16, 16, 16, 64, 96), vp(16), 0, 64, vp(256), sz(1 << 30), vp(0)) == -2
+    assert lib.dfp4_gemm_native(a, w, vp(16), 3, 64, vp(256), sz(1 << 30), vp(0)) == -4
+    assert lib.dfp4_gemm_native_packed_w(a, vp(0), 64, vp(16), 0, 64, vp(256), sz(1 << 30), vp(0)) == -1
+    assert lib.dfp4_gemm_native_packed(vp(256), 64, vp(256), 64, 48, vp(16), 0, 64, vp(0), sz(0), vp(0)) == -2
+    assert lib.dfp4_gemm_native_packed(vp(256), 64, vp(128), 64, 64, vp(16), 0, 64, vp(0), sz(0), vp(0)) == -3
+    assert lib.dfp4_gemm_native_packed(vp(256), 0, vp(256), 64, 64, vp(16), 0, 64, vp(0), sz(0), vp(0)) == 0
