@@ -98,6 +98,16 @@ int dfp4_quantize_t(const void* x_bf16, int64_t rows, int64_t cols, int64_t ld_e
                     dfp4_tensor out, void* stream);
 int mxfp4_quantize_t(const void* x_bf16, int64_t rows, int64_t cols, int64_t ld_elems,
                      dfp4_tensor out, void* stream);
+/*
+ * The same into a longer tensor (Appendix C, value cache: values are stored in 4-bit chunks
+ * of one block of tokens; only the most recent, incomplete chunk stays in high precision and
+ * is quantized once it holds 32 tokens): x holds `rows` consecutive tokens (a multiple of 32)
+ * starting at token `row_offset` (a multiple of 32); `out` is the quantized transpose of the
+ * whole sequence, out.rows = cols, out.K = capacity in tokens >= row_offset + rows.  Only the
+ * blocks of these tokens are written.
+ */
+int dfp4_quantize_t_at(const void* x_bf16, int64_t rows, int64_t cols, int64_t ld_elems,
+                       dfp4_tensor out, int64_t row_offset, void* stream);
 
 /*
  * Offline DialectFP4 quantization with MSE-based dialect selection (Section 3.2:

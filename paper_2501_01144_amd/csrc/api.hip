@@ -64,25 +64,35 @@ int dfp4_quantize(const void* x_bf16, int64_t rows, int64_t K, int64_t ld_elems,
     return launch_quantize(false, x_bf16, rows, K, ld_elems, out, static_cast<hipStream_t>(stream));
 }
 
+// x [rows, cols] quantized along its rows into rows [row_offset, row_offset + rows) of the K axis of `out`
+// (the quantized transpose [cols, out.K])
 static int quantize_t_common(bool mx, const void* x, int64_t rows, int64_t cols, int64_t ld, dfp4_tensor out,
-                             void* stream) {
+                             int64_t row_offset, void* stream) {
     if (rows < 0 || cols < 0 || rows % kBlock != 0 || cols % 8 != 0 || ld < cols || out.rows != cols ||
-        out.K != rows)
+        row_offset < 0 || row_offset % kBlock != 0 || out.K % kBlock != 0 || row_offset + rows > out.K)
         return DFP4_ERR_SHAPE;
     if (rows == 0 || cols == 0) return DFP4_OK;
     if (!x || !out.codes || !out.exponent || (!mx && !out.dialect)) return DFP4_ERR_NULL;
     if (ld % 8 != 0 || !aligned(x, 16) || !aligned(out.codes, 4)) return DFP4_ERR_ALIGN;
-    return launch_quantize_t(mx, x, rows, cols, ld, out, static_cast<hipStream_t>(stream));
+    if (out.K / kBlock >= ((int64_t)1 << 31) / (cols > 0 ? cols : 1)) return DFP4_ERR_SHAPE;
+    return launch_quantize_t(mx, x, rows, cols, ld, out, row_offset, static_cast<hipStream_t>(stream));
 }
 
 int dfp4_quantize_t(const void* x_bf16, int64_t rows, int64_t cols, int64_t ld_elems, dfp4_tensor out,
                     void* stream) {
-    return quantize_t_common(false, x_bf16, rows, cols, ld_elems, out, stream);
+    if (out.K != rows) return DFP4_ERR_SHAPE;
+    return quantize_t_common(false, x_bf16, rows, cols, ld_elems, out, 0, stream);
 }
 
 int mxfp4_quantize_t(const void* x_bf16, int64_t rows, int64_t cols, int64_t ld_elems, dfp4_tensor out,
                      void* stream) {
-    return quantize_t_common(true, x_bf16, rows, cols, ld_elems, out, stream);
+    if (out.K != rows) return DFP4_ERR_SHAPE;
+    return quantize_t_common(true, x_bf16, rows, cols, ld_elems, out, 0, stream);
+}
+
+int dfp4_quantize_t_at(const void* x_bf16, int64_t rows, int64_t cols, int64_t ld_elems, dfp4_tensor out,
+                       int64_t row_offset, void* stream) {
+    return quantize_t_common(false, x_bf16, rows, cols, ld_elems, out, row_offset, stream);
 }
 
 int dfp4_quantize_mse(const void* x_bf16, int64_t rows, int64_t K, int64_t ld_elems, dfp4_tensor out,

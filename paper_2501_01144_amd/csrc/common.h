@@ -24,7 +24,7 @@ int check_quant_args(const void* dense, int64_t rows, int64_t K, int64_t ld, con
 int launch_quantize(bool mx, const void* x, int64_t rows, int64_t K, int64_t ld, dfp4_tensor out,
                     hipStream_t stream);
 int launch_quantize_t(bool mx, const void* x, int64_t rows, int64_t cols, int64_t ld, dfp4_tensor out,
-                      hipStream_t stream);
+                      int64_t row_offset, hipStream_t stream);
 int launch_quantize_native(const void* x, int64_t rows, int64_t K, int64_t ld, void* packed, size_t sc_offset,
                            hipStream_t stream);
 size_t native_scale_offset(int64_t rows, int64_t K, bool fp6);

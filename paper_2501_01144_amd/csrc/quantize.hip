@@ -224,7 +224,7 @@ constexpr int kTRows = 128, kTCols = 64, kTPitch = 66;     // LDS row pitch in b
 
 template <bool MX>
 __global__ __launch_bounds__(256) void quantize_t_kernel(
-    const uint16_t* __restrict__ x, int64_t ld, uint32_t rows, uint32_t cols,
+    const uint16_t* __restrict__ x, int64_t ld, uint32_t rows, uint32_t cols, uint32_t out_blocks, uint32_t block0,
     uint32_t* __restrict__ codes, uint8_t* __restrict__ dialect, uint8_t* __restrict__ exponent) {
     __shared__ __attribute__((aligned(16))) uint8_t lds_q[MX ? 64 : kDialects * 1024];
     __shared__ __attribute__((aligned(16))) uint8_t lds_s[MX ? 16 : kPairs * 1024];
@@ -250,7 +250,9 @@ __global__ __launch_bounds__(256) void quantize_t_kernel(
     }
     __syncthreads();
     const uint32_t c = tid >> 2, sub = tid & 3u;
-    const uint32_t kb_per_col = rows / kBlock;                 // blocks of x^T's row `c0 + c`
+    // blocks per row of the output tensor (out_blocks >= rows / 32: the input may be a chunk of the
+    // rows of a longer sequence, written at block column block0)
+    const uint32_t kb_in = rows / kBlock;
     const bool col_ok = c0 + c < cols;
 #pragma unroll
     for (uint32_t p = 0; p < kTRows / kBlock; ++p) {
@@ -264,8 +266,8 @@ __global__ __launch_bounds__(256) void quantize_t_kernel(
         if constexpr (MX) mxfp4_pass(wv, lds_q, code, eb);
         else dfp4_pass(wv, lds_s, lds_q, code, eb, dl);
         const uint32_t blk_row = (r0 >> 5) + p;                // block index along the original rows
-        if (col_ok && blk_row < kb_per_col) {
-            const size_t blk = (size_t)(c0 + c) * kb_per_col + blk_row;
+        if (col_ok && blk_row < kb_in) {
+            const size_t blk = (size_t)(c0 + c) * out_blocks + block0 + blk_row;
             codes[blk * 4u + sub] = code;
             if (sub == 0) {
                 exponent[blk] = (uint8_t)eb;
@@ -394,7 +396,7 @@ int launch_quantize_native(const void* x, int64_t rows, int64_t K, int64_t ld, v
 }
 
 int launch_quantize_t(bool mx, const void* x, int64_t rows, int64_t cols, int64_t ld, dfp4_tensor out,
-                      hipStream_t stream) {
+                      int64_t row_offset, hipStream_t stream) {
     if (rows == 0 || cols == 0) return DFP4_OK;
     if (rows * (cols / 1) >= ((int64_t)1 << 34) || rows >= ((int64_t)1 << 31) || cols >= ((int64_t)1 << 31))
         return DFP4_ERR_SHAPE;
@@ -404,10 +406,12 @@ int launch_quantize_t(bool mx, const void* x, int64_t rows, int64_t cols, int64_
     uint32_t* cp = reinterpret_cast<uint32_t*>(out.codes);
     if (mx)
         hipLaunchKernelGGL((quantize_t_kernel<true>), grid, dim3(256), 0, stream, xp, ld, (uint32_t)rows,
-                           (uint32_t)cols, cp, out.dialect, out.exponent);
+                           (uint32_t)cols, (uint32_t)(out.K / kBlock), (uint32_t)(row_offset / kBlock), cp,
+                           out.dialect, out.exponent);
     else
         hipLaunchKernelGGL((quantize_t_kernel<false>), grid, dim3(256), 0, stream, xp, ld, (uint32_t)rows,
-                           (uint32_t)cols, cp, out.dialect, out.exponent);
+                           (uint32_t)cols, (uint32_t)(out.K / kBlock), (uint32_t)(row_offset / kBlock), cp,
+                           out.dialect, out.exponent);
     return check_launch();
 }
 

@@ -25,7 +25,7 @@ class _CTensor(ctypes.Structure):
 
 
 SYMBOLS = [
-    "dfp4_quantize", "dfp4_quantize_mse", "dfp4_quantize_t", "mxfp4_quantize_t", "dfp4_dequantize", "dfp4_gemm", "dfp4_gemm_batched", "dfp4_gemm_workspace_bytes",
+    "dfp4_quantize", "dfp4_quantize_mse", "dfp4_quantize_t", "mxfp4_quantize_t", "dfp4_quantize_t_at", "dfp4_dequantize", "dfp4_gemm", "dfp4_gemm_batched", "dfp4_gemm_workspace_bytes",
     "mxfp4_gemm_native", "dfp4_gemm_native", "dfp4_gemm_native_workspace_bytes", "dfp4_native_packed_bytes",
     "dfp4_quantize_native", "dfp4_native_pack", "mxfp4_native_pack", "dfp4_gemm_native_packed_w", "mxfp4_gemm_native_packed_w",
     "dfp4_gemm_native_packed", "mxfp4_gemm_native_packed", "dfp4_gemm_native_splitk_bytes",
@@ -52,6 +52,8 @@ def load():
     lib.dfp4_quantize_mse.argtypes = [vp, i64, i64, i64, _CTensor, vp]
     lib.dfp4_quantize_t.argtypes = [vp, i64, i64, i64, _CTensor, vp]
     lib.mxfp4_quantize_t.argtypes = [vp, i64, i64, i64, _CTensor, vp]
+    lib.dfp4_quantize_t_at.argtypes = [vp, i64, i64, i64, _CTensor, i64, vp]
+    lib.dfp4_quantize_t_at.restype = ci
     lib.dfp4_dequantize.argtypes = [_CTensor, vp, ci, i64, vp]
     lib.mxfp4_dequantize.argtypes = [_CTensor, vp, ci, i64, vp]
     lib.dfp4_gemm.argtypes = [_CTensor, _CTensor, vp, ci, i64, vp, ctypes.c_size_t, vp]
@@ -168,6 +170,16 @@ def _quantize_t(fn, what, x, out, mx):
 def quantize_t(x, out=None):
     """dfp4_quantize_t: bf16 [rows, cols] -> QTensor of x^T (blocks of 32 along the rows of x)."""
     return _quantize_t(load().dfp4_quantize_t, "dfp4_quantize_t", x, out, False)
+
+
+def quantize_t_at(x, out, row_offset):
+    """dfp4_quantize_t_at: quantize `x` [rows, cols] (rows a multiple of 32) along its rows into the
+    quantized transpose `out` [cols, capacity] at token `row_offset`."""
+    assert x.dtype == torch.bfloat16 and x.dim() == 2 and x.is_cuda and x.stride(1) == 1
+    rows, cols = x.shape
+    ld = x.stride(0) if rows > 1 else cols
+    _check(load().dfp4_quantize_t_at(_ptr(x), rows, cols, ld, out.c(), row_offset, _stream()), "dfp4_quantize_t_at")
+    return out
 
 
 def mxfp4_quantize_t(x, out=None):

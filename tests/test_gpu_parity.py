@@ -674,3 +674,35 @@ def test_quantize_native_equals_quantize_then_pack(rows, K):
     torch.cuda.synchronize()
     ref, absdot = _gemm_ref(synth.to_f64(x.cpu()), synth.to_f64(w))
     _assert_gemm_close(out, ref, absdot, "quantize_native product")
+
+
+# --------------------------------------------------------------------------
+# value cache with a high-precision residual chunk (Appendix C)
+# --------------------------------------------------------------------------
+def test_value_cache_appends_match_quantizing_the_transpose():
+    from paper_2501_01144_amd.kvcache import ValueCache
+    D, cap = 64, 256
+    v = synth.gaussian_outlier_channels(200, D, 2, 30.0, 1.0, seed=41)
+    cache = ValueCache(D, cap, "cuda")
+    pos = 0
+    for step in (1, 5, 26, 1, 64, 31, 40, 32):          # odd sizes: chunks complete at different points
+        cache.append(v[pos:pos + step].cuda())
+        pos += step
+        torch.cuda.synchronize()
+        assert cache.n_tokens == pos and cache.n_quantized == pos // 32 * 32
+        nq = cache.n_quantized
+        if nq:
+            codes, dialect, expo = O.dfp4_quantize(synth.to_f64(v[:nq]).T.copy())
+            assert np.array_equal(_np(cache.q.codes)[:, :nq // 2], codes)
+            assert np.array_equal(_np(cache.q.dialect)[:, :nq // 32], dialect)
+            assert np.array_equal(_np(cache.q.exponent)[:, :nq // 32], expo)
+        assert not _np(cache.q.codes)[:, nq // 2:].any()                      # later blocks untouched
+        assert torch.equal(cache.residual_values().cpu(), v[nq:pos])
+    # P V over the whole capacity with zero-padded probabilities = product over the quantized tokens
+    nq = cache.n_quantized
+    p = torch.zeros(4, cap, dtype=torch.bfloat16)
+    p[:, :nq] = synth.softmax_rows(4, nq, seed=42)
+    out = dfp4.gemm(dfp4.quantize(_dev(p)), cache.q)
+    torch.cuda.synchronize()
+    ref, absdot = _gemm_ref(synth.to_f64(p[:, :nq]), synth.to_f64(v[:nq]).T.copy())
+    _assert_gemm_close(out, ref, absdot, "P V through the cache")
