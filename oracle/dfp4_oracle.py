@@ -163,6 +163,34 @@ def dfp4_quantize(x, chunk_blocks=1 << 15):
     return codes, dialect.reshape(rows, K // BLOCK), exponent.reshape(rows, K // BLOCK)
 
 
+def dfp4_quantize_block64(x, chunk_blocks=1 << 14):
+    """DialectFP4 with blocks of 64 (Section 4.3 varies the block size): the same steps
+    on 64 consecutive elements -- one shared exponent, one dialect chosen from the votes
+    of all 64.  Returned in the layout of the 32-element format: each block's exponent
+    byte and dialect id appear twice (once per 32 elements), so that every consumer of
+    the 32-element layout reads it unchanged."""
+    x = np.asarray(x, dtype=np.float64)
+    assert x.ndim == 2 and x.shape[1] % 64 == 0
+    assert np.isfinite(x).all()
+    rows, K = x.shape
+    nb = rows * (K // 64)
+    xb = x.reshape(nb, 64)
+    index = np.empty((nb, 64), dtype=np.uint8)
+    dialect = np.empty(nb, dtype=np.uint8)
+    exponent = np.empty(nb, dtype=np.uint8)
+    for b0 in range(0, nb, chunk_blocks):
+        mag = np.abs(xb[b0:b0 + chunk_blocks])
+        e = shared_exponent(mag.max(axis=1))
+        s = np.ldexp(mag, (-e)[:, None].astype(np.int32))
+        d = select_dialect(s)
+        index[b0:b0 + chunk_blocks] = nearest_index(s, d)
+        dialect[b0:b0 + chunk_blocks] = d
+        exponent[b0:b0 + chunk_blocks] = e + EXP_BIAS
+    codes = pack_codes(np.signbit(xb), index).reshape(rows, K // 2)
+    return (codes, np.repeat(dialect.reshape(rows, K // 64), 2, axis=1),
+            np.repeat(exponent.reshape(rows, K // 64), 2, axis=1))
+
+
 def select_dialect_mse(s):
     """Dialect with the smallest squared error (Section 3.2: for weights, known in
     advance, the best dialect of a block can be found by computing the exact mean

@@ -505,3 +505,33 @@ def test_gemm_requant_is_quantized_rounded_product():
     amax = np.abs(prod).max(axis=1, keepdims=True)
     assert (np.abs(deq - prod) <= amax * (1.5 / 4.0) + 1e-30).all()
     assert codes.shape == (3, 16) and dialect.shape == (3, 1)
+
+
+# --------------------------------------------------------------------------
+# blocks of 64
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("kind", ["gauss", "outlier", "wide", "grid"])
+def test_block64_vs_exact_brute_force(kind):
+    rng = np.random.default_rng({"gauss": 51, "outlier": 53, "wide": 54, "grid": 55}[kind])
+    x = _random_blocks(rng, 96, kind).reshape(48, 64)
+    codes, dialect, expo = O.dfp4_quantize_block64(x)
+    nib = _nibbles(codes)
+    for b in range(x.shape[0]):
+        e, d, idx = BF.quantize_block([Fraction(v) for v in x[b]], BOOK_FR)     # exhaustive, any block length
+        assert (int(expo[b, 0]) - 127, int(expo[b, 1]) - 127) == (e, e), (kind, b)
+        assert (int(dialect[b, 0]), int(dialect[b, 1])) == (d, d), (kind, b)
+        assert list(nib[b] & 7) == idx, (kind, b)
+
+
+def test_block64_output_reads_as_the_32_element_format():
+    # dequantizing through the ordinary (32-element) path gives values of the chosen dialect scaled by the
+    # 64-element block's exponent; a block of 64 whose halves have very different maxima shows the difference
+    x = np.zeros((1, 64))
+    x[0, :32] = 6.5
+    x[0, 32:] = 0.4
+    codes, dialect, expo = O.dfp4_quantize_block64(x)
+    assert int(expo[0, 0]) == int(expo[0, 1]) == 127 and int(dialect[0, 0]) == int(dialect[0, 1])
+    deq = O.dfp4_dequantize(codes, dialect, expo)
+    assert np.array_equal(deq[0, :32], np.full(32, 6.5)) and np.array_equal(deq[0, 32:], np.full(32, 0.5))
+    c32, d32, e32 = O.dfp4_quantize(x)
+    assert int(e32[0, 1]) < 127            # with blocks of 32 the second half gets its own, smaller exponent
