@@ -102,6 +102,14 @@ int dfp4_quantize_mse(const void* x_bf16, int64_t rows, int64_t K, int64_t ld_el
     return launch_quantize_mse(x_bf16, rows, K, ld_elems, out, static_cast<hipStream_t>(stream));
 }
 
+int dfp4_quantize_b64(const void* x_bf16, int64_t rows, int64_t K, int64_t ld_elems, dfp4_tensor out,
+                      void* stream) {
+    if (K % 64 != 0) return DFP4_ERR_SHAPE;
+    const int rc = check_quant_args(x_bf16, rows, K, ld_elems, out, true);
+    if (rc != DFP4_OK) return rc;
+    return launch_quantize(false, x_bf16, rows, K, ld_elems, out, static_cast<hipStream_t>(stream), true);
+}
+
 int mxfp4_quantize(const void* x_bf16, int64_t rows, int64_t K, int64_t ld_elems, dfp4_tensor out,
                    void* stream) {
     const int rc = check_quant_args(x_bf16, rows, K, ld_elems, out, false);

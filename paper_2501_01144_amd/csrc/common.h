@@ -22,7 +22,7 @@ int check_quant_args(const void* dense, int64_t rows, int64_t K, int64_t ld, con
 
 // kernels (defined in the .hip files)
 int launch_quantize(bool mx, const void* x, int64_t rows, int64_t K, int64_t ld, dfp4_tensor out,
-                    hipStream_t stream);
+                    hipStream_t stream, bool wide = false);
 int launch_quantize_t(bool mx, const void* x, int64_t rows, int64_t cols, int64_t ld, dfp4_tensor out,
                       int64_t row_offset, hipStream_t stream);
 int launch_quantize_native(const void* x, int64_t rows, int64_t K, int64_t ld, void* packed, size_t sc_offset,

@@ -34,7 +34,15 @@ __device__ __forceinline__ uint32_t sign_nibbles(const uint32_t (&w)[4]) {
     return (hi & 0x80808080u) | ((lo >> 4) & 0x08080808u);
 }
 
-// Block maximum over the quad's 32 elements, as bf16 bits (sign cleared).
+// value of the lane that mirrors this one inside its group of 8 lanes (lane i <-> 7 - i): after a
+// reduction over the quad it is the other quad's result
+__device__ __forceinline__ uint32_t other_quad(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x141, 0xf, 0xf, true);
+}
+
+// Block maximum over the quad's 32 elements (WIDE: over the 64 elements of two neighbouring quads),
+// as bf16 bits (sign cleared).
+template <bool WIDE = false>
 __device__ __forceinline__ uint32_t block_amax_bits(const uint32_t (&w)[4]) {
     float m = 0.0f;
 #pragma unroll
@@ -46,15 +54,18 @@ __device__ __forceinline__ uint32_t block_amax_bits(const uint32_t (&w)[4]) {
     uint32_t u = as_u(m);
     u = max(u, quad<0xB1>(u));
     u = max(u, quad<0x4E>(u));
+    if constexpr (WIDE) u = max(u, other_quad(u));
     return u >> 16;
 }
 
-// One lane's share (8 elements) of one DialectFP4 block.
+// One lane's share (8 elements) of one DialectFP4 block.  WIDE: blocks of 64 elements (two
+// neighbouring quads share the exponent and the dialect; Section 4.3 varies the block size).
+template <bool WIDE = false>
 __device__ __forceinline__ void dfp4_pass(const uint4& wv, const uint8_t* __restrict__ lut_s,
                                           const uint8_t* __restrict__ lut_q, uint32_t& code,
                                           uint32_t& ebyte, uint32_t& dial) {
     const uint32_t w[4] = {wv.x, wv.y, wv.z, wv.w};
-    const uint32_t ab = block_amax_bits(w);
+    const uint32_t ab = block_amax_bits<WIDE>(w);
     // exponent byte = biased exponent of the maximum, minus 2, floored at 0
     const int byte = max((int)(ab >> 7) - 2, 0);
     const int n = 129 - byte;                       // 4 |x| / 2^e = |x| * 2^n
@@ -75,6 +86,7 @@ __device__ __forceinline__ void dfp4_pass(const uint4& wv, const uint8_t* __rest
     uint32_t v = (uint32_t)((int)s[key[0]] + (int)s[key[1]] + (int)s[key[2]] + (int)s[key[3]]);
     v += quad<0xB1>(v);
     v += quad<0x4E>(v);
+    if constexpr (WIDE) v += other_quad(v);
     dial = 2u * pair + (v >> 31);
     const uint8_t* q = lut_q + dial * 1024u;
     const us2 qe = {q[key[0]], q[key[2]]}, qo = {q[key[1]], q[key[3]]};   // bytes 0, 2 and bytes 1, 3

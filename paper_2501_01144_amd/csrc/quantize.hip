@@ -57,7 +57,9 @@ __device__ __forceinline__ void load_super(const uint16_t* __restrict__ x, int64
     }
 }
 
-template <bool MX, bool CONTIG>
+// WIDE: blocks of 64 (each 64-element block is two neighbouring quads; its exponent byte and dialect
+// id are written for both 32-element halves, so that the output reads as the 32-element format)
+template <bool MX, bool CONTIG, bool WIDE>
 __global__ __launch_bounds__(kThreads) void quantize_kernel(
     const uint16_t* __restrict__ x, int64_t ld, uint32_t blocks_per_row, uint32_t nblocks,
     uint32_t* __restrict__ codes, uint8_t* __restrict__ dialect, uint8_t* __restrict__ exponent) {
@@ -101,7 +103,7 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(
                     mxfp4_pass(w[p], lds_q, code, eb[p]);
                     dl[p] = 0;
                 } else {
-                    dfp4_pass(w[p], lds_s, lds_q, code, eb[p], dl[p]);
+                    dfp4_pass<WIDE>(w[p], lds_s, lds_q, code, eb[p], dl[p]);
                 }
                 cdst[p * 64 + lane] = code;
                 w[p] = nbase[p * 64 + lane];
@@ -119,7 +121,7 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(
                     mxfp4_pass(w[p], lds_q, code, eb[p]);
                     dl[p] = 0;
                 } else {
-                    dfp4_pass(w[p], lds_s, lds_q, code, eb[p], dl[p]);
+                    dfp4_pass<WIDE>(w[p], lds_s, lds_q, code, eb[p], dl[p]);
                 }
                 if (full || sc * 64u + p * kBlocksPerPass + quad_id < nblocks) cdst[p * 64 + lane] = code;
             }
@@ -355,7 +357,7 @@ __global__ __launch_bounds__(256) void quantize_mse_kernel(
 }  // namespace
 
 int launch_quantize(bool mx, const void* x, int64_t rows, int64_t K, int64_t ld, dfp4_tensor out,
-                    hipStream_t stream) {
+                    hipStream_t stream, bool wide) {
     const int64_t nblocks64 = rows * (K / kBlock);
     if (nblocks64 == 0) return DFP4_OK;
     if (nblocks64 >= (int64_t)1 << 31) return DFP4_ERR_SHAPE;
@@ -368,13 +370,15 @@ int launch_quantize(bool mx, const void* x, int64_t rows, int64_t K, int64_t ld,
     const uint16_t* xp = static_cast<const uint16_t*>(x);
     uint32_t* cp = reinterpret_cast<uint32_t*>(out.codes);
     const uint32_t kb = (uint32_t)(K / kBlock);
-#define DFP4_LAUNCH(MXV, CV)                                                                    \
-    hipLaunchKernelGGL((quantize_kernel<MXV, CV>), dim3(grid), dim3(kThreads), 0, stream, xp, ld, \
+#define DFP4_LAUNCH(MXV, CV, WV)                                                                    \
+    hipLaunchKernelGGL((quantize_kernel<MXV, CV, WV>), dim3(grid), dim3(kThreads), 0, stream, xp, ld, \
                        kb, nblocks, cp, out.dialect, out.exponent)
     if (mx) {
-        if (contig) DFP4_LAUNCH(true, true); else DFP4_LAUNCH(true, false);
+        if (contig) DFP4_LAUNCH(true, true, false); else DFP4_LAUNCH(true, false, false);
+    } else if (wide) {
+        if (contig) DFP4_LAUNCH(false, true, true); else DFP4_LAUNCH(false, false, true);
     } else {
-        if (contig) DFP4_LAUNCH(false, true); else DFP4_LAUNCH(false, false);
+        if (contig) DFP4_LAUNCH(false, true, false); else DFP4_LAUNCH(false, false, false);
     }
 #undef DFP4_LAUNCH
     return check_launch();

@@ -25,7 +25,7 @@ class _CTensor(ctypes.Structure):
 
 
 SYMBOLS = [
-    "dfp4_quantize", "dfp4_quantize_mse", "dfp4_quantize_t", "mxfp4_quantize_t", "dfp4_quantize_t_at", "dfp4_dequantize", "dfp4_gemm", "dfp4_gemm_batched", "dfp4_gemm_workspace_bytes",
+    "dfp4_quantize", "dfp4_quantize_b64", "dfp4_quantize_mse", "dfp4_quantize_t", "mxfp4_quantize_t", "dfp4_quantize_t_at", "dfp4_dequantize", "dfp4_gemm", "dfp4_gemm_batched", "dfp4_gemm_workspace_bytes",
     "mxfp4_gemm_native", "dfp4_gemm_native", "dfp4_gemm_native_workspace_bytes", "dfp4_native_packed_bytes",
     "dfp4_quantize_native", "dfp4_native_pack", "mxfp4_native_pack", "dfp4_gemm_native_packed_w", "mxfp4_gemm_native_packed_w",
     "dfp4_gemm_native_packed", "mxfp4_gemm_native_packed", "dfp4_gemm_native_splitk_bytes",
@@ -50,6 +50,7 @@ def load():
     lib.dfp4_quantize.argtypes = [vp, i64, i64, i64, _CTensor, vp]
     lib.mxfp4_quantize.argtypes = [vp, i64, i64, i64, _CTensor, vp]
     lib.dfp4_quantize_mse.argtypes = [vp, i64, i64, i64, _CTensor, vp]
+    lib.dfp4_quantize_b64.argtypes = [vp, i64, i64, i64, _CTensor, vp]
     lib.dfp4_quantize_t.argtypes = [vp, i64, i64, i64, _CTensor, vp]
     lib.mxfp4_quantize_t.argtypes = [vp, i64, i64, i64, _CTensor, vp]
     lib.dfp4_quantize_t_at.argtypes = [vp, i64, i64, i64, _CTensor, i64, vp]
@@ -92,7 +93,7 @@ def load():
     lib.dfp4_formatbook.argtypes = [vp]
     lib.dfp4_strerror.argtypes = [ci]
     lib.dfp4_strerror.restype = ctypes.c_char_p
-    for name in ("dfp4_quantize", "dfp4_quantize_mse", "dfp4_quantize_t", "mxfp4_quantize_t", "mxfp4_quantize", "dfp4_dequantize", "mxfp4_dequantize", "dfp4_gemm",
+    for name in ("dfp4_quantize", "dfp4_quantize_b64", "dfp4_quantize_mse", "dfp4_quantize_t", "mxfp4_quantize_t", "mxfp4_quantize", "dfp4_dequantize", "mxfp4_dequantize", "dfp4_gemm",
                  "mxfp4_gemm", "dfp4_gemm_batched", "dfp4_formatbook"):
         getattr(lib, name).restype = ci
     _lib = lib
@@ -150,6 +151,11 @@ def _quantize(fn, what, x, out, mx):
 def quantize(x, out=None):
     """dfp4_quantize: bf16 [rows, K] (row stride allowed) -> QTensor."""
     return _quantize(load().dfp4_quantize, "dfp4_quantize", x, out, False)
+
+
+def quantize_b64(x, out=None):
+    """dfp4_quantize_b64: blocks of 64 elements, output in the layout of the 32-element format."""
+    return _quantize(load().dfp4_quantize_b64, "dfp4_quantize_b64", x, out, False)
 
 
 def quantize_mse(x, out=None):

@@ -706,3 +706,28 @@ def test_value_cache_appends_match_quantizing_the_transpose():
     torch.cuda.synchronize()
     ref, absdot = _gemm_ref(synth.to_f64(p[:, :nq]), synth.to_f64(v[:nq]).T.copy())
     _assert_gemm_close(out, ref, absdot, "P V through the cache")
+
+
+# --------------------------------------------------------------------------
+# blocks of 64
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("rows,K", [(1, 64), (7, 192), (33, 4096), (257, 1088)])
+def test_quantize_block64(rows, K):
+    print(f"quantize_b64 parity: {rows}x{K}", flush=True)
+    for x in (synth.student_t(rows, K, 3.0, seed=rows + K),
+              synth.gaussian_outlier_channels(rows, K, max(1, K // 100), 50.0, 1.0, seed=rows)):
+        q = dfp4.quantize_b64(_dev(x))
+        torch.cuda.synchronize()
+        _assert_quant_equal(q, O.dfp4_quantize_block64(synth.to_f64(x)), "block 64")
+    # strided input, and the result multiplies like any other quantized tensor
+    wide = torch.zeros(rows, K + 64, dtype=torch.bfloat16, device="cuda")
+    wide[:, 32:32 + K] = x.cuda()
+    q2 = dfp4.quantize_b64(wide[:, 32:32 + K])
+    torch.cuda.synchronize()
+    _assert_quant_equal(q2, O.dfp4_quantize_block64(synth.to_f64(x)), "block 64 strided")
+    w = synth.gaussian(40, K, 0.02, seed=K)
+    out = dfp4.gemm(q, dfp4.quantize_b64(_dev(w)))
+    torch.cuda.synchronize()
+    ad = O.dfp4_dequantize(*O.dfp4_quantize_block64(synth.to_f64(x)))
+    wd = O.dfp4_dequantize(*O.dfp4_quantize_block64(synth.to_f64(w)))
+    _assert_gemm_close(out, ad @ wd.T, np.abs(ad) @ np.abs(wd).T, "block 64 product")
