@@ -27,6 +27,14 @@ Parity status of each function against something other than itself:
                                     exhaustive brute force with exact rationals)
   dequantize / gemm ............... pinned (closed form, integer formulation in
                                     exact rationals, hand-worked block)
+  dfp4_quantize_mse ............... pinned (exhaustive exact-rational search over the 16
+                                    dialects; never worse than the two-stage choice;
+                                    lossless on a dialect's own grid); the tie rule
+                                    (lowest id) is a reading the paper does not fix
+  dfp4_quantize_block64 ........... pinned (the exhaustive per-block search run on
+                                    64-element blocks)
+  round_to_bf16, dfp4_gemm_requant  pinned (library bf16 conversion; dequantized
+                                    result bounded by the dialect gaps)
   mxfp4_* ......................... rounding mode is a reading (round to nearest,
                                     ties to even code, saturating): pinned against an
                                     exact-rational brute force of that reading only
