@@ -239,6 +239,73 @@ __global__ __launch_bounds__(256, 1) void gemm_native_kernel(NativeParams p) {
 #undef DFP4_NATIVE_STORE
 }
 
+// Few rows of A (decode shapes, M <= 64): 32 W rows per workgroup, its 16 waves share K (wave w
+// takes a contiguous range of steps), one or two MFMAs per step; the 16 partial tiles are added in
+// a fixed order through LDS.  No vector-ALU work: both operands arrive packed.
+template <int FMT, bool BF16>
+__global__ __launch_bounds__(1024) void gemm_native_small_kernel(NativeParams p) {
+    constexpr bool kFp6 = FMT == kFmtFp6;
+    constexpr int kStride = kFp6 ? kFp6ChunkBytes : 1024;
+    __shared__ float s_red[8][2][16][64];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int kh = lane >> 5, c = lane & 31;
+    const int S = p.S, t = blockIdx.x, mt = (p.M + 31) / 32;           // mt = 1 or 2 row tiles of A
+    const int per = (S + 15) / 16, s_lo = wave * per, s_hi = min(S, s_lo + per);
+    auto load = [&](const PackedOperand& src, int tile, int s, v8i& v, int& sc) {
+        const uint8_t* q = src.bits + ((int64_t)tile * S + s) * kStride;
+        const uint4 lo = *reinterpret_cast<const uint4*>(q + lane * 16);
+        v = v8i{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, 0, 0, 0, 0};
+        if constexpr (kFp6) {
+            const uint32_t* hi = reinterpret_cast<const uint32_t*>(q + 1024 + lane * 12);
+            v[4] = (int)hi[0];
+            v[5] = (int)hi[1];
+        }
+        sc = (int)(src.sc[((int64_t)(tile >> 2) * S + s) * 64 + lane] >> (8 * (tile & 3)));
+    };
+    v16f acc[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int x = 0; x < 16; ++x) acc[i][x] = 0.0f;
+    for (int s = s_lo; s < s_hi; ++s) {
+        v8i w, a0, a1 = v8i{0, 0, 0, 0, 0, 0, 0, 0};
+        int sw, s0, s1 = 0;
+        load(p.w, t, s, w, sw);
+        load(p.a, 0, s, a0, s0);
+        if (mt > 1) load(p.a, 1, s, a1, s1);
+        acc[0] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a0, w, acc[0], FMT, FMT, 0, s0, 0, sw);
+        if (mt > 1) acc[1] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a1, w, acc[1], FMT, FMT, 0, s1, 0, sw);
+    }
+    // the 16 partial tiles, added in a fixed order: waves 8..15 hand theirs to waves 0..7
+    if (wave >= 8) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int x = 0; x < 16; ++x) s_red[wave - 8][i][x][lane] = acc[i][x];
+    }
+    __syncthreads();
+    if (wave < 8) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int x = 0; x < 16; ++x) s_red[wave][i][x][lane] += acc[i][x];
+    }
+    __syncthreads();
+    const int n = t * 32 + c;
+    for (int i = 0; i < mt; ++i) {
+        const int x = wave;                                    // thread (x, lane) finishes one output per row tile
+        float sum = 0.0f;
+#pragma unroll
+        for (int w8 = 0; w8 < 8; ++w8) sum += s_red[w8][i][x][lane];
+        const int m = i * 32 + 8 * (x >> 2) + 4 * kh + (x & 3);
+        if (m < p.M && n < p.N) {
+            const int64_t o = (int64_t)m * p.ldc + n;
+            if constexpr (BF16) static_cast<uint16_t*>(p.out)[o] = f32_to_bf16_rne_n(sum);
+            else static_cast<float*>(p.out)[o] = sum;
+        }
+    }
+}
+
 // Split K: out = sum of the ranges' fp32 partial tiles, added in range order, converted once.
 template <bool BF16>
 __global__ __launch_bounds__(256) void native_reduce_kernel(const float* __restrict__ part, void* out, int M, int N,
@@ -325,6 +392,20 @@ int launch_gemm_native_packed(bool fp6, const void* a_packed, const void* w_pack
     p.a = PackedOperand{ap, reinterpret_cast<uint32_t*>(ap + operand_layout(M, KB, fp6).sc)};
     p.w = PackedOperand{wp, reinterpret_cast<uint32_t*>(wp + operand_layout(N, KB, fp6).sc)};
     p.out = out; p.M = (int)M; p.N = (int)N; p.S = (int)((KB + 1) / 2); p.ldc = ldc;
+    if (M <= 64) {
+        // decode shapes: one workgroup per 32 W rows (A occupies the first one or two row tiles of its layout)
+        p.ksplit = 1;
+        dim3 gs((unsigned)((N + 31) / 32));
+        const bool b16 = out_dtype == DFP4_BF16;
+        if (fp6) {
+            if (b16) hipLaunchKernelGGL((gemm_native_small_kernel<kFmtFp6, true>), gs, dim3(1024), 0, stream, p);
+            else hipLaunchKernelGGL((gemm_native_small_kernel<kFmtFp6, false>), gs, dim3(1024), 0, stream, p);
+        } else {
+            if (b16) hipLaunchKernelGGL((gemm_native_small_kernel<kFmtFp4, true>), gs, dim3(1024), 0, stream, p);
+            else hipLaunchKernelGGL((gemm_native_small_kernel<kFmtFp4, false>), gs, dim3(1024), 0, stream, p);
+        }
+        return check_launch();
+    }
     p.ksplit = native_ksplit(M, N, KB);
     if (p.ksplit > 1 && (!splitk || splitk_bytes < native_splitk_bytes(M, N, K))) p.ksplit = 1;
     p.part = static_cast<float*>(splitk);

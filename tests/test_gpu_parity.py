@@ -731,3 +731,23 @@ def test_quantize_block64(rows, K):
     ad = O.dfp4_dequantize(*O.dfp4_quantize_block64(synth.to_f64(x)))
     wd = O.dfp4_dequantize(*O.dfp4_quantize_block64(synth.to_f64(w)))
     _assert_gemm_close(out, ad @ wd.T, np.abs(ad) @ np.abs(wd).T, "block 64 product")
+
+
+@pytest.mark.parametrize("M,N,K", [(5, 40, 64), (16, 4096, 4096), (33, 100, 1056), (64, 96, 256)])
+def test_gemm_native_few_rows(M, N, K):
+    # decode shapes on the block-scaled instruction: 32 W rows per workgroup, 16 waves share K
+    print(f"native few rows parity: {M}x{N}x{K}", flush=True)
+    a = synth.gaussian_outlier_channels(M, K, max(1, K // 200), 50.0, 1.0, seed=110 + M)
+    w = synth.gaussian(N, K, 0.02, seed=210 + N)
+    ref, absdot = _gemm_ref(synth.to_f64(a), synth.to_f64(w))
+    wp = dfp4.native_pack(dfp4.quantize(_dev(w)))
+    out = dfp4.gemm_native_packed(dfp4.quantize_native(_dev(a)), wp)
+    torch.cuda.synchronize()
+    _assert_gemm_close(out, ref, absdot, "native few rows f32")
+    outb = dfp4.gemm_native(dfp4.quantize(_dev(a)), dfp4.quantize(_dev(w)), dtype=torch.bfloat16)
+    torch.cuda.synchronize()
+    _assert_gemm_close(outb, ref, absdot, "native few rows bf16", bf16=True)
+    refm, absm = _gemm_ref(synth.to_f64(a), synth.to_f64(w), mx=True)
+    outm = dfp4.mxfp4_gemm_native(dfp4.mxfp4_quantize(_dev(a)), dfp4.mxfp4_quantize(_dev(w)))
+    torch.cuda.synchronize()
+    _assert_gemm_close(outm, refm, absm, "native few rows mxfp4")
