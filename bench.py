@@ -190,7 +190,10 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    evs = [_events(len(names), torch) for _ in range(args.steps)]
+    # HIP events around every call of every EVERY-th step of the timed region (events between all kernels of
+    # all steps would add their own gaps to the step time)
+    EVERY = 8
+    evs = [_events(len(names), torch) if s % EVERY == 0 else None for s in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for s in range(args.steps):
@@ -199,7 +202,8 @@ def main():
     dt = time.perf_counter() - t0
     ms_per_step = dt / args.steps * 1e3
 
-    kern_ms = {n: sum(e[i][0].elapsed_time(e[i][1]) for e in evs) / args.steps for i, n in enumerate(names)}
+    evs = [e for e in evs if e is not None]
+    kern_ms = {n: sum(e[i][0].elapsed_time(e[i][1]) for e in evs) / len(evs) for i, n in enumerate(names)}
     gemm_ops = {"gemm_gate": 2.0 * M * I * H, "gemm_up": 2.0 * M * I * H, "gemm_down": 2.0 * M * H * I}
     total_ops = sum(gemm_ops.values())
     gemm_ms = sum(kern_ms[n] for n in gemm_ops)
@@ -293,13 +297,14 @@ def main():
     for _ in range(max(3, args.warmup // 2)):
         step_native()
     torch.cuda.synchronize()
-    nev = [_events(len(nnames), torch) for _ in range(nn)]
+    nev = [_events(len(nnames), torch) if s % EVERY == 0 else None for s in range(nn)]
     t0 = time.perf_counter()
     for s in range(nn):
         step_native(nev[s])
     torch.cuda.synchronize()
     ms_n = (time.perf_counter() - t0) / nn * 1e3
-    nk = {n: sum(e[i][0].elapsed_time(e[i][1]) for e in nev) / nn for i, n in enumerate(nnames)}
+    nev = [e for e in nev if e is not None]
+    nk = {n: sum(e[i][0].elapsed_time(e[i][1]) for e in nev) / len(nev) for i, n in enumerate(nnames)}
     n_gemm_ms = sum(nk[n] for n in gemm_ops)
     n_tops = total_ops / (n_gemm_ms * 1e-3) / 1e12
     out["native_fp6_step"] = {
