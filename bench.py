@@ -132,13 +132,14 @@ def main():
     if not args.no_mfma_peak:
         exe = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2501_01144_amd", "mfma_peak")
         if not os.path.exists(exe):
-            print(f"bench.py: {exe} not found: build it with `python -m paper_2501_01144_amd.build`", file=sys.stderr)
-            sys.exit(1)
-        r = subprocess.run([exe], capture_output=True, text=True, timeout=120)
-        if r.returncode != 0:
-            print("bench.py: mfma_peak failed: " + r.stderr, file=sys.stderr)
-            sys.exit(1)
-        peak = json.loads(r.stdout.strip().splitlines()[-1])
+            print(f"bench.py: {exe} not found (build it with `python -m paper_2501_01144_amd.build`); "
+                  "the register-only MFMA loop is left out of the report", file=sys.stderr)
+        else:
+            r = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+            if r.returncode == 0 and r.stdout.strip():
+                peak = json.loads(r.stdout.strip().splitlines()[-1])
+            else:
+                print("bench.py: mfma_peak failed: " + r.stderr, file=sys.stderr)
 
     import torch
     from paper_2501_01144_amd import dfp4, synth
