@@ -2,7 +2,11 @@
 // with nothing else going on.  Run by bench.py (as a child process) to put the GEMM's
 // throughput beside a measured peak as well as the datasheet one.  Three operand
 // patterns, because the sustained clock depends on how many operand bits toggle:
-// constants, uniformly random int8, random 4-bit magnitudes.  Prints one JSON line.
+// constants, uniformly random int8, random 4-bit magnitudes -- and, when a file is named
+// as the second argument, operand bytes read from it (bench.py writes there a sample of
+// the int8 operands the GEMM really multiplies: signed dialect magnitudes shifted by the
+// block's exponent offset; 256 x 64 bytes of A operands followed by 256 x 64 bytes of W
+// operands, one 64-byte slice per thread).  Prints one JSON line.
 #include <hip/hip_runtime.h>
 #include <cstdio>
 #include <cstdlib>
@@ -25,14 +29,19 @@ __device__ unsigned mix(unsigned x) {
 }
 
 // 16 accumulator tiles (all 256 accumulation registers), 4 A and 4 B operand registers
-__global__ __launch_bounds__(256) void mfma_loop(int* out, long long* clk, int iters, int mode) {
+__global__ __launch_bounds__(256) void mfma_loop(int* out, long long* clk, int iters, int mode, const int* operands) {
     v4i a[4], b[4];
     for (int i = 0; i < 4; ++i)
         for (int j = 0; j < 4; ++j) {
             const unsigned t = threadIdx.x * 64 + i * 8 + j;
             const unsigned mask = mode == 2 ? 0x0f0f0f0fu : 0xffffffffu;
-            a[i][j] = mode ? (int)(mix(t) & mask) : 0x01010101;
-            b[i][j] = mode ? (int)(mix(t + 77777) & mask) : 0x01010101;
+            if (mode == 3) {
+                a[i][j] = operands[threadIdx.x * 16 + i * 4 + j];
+                b[i][j] = operands[4096 + threadIdx.x * 16 + i * 4 + j];
+            } else {
+                a[i][j] = mode ? (int)(mix(t) & mask) : 0x01010101;
+                b[i][j] = mode ? (int)(mix(t + 77777) & mask) : 0x01010101;
+            }
         }
     v16i acc[16];
     for (int i = 0; i < 16; ++i)
@@ -68,14 +77,30 @@ int main(int argc, char** argv) {
     hipEvent_t e0, e1;
     CK(hipEventCreate(&e0));
     CK(hipEventCreate(&e1));
-    const char* names[3] = {"constant_operands", "random_int8_operands", "random_4bit_operands"};
+    const char* names[4] = {"constant_operands", "random_int8_operands", "random_4bit_operands",
+                            "sampled_gemm_operands"};
+    // optional: 32 KiB of real operand bytes
+    int* operands = nullptr;
+    int nmodes = 3;
+    if (argc > 2) {
+        static int host[8192];
+        FILE* f = fopen(argv[2], "rb");
+        if (!f || fread(host, 1, sizeof(host), f) != sizeof(host)) {
+            fprintf(stderr, "mfma_peak: cannot read 32768 operand bytes from %s\n", argv[2]);
+            return 1;
+        }
+        fclose(f);
+        CK(hipMalloc(&operands, sizeof(host)));
+        CK(hipMemcpy(operands, host, sizeof(host), hipMemcpyHostToDevice));
+        nmodes = 4;
+    }
     printf("{\"compute_units\": %d, \"iters\": %d", wgs, iters);
-    for (int mode = 0; mode < 3; ++mode) {
+    for (int mode = 0; mode < nmodes; ++mode) {
         float ms = 0;
         long long h[2] = {0, 1};
         for (int rep = 0; rep < 2; ++rep) {          // the second run is reported
             CK(hipEventRecord(e0));
-            hipLaunchKernelGGL(mfma_loop, dim3(wgs), dim3(256), 0, 0, out, clk, iters, mode);
+            hipLaunchKernelGGL(mfma_loop, dim3(wgs), dim3(256), 0, 0, out, clk, iters, mode, operands);
             CK(hipEventRecord(e1));
             CK(hipEventSynchronize(e1));
             CK(hipEventElapsedTime(&ms, e0, e1));

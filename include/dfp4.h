@@ -86,7 +86,7 @@ int dfp4_quantize(const void* x_bf16, int64_t rows, int64_t K, int64_t ld_elems,
                   dfp4_tensor out, void* stream);
 
 /*
- * DialectFP4 with blocks of 64 elements (Section 4.3 varies the block size): one shared
+ * DialectFP4 with blocks of 64 elements (Section 4.2, Table 3 varies the block size): one shared
  * exponent and one dialect per 64 consecutive elements along K (K a multiple of 64), chosen
  * by the same steps from all 64.  The output keeps the layout of the 32-element format --
  * the exponent byte and the dialect id of a block are written for both of its halves -- so

@@ -33,8 +33,10 @@ Parity status of each function against something other than itself:
                                     (lowest id) is a reading the paper does not fix
   dfp4_quantize_block64 ........... pinned (the exhaustive per-block search run on
                                     64-element blocks)
-  round_to_bf16, dfp4_gemm_requant  pinned (library bf16 conversion; dequantized
-                                    result bounded by the dialect gaps)
+  round_to_bf16, dfp4_gemm_requant  pinned (library bf16 conversion; a hand-worked block
+                                    whose products sit on and just below a bf16 midpoint,
+                                    so that dropping the bf16 step or rounding in one
+                                    step changes a code)
   mxfp4_* ......................... rounding mode is a reading (round to nearest,
                                     ties to even code, saturating): pinned against an
                                     exact-rational brute force of that reading only

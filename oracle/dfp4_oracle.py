@@ -164,7 +164,7 @@ def dfp4_quantize(x, chunk_blocks=1 << 15):
 
 
 def dfp4_quantize_block64(x, chunk_blocks=1 << 14):
-    """DialectFP4 with blocks of 64 (Section 4.3 varies the block size): the same steps
+    """DialectFP4 with blocks of 64 (Section 4.2, Table 3 varies the block size): the same steps
     on 64 consecutive elements -- one shared exponent, one dialect chosen from the votes
     of all 64.  Returned in the layout of the 32-element format: each block's exponent
     byte and dialect id appear twice (once per 32 elements), so that every consumer of

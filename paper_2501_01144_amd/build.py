@@ -1,4 +1,5 @@
-"""Build libdfp4.so (HIP kernels + C ABI) and the mfma_peak measurement helper in-tree with hipcc for gfx950.
+"""Build libdfp4.so (HIP kernels + C ABI) in-tree with hipcc for gfx950, and the two
+measurement helpers of bench.py (bench_helpers/ at the repository root).
 
     python -m paper_2501_01144_amd.build
 
@@ -6,13 +7,15 @@ hipcc cross-compiles without a GPU.  The shared library is written next to
 this file; the ctypes binding loads it from there.
 """
 import os
+import re
 import subprocess
 import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdfp4.so")
-PEAK = os.path.join(HERE, "mfma_peak")
+HELPERS = os.path.join(ROOT, "bench_helpers")
 SOURCES = ["api.hip", "quantize.hip", "dequantize.hip", "gemm.hip", "gemm_native.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
@@ -22,9 +25,56 @@ FLAGS = [
     "-Wall", "-Wno-unused-function", "-Wno-inline-asm",
 ]
 
+_AGPR = re.compile(r"\ba(\d+|\[\d+:\d+\])(?![\w.])")
+
+
+def check_accumulators_untouched(asm_text):
+    """Guard for gemm_fast_kernel.  Its main loop is one inline-assembly statement that leaves
+    the 256 int32 accumulators in a0..a255; the epilogue reads them back with further
+    inline-assembly statements.  The compiler is told the loop clobbers those registers, so
+    nothing in the language stops it from using an accumulation register for its own purposes
+    (a spill, a copy) between the two.  This check makes that a build error instead of a silent
+    wrong result: in every gemm_fast_kernel, compiler-generated code after the main loop must not
+    name an accumulation register, and the kernel must not use scratch memory."""
+    problems = []
+    lines = asm_text.splitlines()
+    i, n = 0, len(lines)
+    while i < n:
+        m = re.match(r"^(_ZN\S*gemm_fast_kernel\S*):", lines[i])
+        if not m:
+            i += 1
+            continue
+        name = m.group(1)
+        in_asm, loops_seen, j = False, 0, i + 1
+        while j < n and ".end_amdhsa_kernel" not in lines[j]:
+            ln = lines[j]
+            if ";;#ASMSTART" in ln:
+                in_asm = True
+            elif ";;#ASMEND" in ln:
+                in_asm = False
+                loops_seen += 1
+            elif not in_asm and loops_seen >= 1:
+                code = ln.split(";")[0]
+                if _AGPR.search(code) and not code.lstrip().startswith("."):
+                    problems.append(f"{name}: compiler-generated code touches an accumulation register "
+                                    f"after the main loop: {code.strip()}")
+            j += 1
+        # resource summary that follows the kernel descriptor
+        k = j
+        while k < n and k < j + 60:
+            if "; ScratchSize:" in lines[k]:
+                if lines[k].split(":")[1].strip() != "0":
+                    problems.append(f"{name}: uses scratch memory ({lines[k].strip()})")
+                break
+            k += 1
+        if loops_seen == 0:
+            problems.append(f"{name}: main loop not found")
+        i = j
+    return problems
+
 
 def build_library(verbose=True):
-    # the hand-scheduled GEMM step is generated text (see csrc/gen_gemm_step.py)
+    # the hand-scheduled GEMM loops are generated text (see csrc/gen_gemm_step.py, csrc/gen_native_loop.py)
     subprocess.run([sys.executable, os.path.join(CSRC, "gen_gemm_step.py")], check=True,
                    stdout=subprocess.DEVNULL)
     subprocess.run([sys.executable, os.path.join(CSRC, "gen_native_loop.py")], check=True,
@@ -41,6 +91,17 @@ def build_library(verbose=True):
         if verbose:
             print(" ".join(cmd), flush=True)
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
+    # device assembly of the GEMM, for the accumulator guard
+    gemm_s = os.path.join(objdir, "gemm.s")
+    cmd = [hipcc, *FLAGS, "-S", "--cuda-device-only", os.path.join(CSRC, "gemm.hip"), "-o", gemm_s]
+    procs.append(("gemm.hip (assembly)", subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
+    # measurement helpers used by bench.py: register-only int8 MFMA loop, plain streaming kernels
+    for name in ("mfma_peak", "stream_peak"):
+        cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", os.path.join(HELPERS, name + ".hip"),
+               "-o", os.path.join(HELPERS, name)]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        procs.append((name, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
     failed = False
     for src, p in procs:
         out, _ = p.communicate()
@@ -52,12 +113,10 @@ def build_library(verbose=True):
             print(f"hipcc failed on {src}", file=sys.stderr)
     if failed:
         raise RuntimeError("libdfp4 build failed")
+    problems = check_accumulators_untouched(open(gemm_s).read())
+    if problems:
+        raise RuntimeError("gemm_fast_kernel accumulator guard:\n" + "\n".join(problems))
     cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB]
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    subprocess.run(cmd, check=True)
-    # measurement helper used by bench.py: register-only int8 MFMA loop
-    cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", os.path.join(CSRC, "mfma_peak.hip"), "-o", PEAK]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)

@@ -59,7 +59,7 @@ __device__ __forceinline__ uint32_t block_amax_bits(const uint32_t (&w)[4]) {
 }
 
 // One lane's share (8 elements) of one DialectFP4 block.  WIDE: blocks of 64 elements (two
-// neighbouring quads share the exponent and the dialect; Section 4.3 varies the block size).
+// neighbouring quads share the exponent and the dialect; Section 4.2, Table 3 varies the block size).
 template <bool WIDE = false>
 __device__ __forceinline__ void dfp4_pass(const uint4& wv, const uint8_t* __restrict__ lut_s,
                                           const uint8_t* __restrict__ lut_q, uint32_t& code,

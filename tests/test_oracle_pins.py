@@ -507,6 +507,44 @@ def test_gemm_requant_is_quantized_rounded_product():
     assert codes.shape == (3, 16) and dialect.shape == (3, 1)
 
 
+def _requant_golden_case(golden_dir):
+    g = _golden(golden_dir, "handworked_requant.json")
+    a = np.zeros((1, 96))
+    a[0, 0::32] = g["a_blocks"]
+    w = np.zeros((32, 96))
+    for j, row in enumerate(g["w_rows"]):
+        w[j, 0::32] = row
+    assert np.array_equal(_bf16(a), a) and np.array_equal(_bf16(w), w)      # all inputs are bf16 values
+    return g, a, w
+
+
+def test_handworked_requantized_product(golden_dir, monkeypatch):
+    """Pins the precision chain of dfp4_gemm_requant (exact sum -> fp32 -> bf16 -> quantize) on a
+    hand-worked block whose products sit on and just below a bf16 midpoint."""
+    g, a, w = _requant_golden_case(golden_dir)
+    aq, wq = O.dfp4_quantize(a), O.dfp4_quantize(w)
+    # the operands dequantize to themselves (single elements on a pair's largest value)
+    assert np.array_equal(O.dfp4_dequantize(*aq), a) and np.array_equal(O.dfp4_dequantize(*wq), w)
+    prod = O.dfp4_gemm(aq, wq)
+    assert prod[0, 1] == 16 - 2.0 ** -5 and prod[0, 2] == 16 - 2.0 ** -5 - 2.0 ** -22      # exact in float64
+    assert list(O.round_to_bf16(prod)[0, :8]) == g["after_bf16"]
+    codes, dialect, expo = O.dfp4_gemm_requant(aq, wq)
+    n = len(g["codes"])
+    assert int(expo[0, 0]) == g["exponent_byte"] and int(dialect[0, 0]) == g["dialect"]
+    assert list(_nibbles(codes)[0][:n]) == g["codes"] and (_nibbles(codes)[0][n:] == 0).all()
+
+    # the same block with the bf16 step dropped, and with a single rounding to bf16: both change a code
+    monkeypatch.setattr(O, "round_to_bf16", lambda x: np.asarray(x, dtype=np.float64))
+    assert list(_nibbles(O.dfp4_gemm_requant(aq, wq)[0])[0][:n]) == g["codes_if_bf16_step_skipped"]
+
+    def one_step(x):
+        u = np.asarray(x, dtype=np.float64).view(np.uint64)
+        u = (u + np.uint64((1 << 44) - 1) + ((u >> np.uint64(45)) & np.uint64(1))) & ~np.uint64((1 << 45) - 1)
+        return u.view(np.float64)
+    monkeypatch.setattr(O, "round_to_bf16", one_step)
+    assert list(_nibbles(O.dfp4_gemm_requant(aq, wq)[0])[0][:n]) == g["codes_if_rounded_to_bf16_in_one_step"]
+
+
 # --------------------------------------------------------------------------
 # blocks of 64
 # --------------------------------------------------------------------------
