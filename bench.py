@@ -130,7 +130,7 @@ def main():
     # register-only int8 MFMA loop in a child process, before this process touches the GPU
     peak = None
     if not args.no_mfma_peak:
-        exe = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2501_01144_amd", "mfma_peak")
+        exe = os.path.join(ROOT, "bench_helpers", "mfma_peak")
         if not os.path.exists(exe):
             print(f"bench.py: {exe} not found (build it with `python -m paper_2501_01144_amd.build`); "
                   "the register-only MFMA loop is left out of the report", file=sys.stderr)

@@ -173,6 +173,22 @@ int dfp4_gemm_batched(dfp4_tensor A, dfp4_tensor W, void* out, int out_dtype, in
 size_t dfp4_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
 
 /*
+ * dfp4_gemm for callers that cannot allocate device memory or pass a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same product,
+ * same kernels and bit-identical results; the workspace is an array of
+ * DFP4_NOALLOC_SCRATCH_BYTES that is part of the library's device code (each GPU the
+ * library runs on holds its own copy until the process ends).  The call allocates and
+ * frees nothing.  Products with dfp4_gemm_workspace_bytes(M, N, K) above that size are
+ * refused with DFP4_ERR_WORKSPACE (64 MiB covers M = 2048, N = 14336, K = 4096).
+ * All calls on one GPU share that GPU's array: calls that may overlap in time on one GPU
+ * (different streams, different threads) race and must be ordered by the caller; calls on
+ * one stream are ordered by the stream.  Every call initializes what it reads, so nothing
+ * carries over from one call to the next.
+ */
+#define DFP4_NOALLOC_SCRATCH_BYTES (64 << 20)
+int dfp4_gemm_noalloc(dfp4_tensor A, dfp4_tensor W, void* out, int out_dtype, int64_t ldc, void* stream);
+
+/*
  * Matrix multiply on the block-scaled matrix instruction of the GPU
  * (v_mfma_scale_f32_32x32x64_f8f6f4): out = A * W^T as dfp4_gemm / mxfp4_gemm, but
  * with the power-of-two block scales applied and the sum accumulated in fp32 by

@@ -51,6 +51,30 @@ static int check_gemm_args(const dfp4_tensor& A, const dfp4_tensor& W, const voi
     return DFP4_OK;
 }
 
+// Device memory of dfp4_gemm_noalloc: one array per GPU, part of the library's code object, so
+// that the call needs no allocation at all.  Every call on a GPU shares that GPU's array.
+static __device__ __align__(256) uint8_t scratch[DFP4_NOALLOC_SCRATCH_BYTES];
+
+// Address of `scratch` on the current device (looked up once per device, with that device current;
+// in host code the array's name is only a handle for this lookup, never an address).
+static int noalloc_scratch(void** out) {
+    static std::mutex mu;
+    static void* ptr[64] = {nullptr};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return DFP4_ERR_LAUNCH;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+            (void)hipGetLastError();
+            return DFP4_ERR_LAUNCH;
+        }
+        ptr[dev] = p;
+    }
+    *out = ptr[dev];
+    return DFP4_OK;
+}
+
 }  // namespace dfp4
 
 using namespace dfp4;
@@ -137,6 +161,22 @@ int dfp4_gemm(dfp4_tensor A, dfp4_tensor W, void* out, int out_dtype, int64_t ld
     const int rc = check_gemm_args(A, W, out, out_dtype, ldc, true, workspace, workspace_bytes);
     if (rc != DFP4_OK) return rc;
     return launch_gemm(false, A, W, out, out_dtype, ldc, 1, 0, 0, 0, workspace, workspace_bytes,
+                       static_cast<hipStream_t>(stream));
+}
+
+int dfp4_gemm_noalloc(dfp4_tensor A, dfp4_tensor W, void* out, int out_dtype, int64_t ldc, void* stream) {
+    if (A.rows < 0 || W.rows < 0 || A.K < 0) return DFP4_ERR_SHAPE;
+    // the size check comes first: a product that does not fit is refused whatever else is wrong with it
+    if (gemm_workspace_bytes(A.rows, W.rows, A.K) > (size_t)DFP4_NOALLOC_SCRATCH_BYTES) return DFP4_ERR_WORKSPACE;
+    // argument checks first (with a stand-in for the workspace pointer), then the scratch array's address
+    int rc = check_gemm_args(A, W, out, out_dtype, ldc, true, reinterpret_cast<void*>(uintptr_t{256}),
+                             DFP4_NOALLOC_SCRATCH_BYTES);
+    if (rc != DFP4_OK) return rc;
+    if (A.rows == 0 || W.rows == 0) return DFP4_OK;
+    void* ws = nullptr;
+    rc = noalloc_scratch(&ws);
+    if (rc != DFP4_OK) return rc;
+    return launch_gemm(false, A, W, out, out_dtype, ldc, 1, 0, 0, 0, ws, DFP4_NOALLOC_SCRATCH_BYTES,
                        static_cast<hipStream_t>(stream));
 }
 

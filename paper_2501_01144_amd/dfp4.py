@@ -25,7 +25,7 @@ class _CTensor(ctypes.Structure):
 
 
 SYMBOLS = [
-    "dfp4_quantize", "dfp4_quantize_b64", "dfp4_quantize_mse", "dfp4_quantize_t", "mxfp4_quantize_t", "dfp4_quantize_t_at", "dfp4_dequantize", "dfp4_gemm", "dfp4_gemm_batched", "dfp4_gemm_workspace_bytes",
+    "dfp4_quantize", "dfp4_quantize_b64", "dfp4_quantize_mse", "dfp4_quantize_t", "mxfp4_quantize_t", "dfp4_quantize_t_at", "dfp4_dequantize", "dfp4_gemm", "dfp4_gemm_batched", "dfp4_gemm_workspace_bytes", "dfp4_gemm_noalloc",
     "mxfp4_gemm_native", "dfp4_gemm_native", "dfp4_gemm_native_workspace_bytes", "dfp4_native_packed_bytes",
     "dfp4_quantize_native", "dfp4_native_pack", "mxfp4_native_pack", "dfp4_gemm_native_packed_w", "mxfp4_gemm_native_packed_w",
     "dfp4_gemm_native_packed", "mxfp4_gemm_native_packed", "dfp4_gemm_native_splitk_bytes",
@@ -61,6 +61,8 @@ def load():
     lib.mxfp4_gemm.argtypes = [_CTensor, _CTensor, vp, ci, i64, vp, ctypes.c_size_t, vp]
     lib.dfp4_gemm_batched.argtypes = [_CTensor, _CTensor, vp, ci, i64, i64, i64, i64, i64, vp,
                                       ctypes.c_size_t, vp]
+    lib.dfp4_gemm_noalloc.argtypes = [_CTensor, _CTensor, vp, ci, i64, vp]
+    lib.dfp4_gemm_noalloc.restype = ci
     lib.dfp4_gemm_workspace_bytes.argtypes = [i64, i64, i64]
     lib.dfp4_gemm_workspace_bytes.restype = ctypes.c_size_t
     lib.mxfp4_gemm_native.argtypes = [_CTensor, _CTensor, vp, ci, i64, vp, ctypes.c_size_t, vp]
@@ -238,6 +240,19 @@ def _gemm(fn, what, a, w, dtype, out, workspace):
 def gemm(a, w, dtype=torch.float32, out=None, workspace=None):
     """dfp4_gemm: out[M, N] = A[M, K] * W[N, K]^T on quantized operands."""
     return _gemm(load().dfp4_gemm, "dfp4_gemm", a, w, dtype, out, workspace)
+
+
+NOALLOC_SCRATCH_BYTES = 64 << 20
+
+
+def gemm_noalloc(a, w, out):
+    """dfp4_gemm_noalloc: dfp4_gemm on the library's own fixed scratch array; `out` must be given
+    (nothing is allocated on either side of the boundary)."""
+    assert out.dtype in (torch.float32, torch.bfloat16) and out.stride(1) == 1
+    ldc = out.stride(0) if a.rows > 1 else w.rows
+    _check(load().dfp4_gemm_noalloc(a.c(), w.c(), _ptr(out), F32 if out.dtype == torch.float32 else BF16, ldc,
+                                    _stream()), "dfp4_gemm_noalloc")
+    return out
 
 
 def mxfp4_gemm(a, w, dtype=torch.float32, out=None, workspace=None):

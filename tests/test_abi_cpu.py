@@ -132,3 +132,17 @@ def test_argument_errors_of_the_later_entry_points(lib):
     assert lib.dfp4_gemm_native_packed(vp(256), 64, vp(256), 64, 48, vp(16), 0, 64, vp(0), sz(0), vp(0)) == -2
     assert lib.dfp4_gemm_native_packed(vp(256), 64, vp(128), 64, 64, vp(16), 0, 64, vp(0), sz(0), vp(0)) == -3
     assert lib.dfp4_gemm_native_packed(vp(256), 0, vp(256), 64, 64, vp(16), 0, 64, vp(0), sz(0), vp(0)) == 0
+
+
+def test_gemm_noalloc_argument_errors(lib):
+    vp = ctypes.c_void_p
+    # a product whose workspace exceeds the library's fixed scratch array is refused before anything else
+    big_a, big_w = _t(16, 16, 16, 2048, 14336), _t(16, 16, 16, 4096, 14336)
+    assert lib.dfp4_gemm_workspace_bytes(2048, 4096, 14336) > (64 << 20)
+    assert lib.dfp4_gemm_noalloc(big_a, big_w, vp(16), 0, 4096, vp(0)) == -5
+    assert b"workspace" in lib.dfp4_strerror(-5)
+    # the other checks are those of dfp4_gemm
+    assert lib.dfp4_gemm_noalloc(_t(16, 16, 16, 4, 64), _t(16, 16, 16, 4, 96), vp(16), 0, 4, vp(0)) == -2
+    assert lib.dfp4_gemm_noalloc(_t(16, 16, 16, 4, 64), _t(16, 16, 16, 4, 64), vp(16), 9, 4, vp(0)) == -4
+    assert lib.dfp4_gemm_noalloc(_t(16, 16, 16, 4, 64), _t(16, 16, 16, 4, 64), vp(0), 0, 4, vp(0)) == -1
+    assert lib.dfp4_gemm_noalloc(_t(0, 0, 0, 0, 64), _t(16, 16, 16, 4, 64), vp(0), 0, 4, vp(0)) == 0
