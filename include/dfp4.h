@@ -16,8 +16,11 @@
  *     never allocates, frees or keeps user memory and never synchronizes.
  *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL is the
  *     default stream) of the current device.
- *   - Return value: DFP4_OK (0), or a negative DFP4_ERR_* code; on error nothing
- *     has been enqueued.  dfp4_strerror() names a code.
+ *   - Return value: DFP4_OK (0), or a negative DFP4_ERR_* code.  Arguments, shapes and
+ *     workspace sizes are checked before the first kernel is enqueued, so on any error
+ *     other than DFP4_ERR_LAUNCH nothing has been enqueued; DFP4_ERR_LAUNCH (the HIP
+ *     runtime refused a launch) may leave earlier kernels of the same call enqueued.
+ *     dfp4_strerror() names a code.
  *   - A block is 32 consecutive elements along K (the contraction dimension,
  *     Appendix C: every operand is quantized along its multiplication
  *     dimension).  K must be a multiple of 32.
@@ -147,7 +150,10 @@ int dfp4_dequantize(dfp4_tensor in, void* y, int y_dtype, int64_t ld_elems, void
  * Where the block exponents of a tile span at most 12 binades per row the
  * outer sum is exact as well (exponent offsets folded into the int8 operands,
  * one conversion to fp32 at the end); otherwise it is accumulated in fp32,
- * one addition per block.
+ * one addition per block.  That slower per-block path also takes every product
+ * with K > 16384 and, at its own pace, every product with M <= 64 (few rows);
+ * 512 x 128 output tiles whose exponents spread further are computed that way by
+ * the workgroup that finds them (dfp4_gemm_declined_tiles counts them).
  *   A        quantized [M, K]; W quantized [N, K] (both blocked along K)
  *   out      device, [M, N] row-major, leading dimension ldc (elements, N <= ldc < 2^27);
  *            out_dtype DFP4_F32 or DFP4_BF16 (round to nearest even)
@@ -165,12 +171,52 @@ int dfp4_gemm(dfp4_tensor A, dfp4_tensor W, void* out, int out_dtype, int64_t ld
  *   A.codes + b * strideA_rows * K/2, A.dialect/exponent + b * strideA_rows * K/32
  * (and likewise W with strideW_rows), and out + b * strideC elements.
  * A.rows = M and W.rows = N are the per-problem sizes.
+ *   workspace   at least batch * dfp4_gemm_workspace_bytes(M, N, K) bytes.
  */
 int dfp4_gemm_batched(dfp4_tensor A, dfp4_tensor W, void* out, int out_dtype, int64_t ldc,
                       int64_t batch, int64_t strideA_rows, int64_t strideW_rows, int64_t strideC,
                       void* workspace, size_t workspace_bytes, void* stream);
 
 size_t dfp4_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
+
+/*
+ * The same product with the per-operand work of dfp4_gemm done ahead (Section 3.3: the cost
+ * of preparing a quantized activation block is amortized over the many weight blocks it is
+ * multiplied with; weights are known in advance).  dfp4_gemm spends part of every call on
+ * each operand alone: per-row reference exponents, per-block tables, and for A the 4-bit
+ * codes expanded through the dialect tables to the int8 operands of the matrix cores.
+ * dfp4_gemm_prepare does that once per tensor:
+ *   is_weight != 0   T is a W operand [N, K] (offline, once per weight matrix)
+ *   is_weight == 0   T is an A operand [M, K] (online, once per activation tensor, however
+ *                    many products consume it: gate and up projections share one)
+ *   prepared         device, 256-byte aligned, at least dfp4_gemm_prepared_bytes(rows, K,
+ *                    is_weight) bytes; the layout is private to the library.  A size of 0
+ *                    means nothing is prepared for this operand (K > 16384, or an A with
+ *                    at most 64 rows): NULL may be passed then.
+ * dfp4_gemm_prepared multiplies.  The quantized tensors are still passed: paths that do not
+ * use the prepared form read them.  a_prepared is written to (arrival counters of tiles
+ * whose K is split between workgroups), so one prepared A serves one product at a time:
+ * products on one stream are ordered by the stream, products that may overlap in time need
+ * their own prepared copy.  Results are bit-identical to dfp4_gemm.
+ *   workspace   at least dfp4_gemm_prepared_workspace_bytes(M, N, K) bytes (partial tiles
+ *               where K is split; 0 for products with many output tiles), 256-byte aligned
+ * Limits: ceil(rows / 512) * (K/32 + 1) * 49152 < 2^31 for A, rows * K / 2 < 2^31 for W
+ * (DFP4_ERR_SHAPE; dfp4_gemm itself cuts larger products into pieces).
+ */
+size_t dfp4_gemm_prepared_bytes(int64_t rows, int64_t K, int is_weight);
+int dfp4_gemm_prepare(dfp4_tensor T, int is_weight, void* prepared, size_t bytes, void* stream);
+int mxfp4_gemm_prepare(dfp4_tensor T, int is_weight, void* prepared, size_t bytes, void* stream);
+size_t dfp4_gemm_prepared_workspace_bytes(int64_t M, int64_t N, int64_t K);
+int dfp4_gemm_prepared(dfp4_tensor A, void* a_prepared, dfp4_tensor W, const void* w_prepared, void* out,
+                       int out_dtype, int64_t ldc, void* workspace, size_t workspace_bytes, void* stream);
+int mxfp4_gemm_prepared(dfp4_tensor A, void* a_prepared, dfp4_tensor W, const void* w_prepared, void* out,
+                        int out_dtype, int64_t ldc, void* workspace, size_t workspace_bytes, void* stream);
+/*
+ * Diagnostic: number of 512 x 128 output tiles that products on this prepared A ([M, K]) have
+ * computed on the per-block fp32 path since it was prepared (exponent spread beyond what the
+ * exact path folds into its operands).  `count` is a HOST pointer.  Synchronizes with the device.
+ */
+int dfp4_gemm_declined_tiles(const void* a_prepared, int64_t M, int64_t K, uint32_t* count);
 
 /*
  * dfp4_gemm for callers that cannot allocate device memory or pass a workspace: code under

@@ -34,8 +34,9 @@ def check_accumulators_untouched(asm_text):
     inline-assembly statements.  The compiler is told the loop clobbers those registers, so
     nothing in the language stops it from using an accumulation register for its own purposes
     (a spill, a copy) between the two.  This check makes that a build error instead of a silent
-    wrong result: in every gemm_fast_kernel, compiler-generated code after the main loop must not
-    name an accumulation register, and the kernel must not use scratch memory."""
+    wrong result: in every gemm_fast_kernel, no compiler-generated instruction that can execute
+    after the main loop (followed through the kernel's branches) may name an accumulation
+    register, and the kernel must not use scratch memory."""
     problems = []
     lines = asm_text.splitlines()
     i, n = 0, len(lines)
@@ -45,20 +46,46 @@ def check_accumulators_untouched(asm_text):
             i += 1
             continue
         name = m.group(1)
-        in_asm, loops_seen, j = False, 0, i + 1
+        j = i + 1
         while j < n and ".end_amdhsa_kernel" not in lines[j]:
-            ln = lines[j]
+            j += 1
+        body = lines[i + 1:j]
+        labels = {}
+        in_asm, asm_region, first_end = False, [], None
+        for k, ln in enumerate(body):
             if ";;#ASMSTART" in ln:
                 in_asm = True
             elif ";;#ASMEND" in ln:
                 in_asm = False
-                loops_seen += 1
-            elif not in_asm and loops_seen >= 1:
-                code = ln.split(";")[0]
-                if _AGPR.search(code) and not code.lstrip().startswith("."):
-                    problems.append(f"{name}: compiler-generated code touches an accumulation register "
-                                    f"after the main loop: {code.strip()}")
-            j += 1
+                if first_end is None:
+                    first_end = k
+            asm_region.append(in_asm)
+            lm = re.match(r"^(\.LBB\w+):", ln)
+            if lm and not in_asm:
+                labels[lm.group(1)] = k
+        if first_end is None:
+            problems.append(f"{name}: main loop not found")
+        else:
+            seen, work = set(), [first_end + 1]
+            while work:
+                k = work.pop()
+                while k < len(body) and k not in seen:
+                    seen.add(k)
+                    code = body[k].split(";")[0].strip()
+                    if not asm_region[k] and code and not code.startswith("."):
+                        if _AGPR.search(code):
+                            problems.append(f"{name}: compiler-generated code touches an accumulation register "
+                                            f"after the main loop: {code}")
+                        op = code.split()[0]
+                        tm = re.search(r"(\.LBB\w+)", code)
+                        if op.startswith("s_cbranch") or op == "s_branch":
+                            if tm and tm.group(1) in labels:
+                                work.append(labels[tm.group(1)])
+                            if op == "s_branch":
+                                break
+                        elif op in ("s_endpgm", "s_setpc_b64"):
+                            break
+                    k += 1
         # resource summary that follows the kernel descriptor
         k = j
         while k < n and k < j + 60:
@@ -67,8 +94,6 @@ def check_accumulators_untouched(asm_text):
                     problems.append(f"{name}: uses scratch memory ({lines[k].strip()})")
                 break
             k += 1
-        if loops_seen == 0:
-            problems.append(f"{name}: main loop not found")
         i = j
     return problems
 

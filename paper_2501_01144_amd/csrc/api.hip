@@ -48,7 +48,7 @@ static int check_gemm_args(const dfp4_tensor& A, const dfp4_tensor& W, const voi
         if (!workspace || workspace_bytes < need) return DFP4_ERR_WORKSPACE;
         if (!aligned(workspace, 256)) return DFP4_ERR_ALIGN;
     }
-    return DFP4_OK;
+    return gemm_shape_check(A, W, ldc, 1, false);
 }
 
 // Device memory of dfp4_gemm_noalloc: one array per GPU, part of the library's code object, so
@@ -194,6 +194,7 @@ int dfp4_gemm_batched(dfp4_tensor A, dfp4_tensor W, void* out, int out_dtype, in
     if (batch < 0 || strideA_rows < 0 || strideW_rows < 0 || strideC < 0) return DFP4_ERR_SHAPE;
     const int rc = check_gemm_args(A, W, out, out_dtype, ldc, true, workspace, workspace_bytes);
     if (rc != DFP4_OK) return rc;
+    if (batch > 0 && workspace_bytes / (size_t)batch < gemm_workspace_bytes(A.rows, W.rows, A.K)) return DFP4_ERR_WORKSPACE;
     return launch_gemm(false, A, W, out, out_dtype, ldc, batch, strideA_rows, strideW_rows, strideC,
                        workspace, workspace_bytes, static_cast<hipStream_t>(stream));
 }
@@ -201,6 +202,78 @@ int dfp4_gemm_batched(dfp4_tensor A, dfp4_tensor W, void* out, int out_dtype, in
 size_t dfp4_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K) {
     if (M < 0 || N < 0 || K < 0) return 0;
     return gemm_workspace_bytes(M, N, K);
+}
+
+size_t dfp4_gemm_prepared_bytes(int64_t rows, int64_t K, int is_weight) {
+    if (rows < 0 || K < 0 || K % kBlock != 0) return 0;
+    return gemm_prepared_bytes(rows, K, is_weight != 0);
+}
+
+static int gemm_prepare_common(bool mx, dfp4_tensor T, int is_weight, void* prepared, size_t bytes, void* stream) {
+    if (T.rows < 0 || T.K < 0 || T.K % kBlock != 0) return DFP4_ERR_SHAPE;
+    const size_t need = gemm_prepared_bytes(T.rows, T.K, is_weight != 0);
+    if (need == 0) return DFP4_OK;                    // nothing to prepare: the products of this operand read it as it is
+    if (!T.codes || !T.exponent || (!mx && !T.dialect)) return DFP4_ERR_NULL;
+    if (!prepared || bytes < need) return DFP4_ERR_WORKSPACE;
+    if (!aligned(T.codes, 16) || !aligned(prepared, 256)) return DFP4_ERR_ALIGN;
+    return launch_gemm_prepare(mx, T, is_weight != 0, prepared, static_cast<hipStream_t>(stream));
+}
+
+int dfp4_gemm_prepare(dfp4_tensor T, int is_weight, void* prepared, size_t bytes, void* stream) {
+    return gemm_prepare_common(false, T, is_weight, prepared, bytes, stream);
+}
+
+int mxfp4_gemm_prepare(dfp4_tensor T, int is_weight, void* prepared, size_t bytes, void* stream) {
+    return gemm_prepare_common(true, T, is_weight, prepared, bytes, stream);
+}
+
+size_t dfp4_gemm_prepared_workspace_bytes(int64_t M, int64_t N, int64_t K) {
+    if (M < 0 || N < 0 || K < 0) return 0;
+    return gemm_prepared_workspace_bytes(M, N, K);
+}
+
+static int gemm_prepared_common(bool mx, dfp4_tensor A, void* a_prepared, dfp4_tensor W, const void* w_prepared,
+                                void* out, int out_dtype, int64_t ldc, void* workspace, size_t workspace_bytes,
+                                void* stream) {
+    // the checks of dfp4_gemm, with the prepared-path workspace (partial tiles only) in place of its own
+    int rc = check_gemm_args(A, W, out, out_dtype, ldc, !mx, reinterpret_cast<void*>(uintptr_t{256}), ~(size_t)0);
+    if (rc != DFP4_OK) return rc;
+    if (A.rows == 0 || W.rows == 0) return DFP4_OK;
+    if (gemm_prepared_bytes(A.rows, A.K, false) > 0 && (!a_prepared || !w_prepared)) return DFP4_ERR_NULL;
+    if ((a_prepared && !aligned(a_prepared, 256)) || (w_prepared && !aligned(w_prepared, 256))) return DFP4_ERR_ALIGN;
+    const size_t need = gemm_prepared_workspace_bytes(A.rows, W.rows, A.K);
+    if (need > 0) {
+        if (!workspace || workspace_bytes < need) return DFP4_ERR_WORKSPACE;
+        if (!aligned(workspace, 256)) return DFP4_ERR_ALIGN;
+    }
+    return launch_gemm_prepared(mx, A, a_prepared, W, w_prepared, out, out_dtype, ldc, workspace, workspace_bytes,
+                                static_cast<hipStream_t>(stream));
+}
+
+int dfp4_gemm_prepared(dfp4_tensor A, void* a_prepared, dfp4_tensor W, const void* w_prepared, void* out, int out_dtype,
+                       int64_t ldc, void* workspace, size_t workspace_bytes, void* stream) {
+    return gemm_prepared_common(false, A, a_prepared, W, w_prepared, out, out_dtype, ldc, workspace, workspace_bytes,
+                                stream);
+}
+
+int mxfp4_gemm_prepared(dfp4_tensor A, void* a_prepared, dfp4_tensor W, const void* w_prepared, void* out,
+                        int out_dtype, int64_t ldc, void* workspace, size_t workspace_bytes, void* stream) {
+    return gemm_prepared_common(true, A, a_prepared, W, w_prepared, out, out_dtype, ldc, workspace, workspace_bytes,
+                                stream);
+}
+
+int dfp4_gemm_declined_tiles(const void* a_prepared, int64_t M, int64_t K, uint32_t* count) {
+    if (!count) return DFP4_ERR_NULL;
+    *count = 0;
+    if (M < 0 || K < 0 || K % kBlock != 0) return DFP4_ERR_SHAPE;
+    if (gemm_prepared_bytes(M, K, false) == 0) return DFP4_OK;
+    if (!a_prepared) return DFP4_ERR_NULL;
+    const uint8_t* src = static_cast<const uint8_t*>(a_prepared) + gemm_prepared_declined_offset(M, K);
+    if (hipMemcpy(count, src, sizeof(uint32_t), hipMemcpyDeviceToHost) != hipSuccess) {
+        (void)hipGetLastError();
+        return DFP4_ERR_LAUNCH;
+    }
+    return DFP4_OK;
 }
 
 // Native block-scaled GEMM.  w_packed == nullptr: both operands are packed into the workspace

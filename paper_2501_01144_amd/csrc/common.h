@@ -34,6 +34,13 @@ int launch_gemm(bool mx, dfp4_tensor A, dfp4_tensor W, void* out, int out_dtype,
                 int64_t batch, int64_t strideA_rows, int64_t strideW_rows, int64_t strideC,
                 void* workspace, size_t workspace_bytes, hipStream_t stream, const dfp4_tensor* rq = nullptr);
 size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
+int gemm_shape_check(dfp4_tensor A, dfp4_tensor W, int64_t ldc, int64_t batch, bool rq);
+size_t gemm_prepared_bytes(int64_t rows, int64_t K, bool weight);
+size_t gemm_prepared_workspace_bytes(int64_t M, int64_t N, int64_t K);
+size_t gemm_prepared_declined_offset(int64_t M, int64_t K);
+int launch_gemm_prepare(bool mx, dfp4_tensor T, bool weight, void* prepared, hipStream_t stream);
+int launch_gemm_prepared(bool mx, dfp4_tensor A, void* a_prepared, dfp4_tensor W, const void* w_prepared, void* out,
+                         int out_dtype, int64_t ldc, void* workspace, size_t workspace_bytes, hipStream_t stream);
 size_t gemm_requant_workspace_bytes(int64_t M, int64_t N, int64_t K);
 size_t native_packed_bytes(int64_t rows, int64_t K, bool fp6);
 size_t gemm_native_workspace_bytes(int64_t M, int64_t N, int64_t K, bool fp6);

@@ -81,15 +81,22 @@ constexpr int kBBufBytes = 8 * 1024;  // int8 W operands of one step: 4 column t
 constexpr int kRqPitch = 136;         // bf16 per staged output row (128 + 8: rows stay 16-byte aligned)
 constexpr int kVisitPad = 12;         // padding visits after the last one (the loop looks 5 steps ahead)
 constexpr int kVisitCap = (kMaxClass + 1) * (kMaxKB + 1) + kVisitPad + 4;
+constexpr int kMaxSplitTiles = 2048;  // arrival counters per prepared A: K is split only below this many tiles
 
 struct GemmParams {
     const uint8_t *a_codes, *a_dial, *a_exp, *w_codes, *w_dial, *w_exp;
     void* out;
     int M, N, KB;
     int64_t ldc, strideA_rows, strideW_rows, strideC;
-    // workspace (per batch entry: ws + batch * ws_stride)
-    uint8_t* ws;
-    int64_t ws_stride, off_refa, off_refw, off_spreadw, off_wmeta, off_mask, off_flag, off_list, off_part, off_a8;
+    // prepared operands (per batch entry: base + batch * stride) and their regions
+    uint8_t* a_prep;
+    uint8_t* w_prep;
+    int64_t a_prep_stride, w_prep_stride;
+    int64_t off_refa, off_mask, off_cnt, off_a8;      // inside a prepared A
+    int64_t off_refw, off_spreadw, off_wmeta;         // inside a prepared W
+    // exact int32 partial tiles of workgroups that share an output tile (split K)
+    int* part;
+    int64_t part_stride;              // ints per batch entry
     int tiles_m, tiles_n;             // 512 x 128 output tiles
     int ksplit;                       // workgroups sharing one output tile (each takes a range of K)
     // requantizing epilogue: the quantized [M, N] output (blocks of 32 along N)
@@ -97,36 +104,50 @@ struct GemmParams {
     uint8_t *q_dial, *q_exp;
 };
 
-struct Layout {
-    int64_t off_refa, off_refw, off_spreadw, off_wmeta, off_mask, off_flag, off_list, off_part, off_a8, total;
-    int ksplit;
-};
 __host__ __device__ inline int64_t align256(int64_t x) { return (x + 255) & ~(int64_t)255; }
+
+// Prepared A [M, K] (see gemm_prep_kernel): per-row reference exponents (rows padded to 512), one
+// class mask per (512-row tile, block), arrival counters of the tiles whose K is split, and the
+// operand expanded to pre-shifted int8 in MFMA fragment order:
+// [class][tile][32-row group][block 0..KB][1 KiB]; block KB of class 0 is all zeros.
+struct PrepALayout { int64_t off_refa, off_mask, off_cnt, off_a8, total; };
+inline PrepALayout prep_a_layout(int64_t M, int64_t KB) {
+    const int64_t tm = (M + kTileM - 1) / kTileM;
+    PrepALayout l{};
+    l.off_refa = 0;
+    l.off_mask = align256(tm * kTileM);
+    l.off_cnt = align256(l.off_mask + tm * KB);
+    l.off_a8 = align256(l.off_cnt + (int64_t)(kMaxSplitTiles + 1) * 4);    // + the count of declined tiles
+    l.total = align256(l.off_a8 + (kMaxClass + 1) * tm * kGroups * (KB + 1) * 1024);
+    return l;
+}
+// Prepared W [N, K]: per-row reference exponents and exponent spreads (rows padded to 128) and one
+// dword per block naming its (dialect, shift) table.  W itself stays 4-bit.
+struct PrepWLayout { int64_t off_refw, off_spreadw, off_wmeta, total; };
+inline PrepWLayout prep_w_layout(int64_t N, int64_t KB) {
+    const int64_t tn = (N + kTileN - 1) / kTileN;
+    PrepWLayout l{};
+    l.off_refw = 0;
+    l.off_spreadw = align256(tn * kTileN);
+    l.off_wmeta = align256(l.off_spreadw + tn * kTileN);
+    l.total = align256(l.off_wmeta + N * KB * 4);
+    return l;
+}
 // Workgroups per output tile: when there are fewer tiles than compute units, K is split
-// between 2, 4 or 8 workgroups whose exact int32 partial sums the follow-up kernel adds.
+// between 2, 4 or 8 workgroups; the last of them to finish adds the others' exact int32 sums.
 inline int choose_ksplit(int64_t tiles, int64_t KB) {
     const int64_t cu = device_cu_count();
     int s = 1;
     while (s < 8 && tiles * s * 2 <= cu && KB / (2 * s) >= 16) s *= 2;
-    return s;
+    return tiles <= kMaxSplitTiles ? s : 1;
 }
-inline Layout make_layout(int64_t M, int64_t N, int64_t KB) {
-    const int64_t tm = (M + kTileM - 1) / kTileM, tn = (N + kTileN - 1) / kTileN;
-    Layout l{};
-    l.ksplit = choose_ksplit(tm * tn, KB);
-    l.off_refa = 0;
-    l.off_refw = align256(l.off_refa + tm * kTileM);
-    l.off_spreadw = align256(l.off_refw + tn * kTileN);
-    l.off_wmeta = align256(l.off_spreadw + tn * kTileN);
-    l.off_mask = align256(l.off_wmeta + N * KB * 4);          // one table offset (dword) per W block
-    l.off_flag = align256(l.off_mask + tm * KB);
-    l.off_list = align256(l.off_flag + tm * tn);               // count, then ids of declined tiles
-    l.off_part = align256(l.off_list + (tm * tn + 1) * 4);
-    l.off_a8 = align256(l.off_part + (l.ksplit > 1 ? (int64_t)l.ksplit * tm * tn * kTileM * kTileN * 4 : 0));
-    // A fragments: [class][tile][group][block 0..KB][1 KiB]; block KB of class 0 is all zeros
-    l.total = align256(l.off_a8 + (kMaxClass + 1) * tm * kGroups * (KB + 1) * 1024);
-    return l;
+inline int64_t partial_bytes(int64_t M, int64_t N, int64_t KB, int64_t batch) {
+    const int64_t tiles = ((M + kTileM - 1) / kTileM) * ((N + kTileN - 1) / kTileN);
+    const int s = choose_ksplit(tiles * batch, KB);
+    return s > 1 ? align256((int64_t)s * tiles * kTileM * kTileN * 4) : 0;
 }
+inline bool takes_small_kernel(int64_t M, int64_t KB) { return M <= 64 && KB > 0 && KB <= 512; }
+inline bool takes_fast_kernel(int64_t M, int64_t KB) { return !takes_small_kernel(M, KB) && KB > 0 && KB <= kMaxKB; }
 
 // 8 codes (one dword) -> 8 signed int8 through one dialect table:
 // returns the even-numbered elements in one dword and the odd ones in another.
@@ -202,7 +223,8 @@ __global__ __launch_bounds__(1024) void gemm_prep_kernel(GemmParams p, int n_a, 
     __shared__ uint32_t s_present;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int64_t bz = blockIdx.z;
-    uint8_t* ws = p.ws + bz * p.ws_stride;
+    uint8_t* ap = p.a_prep + bz * p.a_prep_stride;    // only touched by the A workgroups
+    uint8_t* wp = p.w_prep + bz * p.w_prep_stride;    // only touched by the W workgroups
     const int KB = p.KB;
 
     if ((int)blockIdx.x >= n_a) {
@@ -233,10 +255,10 @@ __global__ __launch_bounds__(1024) void gemm_prep_kernel(GemmParams p, int n_a, 
         }
         if (!valid) return;
         if (seg == 0) {
-            ws[p.off_refw + row] = (uint8_t)mn;
-            ws[p.off_spreadw + row] = (uint8_t)min(mx - mn, 255);
+            wp[p.off_refw + row] = (uint8_t)mn;
+            wp[p.off_spreadw + row] = (uint8_t)min(mx - mn, 255);
         }
-        uint32_t* wmeta = reinterpret_cast<uint32_t*>(ws + p.off_wmeta) + (int64_t)row * KB + k0;
+        uint32_t* wmeta = reinterpret_cast<uint32_t*>(wp + p.off_wmeta) + (int64_t)row * KB + k0;
         if (nb == 16) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
@@ -263,10 +285,10 @@ __global__ __launch_bounds__(1024) void gemm_prep_kernel(GemmParams p, int n_a, 
     for (int i = tid; i < kDialects * 16; i += 1024) s_tab[i] = (&g_shifted_book.w[0][0][0])[i];
     if (tid == 0) s_present = 0;
     if (blockIdx.x == 0) {
-        // per-tile "declined" flags of the fast kernel
-        const int tiles = p.tiles_m * p.tiles_n;
-        for (int i = tid; i < tiles; i += 1024) ws[p.off_flag + i] = 0;
-        if (tid == 0) *reinterpret_cast<uint32_t*>(ws + p.off_list) = 0;
+        // arrival counters of output tiles whose K is split between workgroups: zero here; the
+        // workgroup that arrives last at a tile puts its counter back to zero
+        uint32_t* cnt = reinterpret_cast<uint32_t*>(ap + p.off_cnt);
+        for (int i = tid; i <= kMaxSplitTiles; i += 1024) cnt[i] = 0;     // the last one counts declined tiles
     }
     __syncthreads();
 
@@ -304,7 +326,7 @@ __global__ __launch_bounds__(1024) void gemm_prep_kernel(GemmParams p, int n_a, 
         for (int i = n16 * 16 + t; i < KB; i += 2) mn = min(mn, (int)erow[i]);
         mn = min(mn, __shfl_xor(mn, 32));
         const bool row_valid = row0 + r < p.M;
-        if (chunk == 0 && t == 0) ws[p.off_refa + row0 + r] = row_valid ? (uint8_t)mn : (uint8_t)0;
+        if (chunk == 0 && t == 0) ap[p.off_refa + row0 + r] = row_valid ? (uint8_t)mn : (uint8_t)0;
         uint32_t word = 0;
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
@@ -321,14 +343,14 @@ __global__ __launch_bounds__(1024) void gemm_prep_kernel(GemmParams p, int n_a, 
         for (int q = 0; q < 4; ++q)
             *reinterpret_cast<uint4*>(&s_codes[wave][(q * 8 + (lane >> 3)) * kPitch + (lane & 7) * 16]) = craw[q];
     } else if (chunk == 0 && t == 0) {
-        ws[p.off_refa + row0 + r] = 0;                // padding rows of the last tile
+        ap[p.off_refa + row0 + r] = 0;                // padding rows of the last tile
     }
     __syncthreads();
     const uint32_t present = s_present;
-    if (wave == 0 && lane < nk) ws[p.off_mask + (int64_t)tile * KB + kc + lane] = (uint8_t)((present >> (4 * lane)) & 15u);
+    if (wave == 0 && lane < nk) ap[p.off_mask + (int64_t)tile * KB + kc + lane] = (uint8_t)((present >> (4 * lane)) & 15u);
     const int64_t grp = (int64_t)tile * kGroups + wave;
     if (chunk == 0)                                   // the all-zero block (index KB) of this group, class 0
-        *reinterpret_cast<uint4*>(ws + p.off_a8 + (grp * (KB + 1) + KB) * 1024 + lane * 16) = make_uint4(0, 0, 0, 0);
+        *reinterpret_cast<uint4*>(ap + p.off_a8 + (grp * (KB + 1) + KB) * 1024 + lane * 16) = make_uint4(0, 0, 0, 0);
     if (!group_valid) return;
     const int64_t cls_stride = (int64_t)p.tiles_m * kGroups * (KB + 1) * 1024;
 #pragma unroll
@@ -338,12 +360,127 @@ __global__ __launch_bounds__(1024) void gemm_prep_kernel(GemmParams p, int n_a, 
         const uint32_t dial = (uint32_t)(d8 >> (8 * k)) & 15u;
         const uint4 tab = *reinterpret_cast<const uint4*>(&s_tab[(dial * 4 + sh[k]) * 4]);
         const v4i data = unpack16(c.x, c.y, tab);
-        uint8_t* dst = ws + p.off_a8 + (grp * (KB + 1) + kc + k) * 1024 + t * 512 + r * 16;
+        uint8_t* dst = ap + p.off_a8 + (grp * (KB + 1) + kc + k) * 1024 + t * 512 + r * 16;
 #pragma unroll
         for (int cc = 0; cc <= kMaxClass; ++cc)
             if ((present >> (4 * k + cc)) & 1u)
                 *reinterpret_cast<v4i*>(dst + cc * cls_stride) = cls[k] == cc ? data : v4i{0, 0, 0, 0};
     }
+}
+
+// ---------------------------------------------------------------------------
+// Per-block flush (always correct): 128 x 128 outputs per workgroup of 256 threads,
+// operands straight from global memory, one fp32 scale-and-add per block as in the
+// paper's MAC (Section 3.3).  Used by gemm_block_kernel for products the single-
+// accumulator kernel does not take, and by that kernel itself for tiles it declines.
+// ---------------------------------------------------------------------------
+template <bool MX, bool BF16>
+__device__ __forceinline__ void block_flush_tile(const GemmParams& p, int64_t bz, int by, int bx,
+                                                 uint8_t (&s_exp)[2][256]) {
+    const int KB = p.KB;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int m0 = by * 128, n0 = bx * 128;
+    const int64_t a_row0 = bz * p.strideA_rows, w_row0 = bz * p.strideW_rows;
+    const int half = lane >> 5, l32 = lane & 31;
+
+    int64_t a_row[2], w_row[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        a_row[i] = a_row0 + min(m0 + wm * 64 + i * 32 + l32, p.M - 1);
+        w_row[i] = w_row0 + min(n0 + wn * 64 + i * 32 + l32, p.N - 1);
+    }
+    const int t = threadIdx.x;
+    const int64_t e_row = t < 128 ? a_row0 + min(m0 + t, p.M - 1) : w_row0 + min(n0 + t - 128, p.N - 1);
+    const uint8_t* e_src = (t < 128 ? p.a_exp : p.w_exp) + e_row * KB;
+
+    float acc[2][2][16];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int x = 0; x < 16; ++x) acc[i][j][x] = 0.0f;
+
+    for (int kb = 0; kb < KB; ++kb) {
+        uint8_t* se = s_exp[kb & 1];
+        se[t] = e_src[kb];
+        v4i a[2], b[2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const uint2 ca = *reinterpret_cast<const uint2*>(p.a_codes + (a_row[i] * KB + kb) * 16 + half * 8);
+            const uint2 cw = *reinterpret_cast<const uint2*>(p.w_codes + (w_row[i] * KB + kb) * 16 + half * 8);
+            const uint32_t da = MX ? 7u : ((uint32_t)p.a_dial[a_row[i] * KB + kb] & 15u);
+            const uint32_t dw = MX ? 7u : ((uint32_t)p.w_dial[w_row[i] * KB + kb] & 15u);
+            a[i] = unpack16(ca.x, ca.y, *reinterpret_cast<const uint4*>(g_shifted_book.w[da][0]));
+            b[i] = unpack16(cw.x, cw.y, *reinterpret_cast<const uint4*>(g_shifted_book.w[dw][0]));
+        }
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                v16i pr = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+                pr = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i], b[j], pr, 0, 0, 0);
+                const int ew = se[128 + wn * 64 + j * 32 + l32];
+#pragma unroll
+                for (int x = 0; x < 16; ++x) {
+                    const int row = 8 * (x >> 2) + 4 * half + (x & 3);
+                    const int ea = se[wm * 64 + i * 32 + row];
+                    acc[i][j][x] += ldexpf((float)pr[x], ea + ew - 256);
+                }
+            }
+    }
+
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int n = n0 + wn * 64 + j * 32 + l32;
+#pragma unroll
+            for (int x = 0; x < 16; ++x) {
+                const int m = m0 + wm * 64 + i * 32 + 8 * (x >> 2) + 4 * half + (x & 3);
+                if (m < p.M && n < p.N) {
+                    const int64_t o = bz * p.strideC + (int64_t)m * p.ldc + n;
+                    if constexpr (BF16)
+                        static_cast<uint16_t*>(p.out)[o] = f32_to_bf16_rne(acc[i][j][x]);
+                    else
+                        static_cast<float*>(p.out)[o] = acc[i][j][x];
+                }
+            }
+        }
+}
+
+// Requantizing GEMM, tiles that went through the per-block flush: quantize the 128 x 128 bf16
+// results the workgroup has just written to the temporary `p.out` (16 rows x 4 blocks per sweep,
+// 4 lanes per block).  lds_s / lds_q: the quantizer's tables.
+template <bool MX>
+__device__ __forceinline__ void quantize_flushed_piece(const GemmParams& p, int64_t bz, int by, int bx,
+                                                       const uint8_t* lds_s, const uint8_t* lds_q) {
+    __threadfence_block();
+    __syncthreads();
+    const int tid = threadIdx.x;
+    const int nb_row = p.N / kBlock;
+    const uint16_t* src = static_cast<const uint16_t*>(p.out) + bz * p.strideC;
+    for (int sweep = 0; sweep < 8; ++sweep) {
+        const int q = tid >> 2, sub = tid & 3;
+        const int m = by * 128 + sweep * 16 + (q >> 2), nb = bx * 4 + (q & 3);
+        const bool valid = m < p.M && nb < nb_row;      // the same for the 4 lanes of a block
+        uint4 wv = make_uint4(0, 0, 0, 0);
+        if (valid) wv = *reinterpret_cast<const uint4*>(src + (int64_t)m * p.ldc + nb * kBlock + sub * 8);
+        uint32_t code, eb, dl = 0;
+        if constexpr (MX) mxfp4_pass(wv, lds_q, code, eb);
+        else dfp4_pass(wv, lds_s, lds_q, code, eb, dl);
+        if (valid) {
+            const size_t blk = (size_t)(bz * p.M + m) * nb_row + nb;
+            p.q_codes[blk * 4 + sub] = code;
+            if (sub == 0) {
+                p.q_exp[blk] = (uint8_t)eb;
+                if constexpr (!MX) p.q_dial[blk] = (uint8_t)dl;
+            }
+        }
+    }
+    __syncthreads();
 }
 
 // ---------------------------------------------------------------------------
@@ -370,9 +507,9 @@ __global__ __launch_bounds__(256, 1) void gemm_fast_kernel(GemmParams p) {
     const int m0 = blockIdx.y * kTileM, n0 = blockIdx.x * kTileN;
     const int S = p.ksplit, sidx = (int)(blockIdx.z % (unsigned)S);
     const int64_t bz = blockIdx.z / (unsigned)S;
-    uint8_t* ws = p.ws + bz * p.ws_stride;
+    const uint8_t* ap = p.a_prep + bz * p.a_prep_stride;
+    const uint8_t* wp = p.w_prep + bz * p.w_prep_stride;
     const int tile_id = blockIdx.y * p.tiles_n + blockIdx.x;
-    volatile uint8_t* flag = ws + p.off_flag + tile_id;
     // this workgroup's range of blocks
     const int kb_per = (KB + S - 1) / S;
     const int kb_lo = sidx * kb_per, kb_hi = min(KB, kb_lo + kb_per);
@@ -380,28 +517,33 @@ __global__ __launch_bounds__(256, 1) void gemm_fast_kernel(GemmParams p) {
     // ---- prologue: tables, references, list of (block, class) visits
     for (int i = tid; i < kDialects * 16; i += 256) s_tab[i] = (&g_shifted_book.w[0][0][0])[i];
     {
-        for (int i = tid; i < kTileM; i += 256) s_refa[i] = ws[p.off_refa + m0 + i];
+        for (int i = tid; i < kTileM; i += 256) s_refa[i] = ap[p.off_refa + m0 + i];
         int spread = 0;
         if (tid < kTileN) {
             const int ncol = n0 + tid;
-            s_refw[tid] = ncol < p.N ? ws[p.off_refw + ncol] : 0;
-            spread = ncol < p.N ? ws[p.off_spreadw + ncol] : 0;
+            s_refw[tid] = ncol < p.N ? wp[p.off_refw + ncol] : 0;
+            spread = ncol < p.N ? wp[p.off_spreadw + ncol] : 0;
         }
         if (tid < 8) s_ctl[tid] = 0;
         __syncthreads();
         if (spread > 3) s_ctl[4] = 1;                                 // a W row spans more than one class
     }
     if (wave == 0) {
-        const uint8_t* mask = ws + p.off_mask + (int64_t)blockIdx.y * KB;
-        int pos = 0;
+        // The list holds the visits of this workgroup's range of blocks; whether the tile can be
+        // taken at all is decided from the classes of ALL blocks, so that every workgroup that shares
+        // the tile decides the same.
+        const uint8_t* mask = ap + p.off_mask + (int64_t)blockIdx.y * KB;
+        int pos = 0, weight = 0;                                      // weight: n0 + 16 n1 + 256 n2 over all of K
         for (int c = kMaxClass; c >= 0; --c) {
-            for (int base = kb_lo; base < kb_hi; base += 64) {
+            for (int base = 0; base < KB; base += 64) {
                 const int kb = base + lane;
-                const uint32_t mk = kb < kb_hi ? mask[kb] : 0u;
+                const uint32_t mk = kb < KB ? mask[kb] : 0u;
                 if (mk & (1u << (kMaxClass + 1))) s_ctl[4] = 1;       // offset beyond the classes kept
                 const bool f = (mk >> c) & 1u;
-                const unsigned long long bal = __ballot(f);
-                if (f) s_vl[pos + __popcll(bal & ((1ull << lane) - 1ull))] = (uint16_t)(kb | (c << 10));
+                weight += __popcll(__ballot(f)) << (4 * c);
+                const bool mine = f && kb >= kb_lo && kb < kb_hi;
+                const unsigned long long bal = __ballot(mine);
+                if (mine) s_vl[pos + __popcll(bal & ((1ull << lane) - 1ull))] = (uint16_t)(kb | (c << 10));
                 pos += __popcll(bal);
             }
             if (pos & 1) {                                            // a step takes two visits
@@ -411,23 +553,37 @@ __global__ __launch_bounds__(256, 1) void gemm_fast_kernel(GemmParams p) {
             if (lane == 0) s_ctl[kMaxClass - c] = pos;                // s_ctl[0..2]: end of class 2, 1, 0
         }
         if (lane < kVisitPad) s_vl[pos + lane] = (uint16_t)KB;        // the loop looks five steps ahead
+        if (lane == 0 && weight > kIntBound) s_ctl[4] = 1;            // the int32 accumulator could overflow
     }
     __syncthreads();
-    const int end2 = s_ctl[0] / 2, end1 = s_ctl[1] / 2, total = s_ctl[2] / 2;   // in steps
-    {
-        const int n2 = s_ctl[0], n1 = s_ctl[1] - s_ctl[0], n0c = s_ctl[2] - s_ctl[1];
-        const int64_t a8_bytes = (int64_t)(kMaxClass + 1) * p.tiles_m * kGroups * (KB + 1) * 1024;
-        const bool ok = s_ctl[4] == 0 && (n0c + 16 * n1 + 256 * n2) * S <= kIntBound &&
-                        a8_bytes < ((int64_t)1 << 31) && (int64_t)p.N * KB * 16 < ((int64_t)1 << 31);
-        if (!ok) {
-            // decline the tile: the block-flush kernel computes it
-            if (tid == 0) {
-                *flag = 1;
-                uint32_t* list = reinterpret_cast<uint32_t*>(ws + p.off_list);
-                if (sidx == 0) list[1 + atomicAdd(list, 1u)] = (uint32_t)tile_id;
+    // segment ends in steps (uniform: they go to the loop in scalar registers)
+    const int end2 = __builtin_amdgcn_readfirstlane(s_ctl[0] / 2), end1 = __builtin_amdgcn_readfirstlane(s_ctl[1] / 2),
+              total = __builtin_amdgcn_readfirstlane(s_ctl[2] / 2);
+    if (s_ctl[4] != 0) {
+        // The tile cannot be taken (every workgroup sharing it sees the same): the first of them
+        // computes it with one fp32 scale-and-add per block, 128 rows at a time; the others leave.
+        if (sidx != 0) return;
+        if (tid == 0)
+            atomicAdd(reinterpret_cast<uint32_t*>(const_cast<uint8_t*>(ap) + p.off_cnt) + kMaxSplitTiles, 1u);
+        if constexpr (RQ) {
+            if constexpr (MX) {
+                if (tid < 64) s_rq_q[tid] = g_quant_tables.mx[tid];
+            } else {
+                const uint4* gq = reinterpret_cast<const uint4*>(g_quant_tables.q);
+                const uint4* gs = reinterpret_cast<const uint4*>(g_quant_tables.s);
+                for (int i = tid; i < 1024; i += 256) reinterpret_cast<uint4*>(s_rq_q)[i] = gq[i];
+                for (int i = tid; i < 512; i += 256) reinterpret_cast<uint4*>(s_rq_s)[i] = gs[i];
             }
-            return;
         }
+        uint8_t (&s_exp)[2][256] = *reinterpret_cast<uint8_t (*)[2][256]>(&s_b[0][0]);
+        for (int piece = 0; piece < 4; ++piece) {
+            const int by = (int)blockIdx.y * 4 + piece;
+            if (by * 128 >= p.M) break;
+            __syncthreads();
+            block_flush_tile<MX, BF16>(p, bz, by, (int)blockIdx.x, s_exp);
+            if constexpr (RQ) quantize_flushed_piece<MX>(p, bz, by, (int)blockIdx.x, s_rq_s, s_rq_q);
+        }
+        return;
     }
 
     const int h = lane >> 5, r = lane & 31;            // MFMA operand: lanes 32.. hold the pair's second block
@@ -441,9 +597,9 @@ __global__ __launch_bounds__(256, 1) void gemm_fast_kernel(GemmParams p) {
     const uint32_t grp_stride = (uint32_t)(KB + 1) * 1024u;
     const uint32_t cls_stride = (uint32_t)p.tiles_m * kGroups * grp_stride;
     const uint32_t tile_off = (uint32_t)blockIdx.y * kGroups * grp_stride;
-    const uint8_t* a8w = ws + p.off_a8 + (uint64_t)wave_u * 4u * grp_stride;   // uniform per wave
+    const uint8_t* a8w = ap + p.off_a8 + (uint64_t)wave_u * 4u * grp_stride;   // uniform per wave
     const uint8_t* wcodes = p.w_codes + bz * p.strideW_rows * KB * 16;        // uniform
-    const uint8_t* wmeta = ws + p.off_wmeta;                                  // uniform
+    const uint8_t* wmeta = wp + p.off_wmeta;                                  // uniform
     const int ncol = min(n0 + wave * 32 + r, p.N - 1);                        // this lane's W row
     const uint32_t w_row_codes = (uint32_t)ncol * (uint32_t)KB * 16u;
     const uint32_t w_row_meta = (uint32_t)ncol * (uint32_t)KB * 4u;
@@ -491,29 +647,58 @@ __global__ __launch_bounds__(256, 1) void gemm_fast_kernel(GemmParams p) {
         }
         __syncthreads();
     }
-    if (m0 + (int)wave_u * 128 >= p.M) return;
-#define DFP4_READ_TILE(G, V)                                                                        \
+    const bool active = m0 + (int)wave_u * 128 < p.M;      // wave-uniform
+#define DFP4_READ_ACC(G, V)                                                                         \
     asm volatile(DFP4_ACC_READ_ASM_##G                                                              \
                  : "=v"(V[0]), "=v"(V[1]), "=v"(V[2]), "=v"(V[3]), "=v"(V[4]), "=v"(V[5]),          \
                    "=v"(V[6]), "=v"(V[7]), "=v"(V[8]), "=v"(V[9]), "=v"(V[10]), "=v"(V[11]),        \
                    "=v"(V[12]), "=v"(V[13]), "=v"(V[14]), "=v"(V[15]))
 #define DFP4_FOR_TILES(F)                                                                           \
     F(0) F(1) F(2) F(3) F(4) F(5) F(6) F(7) F(8) F(9) F(10) F(11) F(12) F(13) F(14) F(15)
+    // partial tiles of the workgroups that share this output tile: [range][(16 tile + x) * 256 + thread]
+    const int* part = S > 1 ? p.part + bz * p.part_stride + (int64_t)tile_id * S * (kTileM * kTileN) : nullptr;
     if (S > 1) {
-        // K is shared with other workgroups: publish this one's exact int32 sums (the sum of
-        // all ranges is exact and does not depend on their order); gemm_block_kernel adds the
-        // ranges up and stores the tile
-        int* mine = reinterpret_cast<int*>(ws + p.off_part) +
-                    ((int64_t)tile_id * S + sidx) * (kTileM * kTileN);
+        // K is shared with other workgroups.  Every one publishes its exact int32 sums and then
+        // counts itself in; the one that arrives last adds the others' sums to its own (the total
+        // is exact and does not depend on the order) and goes on to the conversion and the stores.
+        // The sums travel as device-scope relaxed atomic stores and loads (they pass the per-XCD
+        // L2 instead of being written back and invalidated wholesale by a fence); "all my stores
+        // have completed" is the wait on the memory counter before the barrier.
+        if (active) {
+            int* mine = const_cast<int*>(part) + (int64_t)sidx * (kTileM * kTileN);
 #define DFP4_PUBLISH(G)                                                                             \
-        {                                                                                           \
-            int v[16];                                                                              \
-            DFP4_READ_TILE(G, v);                                                                   \
-            _Pragma("unroll") for (int x = 0; x < 16; ++x) mine[(G * 16 + x) * 256 + tid] = v[x];   \
-        }
-        DFP4_FOR_TILES(DFP4_PUBLISH)
+            {                                                                                       \
+                int v[16];                                                                          \
+                DFP4_READ_ACC(G, v);                                                                \
+                _Pragma("unroll") for (int x = 0; x < 16; ++x)                                      \
+                    __hip_atomic_store(&mine[(G * 16 + x) * 256 + tid], v[x], __ATOMIC_RELAXED,     \
+                                       __HIP_MEMORY_SCOPE_AGENT);                                   \
+            }
+            DFP4_FOR_TILES(DFP4_PUBLISH)
 #undef DFP4_PUBLISH
-        return;
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (tid == 0) {
+            uint32_t* cnt = reinterpret_cast<uint32_t*>(const_cast<uint8_t*>(ap) + p.off_cnt) + tile_id;
+            const uint32_t arrived = atomicAdd(cnt, 1u);
+            if (arrived == (uint32_t)S - 1u) atomicExch(cnt, 0u);       // ready for the next product
+            s_ctl[5] = (int)arrived;
+        }
+        __syncthreads();
+        if (s_ctl[5] != S - 1) return;
+    }
+    if (!active) return;                                   // nothing to store for rows beyond M
+#define DFP4_READ_TILE(G, V)                                                                        \
+    DFP4_READ_ACC(G, V);                                                                            \
+    if (S > 1) {                                                                                    \
+        for (int s_ = 0; s_ < S; ++s_) {                                                            \
+            if (s_ == sidx) continue;                                                               \
+            const int* other_ = part + (int64_t)s_ * (kTileM * kTileN);                             \
+            _Pragma("unroll") for (int x = 0; x < 16; ++x)                                          \
+                V[x] += __hip_atomic_load(&other_[(G * 16 + x) * 256 + tid], __ATOMIC_RELAXED,      \
+                                          __HIP_MEMORY_SCOPE_AGENT);                                \
+        }                                                                                           \
     }
     if constexpr (RQ) {
         // Requantizing epilogue (Section 3.3: results are quantized again for the next
@@ -641,132 +826,7 @@ __global__ __launch_bounds__(256, 1) void gemm_fast_kernel(GemmParams p) {
     }
 #undef DFP4_FOR_TILES
 #undef DFP4_READ_TILE
-}
-
-// ---------------------------------------------------------------------------
-// Sum of the K ranges of one 128 x 128 piece of a fast-kernel tile (split K):
-// the exact int32 partial sums the ranges published are added, converted once
-// and stored.  Wave w of the fast kernel holds rows 128w .. 128w+127 of the tile:
-// accumulator x of its lane (h, r) in tile i = 4*gi + n is row 128w + 32gi +
-// 8*(x/4) + 4h + x%4, column 32n + r, published at [(16i + x) * 256 + 64w + lane].
-// ---------------------------------------------------------------------------
-template <bool BF16>
-__device__ __forceinline__ void reduce_ranges(const GemmParams& p) {
-    const int tid = threadIdx.x, lane = tid & 63, n = tid >> 6;
-    const int h = lane >> 5, r = lane & 31;
-    const int64_t bz = blockIdx.z;
-    const uint8_t* ws = p.ws + bz * p.ws_stride;
-    const int tile_m = blockIdx.y >> 2, w = blockIdx.y & 3, S = p.ksplit;
-    const int tile_id = tile_m * p.tiles_n + blockIdx.x;
-    const int* part = reinterpret_cast<const int*>(ws + p.off_part) + (int64_t)tile_id * S * (kTileM * kTileN);
-    const int col = blockIdx.x * kTileN + n * 32 + r;
-    const int ew = col < p.N ? (int)ws[p.off_refw + col] - 256 : 0;
-#pragma unroll
-    for (int gi = 0; gi < 4; ++gi) {
-        const int i = gi * 4 + n;
-        int v[16];
-#pragma unroll
-        for (int x = 0; x < 16; ++x) v[x] = part[(i * 16 + x) * 256 + w * 64 + lane];
-        for (int s = 1; s < S; ++s) {
-            const int* other = part + (int64_t)s * (kTileM * kTileN);
-#pragma unroll
-            for (int x = 0; x < 16; ++x) v[x] += other[(i * 16 + x) * 256 + w * 64 + lane];
-        }
-#pragma unroll
-        for (int x = 0; x < 16; ++x) {
-            const int m = tile_m * kTileM + w * 128 + gi * 32 + 8 * (x >> 2) + 4 * h + (x & 3);
-            if (m < p.M && col < p.N) {
-                const float f = ldexpf((float)v[x], (int)ws[p.off_refa + m] + ew);
-                const int64_t o = bz * p.strideC + (int64_t)m * p.ldc + col;
-                if constexpr (BF16)
-                    static_cast<uint16_t*>(p.out)[o] = f32_to_bf16_rne(f);
-                else
-                    static_cast<float*>(p.out)[o] = f;
-            }
-        }
-    }
-}
-
-// ---------------------------------------------------------------------------
-// Per-block-flush kernel (always correct): 128 x 128 outputs per workgroup,
-// operands straight from global memory, one fp32 scale-and-add per block.
-// When `flags` is set it only computes tiles the fast kernel declined.
-// ---------------------------------------------------------------------------
-template <bool MX, bool BF16>
-__device__ __forceinline__ void block_flush_tile(const GemmParams& p, int64_t bz, int by, int bx,
-                                                 uint8_t (&s_exp)[2][256]) {
-    const int KB = p.KB;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
-    const int m0 = by * 128, n0 = bx * 128;
-    const int64_t a_row0 = bz * p.strideA_rows, w_row0 = bz * p.strideW_rows;
-    const int half = lane >> 5, l32 = lane & 31;
-
-    int64_t a_row[2], w_row[2];
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        a_row[i] = a_row0 + min(m0 + wm * 64 + i * 32 + l32, p.M - 1);
-        w_row[i] = w_row0 + min(n0 + wn * 64 + i * 32 + l32, p.N - 1);
-    }
-    const int t = threadIdx.x;
-    const int64_t e_row = t < 128 ? a_row0 + min(m0 + t, p.M - 1) : w_row0 + min(n0 + t - 128, p.N - 1);
-    const uint8_t* e_src = (t < 128 ? p.a_exp : p.w_exp) + e_row * KB;
-
-    float acc[2][2][16];
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int x = 0; x < 16; ++x) acc[i][j][x] = 0.0f;
-
-    for (int kb = 0; kb < KB; ++kb) {
-        uint8_t* se = s_exp[kb & 1];
-        se[t] = e_src[kb];
-        v4i a[2], b[2];
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const uint2 ca = *reinterpret_cast<const uint2*>(p.a_codes + (a_row[i] * KB + kb) * 16 + half * 8);
-            const uint2 cw = *reinterpret_cast<const uint2*>(p.w_codes + (w_row[i] * KB + kb) * 16 + half * 8);
-            const uint32_t da = MX ? 7u : ((uint32_t)p.a_dial[a_row[i] * KB + kb] & 15u);
-            const uint32_t dw = MX ? 7u : ((uint32_t)p.w_dial[w_row[i] * KB + kb] & 15u);
-            a[i] = unpack16(ca.x, ca.y, *reinterpret_cast<const uint4*>(g_shifted_book.w[da][0]));
-            b[i] = unpack16(cw.x, cw.y, *reinterpret_cast<const uint4*>(g_shifted_book.w[dw][0]));
-        }
-        __syncthreads();
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                v16i pr = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-                pr = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i], b[j], pr, 0, 0, 0);
-                const int ew = se[128 + wn * 64 + j * 32 + l32];
-#pragma unroll
-                for (int x = 0; x < 16; ++x) {
-                    const int row = 8 * (x >> 2) + 4 * half + (x & 3);
-                    const int ea = se[wm * 64 + i * 32 + row];
-                    acc[i][j][x] += ldexpf((float)pr[x], ea + ew - 256);
-                }
-            }
-    }
-
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const int n = n0 + wn * 64 + j * 32 + l32;
-#pragma unroll
-            for (int x = 0; x < 16; ++x) {
-                const int m = m0 + wm * 64 + i * 32 + 8 * (x >> 2) + 4 * half + (x & 3);
-                if (m < p.M && n < p.N) {
-                    const int64_t o = bz * p.strideC + (int64_t)m * p.ldc + n;
-                    if constexpr (BF16)
-                        static_cast<uint16_t*>(p.out)[o] = f32_to_bf16_rne(acc[i][j][x]);
-                    else
-                        static_cast<float*>(p.out)[o] = acc[i][j][x];
-                }
-            }
-        }
+#undef DFP4_READ_ACC
 }
 
 // ---------------------------------------------------------------------------
@@ -780,6 +840,7 @@ __device__ __forceinline__ void block_flush_tile(const GemmParams& p, int64_t bz
 constexpr int kSmallWaves = 16;
 constexpr int kSmallMaxKB = 512;      // LDS holds the 32 rows' exponent bytes of all blocks
 constexpr int kSmallMaxM = 64;
+static_assert(kSmallMaxM == 64 && kSmallMaxKB == 512, "takes_small_kernel() states these limits");
 
 template <bool MX, bool BF16>
 __global__ __launch_bounds__(kSmallWaves * 64) void gemm_small_kernel(GemmParams p) {
@@ -870,187 +931,245 @@ __global__ __launch_bounds__(kSmallWaves * 64) void gemm_small_kernel(GemmParams
     }
 }
 
-// mode 0: every 128 x 128 tile of the grid (no fast kernel ran).
-// mode 1: the grid covers all tiles; tiles the fast kernel declined are computed, the others
-//         have their K ranges summed (split K).
-// mode 2: a small grid walks the list of declined tiles (usually empty).
+// Whole product through the per-block flush (K beyond the single-accumulator kernel's limit).
 template <bool MX, bool BF16>
-__global__ __launch_bounds__(256) void gemm_block_kernel(GemmParams p, int mode) {
+__global__ __launch_bounds__(256) void gemm_block_kernel(GemmParams p) {
     __shared__ uint8_t s_exp[2][256];
-    // requantizing GEMM only (mode 2 with a quantized output): quantizer tables
-    __shared__ __attribute__((aligned(16))) uint8_t lds_q[BF16 ? (MX ? 64 : kDialects * 1024) : 16];
-    __shared__ __attribute__((aligned(16))) uint8_t lds_s[BF16 ? (MX ? 16 : kPairs * 1024) : 16];
-    const int64_t bz = blockIdx.z;
-    const uint8_t* ws = p.ws + bz * p.ws_stride;
-    if (mode == 2) {
-        const uint32_t* list = reinterpret_cast<const uint32_t*>(ws + p.off_list);
-        const uint32_t n = list[0];
-        if (n == 0) return;
-        const int tid = threadIdx.x;
-        const bool rq = BF16 && p.q_codes != nullptr;
-        if constexpr (BF16) {
-            if (rq) {
-                if constexpr (MX) {
-                    if (tid < 64) lds_q[tid] = g_quant_tables.mx[tid];
-                } else {
-                    const uint4* gq = reinterpret_cast<const uint4*>(g_quant_tables.q);
-                    const uint4* gs = reinterpret_cast<const uint4*>(g_quant_tables.s);
-                    for (int i = tid; i < 1024; i += 256) reinterpret_cast<uint4*>(lds_q)[i] = gq[i];
-                    for (int i = tid; i < 512; i += 256) reinterpret_cast<uint4*>(lds_s)[i] = gs[i];
-                }
-            }
-        }
-        __syncthreads();
-        for (uint32_t i = blockIdx.x; i < n * 4u; i += gridDim.x) {
-            const int tile = (int)list[1 + (i >> 2)], by = (tile / p.tiles_n) * 4 + (int)(i & 3u);
-            const int bx = tile % p.tiles_n;
-            if (by * 128 < p.M) block_flush_tile<MX, BF16>(p, bz, by, bx, s_exp);
-            __syncthreads();
-            if constexpr (BF16) {
-                if (rq && by * 128 < p.M) {
-                    // requantizing GEMM: quantize the 128 x 128 bf16 results this workgroup has
-                    // just written to the temporary (16 rows x 4 blocks per sweep, 4 lanes per block)
-                    __threadfence_block();
-                    const int nb_row = p.N / kBlock;
-                    const uint16_t* src = static_cast<const uint16_t*>(p.out) + bz * p.strideC;
-                    for (int sweep = 0; sweep < 8; ++sweep) {
-                        const int q = tid >> 2, sub = tid & 3;
-                        const int m = by * 128 + sweep * 16 + (q >> 2), nb = bx * 4 + (q & 3);
-                        const bool valid = m < p.M && nb < nb_row;      // the same for the 4 lanes of a block
-                        uint4 wv = make_uint4(0, 0, 0, 0);
-                        if (valid)
-                            wv = *reinterpret_cast<const uint4*>(src + (int64_t)m * p.ldc + nb * kBlock + sub * 8);
-                        uint32_t code, eb, dl = 0;
-                        if constexpr (MX) mxfp4_pass(wv, lds_q, code, eb);
-                        else dfp4_pass(wv, lds_s, lds_q, code, eb, dl);
-                        if (valid) {
-                            const size_t blk = (size_t)(bz * p.M + m) * nb_row + nb;
-                            p.q_codes[blk * 4 + sub] = code;
-                            if (sub == 0) {
-                                p.q_exp[blk] = (uint8_t)eb;
-                                if constexpr (!MX) p.q_dial[blk] = (uint8_t)dl;
-                            }
-                        }
-                    }
-                    __syncthreads();
-                }
-            }
-        }
-        return;
-    }
-    if (mode == 1 && ws[p.off_flag + (int64_t)(blockIdx.y / 4) * p.tiles_n + blockIdx.x] == 0) {
-        reduce_ranges<BF16>(p);
-        return;
-    }
-    block_flush_tile<MX, BF16>(p, bz, (int)blockIdx.y, (int)blockIdx.x, s_exp);
+    block_flush_tile<MX, BF16>(p, blockIdx.z, (int)blockIdx.y, (int)blockIdx.x, s_exp);
 }
 
 }  // namespace
 
+// Largest operands the single-accumulator kernel addresses with its 32-bit offsets: the expanded
+// A (all classes) and the 4-bit codes of W each stay below 2 GiB.  Larger products are cut into
+// pieces of at most this many rows on the host.
+static int64_t max_rows_a(int64_t KB) {
+    const int64_t tiles = (((int64_t)1 << 31) - 1) / ((int64_t)(kMaxClass + 1) * kGroups * (KB + 1) * 1024);
+    return (tiles < 65535 ? tiles : 65535) * kTileM;
+}
+static int64_t max_rows_w(int64_t KB) { return ((((int64_t)1 << 31) - 1) / (KB * 16)) / kTileN * kTileN; }
+
+size_t gemm_prepared_bytes(int64_t rows, int64_t K, bool weight) {
+    const int64_t KB = K / kBlock;
+    if (rows <= 0 || KB <= 0 || KB > kMaxKB) return 0;
+    if (!weight && takes_small_kernel(rows, KB)) return 0;
+    return (size_t)(weight ? prep_w_layout(rows, KB).total : prep_a_layout(rows, KB).total);
+}
+
+// byte offset, inside a prepared A, of the dword that counts tiles declined since it was prepared
+size_t gemm_prepared_declined_offset(int64_t M, int64_t K) {
+    return (size_t)prep_a_layout(M, K / kBlock).off_cnt + (size_t)kMaxSplitTiles * 4;
+}
+
+size_t gemm_prepared_workspace_bytes(int64_t M, int64_t N, int64_t K) {
+    const int64_t KB = K / kBlock;
+    if (M <= 0 || N <= 0 || !takes_fast_kernel(M, KB)) return 0;
+    return (size_t)partial_bytes(M, N, KB, 1);
+}
+
 size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K) {
-    if (M == 0 || N == 0) return 0;
-    return (size_t)make_layout(M, N, K / kBlock).total;
+    const int64_t KB = K / kBlock;
+    if (M <= 0 || N <= 0 || !takes_fast_kernel(M, KB)) return 0;
+    const int64_t Mc = M < max_rows_a(KB) ? M : max_rows_a(KB), Nc = N < max_rows_w(KB) ? N : max_rows_w(KB);
+    return (size_t)(prep_a_layout(Mc, KB).total + prep_w_layout(Nc, KB).total + partial_bytes(Mc, Nc, KB, 1));
 }
 
 size_t gemm_requant_workspace_bytes(int64_t M, int64_t N, int64_t K) {
-    if (M == 0 || N == 0) return 0;
-    return (size_t)align256(make_layout(M, N, K / kBlock).total) + (size_t)align256(M * N * 2);
+    if (M <= 0 || N <= 0) return 0;
+    return (size_t)align256((int64_t)gemm_workspace_bytes(M, N, K)) + (size_t)align256(M * N * 2);
 }
 
-// `rq` (optional): quantize the result along N into *rq.  `out` must then be a bf16 [M, N]
-// temporary (ldc = N, batch 1): it receives the results of every path that is not fused.
+namespace {
+
+template <typename F>
+void dispatch_mx_bf16(bool mx, bool bf16, F&& f) {
+    if (mx) {
+        if (bf16) f(std::true_type{}, std::true_type{}); else f(std::true_type{}, std::false_type{});
+    } else {
+        if (bf16) f(std::false_type{}, std::true_type{}); else f(std::false_type{}, std::false_type{});
+    }
+}
+
+void fill_params(GemmParams& p, const dfp4_tensor& A, const dfp4_tensor& W, void* out, int64_t ldc,
+                 int64_t strideA_rows, int64_t strideW_rows, int64_t strideC, const dfp4_tensor* rq) {
+    p.a_codes = A.codes; p.a_dial = A.dialect; p.a_exp = A.exponent;
+    p.w_codes = W.codes; p.w_dial = W.dialect; p.w_exp = W.exponent;
+    p.out = out; p.M = (int)A.rows; p.N = (int)W.rows; p.KB = (int)(A.K / kBlock);
+    p.ldc = ldc; p.strideA_rows = strideA_rows; p.strideW_rows = strideW_rows; p.strideC = strideC;
+    p.tiles_m = (int)((A.rows + kTileM - 1) / kTileM); p.tiles_n = (int)((W.rows + kTileN - 1) / kTileN);
+    p.ksplit = 1;
+    if (rq) {
+        p.q_codes = reinterpret_cast<uint32_t*>(rq->codes); p.q_dial = rq->dialect; p.q_exp = rq->exponent;
+    }
+}
+
+void set_prepared(GemmParams& p, uint8_t* a_prep, int64_t a_stride, uint8_t* w_prep, int64_t w_stride) {
+    const PrepALayout la = prep_a_layout(p.M, p.KB);
+    const PrepWLayout lw = prep_w_layout(p.N, p.KB);
+    p.a_prep = a_prep; p.a_prep_stride = a_stride;
+    p.w_prep = w_prep; p.w_prep_stride = w_stride;
+    p.off_refa = la.off_refa; p.off_mask = la.off_mask; p.off_cnt = la.off_cnt; p.off_a8 = la.off_a8;
+    p.off_refw = lw.off_refw; p.off_spreadw = lw.off_spreadw; p.off_wmeta = lw.off_wmeta;
+}
+
+// prepass: A workgroups (when do_a) and W workgroups (when do_w) in one launch
+int launch_prep(bool mx, const GemmParams& p, bool do_a, bool do_w, int64_t batch, hipStream_t stream) {
+    const int64_t KB = p.KB;
+    const int chunks_a = (int)((KB + 7) / 8);
+    const int64_t n_a = do_a ? (int64_t)p.tiles_m * chunks_a : 0;
+    int segs = 1;
+    while (segs * 16 < KB) segs <<= 1;
+    const int64_t n_w = do_w ? (p.N + 16 * (64 / segs) - 1) / (16 * (64 / segs)) : 0;
+    if (n_a + n_w == 0) return DFP4_OK;
+    if (n_a + n_w > 0x7fffffff || batch > 65535) return DFP4_ERR_SHAPE;
+    dim3 gp((unsigned)(n_a + n_w), 1, (unsigned)batch);
+    if (mx)
+        hipLaunchKernelGGL((gemm_prep_kernel<true>), gp, dim3(1024), 0, stream, p, (int)n_a, chunks_a);
+    else
+        hipLaunchKernelGGL((gemm_prep_kernel<false>), gp, dim3(1024), 0, stream, p, (int)n_a, chunks_a);
+    return check_launch();
+}
+
+// single-accumulator kernel on prepared operands; `part`: room for the partial tiles where K is split
+int launch_fast(bool mx, bool bf16, GemmParams& p, int64_t batch, int* part, size_t part_bytes, bool rq,
+                hipStream_t stream) {
+    const int64_t tiles = (int64_t)p.tiles_m * p.tiles_n;
+    p.ksplit = choose_ksplit(tiles * batch, p.KB);
+    const size_t per_batch = (size_t)p.ksplit * tiles * kTileM * kTileN * 4;
+    if (p.ksplit > 1 && (!part || per_batch * (size_t)batch > part_bytes)) p.ksplit = 1;   // no room: no split
+    p.part = part;
+    p.part_stride = (int64_t)(per_batch / 4);
+    if (batch * p.ksplit > 65535 || p.tiles_m > 65535) return DFP4_ERR_SHAPE;
+    dim3 gf((unsigned)p.tiles_n, (unsigned)p.tiles_m, (unsigned)(batch * p.ksplit));
+    if (rq) {
+        if (mx) hipLaunchKernelGGL((gemm_fast_kernel<true, true, true>), gf, dim3(256), 0, stream, p);
+        else hipLaunchKernelGGL((gemm_fast_kernel<false, true, true>), gf, dim3(256), 0, stream, p);
+    } else {
+        dispatch_mx_bf16(mx, bf16, [&](auto mxc, auto bc) {
+            hipLaunchKernelGGL((gemm_fast_kernel<decltype(mxc)::value, decltype(bc)::value, false>), gf, dim3(256), 0,
+                               stream, p);
+        });
+    }
+    return check_launch();
+}
+
+// products the single-accumulator kernel does not take: few rows, or K beyond its limit
+int launch_other(bool mx, bool bf16, GemmParams& p, int64_t batch, const dfp4_tensor* rq, hipStream_t stream) {
+    if (batch > 65535) return DFP4_ERR_SHAPE;
+    if (takes_small_kernel(p.M, p.KB)) {
+        dim3 gs((unsigned)((p.N + 31) / 32), (unsigned)((p.M + 31) / 32), (unsigned)batch);
+        dispatch_mx_bf16(mx, bf16, [&](auto mxc, auto bc) {
+            hipLaunchKernelGGL((gemm_small_kernel<decltype(mxc)::value, decltype(bc)::value>), gs,
+                               dim3(kSmallWaves * 64), 0, stream, p);
+        });
+    } else {
+        dim3 gb((unsigned)((p.N + 127) / 128), (unsigned)((p.M + 127) / 128), (unsigned)batch);
+        if (gb.y > 65535) return DFP4_ERR_SHAPE;
+        dispatch_mx_bf16(mx, bf16, [&](auto mxc, auto bc) {
+            hipLaunchKernelGGL((gemm_block_kernel<decltype(mxc)::value, decltype(bc)::value>), gb, dim3(256), 0,
+                               stream, p);
+        });
+    }
+    const int rc = check_launch();
+    if (rc != DFP4_OK || !rq) return rc;
+    // the bf16 temporary holds [batch * M, N]
+    return launch_quantize(mx, p.out, (int64_t)p.M * batch, p.N, p.ldc, *rq, stream);
+}
+
+bool shape_in_range(int64_t M, int64_t N, int64_t KB, int64_t batch, int64_t ldc) {
+    return M < (1 << 30) && N < (1 << 30) && KB < (1 << 26) && batch <= 65535 && ldc < (1 << 27);
+}
+
+}  // namespace
+
+// Shape limits of launch_gemm, so that callers can refuse a product before they enqueue anything.
+int gemm_shape_check(dfp4_tensor A, dfp4_tensor W, int64_t ldc, int64_t batch, bool rq) {
+    const int64_t M = A.rows, N = W.rows, KB = A.K / kBlock;
+    if (M == 0 || N == 0 || batch == 0) return DFP4_OK;
+    if (!shape_in_range(M, N, KB, batch, ldc)) return DFP4_ERR_SHAPE;
+    if (takes_fast_kernel(M, KB) && (rq || batch > 1) && (M > max_rows_a(KB) || N > max_rows_w(KB)))
+        return DFP4_ERR_SHAPE;         // only the plain single product is cut into pieces
+    if (!takes_fast_kernel(M, KB) && !takes_small_kernel(M, KB) && (M + 127) / 128 > 65535) return DFP4_ERR_SHAPE;
+    return DFP4_OK;
+}
+
+// `rq` (optional): quantize the result along N into *rq.  `out` must then be a bf16 [batch * M, N]
+// temporary (ldc = N): it receives the results of every path that does not quantize in its epilogue.
 int launch_gemm(bool mx, dfp4_tensor A, dfp4_tensor W, void* out, int out_dtype, int64_t ldc,
                 int64_t batch, int64_t strideA_rows, int64_t strideW_rows, int64_t strideC,
                 void* workspace, size_t workspace_bytes, hipStream_t stream, const dfp4_tensor* rq) {
     const int64_t M = A.rows, N = W.rows, KB = A.K / kBlock;
     if (M == 0 || N == 0 || batch == 0) return DFP4_OK;
-    if (M >= (1 << 30) || N >= (1 << 30) || KB >= (1 << 26) || batch > 65535 || ldc >= (1 << 27))
-        return DFP4_ERR_SHAPE;
-    const Layout lay = make_layout(M, N, KB);
-    if ((size_t)lay.total * (size_t)batch > workspace_bytes) return DFP4_ERR_WORKSPACE;
-
-    GemmParams p{};
-    p.a_codes = A.codes; p.a_dial = A.dialect; p.a_exp = A.exponent;
-    p.w_codes = W.codes; p.w_dial = W.dialect; p.w_exp = W.exponent;
-    p.out = out; p.M = (int)M; p.N = (int)N; p.KB = (int)KB;
-    p.ldc = ldc; p.strideA_rows = strideA_rows; p.strideW_rows = strideW_rows; p.strideC = strideC;
-    p.ws = static_cast<uint8_t*>(workspace); p.ws_stride = lay.total;
-    p.off_refa = lay.off_refa; p.off_refw = lay.off_refw; p.off_spreadw = lay.off_spreadw;
-    p.off_wmeta = lay.off_wmeta; p.off_mask = lay.off_mask; p.off_flag = lay.off_flag;
-    p.off_list = lay.off_list; p.off_part = lay.off_part; p.off_a8 = lay.off_a8;
-    p.tiles_m = (int)((M + kTileM - 1) / kTileM); p.tiles_n = (int)((N + kTileN - 1) / kTileN);
-    if (p.tiles_m > 16383 || p.tiles_n > (1 << 20)) return DFP4_ERR_SHAPE;
-
+    int rc = gemm_shape_check(A, W, ldc, batch, rq != nullptr);
+    if (rc != DFP4_OK) return rc;
     const bool bf16 = out_dtype == DFP4_BF16;
-    if (rq) {
-        p.q_codes = reinterpret_cast<uint32_t*>(rq->codes); p.q_dial = rq->dialect; p.q_exp = rq->exponent;
+    if (!takes_fast_kernel(M, KB)) {
+        GemmParams p{};
+        fill_params(p, A, W, out, ldc, strideA_rows, strideW_rows, strideC, rq);
+        return launch_other(mx, bf16, p, batch, rq, stream);
     }
-    if (M <= kSmallMaxM && KB > 0 && KB <= kSmallMaxKB) {
-        dim3 gs((unsigned)((N + 31) / 32), (unsigned)((M + 31) / 32), (unsigned)batch);
-        if (mx) {
-            if (bf16) hipLaunchKernelGGL((gemm_small_kernel<true, true>), gs, dim3(kSmallWaves * 64), 0, stream, p);
-            else hipLaunchKernelGGL((gemm_small_kernel<true, false>), gs, dim3(kSmallWaves * 64), 0, stream, p);
-        } else {
-            if (bf16) hipLaunchKernelGGL((gemm_small_kernel<false, true>), gs, dim3(kSmallWaves * 64), 0, stream, p);
-            else hipLaunchKernelGGL((gemm_small_kernel<false, false>), gs, dim3(kSmallWaves * 64), 0, stream, p);
+    // pieces of at most mc x nc outputs (one piece for every product of ordinary size)
+    const int64_t mc = M < max_rows_a(KB) ? M : max_rows_a(KB), nc = N < max_rows_w(KB) ? N : max_rows_w(KB);
+    const PrepALayout la = prep_a_layout(mc, KB);
+    const PrepWLayout lw = prep_w_layout(nc, KB);
+    const size_t prep_bytes = (size_t)(la.total + lw.total) * (size_t)batch;
+    if (!workspace || prep_bytes > workspace_bytes) return DFP4_ERR_WORKSPACE;
+    uint8_t* ws = static_cast<uint8_t*>(workspace);
+    const size_t esz = bf16 ? 2 : 4;
+    for (int64_t m0 = 0; m0 < M; m0 += mc) {
+        for (int64_t n0 = 0; n0 < N; n0 += nc) {
+            dfp4_tensor a = A, w = W;
+            a.rows = M - m0 < mc ? M - m0 : mc;
+            w.rows = N - n0 < nc ? N - n0 : nc;
+            a.codes += m0 * KB * 16; a.exponent += m0 * KB; if (a.dialect) a.dialect += m0 * KB;
+            w.codes += n0 * KB * 16; w.exponent += n0 * KB; if (w.dialect) w.dialect += n0 * KB;
+            GemmParams p{};
+            fill_params(p, a, w, static_cast<uint8_t*>(out) + (size_t)(m0 * ldc + n0) * esz, ldc, strideA_rows,
+                        strideW_rows, strideC, rq);
+            // the piece's own layouts (a last piece may be smaller), always within the room of a full one
+            const PrepALayout pa = prep_a_layout(a.rows, KB);
+            const PrepWLayout pw = prep_w_layout(w.rows, KB);
+            set_prepared(p, ws, pa.total, ws + (size_t)la.total * batch, pw.total);
+            rc = launch_prep(mx, p, n0 == 0, true, batch, stream);
+            if (rc != DFP4_OK) return rc;
+            rc = launch_fast(mx, bf16, p, batch, reinterpret_cast<int*>(ws + prep_bytes), workspace_bytes - prep_bytes,
+                             rq != nullptr, stream);
+            if (rc != DFP4_OK) return rc;
         }
-        const int rc = check_launch();
-        if (rc != DFP4_OK || !rq) return rc;
-        return launch_quantize(mx, out, M, N, ldc, *rq, stream);
     }
-    const bool fast = KB > 0 && KB <= kMaxKB;
-    if (fast) {
-        const int chunks_a = (int)((KB + 7) / 8), n_a = p.tiles_m * chunks_a;
-        int segs = 1;
-        while (segs * 16 < KB) segs <<= 1;
-        const int64_t n_w = (N + 16 * (64 / segs) - 1) / (16 * (64 / segs));
-        if (n_a + n_w > 0x7fffffff) return DFP4_ERR_SHAPE;
-        dim3 gp((unsigned)(n_a + n_w), 1, (unsigned)batch);
-        if (mx)
-            hipLaunchKernelGGL((gemm_prep_kernel<true>), gp, dim3(1024), 0, stream, p, n_a, chunks_a);
-        else
-            hipLaunchKernelGGL((gemm_prep_kernel<false>), gp, dim3(1024), 0, stream, p, n_a, chunks_a);
-    }
-    // more problems in the batch means more tiles: never split K more than the layout provides for
-    p.ksplit = choose_ksplit((int64_t)p.tiles_m * p.tiles_n * batch, KB);
-    if (p.ksplit > lay.ksplit) p.ksplit = lay.ksplit;
-    if (batch * p.ksplit > 65535) return DFP4_ERR_SHAPE;
-    dim3 gf((unsigned)p.tiles_n, (unsigned)p.tiles_m, (unsigned)(batch * p.ksplit));
-    dim3 gb((unsigned)((N + 127) / 128), (unsigned)((M + 127) / 128), (unsigned)batch);
-    if (gb.y > 65535) return DFP4_ERR_SHAPE;
-    dim3 gl((unsigned)device_cu_count(), 1, (unsigned)batch);     // walks the list of declined tiles
-    const bool fuse = rq && fast && p.ksplit == 1;       // the fast kernel quantizes its own tiles
-    if (fuse) {
-        if (mx) {
-            hipLaunchKernelGGL((gemm_fast_kernel<true, true, true>), gf, dim3(256), 0, stream, p);
-            hipLaunchKernelGGL((gemm_block_kernel<true, true>), gl, dim3(256), 0, stream, p, 2);
-        } else {
-            hipLaunchKernelGGL((gemm_fast_kernel<false, true, true>), gf, dim3(256), 0, stream, p);
-            hipLaunchKernelGGL((gemm_block_kernel<false, true>), gl, dim3(256), 0, stream, p, 2);
-        }
-        return check_launch();
-    }
-#define DFP4_LAUNCH(MXV, BV)                                                                     \
-    do {                                                                                         \
-        if (fast) {                                                                              \
-            hipLaunchKernelGGL((gemm_fast_kernel<MXV, BV, false>), gf, dim3(256), 0, stream, p); \
-            if (p.ksplit > 1)                                                                    \
-                hipLaunchKernelGGL((gemm_block_kernel<MXV, BV>), gb, dim3(256), 0, stream, p, 1); \
-            else                                                                                 \
-                hipLaunchKernelGGL((gemm_block_kernel<MXV, BV>), gl, dim3(256), 0, stream, p, 2); \
-        } else {                                                                                 \
-            hipLaunchKernelGGL((gemm_block_kernel<MXV, BV>), gb, dim3(256), 0, stream, p, 0);    \
-        }                                                                                        \
-    } while (0)
-    if (mx) {
-        if (bf16) DFP4_LAUNCH(true, true); else DFP4_LAUNCH(true, false);
+    return DFP4_OK;
+}
+
+// One operand prepared ahead of the product (weights: once; an activation: once for all the
+// products that consume it).
+int launch_gemm_prepare(bool mx, dfp4_tensor T, bool weight, void* prepared, hipStream_t stream) {
+    const int64_t KB = T.K / kBlock;
+    GemmParams p{};
+    dfp4_tensor none{};
+    none.K = T.K;
+    if (weight) {
+        if (T.rows > max_rows_w(KB)) return DFP4_ERR_SHAPE;
+        fill_params(p, none, T, nullptr, 0, 0, 0, 0, nullptr);
     } else {
-        if (bf16) DFP4_LAUNCH(false, true); else DFP4_LAUNCH(false, false);
+        if (T.rows > max_rows_a(KB)) return DFP4_ERR_SHAPE;
+        fill_params(p, T, none, nullptr, 0, 0, 0, 0, nullptr);
     }
-#undef DFP4_LAUNCH
-    const int rc = check_launch();
-    if (rc != DFP4_OK || !rq) return rc;
-    return launch_quantize(mx, out, M, N, ldc, *rq, stream);
+    set_prepared(p, static_cast<uint8_t*>(prepared), 0, static_cast<uint8_t*>(prepared), 0);
+    return launch_prep(mx, p, !weight, weight, 1, stream);
+}
+
+int launch_gemm_prepared(bool mx, dfp4_tensor A, void* a_prepared, dfp4_tensor W, const void* w_prepared, void* out,
+                         int out_dtype, int64_t ldc, void* workspace, size_t workspace_bytes, hipStream_t stream) {
+    const int64_t M = A.rows, N = W.rows, KB = A.K / kBlock;
+    if (M == 0 || N == 0) return DFP4_OK;
+    if (!shape_in_range(M, N, KB, 1, ldc)) return DFP4_ERR_SHAPE;
+    const bool bf16 = out_dtype == DFP4_BF16;
+    GemmParams p{};
+    fill_params(p, A, W, out, ldc, 0, 0, 0, nullptr);
+    if (!takes_fast_kernel(M, KB)) return launch_other(mx, bf16, p, 1, nullptr, stream);
+    if (M > max_rows_a(KB) || N > max_rows_w(KB)) return DFP4_ERR_SHAPE;
+    set_prepared(p, static_cast<uint8_t*>(a_prepared), 0, static_cast<uint8_t*>(const_cast<void*>(w_prepared)), 0);
+    return launch_fast(mx, bf16, p, 1, static_cast<int*>(workspace), workspace_bytes, false, stream);
 }
 
 }  // namespace dfp4

@@ -62,6 +62,9 @@ EA, EW, VOFF, VCOFF, VMOFF, VLADDR, SB, SBN, SBW, L16W, T0, T1 = range(232, 244)
 S_ABASE, S_VC, S_SEGEND, S_SEG, S_RET, S_BCUR, S_BNXT, S_BW, S_T0, S_T1 = 60, 76, 77, 78, 80, 82, 83, 84, 85, 86
 S_WC, S_WM = 88, 90
 NSLOT = 32
+# Timing experiments only (results are wrong, every address stays the same): a comma-separated list in
+# DFP4_GEN_EXP drops parts of the step -- noexpand (W expansion), nobarrier, noaload (A loads), nobread (LDS reads of B).
+EXP = set(filter(None, os.environ.get('DFP4_GEN_EXP', '').split(',')))
 FRAG = 1024                    # bytes per operand fragment
 B_BUF_BYTES = 8 * FRAG
 
@@ -188,7 +191,7 @@ def step(v):
     o.append(f"s_call_b64 {sr(S_RET, 2)}, 90f")
     o.append(f"1{v}:")
     # everything issued two steps ago has arrived: this step's A fragments and W codes
-    o.append("s_waitcnt vmcnt(10)")
+    o.append("s_waitcnt vmcnt(2)" if "noaload" in EXP else "s_waitcnt vmcnt(10)")
     first, second = expansion_pieces(v)
     loads = a_loads(ld, VOFF)
     a_load_slot = {1 + 4 * i: i for i in range(8)}                       # slots 1, 5, ..., 29
@@ -203,7 +206,7 @@ def step(v):
         7: [f"s_add_u32 {sr(S_VC)}, {sr(S_VC)}, 1", f"v_add_u32 {vr(VLADDR)}, 4, {vr(VLADDR)}"],
         # every wave has written its share of the W operands of the next step (previous step,
         # waited for at its end) and has finished reading the buffer this step overwrites
-        12: ["s_barrier"],
+        12: [] if "nobarrier" in EXP else ["s_barrier"],
     }
     for k in range(NSLOT):
         t, gi, n = k // 16, (k % 16) // 4, k % 4
@@ -213,7 +216,7 @@ def step(v):
                 o.append(w)
         acc = f"a[{16 * (4 * gi + n)}:{16 * (4 * gi + n) + 15}]"
         o.append(f"v_mfma_i32_32x32x32_i8 {acc}, {vr(ASET[v] + 4 * (4 * t + gi), 4)}, {vr(BBUF[t] + 4 * n, 4)}, {acc}")
-        if k in b_reads:
+        if k in b_reads and "nobread" not in EXP:
             bt, bn = b_reads[k]
             src = SB if bt == 1 else SBN
             o.append(f"ds_read_b128 {vr(BBUF[bt] + 4 * bn, 4)}, {vr(src)} offset:{(2 * bn + bt) * FRAG}")
@@ -223,9 +226,11 @@ def step(v):
             w = lg.need("tab")
             if w:
                 o.append(w)
+        if piece and "noexpand" in EXP:
+            piece = None
         if piece:
             o.append(piece[0])
-        if k in a_load_slot:
+        if k in a_load_slot and "noaload" not in EXP:
             o.append(loads[a_load_slot[k]])
         if k == 11:
             o.append(f"global_load_dwordx4 {vr(CODES[ld], 4)}, {vr(VCOFF)}, {sr(S_WC, 2)}")

@@ -26,6 +26,8 @@ class _CTensor(ctypes.Structure):
 
 SYMBOLS = [
     "dfp4_quantize", "dfp4_quantize_b64", "dfp4_quantize_mse", "dfp4_quantize_t", "mxfp4_quantize_t", "dfp4_quantize_t_at", "dfp4_dequantize", "dfp4_gemm", "dfp4_gemm_batched", "dfp4_gemm_workspace_bytes", "dfp4_gemm_noalloc",
+    "dfp4_gemm_prepared_bytes", "dfp4_gemm_prepare", "mxfp4_gemm_prepare", "dfp4_gemm_prepared_workspace_bytes",
+    "dfp4_gemm_prepared", "mxfp4_gemm_prepared", "dfp4_gemm_declined_tiles",
     "mxfp4_gemm_native", "dfp4_gemm_native", "dfp4_gemm_native_workspace_bytes", "dfp4_native_packed_bytes",
     "dfp4_quantize_native", "dfp4_native_pack", "mxfp4_native_pack", "dfp4_gemm_native_packed_w", "mxfp4_gemm_native_packed_w",
     "dfp4_gemm_native_packed", "mxfp4_gemm_native_packed", "dfp4_gemm_native_splitk_bytes",
@@ -61,6 +63,18 @@ def load():
     lib.mxfp4_gemm.argtypes = [_CTensor, _CTensor, vp, ci, i64, vp, ctypes.c_size_t, vp]
     lib.dfp4_gemm_batched.argtypes = [_CTensor, _CTensor, vp, ci, i64, i64, i64, i64, i64, vp,
                                       ctypes.c_size_t, vp]
+    lib.dfp4_gemm_prepared_bytes.argtypes = [i64, i64, ci]
+    lib.dfp4_gemm_prepared_bytes.restype = ctypes.c_size_t
+    lib.dfp4_gemm_prepared_workspace_bytes.argtypes = [i64, i64, i64]
+    lib.dfp4_gemm_prepared_workspace_bytes.restype = ctypes.c_size_t
+    for name in ("dfp4_gemm_prepare", "mxfp4_gemm_prepare"):
+        getattr(lib, name).argtypes = [_CTensor, ci, vp, ctypes.c_size_t, vp]
+        getattr(lib, name).restype = ci
+    for name in ("dfp4_gemm_prepared", "mxfp4_gemm_prepared"):
+        getattr(lib, name).argtypes = [_CTensor, vp, _CTensor, vp, vp, ci, i64, vp, ctypes.c_size_t, vp]
+        getattr(lib, name).restype = ci
+    lib.dfp4_gemm_declined_tiles.argtypes = [vp, i64, i64, ctypes.POINTER(ctypes.c_uint32)]
+    lib.dfp4_gemm_declined_tiles.restype = ci
     lib.dfp4_gemm_noalloc.argtypes = [_CTensor, _CTensor, vp, ci, i64, vp]
     lib.dfp4_gemm_noalloc.restype = ci
     lib.dfp4_gemm_workspace_bytes.argtypes = [i64, i64, i64]
@@ -240,6 +254,50 @@ def _gemm(fn, what, a, w, dtype, out, workspace):
 def gemm(a, w, dtype=torch.float32, out=None, workspace=None):
     """dfp4_gemm: out[M, N] = A[M, K] * W[N, K]^T on quantized operands."""
     return _gemm(load().dfp4_gemm, "dfp4_gemm", a, w, dtype, out, workspace)
+
+
+@dataclass
+class PreparedOperand:
+    """A quantized tensor together with its prepared form (dfp4_gemm_prepare)."""
+    q: "QTensor"
+    buf: torch.Tensor              # uint8, private layout; None when nothing is prepared for this operand
+    weight: bool
+    mx: bool
+
+
+def gemm_prepare(q, weight, mx=False, buf=None):
+    """dfp4_gemm_prepare / mxfp4_gemm_prepare: the per-operand work of the GEMM, done once."""
+    need = int(load().dfp4_gemm_prepared_bytes(q.rows, q.K, 1 if weight else 0))
+    if need == 0:
+        return PreparedOperand(q, None, weight, mx)
+    if buf is None:
+        buf = torch.empty(need, dtype=torch.uint8, device=q.codes.device)
+    fn = load().mxfp4_gemm_prepare if mx else load().dfp4_gemm_prepare
+    _check(fn(q.c(), 1 if weight else 0, _ptr(buf), buf.numel(), _stream()), "gemm_prepare")
+    return PreparedOperand(q, buf, weight, mx)
+
+
+def gemm_prepared(a, w, dtype=torch.float32, out=None, workspace=None):
+    """dfp4_gemm_prepared / mxfp4_gemm_prepared: a, w are PreparedOperands."""
+    assert not a.weight and w.weight and a.mx == w.mx
+    if out is None:
+        out = torch.empty((a.q.rows, w.q.rows), dtype=dtype, device=a.q.codes.device)
+    assert out.dtype in (torch.float32, torch.bfloat16) and out.stride(1) == 1
+    need = int(load().dfp4_gemm_prepared_workspace_bytes(a.q.rows, w.q.rows, a.q.K))
+    if workspace is None and need > 0:
+        workspace = torch.empty(need, dtype=torch.uint8, device=out.device)
+    fn = load().mxfp4_gemm_prepared if a.mx else load().dfp4_gemm_prepared
+    ldc = out.stride(0) if a.q.rows > 1 else w.q.rows
+    _check(fn(a.q.c(), _ptr(a.buf), w.q.c(), _ptr(w.buf), _ptr(out), F32 if out.dtype == torch.float32 else BF16,
+              ldc, _ptr(workspace), workspace.numel() if workspace is not None else 0, _stream()), "gemm_prepared")
+    return out
+
+
+def gemm_declined_tiles(a):
+    """dfp4_gemm_declined_tiles: tiles of products on this prepared A that took the per-block fp32 path."""
+    n = ctypes.c_uint32(0)
+    _check(load().dfp4_gemm_declined_tiles(_ptr(a.buf), a.q.rows, a.q.K, ctypes.byref(n)), "dfp4_gemm_declined_tiles")
+    return int(n.value)
 
 
 NOALLOC_SCRATCH_BYTES = 64 << 20

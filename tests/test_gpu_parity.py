@@ -526,6 +526,85 @@ def test_quantize_transposed_strided_input_and_pv_product():
 
 
 # --------------------------------------------------------------------------
+# GEMM on operands prepared ahead (dfp4_gemm_prepare / dfp4_gemm_prepared)
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("M,N,K,why", [(600, 352, 512, "whole tiles"), (100, 256, 4096, "split K"),
+                                       (2048, 1024, 2048, "many tiles"), (33, 100, 4096, "few rows: nothing prepared"),
+                                       (70, 200, 160, "ragged")])
+def test_gemm_prepared_matches_oracle_and_gemm(M, N, K, why):
+    print(f"gemm_prepared parity: {why} {M}x{N}x{K}", flush=True)
+    a = synth.gaussian_outlier_channels(M, K, max(1, K // 200), 50.0, 1.0, seed=500 + M)
+    w = synth.gaussian(N, K, 0.02, seed=600 + N)
+    qa, qw = dfp4.quantize(_dev(a)), dfp4.quantize(_dev(w))
+    pa, pw = dfp4.gemm_prepare(qa, weight=False), dfp4.gemm_prepare(qw, weight=True)
+    ref, absdot = _gemm_ref(synth.to_f64(a), synth.to_f64(w))
+    want = dfp4.gemm(qa, qw)
+    # the same prepared A serves several products in a row (its arrival counters return to zero)
+    for rep in range(3):
+        out = dfp4.gemm_prepared(pa, pw)
+        torch.cuda.synchronize()
+        _assert_gemm_close(out, ref, absdot, f"prepared {why} rep {rep}")
+        assert torch.equal(out.view(torch.int32), want.view(torch.int32)), "prepared and plain GEMM differ"
+    outb = dfp4.gemm_prepared(pa, pw, dtype=torch.bfloat16)
+    torch.cuda.synchronize()
+    _assert_gemm_close(outb, ref, absdot, f"prepared {why} bf16", bf16=True)
+    assert dfp4.gemm_declined_tiles(pa) == 0
+    # MXFP4
+    qam, qwm = dfp4.mxfp4_quantize(_dev(a)), dfp4.mxfp4_quantize(_dev(w))
+    outm = dfp4.gemm_prepared(dfp4.gemm_prepare(qam, weight=False, mx=True), dfp4.gemm_prepare(qwm, weight=True, mx=True))
+    torch.cuda.synchronize()
+    refm, absm = _gemm_ref(synth.to_f64(a), synth.to_f64(w), mx=True)
+    _assert_gemm_close(outm, refm, absm, f"prepared mxfp4 {why}")
+
+
+def test_gemm_prepared_declined_tiles_are_counted():
+    # second 512-row tile: block exponents spread over tens of binades -> per-block fp32 path,
+    # computed by the workgroup that finds it; the first tile takes the exact path
+    g = torch.Generator().manual_seed(19)
+    M, N, K = 700, 300, 512
+    a = torch.randn(M, K, generator=g)
+    scale = torch.exp2(torch.randint(-25, 25, (20, K // 32), generator=g).repeat_interleave(32, dim=1).float())
+    a[520:540] *= scale
+    a = a.to(torch.bfloat16)
+    w = (torch.randn(N, K, generator=g) * 0.02).to(torch.bfloat16)
+    qa, qw = dfp4.quantize(_dev(a)), dfp4.quantize(_dev(w))
+    pa, pw = dfp4.gemm_prepare(qa, weight=False), dfp4.gemm_prepare(qw, weight=True)
+    out = dfp4.gemm_prepared(pa, pw)
+    torch.cuda.synchronize()
+    ref, absdot = _gemm_ref(synth.to_f64(a), synth.to_f64(w))
+    _assert_gemm_close(out, ref, absdot, "prepared, mixed exact and declined tiles")
+    assert dfp4.gemm_declined_tiles(pa) == 3              # the three column tiles of the second row tile
+
+
+def test_gemm_prepared_shared_activation_full_size():
+    # LLaMA-3-8B gate and up projections on one prepared activation, then the down projection
+    # (K split between workgroups), sampled outputs against the oracle
+    ops = synth.llama3_8b_mlp(seed=2)
+    x, h = ops["x"], ops["h"]
+    print("gemm_prepared parity: 2048x14336x4096 (gate, up) and 2048x4096x14336 (down) sampled", flush=True)
+    px = dfp4.gemm_prepare(dfp4.quantize(_dev(x)), weight=False)
+    rng = np.random.default_rng(7)
+    rows = np.sort(rng.choice(x.shape[0], 16, replace=False))
+    for name in ("w_gate", "w_up"):
+        w = ops[name]
+        pw = dfp4.gemm_prepare(dfp4.quantize(_dev(w)), weight=True)
+        out = dfp4.gemm_prepared(px, pw)
+        torch.cuda.synchronize()
+        cols = np.sort(rng.choice(w.shape[0], 128, replace=False))
+        ref, absdot = _gemm_ref(synth.to_f64(x[rows]), synth.to_f64(w[cols]))
+        _assert_gemm_close(out[rows][:, cols], ref, absdot, f"prepared {name} sampled")
+    ph = dfp4.gemm_prepare(dfp4.quantize(_dev(h)), weight=False)
+    pw = dfp4.gemm_prepare(dfp4.quantize(_dev(ops["w_down"])), weight=True)
+    for rep in range(2):
+        out = dfp4.gemm_prepared(ph, pw)
+        torch.cuda.synchronize()
+        cols = np.sort(rng.choice(4096, 64, replace=False))
+        ref, absdot = _gemm_ref(synth.to_f64(h[rows]), synth.to_f64(ops["w_down"][cols]))
+        _assert_gemm_close(out[rows][:, cols], ref, absdot, f"prepared down sampled rep {rep}")
+    assert dfp4.gemm_declined_tiles(px) == 0 and dfp4.gemm_declined_tiles(ph) == 0
+
+
+# --------------------------------------------------------------------------
 # GEMM with requantizing epilogue
 # --------------------------------------------------------------------------
 def _requant_ref(a_bf16, w_bf16, mx=False):
