@@ -69,6 +69,14 @@ __device__ const ShiftedBook g_shifted_book = make_shifted_book();
 
 namespace {
 
+// Results leave the kernel once and are not read again by it: stored with the non-temporal hint so
+// that they do not push the operands other workgroups still need out of the caches.
+#ifdef DFP4_PLAIN_OUT_STORES
+#define DFP4_OUT_STORE(PTR, VAL) (*(PTR) = (VAL))
+#else
+#define DFP4_OUT_STORE(PTR, VAL) __builtin_nontemporal_store((VAL), (PTR))
+#endif
+
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
@@ -80,7 +88,9 @@ constexpr int kIntBound = 4660;       // n0 + 16 n1 + 256 n2 <= 2^31 / (32 * 120
 constexpr int kBBufBytes = 8 * 1024;  // int8 W operands of one step: 4 column tiles x 2 x 1 KiB
 constexpr int kRqPitch = 136;         // bf16 per staged output row (128 + 8: rows stay 16-byte aligned)
 constexpr int kVisitPad = 12;         // padding visits after the last one (the loop looks 5 steps ahead)
-constexpr int kVisitCap = (kMaxClass + 1) * (kMaxKB + 1) + kVisitPad + 4;
+constexpr int kClassPairs = (kMaxClass + 1) * (kMaxClass + 2) / 2;   // (class of A, class of W) with sum <= kMaxClass
+constexpr int kVisitCap = kClassPairs * kMaxKB + 2 * (kMaxClass + 1) + kVisitPad + 4;
+constexpr uint32_t kZeroTab = kDialects * 4 * 16;   // byte offset of the all-zero table behind the shifted book in LDS
 constexpr int kMaxSplitTiles = 2048;  // arrival counters per prepared A: K is split only below this many tiles
 
 struct GemmParams {
@@ -93,7 +103,8 @@ struct GemmParams {
     uint8_t* w_prep;
     int64_t a_prep_stride, w_prep_stride;
     int64_t off_refa, off_mask, off_cnt, off_a8;      // inside a prepared A
-    int64_t off_refw, off_spreadw, off_wmeta;         // inside a prepared W
+    int64_t off_refw, off_wmask, off_wmeta;           // inside a prepared W
+    uint32_t wmeta_cls_stride;                        // bytes between the table dwords of two classes
     // exact int32 partial tiles of workgroups that share an output tile (split K)
     int* part;
     int64_t part_stride;              // ints per batch entry
@@ -121,16 +132,18 @@ inline PrepALayout prep_a_layout(int64_t M, int64_t KB) {
     l.total = align256(l.off_a8 + (kMaxClass + 1) * tm * kGroups * (KB + 1) * 1024);
     return l;
 }
-// Prepared W [N, K]: per-row reference exponents and exponent spreads (rows padded to 128) and one
-// dword per block naming its (dialect, shift) table.  W itself stays 4-bit.
-struct PrepWLayout { int64_t off_refw, off_spreadw, off_wmeta, total; };
+// Prepared W [N, K]: per-row reference exponents (rows padded to 128), one class mask per
+// (128-row tile, block), and per class and block one dword naming the block's (dialect, shift)
+// table -- or the all-zero table where the block is of another class: [class][row][block].
+// W itself stays 4-bit.
+struct PrepWLayout { int64_t off_refw, off_wmask, off_wmeta, total; };
 inline PrepWLayout prep_w_layout(int64_t N, int64_t KB) {
     const int64_t tn = (N + kTileN - 1) / kTileN;
     PrepWLayout l{};
     l.off_refw = 0;
-    l.off_spreadw = align256(tn * kTileN);
-    l.off_wmeta = align256(l.off_spreadw + tn * kTileN);
-    l.total = align256(l.off_wmeta + N * KB * 4);
+    l.off_wmask = align256(tn * kTileN);
+    l.off_wmeta = align256(l.off_wmask + tn * KB);
+    l.total = align256(l.off_wmeta + (kMaxClass + 1) * N * KB * 4);
     return l;
 }
 // Workgroups per output tile: when there are fewer tiles than compute units, K is split
@@ -195,7 +208,8 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
 // are read as whole 128-byte lines (8 lanes per row) and redistributed through LDS
 // to the fragment order (lane = (t, row): elements 16t .. 16t+15 of the block).
 //
-// W rows: reference exponent, spread, and one table offset (dword) per block.
+// W rows: reference exponent, per class and block one table offset (dword), and the classes
+// present in each block among the 128 rows of a tile.
 // ---------------------------------------------------------------------------
 __device__ __forceinline__ int min_bytes(uint32_t x) {
     return min(min((int)(x & 0xffu), (int)((x >> 8) & 0xffu)), min((int)((x >> 16) & 0xffu), (int)(x >> 24)));
@@ -228,54 +242,39 @@ __global__ __launch_bounds__(1024) void gemm_prep_kernel(GemmParams p, int n_a, 
     const int KB = p.KB;
 
     if ((int)blockIdx.x >= n_a) {
-        // ---- W rows: `segs` lanes per row, 16 blocks per lane
-        int segs = 1;
-        while (segs * 16 < KB) segs <<= 1;            // <= 32: the fast path has KB <= 512
-        const int rows_per_wave = 64 / segs;
-        const int row = (((int)blockIdx.x - n_a) * 16 + wave) * rows_per_wave + lane / segs;
-        const int seg = lane % segs;
+        // ---- W: a workgroup = (128-row tile, chunk of 64 blocks), 8 lanes per row (lane s takes blocks
+        // s, s + 8, ...).  Every workgroup finds the rows' reference exponents from all of K.
+        __shared__ uint32_t s_wmask[64];
+        const int chunks_w = (KB + 63) / 64;
+        const int tile = ((int)blockIdx.x - n_a) / chunks_w, chunk = ((int)blockIdx.x - n_a) % chunks_w;
+        const int kc = chunk * 64, ke = min(KB, kc + 64);
+        const int row = tile * kTileN + (tid >> 3), seg = tid & 7;
         const bool valid = row < p.N;
         const int64_t base = (bz * p.strideW_rows + min(row, p.N - 1)) * KB;
-        const int k0 = seg * 16, nb = max(0, min(16, KB - k0));
-        const uint8_t* we = p.w_exp + base + k0;
-        const uint8_t* wd = MX ? nullptr : p.w_dial + base + k0;
-        uint32_t e[4] = {0, 0, 0, 0}, d[4] = {0x07070707u, 0x07070707u, 0x07070707u, 0x07070707u};
-        int mn = 255, mx = 0;
-        if (nb == 16) {
-            __builtin_memcpy(e, we, 16);              // no alignment assumed: the compiler picks the access
-            if (!MX) __builtin_memcpy(d, wd, 16);
+        const uint8_t* we = p.w_exp + base;
+        const uint8_t* wd = MX ? nullptr : p.w_dial + base;
+        if (tid < 64) s_wmask[tid] = 0;
+        int mn = 255;
+        for (int kb = seg; kb < KB; kb += 8) mn = min(mn, (int)we[kb]);
+        mn = min(mn, __shfl_xor(mn, 1));
+        mn = min(mn, __shfl_xor(mn, 2));
+        mn = min(mn, __shfl_xor(mn, 4));
+        __syncthreads();
+        if (valid) {
+            if (seg == 0 && chunk == 0) wp[p.off_refw + row] = (uint8_t)mn;
+            uint32_t* wmeta = reinterpret_cast<uint32_t*>(wp + p.off_wmeta) + (int64_t)row * KB;
+            const int64_t cls_stride = (int64_t)p.N * KB;                // dwords
+            for (int kb = kc + seg; kb < ke; kb += 8) {
+                const uint32_t delta = (uint32_t)we[kb] - (uint32_t)mn;
+                const uint32_t cls = min(delta >> 2, (uint32_t)kMaxClass + 1u), dd = MX ? 7u : ((uint32_t)wd[kb] & 15u);
+                const uint32_t tab = (dd * 4u + (delta & 3u)) * 16u;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) { mn = min(mn, min_bytes(e[i])); mx = max(mx, max_bytes(e[i])); }
-        } else {
-            for (int j = 0; j < nb; ++j) { mn = min(mn, (int)we[j]); mx = max(mx, (int)we[j]); }
-        }
-        for (int s = 1; s < segs; s <<= 1) {
-            mn = min(mn, __shfl_xor(mn, s));
-            mx = max(mx, __shfl_xor(mx, s));
-        }
-        if (!valid) return;
-        if (seg == 0) {
-            wp[p.off_refw + row] = (uint8_t)mn;
-            wp[p.off_spreadw + row] = (uint8_t)min(mx - mn, 255);
-        }
-        uint32_t* wmeta = reinterpret_cast<uint32_t*>(wp + p.off_wmeta) + (int64_t)row * KB + k0;
-        if (nb == 16) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                uint32_t o[4];
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const uint32_t ee = (e[i] >> (8 * j)) & 0xffu, dd = (d[i] >> (8 * j)) & 15u;
-                    o[j] = (dd * 4u + ((ee - (uint32_t)mn) & 3u)) * 16u;
-                }
-                __builtin_memcpy(wmeta + 4 * i, o, 16);       // 4-byte aligned only when KB is odd
-            }
-        } else {
-            for (int j = 0; j < nb; ++j) {
-                const uint32_t ee = we[j], dd = MX ? 7u : ((uint32_t)wd[j] & 15u);
-                wmeta[j] = (dd * 4u + ((ee - (uint32_t)mn) & 3u)) * 16u;
+                for (uint32_t c = 0; c <= (uint32_t)kMaxClass; ++c) wmeta[c * cls_stride + kb] = cls == c ? tab : kZeroTab;
+                atomicOr(&s_wmask[kb - kc], 1u << cls);
             }
         }
+        __syncthreads();
+        if (tid < ke - kc) wp[p.off_wmask + (int64_t)tile * KB + kc + tid] = (uint8_t)s_wmask[tid];
         return;
     }
 
@@ -402,18 +401,33 @@ __device__ __forceinline__ void block_flush_tile(const GemmParams& p, int64_t bz
 #pragma unroll
             for (int x = 0; x < 16; ++x) acc[i][j][x] = 0.0f;
 
+    // operands of one block, loaded one iteration ahead so that the memory latency of block kb + 1
+    // passes behind the arithmetic of block kb
+    struct BlockOperands { uint2 ca[2], cw[2]; uint32_t da[2], dw[2], e; };
+    auto load_block = [&](int kb) {
+        BlockOperands o;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            o.ca[i] = *reinterpret_cast<const uint2*>(p.a_codes + (a_row[i] * KB + kb) * 16 + half * 8);
+            o.cw[i] = *reinterpret_cast<const uint2*>(p.w_codes + (w_row[i] * KB + kb) * 16 + half * 8);
+            o.da[i] = MX ? 7u : ((uint32_t)p.a_dial[a_row[i] * KB + kb] & 15u);
+            o.dw[i] = MX ? 7u : ((uint32_t)p.w_dial[w_row[i] * KB + kb] & 15u);
+        }
+        o.e = e_src[kb];
+        return o;
+    };
+    BlockOperands nxt{};
+    if (KB > 0) nxt = load_block(0);              // K = 0: nothing to read, the outputs are zeros
     for (int kb = 0; kb < KB; ++kb) {
+        const BlockOperands cur = nxt;
+        if (kb + 1 < KB) nxt = load_block(kb + 1);
         uint8_t* se = s_exp[kb & 1];
-        se[t] = e_src[kb];
+        se[t] = (uint8_t)cur.e;
         v4i a[2], b[2];
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
-            const uint2 ca = *reinterpret_cast<const uint2*>(p.a_codes + (a_row[i] * KB + kb) * 16 + half * 8);
-            const uint2 cw = *reinterpret_cast<const uint2*>(p.w_codes + (w_row[i] * KB + kb) * 16 + half * 8);
-            const uint32_t da = MX ? 7u : ((uint32_t)p.a_dial[a_row[i] * KB + kb] & 15u);
-            const uint32_t dw = MX ? 7u : ((uint32_t)p.w_dial[w_row[i] * KB + kb] & 15u);
-            a[i] = unpack16(ca.x, ca.y, *reinterpret_cast<const uint4*>(g_shifted_book.w[da][0]));
-            b[i] = unpack16(cw.x, cw.y, *reinterpret_cast<const uint4*>(g_shifted_book.w[dw][0]));
+            a[i] = unpack16(cur.ca[i].x, cur.ca[i].y, *reinterpret_cast<const uint4*>(g_shifted_book.w[cur.da[i]][0]));
+            b[i] = unpack16(cur.cw[i].x, cur.cw[i].y, *reinterpret_cast<const uint4*>(g_shifted_book.w[cur.dw[i]][0]));
         }
         __syncthreads();
 #pragma unroll
@@ -496,8 +510,9 @@ __global__ __launch_bounds__(256, 1) void gemm_fast_kernel(GemmParams p) {
     __shared__ __attribute__((aligned(16))) uint8_t s_rq_q[RQ ? (MX ? 64 : kDialects * 1024) : 16];
     __shared__ __attribute__((aligned(16))) uint8_t s_rq_s[RQ ? (MX ? 16 : kPairs * 1024) : 16];
     __shared__ __attribute__((aligned(16))) uint16_t s_rq[RQ ? 4 * 64 * kRqPitch : 8];
-    __shared__ __attribute__((aligned(16))) uint32_t s_tab[kDialects * 4 * 4];
-    __shared__ uint16_t s_vl[kVisitCap];     // visits: class << 10 | block, classes from high to low
+    __shared__ __attribute__((aligned(16))) uint32_t s_tab[kDialects * 4 * 4 + 4];   // + the all-zero table
+    // visits: block | class of A << 10 | class of W << 12, from the highest class sum to the lowest
+    __shared__ uint16_t s_vl[kVisitCap];
     __shared__ __attribute__((aligned(4))) uint8_t s_refa[kTileM];
     __shared__ uint8_t s_refw[kTileN];
     __shared__ int s_ctl[8];                 // segment ends (entries), feasibility
@@ -514,46 +529,58 @@ __global__ __launch_bounds__(256, 1) void gemm_fast_kernel(GemmParams p) {
     const int kb_per = (KB + S - 1) / S;
     const int kb_lo = sidx * kb_per, kb_hi = min(KB, kb_lo + kb_per);
 
-    // ---- prologue: tables, references, list of (block, class) visits
-    for (int i = tid; i < kDialects * 16; i += 256) s_tab[i] = (&g_shifted_book.w[0][0][0])[i];
-    {
-        for (int i = tid; i < kTileM; i += 256) s_refa[i] = ap[p.off_refa + m0 + i];
-        int spread = 0;
-        if (tid < kTileN) {
-            const int ncol = n0 + tid;
-            s_refw[tid] = ncol < p.N ? wp[p.off_refw + ncol] : 0;
-            spread = ncol < p.N ? wp[p.off_spreadw + ncol] : 0;
-        }
-        if (tid < 8) s_ctl[tid] = 0;
-        __syncthreads();
-        if (spread > 3) s_ctl[4] = 1;                                 // a W row spans more than one class
-    }
+    // ---- prologue: tables, references, list of (block, class of A, class of W) visits
+    for (int i = tid; i < kDialects * 16 + 4; i += 256) s_tab[i] = i < kDialects * 16 ? (&g_shifted_book.w[0][0][0])[i] : 0u;
+    for (int i = tid; i < kTileM; i += 256) s_refa[i] = ap[p.off_refa + m0 + i];
+    if (tid < kTileN) s_refw[tid] = n0 + tid < p.N ? wp[p.off_refw + n0 + tid] : 0;
+    if (tid < 8) s_ctl[tid] = 0;
     if (wave == 0) {
-        // The list holds the visits of this workgroup's range of blocks; whether the tile can be
-        // taken at all is decided from the classes of ALL blocks, so that every workgroup that shares
-        // the tile decides the same.
-        const uint8_t* mask = ap + p.off_mask + (int64_t)blockIdx.y * KB;
-        int pos = 0, weight = 0;                                      // weight: n0 + 16 n1 + 256 n2 over all of K
-        for (int c = kMaxClass; c >= 0; --c) {
-            for (int base = 0; base < KB; base += 64) {
-                const int kb = base + lane;
-                const uint32_t mk = kb < KB ? mask[kb] : 0u;
-                if (mk & (1u << (kMaxClass + 1))) s_ctl[4] = 1;       // offset beyond the classes kept
-                const bool f = (mk >> c) & 1u;
-                weight += __popcll(__ballot(f)) << (4 * c);
-                const bool mine = f && kb >= kb_lo && kb < kb_hi;
-                const unsigned long long bal = __ballot(mine);
-                if (mine) s_vl[pos + __popcll(bal & ((1ull << lane) - 1ull))] = (uint16_t)(kb | (c << 10));
-                pos += __popcll(bal);
+        // A block is visited once for every pair (class present among the tile's 512 rows of A, class
+        // present among its 128 rows of W); rows of other classes contribute zeros.  Visits are
+        // ordered by the class sum, which is the number of 4-bit shifts the accumulators still
+        // receive.  The list holds the visits of this workgroup's range of blocks; whether the tile
+        // can be taken at all is decided from ALL blocks, so that every workgroup sharing the tile
+        // decides the same.
+        const uint8_t* mask_a = ap + p.off_mask + (int64_t)blockIdx.y * KB;
+        const uint8_t* mask_w = wp + p.off_wmask + (int64_t)blockIdx.x * KB;
+        uint32_t ma[kMaxKB / 64], mw[kMaxKB / 64];
+        bool bad = false;
+#pragma unroll
+        for (int j = 0; j < kMaxKB / 64; ++j) {
+            const int kb = j * 64 + lane;
+            ma[j] = kb < KB ? mask_a[kb] : 0u;
+            mw[j] = kb < KB ? mask_w[kb] : 0u;
+            // highest classes present: their sum must not exceed the classes kept
+            const int ha = 31 - __builtin_clz(ma[j] | 1u), hw = 31 - __builtin_clz(mw[j] | 1u);
+            bad |= ha + hw > kMaxClass;
+        }
+        int pos = 0, weight = 0;                                      // weight: sum of 16^(class sum) over all of K
+        for (int ct = kMaxClass; ct >= 0; --ct) {
+            for (int ca = 0; ca <= ct; ++ca) {
+                const int cw = ct - ca;
+#pragma unroll
+                for (int j = 0; j < kMaxKB / 64; ++j) {
+                    if (j * 64 >= KB) break;                          // uniform
+                    const int kb = j * 64 + lane;
+                    const bool f = ((ma[j] >> ca) & 1u) && ((mw[j] >> cw) & 1u);
+                    weight += __popcll(__ballot(f)) << (4 * ct);
+                    const bool mine = f && kb >= kb_lo && kb < kb_hi;
+                    const unsigned long long bal = __ballot(mine);
+                    if (mine) s_vl[pos + __popcll(bal & ((1ull << lane) - 1ull))] = (uint16_t)(kb | (ca << 10) | (cw << 12));
+                    pos += __popcll(bal);
+                }
             }
             if (pos & 1) {                                            // a step takes two visits
                 if (lane == 0) s_vl[pos] = (uint16_t)KB;              // padding: the all-zero block of class 0
                 pos += 1;
             }
-            if (lane == 0) s_ctl[kMaxClass - c] = pos;                // s_ctl[0..2]: end of class 2, 1, 0
+            if (lane == 0) s_ctl[kMaxClass - ct] = pos;               // s_ctl[0..2]: end of class sum 2, 1, 0
         }
         if (lane < kVisitPad) s_vl[pos + lane] = (uint16_t)KB;        // the loop looks five steps ahead
-        if (lane == 0 && weight > kIntBound) s_ctl[4] = 1;            // the int32 accumulator could overflow
+        // exponent offsets beyond the classes kept, or an int32 accumulator that could overflow
+        if (__ballot(bad) != 0ull || weight > kIntBound) {
+            if (lane == 0) s_ctl[4] = 1;
+        }
     }
     __syncthreads();
     // segment ends in steps (uniform: they go to the loop in scalar registers)
@@ -607,9 +634,11 @@ __global__ __launch_bounds__(256, 1) void gemm_fast_kernel(GemmParams p) {
     // W operands of the first two steps (the loop expands those of step s + 2 during step s)
 #pragma unroll
     for (int s = 0; s < 2; ++s) {
-        const uint32_t kb = min((uint32_t)s_vl[2 * s + h] & 1023u, (uint32_t)KB - 1u);
+        const uint32_t entry = s_vl[2 * s + h];
+        const uint32_t kb = min(entry & 1023u, (uint32_t)KB - 1u);
         const uint4 c = *reinterpret_cast<const uint4*>(wcodes + w_row_codes + kb * 16u);
-        const uint32_t meta = *reinterpret_cast<const uint32_t*>(wmeta + w_row_meta + kb * 4u);
+        const uint32_t meta = *reinterpret_cast<const uint32_t*>(wmeta + ((entry >> 12) & 3u) * p.wmeta_cls_stride +
+                                                                 w_row_meta + kb * 4u);
         const uint4 tab = *reinterpret_cast<const uint4*>(reinterpret_cast<const uint8_t*>(s_tab) + meta);
         *reinterpret_cast<v4i*>(&s_b[s][(wave * 2 + 0) * 1024 + lane * 16]) = unpack16(c.x, c.y, tab);
         *reinterpret_cast<v4i*>(&s_b[s][(wave * 2 + 1) * 1024 + lane * 16]) = unpack16(c.z, c.w, tab);
@@ -630,6 +659,7 @@ __global__ __launch_bounds__(256, 1) void gemm_fast_kernel(GemmParams p) {
                        [cstr] "s"(cls_stride), [toff] "s"(tile_off), [kbm] "s"(kbm), [tabb] "s"(lds_tab),
                        [vlb] "s"(lds_vl), [bb] "s"(lds_b), [sel] "s"(sign_sel),
                        [e2] "s"((uint32_t)end2), [e1] "s"((uint32_t)end1), [e0] "s"((uint32_t)total),
+                       [wcs] "s"(p.wmeta_cls_stride),
                        [wv] "s"(wave_u), [alane] "v"(a_lane), [l16] "v"(l16), [wrc] "v"(w_row_codes),
                        [wrm] "v"(w_row_meta), [h2] "v"(h2)
                      : DFP4_LOOP_VGPR_CLOBBERS, DFP4_ACC_CLOBBERS, DFP4_LOOP_SGPR_CLOBBERS, "scc", "memory");
@@ -789,7 +819,7 @@ __global__ __launch_bounds__(256, 1) void gemm_fast_kernel(GemmParams p) {
                         const uint32_t send = (r & 1) ? b0 : b1;
                         const uint32_t recv = (uint32_t)__builtin_amdgcn_mov_dpp((int)send, 0xB1, 0xf, 0xf, true);
                         const uint32_t word = (r & 1) ? (recv | (b1 << 16)) : (b0 | (recv << 16));
-                        *reinterpret_cast<uint32_t*>(rowp + (int64_t)j * row_bytes + lane_off) = word;
+                        DFP4_OUT_STORE(reinterpret_cast<uint32_t*>(rowp + (int64_t)j * row_bytes + lane_off), word);
                     }
                 } else {
 #pragma unroll
@@ -797,9 +827,9 @@ __global__ __launch_bounds__(256, 1) void gemm_fast_kernel(GemmParams p) {
                         if (kFull || (row0 + gi * 32 + 8 * q + 4 * h + j < p.M && n0 + n * 32 + r < p.N)) {
                             uint8_t* dst = rowp + (int64_t)j * row_bytes + lane_off;
                             if constexpr (BF16)
-                                *reinterpret_cast<uint16_t*>(dst) = f32_to_bf16_rne(f[j]);
+                                DFP4_OUT_STORE(reinterpret_cast<uint16_t*>(dst), f32_to_bf16_rne(f[j]));
                             else
-                                *reinterpret_cast<float*>(dst) = f[j];
+                                DFP4_OUT_STORE(reinterpret_cast<float*>(dst), f[j]);
                         }
                     }
                 }
@@ -1009,7 +1039,8 @@ void set_prepared(GemmParams& p, uint8_t* a_prep, int64_t a_stride, uint8_t* w_p
     p.a_prep = a_prep; p.a_prep_stride = a_stride;
     p.w_prep = w_prep; p.w_prep_stride = w_stride;
     p.off_refa = la.off_refa; p.off_mask = la.off_mask; p.off_cnt = la.off_cnt; p.off_a8 = la.off_a8;
-    p.off_refw = lw.off_refw; p.off_spreadw = lw.off_spreadw; p.off_wmeta = lw.off_wmeta;
+    p.off_refw = lw.off_refw; p.off_wmask = lw.off_wmask; p.off_wmeta = lw.off_wmeta;
+    p.wmeta_cls_stride = (uint32_t)((int64_t)p.N * p.KB * 4);
 }
 
 // prepass: A workgroups (when do_a) and W workgroups (when do_w) in one launch
@@ -1017,9 +1048,7 @@ int launch_prep(bool mx, const GemmParams& p, bool do_a, bool do_w, int64_t batc
     const int64_t KB = p.KB;
     const int chunks_a = (int)((KB + 7) / 8);
     const int64_t n_a = do_a ? (int64_t)p.tiles_m * chunks_a : 0;
-    int segs = 1;
-    while (segs * 16 < KB) segs <<= 1;
-    const int64_t n_w = do_w ? (p.N + 16 * (64 / segs) - 1) / (16 * (64 / segs)) : 0;
+    const int64_t n_w = do_w ? (int64_t)p.tiles_n * ((KB + 63) / 64) : 0;
     if (n_a + n_w == 0) return DFP4_OK;
     if (n_a + n_w > 0x7fffffff || batch > 65535) return DFP4_ERR_SHAPE;
     dim3 gp((unsigned)(n_a + n_w), 1, (unsigned)batch);

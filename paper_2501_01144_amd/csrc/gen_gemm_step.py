@@ -25,7 +25,7 @@ One step = one pair of (block, class) visits = 32 MFMAs per wave:
   step from there (three LDS buffers in rotation, one barrier per step).
   The codes and table offsets come by global loads four steps ahead (three
   register sets in rotation).
-  The list of visits sits in LDS (uint16: class << 10 | block); the load offsets
+  The list of visits sits in LDS (uint16: block | class of A << 10 | class of W << 12); the load offsets
   of the next step are computed at the end of each step.
 
 The loop is unrolled three times (register sets); after every step the step
@@ -122,7 +122,7 @@ def expansion_pieces(cset):
 
 def a_offset(entry, dst):
     """byte offset of a visit's A fragments: class * class stride + block * 1 KiB + (tile, lane)"""
-    return [f"v_lshrrev_b32 {vr(T0)}, 10, {vr(entry)}",
+    return [f"v_bfe_u32 {vr(T0)}, {vr(entry)}, 10, 2",
             f"v_mul_lo_u32 {vr(T0)}, {vr(T0)}, %[cstr]",
             f"v_and_b32 {vr(T1)}, 0x3ff, {vr(entry)}",
             f"v_lshl_add_u32 {vr(T0)}, {vr(T1)}, 10, {vr(T0)}",
@@ -130,11 +130,15 @@ def a_offset(entry, dst):
 
 
 def w_offsets(entry, dst_codes, dst_meta):
-    """byte offsets of a visit's W codes and table offset (padding visits read the last block)"""
+    """byte offsets of a visit's W codes and of its table offset for the visit's class of W
+    (padding visits read the last block)"""
     return [f"v_and_b32 {vr(T1)}, 0x3ff, {vr(entry)}",
             f"v_min_u32 {vr(T1)}, %[kbm], {vr(T1)}",
             f"v_lshl_add_u32 {vr(dst_codes)}, {vr(T1)}, 4, %[wrc]",
-            f"v_lshl_add_u32 {vr(dst_meta)}, {vr(T1)}, 2, %[wrm]"]
+            f"v_lshl_add_u32 {vr(dst_meta)}, {vr(T1)}, 2, %[wrm]",
+            f"v_bfe_u32 {vr(T0)}, {vr(entry)}, 12, 2",
+            f"v_mul_lo_u32 {vr(T0)}, {vr(T0)}, %[wcs]",
+            f"v_add_u32 {vr(dst_meta)}, {vr(dst_meta)}, {vr(T0)}"]
 
 
 def a_loads(aset, voff):

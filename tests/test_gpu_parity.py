@@ -576,6 +576,44 @@ def test_gemm_prepared_declined_tiles_are_counted():
     assert dfp4.gemm_declined_tiles(pa) == 3              # the three column tiles of the second row tile
 
 
+@pytest.mark.parametrize("spread_a,spread_w,K,expect_declined", [
+    (0, 7, 1024, False), (7, 0, 1024, False), (3, 7, 1024, False),
+    (4, 4, 512, False),      # class 1 on both sides: visits of class sum 2, 16 blocks stay within the int32 bound
+    (4, 4, 1024, True),      # the same over 32 blocks could overflow int32 in the worst case
+    (7, 7, 1024, True), (0, 13, 1024, True)])
+def test_gemm_prepared_classes_on_both_operands(spread_a, spread_w, K, expect_declined):
+    # block exponents spread over `spread` binades along K on either operand: the exact path takes
+    # every pair (class of A, class of W) whose sum stays within the classes kept; beyond that the
+    # tile is computed block by block in fp32.  Either way the result meets the oracle.
+    M, N = 520, 260
+    g = torch.Generator().manual_seed(100 + 16 * spread_a + spread_w)
+    def operand(rows, spread, std):
+        x = torch.randn(rows, K, generator=g) * std
+        # every block max lands in the same binade, then a per-block power of two spreads them
+        x = x.view(rows, K // 32, 32)
+        x[:, :, 0] = 3.0 * std * torch.sign(x[:, :, 0] + 1e-9)
+        x = torch.clamp(x, -3.0 * std, 3.0 * std)
+        sh = torch.randint(0, spread + 1, (rows, K // 32, 1), generator=g)
+        sh[:, 0] = 0
+        sh[:, 1] = spread
+        return (x * torch.exp2(sh.float())).view(rows, K).to(torch.bfloat16)
+    a, w = operand(M, spread_a, 1.0), operand(N, spread_w, 0.02)
+    qa, qw = dfp4.quantize(_dev(a)), dfp4.quantize(_dev(w))
+    ea, ew = qa.exponent.int(), qw.exponent.int()
+    assert int((ea.max(dim=1).values - ea.min(dim=1).values).max()) == spread_a
+    assert int((ew.max(dim=1).values - ew.min(dim=1).values).max()) == spread_w
+    pa, pw = dfp4.gemm_prepare(qa, weight=False), dfp4.gemm_prepare(qw, weight=True)
+    out = dfp4.gemm_prepared(pa, pw)
+    torch.cuda.synchronize()
+    ref, absdot = _gemm_ref(synth.to_f64(a), synth.to_f64(w))
+    _assert_gemm_close(out, ref, absdot, f"spread A {spread_a} W {spread_w}")
+    assert (dfp4.gemm_declined_tiles(pa) > 0) == expect_declined
+    if not expect_declined:
+        # exact path: one rounding of the exact sum
+        got = out.cpu().double().numpy()
+        assert (np.abs(got - ref) <= np.abs(ref) * 2.0 ** -23 + 1e-300).all()
+
+
 def test_gemm_prepared_shared_activation_full_size():
     # LLaMA-3-8B gate and up projections on one prepared activation, then the down projection
     # (K split between workgroups), sampled outputs against the oracle
