@@ -91,6 +91,7 @@ struct QuantTables {
     uint8_t mx[64];
     uint8_t near_i[kDialects * 32];
     uint8_t near_u[kDialects * 32];
+    uint8_t vote1[kPairs * 32];          // vote of a single magnitude in pair p: +1 even dialect, -1 odd (int8)
 };
 
 constexpr QuantTables make_quant_tables() {
@@ -115,6 +116,9 @@ constexpr QuantTables make_quant_tables() {
             T.near_i[d * 32 + t] = (uint8_t)nearest_index(d, t);
             T.near_u[d * 32 + t] = kBook[d][nearest_index(d, t)];
         }
+    for (int p = 0; p < kPairs; ++p)
+        for (int t = 0; t < 32; ++t)
+            T.vote1[p * 32 + t] = (uint8_t)((in_range(2 * p, t) ? 1 : 0) - (in_range(2 * p + 1, t) ? 1 : 0));
     return T;
 }
 

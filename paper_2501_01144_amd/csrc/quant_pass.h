@@ -94,6 +94,41 @@ __device__ __forceinline__ void dfp4_pass(const uint4& wv, const uint8_t* __rest
     ebyte = (uint32_t)byte;
 }
 
+// The same with tables keyed by ONE 5-bit magnitude (768 bytes in all instead of 24 KiB: twice the
+// lookups, but a workgroup fills them with a single load): lut_i[d * 32 + t] = index of t under
+// dialect d, lut_v[p * 32 + t] = vote of t in pair p (+1 even dialect, -1 odd, as int8).
+__device__ __forceinline__ void dfp4_pass_small(const uint4& wv, const uint8_t* __restrict__ lut_v,
+                                                const uint8_t* __restrict__ lut_i, uint32_t& code,
+                                                uint32_t& ebyte, uint32_t& dial) {
+    const uint32_t w[4] = {wv.x, wv.y, wv.z, wv.w};
+    const uint32_t ab = block_amax_bits<false>(w);
+    const int byte = max((int)(ab >> 7) - 2, 0);
+    const int n = 129 - byte;
+    const uint32_t tmax = (uint32_t)ldexpf(as_f(ab << 16), n);
+    const uint32_t r = min(max((tmax + 1u) >> 1, 8u), 15u);
+    const uint32_t pair = 15u - r;
+    uint32_t t[8];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        t[2 * j] = (uint32_t)ldexpf(__builtin_fabsf(as_f(w[j] << 16)), n);
+        t[2 * j + 1] = (uint32_t)ldexpf(__builtin_fabsf(as_f(w[j])), n);
+    }
+    const int8_t* sv = reinterpret_cast<const int8_t*>(lut_v) + pair * 32u;
+    int votes = 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) votes += (int)sv[t[j]];
+    uint32_t v = (uint32_t)votes;
+    v += quad<0xB1>(v);
+    v += quad<0x4E>(v);
+    dial = 2u * pair + (v >> 31);
+    const uint8_t* q = lut_i + dial * 32u;
+    uint32_t c = 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) c |= (uint32_t)q[t[j]] << (4 * j);
+    code = c | sign_nibbles(w);
+    ebyte = (uint32_t)byte;
+}
+
 // One lane's share of one MXFP4 block: E2M1, round to nearest, ties to even code.
 __device__ __forceinline__ void mxfp4_pass(const uint4& wv, const uint8_t* __restrict__ lut_mx,
                                            uint32_t& code, uint32_t& ebyte) {
