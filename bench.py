@@ -446,7 +446,18 @@ def main():
             ms1 = median_ms(lambda: dfp4.gemm(qa1, qw1, out=o1), torch, 30, 5)
             b1 = gemm_bytes(m1, n1, k1)
             entry = {"ms": round(ms1, 4), "GBps": round(b1 / (ms1 * 1e-3) / 1e9, 1), "algorithmic_bytes": int(b1),
-                     "frac_hbm": round(b1 / (ms1 * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4), "kernel": "gemm_small_kernel"}
+                     "frac_hbm": round(b1 / (ms1 * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                     "kernel": "gemm_small_kernel (dfp4_gemm: per-block fp32 flush, nothing prepared)"}
+            # weights prepared offline, the activation prepared once: exact sums, no per-block floating point
+            pa1, pw1 = dfp4.gemm_prepare(qa1, weight=False), dfp4.gemm_prepare(qw1, weight=True)
+            ms1p = median_ms(lambda: dfp4.gemm_prepared(pa1, pw1, out=o1), torch, 30, 5)
+            ms1a = median_ms(lambda: dfp4.gemm_prepare(qa1, weight=False, buf=pa1.buf), torch, 30, 5)
+            b1p = b1 + n1 * (k1 // 32) * 4          # + one table dword per block of W
+            entry["prepared"] = {"ms": round(ms1p, 4), "GBps": round(b1p / (ms1p * 1e-3) / 1e9, 1),
+                                 "frac_hbm": round(b1p / (ms1p * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                                 "bytes": int(b1p), "prepare_a_ms": round(ms1a, 4),
+                                 "kernel": "gemm_rows_kernel (dfp4_gemm_prepared)"}
+            del pa1, pw1
             # the same on the block-scaled instruction (weights packed beforehand: 7 bits per element instead of 4.5)
             wp1, ap1 = dfp4.native_pack(qw1), dfp4.quantize_native(a1.to(dev))
             ms1n = median_ms(lambda: dfp4.gemm_native_packed(ap1, wp1, out=o1), torch, 30, 5)

@@ -191,13 +191,15 @@ size_t dfp4_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
  *                    many products consume it: gate and up projections share one)
  *   prepared         device, 256-byte aligned, at least dfp4_gemm_prepared_bytes(rows, K,
  *                    is_weight) bytes; the layout is private to the library.  A size of 0
- *                    means nothing is prepared for this operand (K > 16384, or an A with
- *                    at most 64 rows): NULL may be passed then.
+ *                    means nothing is prepared for this operand (K > 16384): NULL may be
+ *                    passed then.
  * dfp4_gemm_prepared multiplies.  The quantized tensors are still passed: paths that do not
  * use the prepared form read them.  a_prepared is written to (arrival counters of tiles
  * whose K is split between workgroups), so one prepared A serves one product at a time:
  * products on one stream are ordered by the stream, products that may overlap in time need
- * their own prepared copy.  Results are bit-identical to dfp4_gemm.
+ * their own prepared copy.  Results are bit-identical to dfp4_gemm, except for products with
+ * at most 64 rows of A: there dfp4_gemm adds one fp32 term per block, while the prepared
+ * form lets the few-rows kernel use the exact scheme too (one rounding of the exact sum).
  *   workspace   at least dfp4_gemm_prepared_workspace_bytes(M, N, K) bytes (partial tiles
  *               where K is split; 0 for products with many output tiles), 256-byte aligned
  * Limits: ceil(rows / 512) * (K/32 + 1) * 49152 < 2^31 for A, rows * K / 2 < 2^31 for W

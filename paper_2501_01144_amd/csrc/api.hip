@@ -239,7 +239,7 @@ static int gemm_prepared_common(bool mx, dfp4_tensor A, void* a_prepared, dfp4_t
     int rc = check_gemm_args(A, W, out, out_dtype, ldc, !mx, reinterpret_cast<void*>(uintptr_t{256}), ~(size_t)0);
     if (rc != DFP4_OK) return rc;
     if (A.rows == 0 || W.rows == 0) return DFP4_OK;
-    if (gemm_prepared_bytes(A.rows, A.K, false) > 0 && (!a_prepared || !w_prepared)) return DFP4_ERR_NULL;
+    if (gemm_prepared_bytes(A.rows, A.K, false) > 0 && (!a_prepared || !w_prepared)) return DFP4_ERR_NULL;   // K <= 16384
     if ((a_prepared && !aligned(a_prepared, 256)) || (w_prepared && !aligned(w_prepared, 256))) return DFP4_ERR_ALIGN;
     const size_t need = gemm_prepared_workspace_bytes(A.rows, W.rows, A.K);
     if (need > 0) {

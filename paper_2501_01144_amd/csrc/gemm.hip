@@ -872,16 +872,21 @@ constexpr int kSmallMaxKB = 512;      // LDS holds the 32 rows' exponent bytes o
 constexpr int kSmallMaxM = 64;
 static_assert(kSmallMaxM == 64 && kSmallMaxKB == 512, "takes_small_kernel() states these limits");
 
+struct SmallTileLds {
+    __attribute__((aligned(16))) uint32_t tab[kDialects * 4];   // shift-0 tables
+    __attribute__((aligned(4))) uint8_t ea[kSmallMaxKB * 32];   // [block][row] exponent bytes of A
+    float red[kSmallWaves / 2][16][64];
+};
+
+// One 32 x 32 output tile by a workgroup of 16 waves, one fp32 scale-and-add per block.
 template <bool MX, bool BF16>
-__global__ __launch_bounds__(kSmallWaves * 64) void gemm_small_kernel(GemmParams p) {
-    __shared__ __attribute__((aligned(16))) uint32_t s_tab[kDialects * 4];   // shift-0 tables
-    __shared__ __attribute__((aligned(4))) uint8_t s_ea[kSmallMaxKB * 32];   // [block][row] exponent bytes of A
-    __shared__ float s_red[kSmallWaves / 2][16][64];
+__device__ __forceinline__ void small_tile(const GemmParams& p, int64_t bz, int m0, int n0, SmallTileLds& lds) {
+    uint32_t (&s_tab)[kDialects * 4] = lds.tab;
+    uint8_t (&s_ea)[kSmallMaxKB * 32] = lds.ea;
+    float (&s_red)[kSmallWaves / 2][16][64] = lds.red;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int h = lane >> 5, r = lane & 31;
     const int KB = p.KB;
-    const int64_t bz = blockIdx.z;
-    const int m0 = blockIdx.y * 32, n0 = blockIdx.x * 32;
     const int64_t a_row0 = bz * p.strideA_rows, w_row0 = bz * p.strideW_rows;
 
     const int64_t arow = a_row0 + min(m0 + r, p.M - 1), wrow = w_row0 + min(n0 + r, p.N - 1);
@@ -961,6 +966,165 @@ __global__ __launch_bounds__(kSmallWaves * 64) void gemm_small_kernel(GemmParams
     }
 }
 
+template <bool MX, bool BF16>
+__global__ __launch_bounds__(kSmallWaves * 64) void gemm_small_kernel(GemmParams p) {
+    __shared__ SmallTileLds lds;
+    small_tile<MX, BF16>(p, blockIdx.z, (int)blockIdx.y * 32, (int)blockIdx.x * 32, lds);
+}
+
+// ---------------------------------------------------------------------------
+// Few rows of A on PREPARED operands (decode shapes with weights prepared offline): the exact
+// scheme of the large kernel -- exponent offsets folded into the int8 operands, classes handled by
+// shifting the int32 accumulators, one conversion at the end -- in the shape of the few-rows kernel:
+// a workgroup of 16 waves owns 32 rows of A x 32 rows of W, the waves share the list of (block,
+// class of A, class of W) visits in equal slices, each expands the 4-bit codes of W for its visits
+// (A comes expanded from the prepared form, which is small and stays in cache), and the 16 exact
+// int32 partial tiles are added through LDS.  No per-block floating-point work at all, so the
+// kernel follows the stream of W.  A tile the scheme cannot take is computed by small_tile().
+// ---------------------------------------------------------------------------
+template <bool MX, bool BF16>
+__global__ __launch_bounds__(kSmallWaves * 64) void gemm_rows_kernel(GemmParams p) {
+    __shared__ __attribute__((aligned(16))) uint32_t s_tab[kDialects * 16 + 4];
+    __shared__ uint16_t s_vl[kVisitCap];
+    __shared__ int s_ctl[8];
+    __shared__ union {
+        int red[kSmallWaves / 2][16][64];
+        SmallTileLds small;
+    } u;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int h = lane >> 5, r = lane & 31;
+    const int KB = p.KB;
+    const int m0 = blockIdx.y * 32, n0 = blockIdx.x * 32;
+    const uint8_t* ap = p.a_prep;
+    const uint8_t* wp = p.w_prep;
+
+    for (int i = tid; i < kDialects * 16 + 4; i += kSmallWaves * 64)
+        s_tab[i] = i < kDialects * 16 ? (&g_shifted_book.w[0][0][0])[i] : 0u;
+    if (tid < 8) s_ctl[tid] = 0;
+    if (wave == 0) {
+        // visits of all of K, ordered by class sum (see gemm_fast_kernel); the masks are those of the
+        // 512-row tile of A and the 128-row tile of W these rows belong to
+        const uint8_t* mask_a = ap + p.off_mask + (int64_t)(m0 / kTileM) * KB;
+        const uint8_t* mask_w = wp + p.off_wmask + (int64_t)(n0 / kTileN) * KB;
+        uint32_t ma[kMaxKB / 64], mw[kMaxKB / 64];
+        bool bad = false;
+#pragma unroll
+        for (int j = 0; j < kMaxKB / 64; ++j) {
+            const int kb = j * 64 + lane;
+            ma[j] = kb < KB ? mask_a[kb] : 0u;
+            mw[j] = kb < KB ? mask_w[kb] : 0u;
+            const int ha = 31 - __builtin_clz(ma[j] | 1u), hw = 31 - __builtin_clz(mw[j] | 1u);
+            bad |= ha + hw > kMaxClass;
+        }
+        int pos = 0, weight = 0;
+        for (int ct = kMaxClass; ct >= 0; --ct) {
+            for (int ca = 0; ca <= ct; ++ca) {
+                const int cw = ct - ca;
+#pragma unroll
+                for (int j = 0; j < kMaxKB / 64; ++j) {
+                    if (j * 64 >= KB) break;                          // uniform
+                    const int kb = j * 64 + lane;
+                    const bool f = ((ma[j] >> ca) & 1u) && ((mw[j] >> cw) & 1u);
+                    const unsigned long long bal = __ballot(f);
+                    weight += __popcll(bal) << (4 * ct);
+                    if (f) s_vl[pos + __popcll(bal & ((1ull << lane) - 1ull))] = (uint16_t)(kb | (ca << 10) | (cw << 12));
+                    pos += __popcll(bal);
+                }
+            }
+            if (pos & 1) {
+                if (lane == 0) s_vl[pos] = (uint16_t)KB;              // padding: the all-zero block of class 0
+                pos += 1;
+            }
+            if (lane == 0) s_ctl[kMaxClass - ct] = pos;               // ends of class sums 2, 1, 0
+        }
+        if ((__ballot(bad) != 0ull || weight > kIntBound) && lane == 0) s_ctl[4] = 1;
+    }
+    __syncthreads();
+    if (s_ctl[4] != 0) {
+        if (tid == 0 && blockIdx.x % (kTileN / 32) == 0)   // counted once per 512 x 128 tile, like the large kernel
+            atomicAdd(reinterpret_cast<uint32_t*>(const_cast<uint8_t*>(ap) + p.off_cnt) + kMaxSplitTiles, 1u);
+        small_tile<MX, BF16>(p, 0, m0, n0, u.small);
+        return;
+    }
+    // this wave's slice of the steps (a step = two visits of the same class sum)
+    const int end2 = s_ctl[0] / 2, end1 = s_ctl[1] / 2, total = s_ctl[2] / 2;
+    const int per = (total + kSmallWaves - 1) / kSmallWaves;
+    const int s_lo = min(total, wave * per), s_hi = min(total, s_lo + per);
+
+    const uint32_t grp_stride = (uint32_t)(KB + 1) * 1024u;
+    const uint32_t cls_stride = (uint32_t)p.tiles_m * kGroups * grp_stride;
+    const uint8_t* a8 = ap + p.off_a8 + (uint64_t)(m0 / 32) * grp_stride + (uint32_t)r * 16u;
+    const int ncol = min(n0 + r, p.N - 1);
+    const uint8_t* wcodes = p.w_codes + (uint64_t)ncol * KB * 16u;
+    const uint8_t* wmeta = wp + p.off_wmeta + (uint64_t)ncol * KB * 4u;
+
+    v16i acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+    constexpr int kU = 4;                              // steps whose loads are issued together
+    for (int s0 = s_lo; s0 < s_hi; s0 += kU) {
+        uint4 wc[kU];
+        uint32_t meta[kU];
+        v4i af[kU][2];
+#pragma unroll
+        for (int q = 0; q < kU; ++q) {
+            const int st = min(s0 + q, s_hi - 1);      // the tail repeats the last step (not used)
+            const uint32_t entry = s_vl[2 * st + h];
+            const uint32_t kb = entry & 1023u, kbw = min(kb, (uint32_t)KB - 1u);
+            wc[q] = *reinterpret_cast<const uint4*>(wcodes + kbw * 16u);
+            meta[q] = *reinterpret_cast<const uint32_t*>(wmeta + ((entry >> 12) & 3u) * (uint64_t)p.wmeta_cls_stride + kbw * 4u);
+            const uint8_t* af_src = a8 + ((entry >> 10) & 3u) * (uint64_t)cls_stride + kb * 1024u;
+            af[q][0] = *reinterpret_cast<const v4i*>(af_src);
+            af[q][1] = *reinterpret_cast<const v4i*>(af_src + 512);
+        }
+#pragma unroll
+        for (int q = 0; q < kU; ++q) {
+            const int st = s0 + q;
+            if (st >= s_hi) break;                     // wave-uniform
+            // between class sums the accumulators move up by four bits (Horner's scheme)
+            const int levels = (st == end2 ? 1 : 0) + (st == end1 ? 1 : 0);      // both when a class sum is absent
+            if (levels != 0 && st != s_lo) {
+#pragma unroll
+                for (int x = 0; x < 16; ++x) acc[x] <<= 4 * levels;
+            }
+            const uint4 tab = *reinterpret_cast<const uint4*>(reinterpret_cast<const uint8_t*>(s_tab) + meta[q]);
+            const v4i b0 = unpack16(wc[q].x, wc[q].y, tab), b1 = unpack16(wc[q].z, wc[q].w, tab);
+            acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[q][0], b0, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[q][1], b1, acc, 0, 0, 0);
+        }
+    }
+    // bring the slice's sum to the weight of class sum 0: one shift per class boundary at or after its end
+    if (s_hi > s_lo) {
+        const int shifts = (s_hi <= end2 ? 1 : 0) + (s_hi <= end1 ? 1 : 0);
+#pragma unroll
+        for (int x = 0; x < 16; ++x) acc[x] <<= 4 * shifts;
+    }
+    // the 16 exact partial tiles: waves 8..15 hand theirs to waves 0..7, then thread (x, lane) finishes one output
+    if (wave >= kSmallWaves / 2) {
+#pragma unroll
+        for (int x = 0; x < 16; ++x) u.red[wave - kSmallWaves / 2][x][lane] = acc[x];
+    }
+    __syncthreads();
+    if (wave < kSmallWaves / 2) {
+#pragma unroll
+        for (int x = 0; x < 16; ++x) u.red[wave][x][lane] += acc[x];
+    }
+    __syncthreads();
+    {
+        const int x = wave;
+        int sum = 0;
+#pragma unroll
+        for (int w = 0; w < kSmallWaves / 2; ++w) sum += u.red[w][x][lane];
+        const int m = m0 + 8 * (x >> 2) + 4 * h + (x & 3), n = n0 + r;
+        if (m < p.M && n < p.N) {
+            const float f = ldexpf((float)sum, (int)ap[p.off_refa + m] + (int)wp[p.off_refw + n] - 256);
+            const int64_t o = (int64_t)m * p.ldc + n;
+            if constexpr (BF16)
+                static_cast<uint16_t*>(p.out)[o] = f32_to_bf16_rne(f);
+            else
+                static_cast<float*>(p.out)[o] = f;
+        }
+    }
+}
+
 // Whole product through the per-block flush (K beyond the single-accumulator kernel's limit).
 template <bool MX, bool BF16>
 __global__ __launch_bounds__(256) void gemm_block_kernel(GemmParams p) {
@@ -982,7 +1146,6 @@ static int64_t max_rows_w(int64_t KB) { return ((((int64_t)1 << 31) - 1) / (KB *
 size_t gemm_prepared_bytes(int64_t rows, int64_t K, bool weight) {
     const int64_t KB = K / kBlock;
     if (rows <= 0 || KB <= 0 || KB > kMaxKB) return 0;
-    if (!weight && takes_small_kernel(rows, KB)) return 0;
     return (size_t)(weight ? prep_w_layout(rows, KB).total : prep_a_layout(rows, KB).total);
 }
 
@@ -1195,9 +1358,18 @@ int launch_gemm_prepared(bool mx, dfp4_tensor A, void* a_prepared, dfp4_tensor W
     const bool bf16 = out_dtype == DFP4_BF16;
     GemmParams p{};
     fill_params(p, A, W, out, ldc, 0, 0, 0, nullptr);
-    if (!takes_fast_kernel(M, KB)) return launch_other(mx, bf16, p, 1, nullptr, stream);
+    if (KB == 0 || KB > kMaxKB) return launch_other(mx, bf16, p, 1, nullptr, stream);
     if (M > max_rows_a(KB) || N > max_rows_w(KB)) return DFP4_ERR_SHAPE;
     set_prepared(p, static_cast<uint8_t*>(a_prepared), 0, static_cast<uint8_t*>(const_cast<void*>(w_prepared)), 0);
+    if (takes_small_kernel(M, KB)) {
+        // few rows: the exact scheme in the shape of the few-rows kernel
+        dim3 gs((unsigned)((N + 31) / 32), (unsigned)((M + 31) / 32), 1);
+        dispatch_mx_bf16(mx, bf16, [&](auto mxc, auto bc) {
+            hipLaunchKernelGGL((gemm_rows_kernel<decltype(mxc)::value, decltype(bc)::value>), gs,
+                               dim3(kSmallWaves * 64), 0, stream, p);
+        });
+        return check_launch();
+    }
     return launch_fast(mx, bf16, p, 1, static_cast<int*>(workspace), workspace_bytes, false, stream);
 }
 

@@ -529,7 +529,7 @@ def test_quantize_transposed_strided_input_and_pv_product():
 # GEMM on operands prepared ahead (dfp4_gemm_prepare / dfp4_gemm_prepared)
 # --------------------------------------------------------------------------
 @pytest.mark.parametrize("M,N,K,why", [(600, 352, 512, "whole tiles"), (100, 256, 4096, "split K"),
-                                       (2048, 1024, 2048, "many tiles"), (33, 100, 4096, "few rows: nothing prepared"),
+                                       (2048, 1024, 2048, "many tiles"), (33, 100, 4096, "few rows"),
                                        (70, 200, 160, "ragged")])
 def test_gemm_prepared_matches_oracle_and_gemm(M, N, K, why):
     print(f"gemm_prepared parity: {why} {M}x{N}x{K}", flush=True)
@@ -544,7 +544,12 @@ def test_gemm_prepared_matches_oracle_and_gemm(M, N, K, why):
         out = dfp4.gemm_prepared(pa, pw)
         torch.cuda.synchronize()
         _assert_gemm_close(out, ref, absdot, f"prepared {why} rep {rep}")
-        assert torch.equal(out.view(torch.int32), want.view(torch.int32)), "prepared and plain GEMM differ"
+        if M > 64:
+            assert torch.equal(out.view(torch.int32), want.view(torch.int32)), "prepared and plain GEMM differ"
+        else:
+            # few rows: the prepared form takes the exact scheme (one rounding of the exact sum),
+            # the plain call adds one fp32 term per block
+            assert (np.abs(out.cpu().double().numpy() - ref) <= np.abs(ref) * 2.0 ** -23 + 1e-300).all()
     outb = dfp4.gemm_prepared(pa, pw, dtype=torch.bfloat16)
     torch.cuda.synchronize()
     _assert_gemm_close(outb, ref, absdot, f"prepared {why} bf16", bf16=True)
@@ -555,6 +560,52 @@ def test_gemm_prepared_matches_oracle_and_gemm(M, N, K, why):
     torch.cuda.synchronize()
     refm, absm = _gemm_ref(synth.to_f64(a), synth.to_f64(w), mx=True)
     _assert_gemm_close(outm, refm, absm, f"prepared mxfp4 {why}")
+
+
+@pytest.mark.parametrize("M,N,K", [(1, 1, 32), (5, 40, 64), (33, 100, 4096), (64, 96, 256), (32, 4096, 4096),
+                                   (16, 14336, 4096), (16, 4096, 14336)])
+def test_gemm_prepared_few_rows(M, N, K):
+    # decode shapes on prepared operands: the few-rows kernel with exact int32 sums
+    print(f"gemm_prepared parity: few rows {M}x{N}x{K}", flush=True)
+    a = synth.gaussian_outlier_channels(M, K, max(1, K // 200), 50.0, 1.0, seed=700 + M)
+    w = synth.gaussian(N, K, 0.02, seed=800 + N)
+    qa, qw = dfp4.quantize(_dev(a)), dfp4.quantize(_dev(w))
+    pa, pw = dfp4.gemm_prepare(qa, weight=False), dfp4.gemm_prepare(qw, weight=True)
+    ref, absdot = _gemm_ref(synth.to_f64(a), synth.to_f64(w))
+    for dtype in (torch.float32, torch.bfloat16):
+        out = dfp4.gemm_prepared(pa, pw, dtype=dtype)
+        torch.cuda.synchronize()
+        _assert_gemm_close(out, ref, absdot, f"few rows prepared {dtype}", bf16=dtype == torch.bfloat16)
+        if dtype == torch.float32:
+            assert (np.abs(out.cpu().double().numpy() - ref) <= np.abs(ref) * 2.0 ** -23 + 1e-300).all()
+    assert dfp4.gemm_declined_tiles(pa) == 0
+    qam, qwm = dfp4.mxfp4_quantize(_dev(a)), dfp4.mxfp4_quantize(_dev(w))
+    outm = dfp4.gemm_prepared(dfp4.gemm_prepare(qam, weight=False, mx=True), dfp4.gemm_prepare(qwm, weight=True, mx=True))
+    torch.cuda.synchronize()
+    refm, absm = _gemm_ref(synth.to_f64(a), synth.to_f64(w), mx=True)
+    _assert_gemm_close(outm, refm, absm, "few rows prepared mxfp4")
+
+
+def test_gemm_prepared_few_rows_wide_exponents():
+    # classes on both operands, absent class sums, and spreads the exact scheme declines
+    # (spreads are those of the drawn powers of two; block maxima of Gaussian data add about one binade)
+    for case, (sa, sw) in enumerate([(5, 2), (9, 0), (0, 9), (30, 30)]):
+        g = torch.Generator().manual_seed(900 + case)
+        M, N, K = 40, 200, 512           # 16 blocks: class sum 2 in every block stays within the int32 bound
+        def operand(rows, spread, std):
+            x = torch.randn(rows, K, generator=g) * std
+            sh = torch.randint(0, spread + 1, (rows, K // 32, 1), generator=g)
+            if case == 1 or case == 2:
+                sh = torch.where(sh >= 4, torch.full_like(sh, 9), torch.zeros_like(sh))    # classes 0 and 2 only
+            return (x.view(rows, K // 32, 32) * torch.exp2(sh.float())).view(rows, K).to(torch.bfloat16)
+        a, w = operand(M, sa, 1.0), operand(N, sw, 0.02)
+        qa, qw = dfp4.quantize(_dev(a)), dfp4.quantize(_dev(w))
+        pa, pw = dfp4.gemm_prepare(qa, weight=False), dfp4.gemm_prepare(qw, weight=True)
+        out = dfp4.gemm_prepared(pa, pw)
+        torch.cuda.synchronize()
+        ref, absdot = _gemm_ref(synth.to_f64(a), synth.to_f64(w))
+        _assert_gemm_close(out, ref, absdot, f"few rows prepared, spreads {sa}/{sw}")
+        assert (dfp4.gemm_declined_tiles(pa) > 0) == (case == 3)
 
 
 def test_gemm_prepared_declined_tiles_are_counted():
