@@ -34,7 +34,7 @@ HBM_PEAK_GBPS = 8000.0
 INT8_PEAK_TOPS = 5000.0
 FP6_PEAK_TOPS = 10100.0
 ALL_SECTIONS = ["step", "mx", "native", "few_rows", "stream", "llama2", "attention", "dequant", "cpu"]
-TRAFFIC_FILE = os.path.join("profiles", "bench_mlp_prefill_hbm_traffic.txt")
+TRAFFIC_FILE = os.path.join("profiles", "bench_hbm_traffic.txt")
 
 
 def _events(n, torch):
