@@ -33,6 +33,11 @@ Parity status of each function against something other than itself:
                                     (lowest id) is a reading the paper does not fix
   dfp4_quantize_block64 ........... pinned (the exhaustive per-block search run on
                                     64-element blocks)
+  dfp4_quantize_block16,
+  dfp4_dequantize_block,
+  dfp4_gemm_blocks ................ pinned (the exhaustive per-block search run on
+                                    16-element blocks; exact-rational product of the
+                                    brute force's own dequantization)
   round_to_bf16, dfp4_gemm_requant  pinned (library bf16 conversion; a hand-worked block
                                     whose products sit on and just below a bf16 midpoint,
                                     so that dropping the bf16 step or rounding in one

@@ -191,6 +191,51 @@ def dfp4_quantize_block64(x, chunk_blocks=1 << 14):
             np.repeat(exponent.reshape(rows, K // 64), 2, axis=1))
 
 
+def dfp4_quantize_block16(x, chunk_blocks=1 << 15):
+    """DialectFP4 with blocks of 16 (Section 4.2, Table 3 varies the block size; smaller blocks
+    for the sublayers most sensitive to quantization): the same steps on 16 consecutive elements.
+    Returned with one exponent byte and one dialect id per 16 elements:
+    codes [rows, K/2], dialect [rows, K/16], exponent [rows, K/16]."""
+    x = np.asarray(x, dtype=np.float64)
+    assert x.ndim == 2 and x.shape[1] % 16 == 0
+    assert np.isfinite(x).all()
+    rows, K = x.shape
+    nb = rows * (K // 16)
+    xb = x.reshape(nb, 16)
+    index = np.empty((nb, 16), dtype=np.uint8)
+    dialect = np.empty(nb, dtype=np.uint8)
+    exponent = np.empty(nb, dtype=np.uint8)
+    for b0 in range(0, nb, chunk_blocks):
+        mag = np.abs(xb[b0:b0 + chunk_blocks])
+        e = shared_exponent(mag.max(axis=1))
+        s = np.ldexp(mag, (-e)[:, None].astype(np.int32))
+        d = select_dialect(s)
+        index[b0:b0 + chunk_blocks] = nearest_index(s, d)
+        dialect[b0:b0 + chunk_blocks] = d
+        exponent[b0:b0 + chunk_blocks] = e + EXP_BIAS
+    codes = pack_codes(np.signbit(xb), index).reshape(rows, K // 2)
+    return codes, dialect.reshape(rows, K // 16), exponent.reshape(rows, K // 16)
+
+
+def dfp4_dequantize_block(codes, dialect, exponent, block):
+    """Section 3.3 dequantization for a tensor whose dialect / exponent arrays hold one entry per
+    `block` elements (16 or 32; blocks of 64 are stored in the 32-element layout)."""
+    assert block in (16, 32)
+    rows = codes.shape[0]
+    nib = unpack_codes(codes).reshape(rows, -1, block)
+    u = np.take_along_axis(FORMATBOOK_HALF_UNITS[dialect.astype(np.int64)],
+                           (nib & 7).astype(np.int64), axis=2)
+    mag = np.ldexp(0.5 * u.astype(np.float64),
+                   (exponent.astype(np.int32) - EXP_BIAS)[:, :, None])
+    return np.where((nib >> 3) == 1, -mag, mag).reshape(rows, -1)
+
+
+def dfp4_gemm_blocks(a_q, block_a, w_q, block_w):
+    """The block MAC of Section 3.3 for operands quantized with different block sizes (per-sublayer
+    block-size mixes of Table 3): the sum over K of the dequantized values, in float64."""
+    return dfp4_dequantize_block(*a_q, block_a) @ dfp4_dequantize_block(*w_q, block_w).T
+
+
 def select_dialect_mse(s):
     """Dialect with the smallest squared error (Section 3.2: for weights, known in
     advance, the best dialect of a block can be found by computing the exact mean

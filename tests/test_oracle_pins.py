@@ -573,3 +573,52 @@ def test_block64_output_reads_as_the_32_element_format():
     assert np.array_equal(deq[0, :32], np.full(32, 6.5)) and np.array_equal(deq[0, 32:], np.full(32, 0.5))
     c32, d32, e32 = O.dfp4_quantize(x)
     assert int(e32[0, 1]) < 127            # with blocks of 32 the second half gets its own, smaller exponent
+
+
+# --------------------------------------------------------------------------
+# blocks of 16
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("kind", ["gauss", "outlier", "wide", "grid"])
+def test_block16_vs_exact_brute_force(kind):
+    rng = np.random.default_rng({"gauss": 61, "outlier": 63, "wide": 64, "grid": 65}[kind])
+    x = _random_blocks(rng, 48, kind).reshape(96, 16)               # 96 blocks of 16, one per row
+    codes, dialect, expo = O.dfp4_quantize_block16(x)
+    assert codes.shape == (96, 8) and dialect.shape == (96, 1) and expo.shape == (96, 1)
+    nib = _nibbles(codes)
+    for b in range(x.shape[0]):
+        e, d, idx = BF.quantize_block([Fraction(v) for v in x[b]], BOOK_FR)     # exhaustive, any block length
+        assert int(expo[b, 0]) - 127 == e and int(dialect[b, 0]) == d, (kind, b)
+        assert [int(v) & 7 for v in nib[b]] == idx, (kind, b)
+        assert [int(v) >> 3 for v in nib[b]] == [1 if np.signbit(v) else 0 for v in x[b]]
+
+
+def test_block16_layout_dequantization_and_mixed_block_product():
+    rng = np.random.default_rng(66)
+    a = _random_blocks(rng, 3 * 4, "outlier").reshape(3, 128)
+    w = _bf16(rng.standard_normal((5, 128)) * 0.02)
+    a16, w32 = O.dfp4_quantize_block16(a), O.dfp4_quantize(w)
+    assert a16[1].shape == (3, 8) and a16[2].shape == (3, 8)
+    # a row quantized in blocks of 16 equals its 16-element pieces quantized one by one
+    for r in range(3):
+        for b in range(8):
+            one = O.dfp4_quantize_block16(a[r:r + 1, 16 * b:16 * b + 16])
+            assert np.array_equal(one[0][0], a16[0][r, 8 * b:8 * b + 8])
+            assert one[1][0, 0] == a16[1][r, b] and one[2][0, 0] == a16[2][r, b]
+    # dequantization: every value is in its own 16-block's dialect, scaled by that block's exponent
+    deq = O.dfp4_dequantize_block(*a16, 16)
+    for r in range(3):
+        for b in range(8):
+            vals = set(np.ldexp(O.FORMATBOOK[a16[1][r, b]], int(a16[2][r, b]) - 127))
+            assert all(abs(v) in vals for v in deq[r, 16 * b:16 * b + 16])
+    # smaller blocks never quantize worse than the blocks of 32 that contain them (same data, finer exponents)
+    err16 = np.abs(deq - a).sum()
+    err32 = np.abs(O.dfp4_dequantize(*O.dfp4_quantize(a)) - a).sum()
+    assert err16 <= err32
+    # the mixed-block product against exact rationals
+    prod = O.dfp4_gemm_blocks(a16, 16, w32, 32)
+    wd = O.dfp4_dequantize(*w32)
+    for r in range(3):
+        for c in range(5):
+            exact = sum(Fraction(float(x)) * Fraction(float(y)) for x, y in zip(deq[r], wd[c]))
+            assert Fraction(float(prod[r, c])) == exact
+    assert np.array_equal(O.dfp4_dequantize_block(*w32, 32), wd)
