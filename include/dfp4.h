@@ -99,6 +99,26 @@ int dfp4_quantize_b64(const void* x_bf16, int64_t rows, int64_t K, int64_t ld_el
                       dfp4_tensor out, void* stream);
 
 /*
+ * Block size as an argument (Section 4.2, Table 3: blocks of 16, 32 or 64, and smaller blocks for
+ * only the sublayers most sensitive to quantization, so that operands of one model -- and the
+ * two operands of one product -- may use different sizes).  block_size is 16, 32 or 64.
+ *   32   as dfp4_quantize / dfp4_dequantize / dfp4_gemm
+ *   64   as dfp4_quantize_b64: stored in the 32-element layout (K a multiple of 64)
+ *   16   one shared exponent and one dialect per 16 consecutive elements, chosen by the same
+ *        steps from those 16: the tensor's dialect and exponent arrays are [rows, K/16]
+ *        (codes unchanged); K must still be a multiple of 32
+ * dfp4_gemm_blocks multiplies operands of any two block sizes.  Where either is 16 the product is
+ * computed as the paper's MAC states it, one fp32 scale-and-add per pair of 16-element blocks
+ * (the exact single-accumulator path needs one exponent per 32 elements; this path runs at about a
+ * tenth of its rate and needs no workspace); otherwise the call is dfp4_gemm.
+ */
+int dfp4_quantize_block(const void* x_bf16, int64_t rows, int64_t K, int64_t ld_elems, int block_size,
+                        dfp4_tensor out, void* stream);
+int dfp4_dequantize_block(dfp4_tensor in, int block_size, void* y, int y_dtype, int64_t ld_elems, void* stream);
+int dfp4_gemm_blocks(dfp4_tensor A, int block_a, dfp4_tensor W, int block_w, void* out, int out_dtype,
+                     int64_t ldc, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Transposing quantizers (Appendix C: every operand is blocked along the dimension
  * it is multiplied over): x [rows, cols] row-major (leading dimension ld_elems) is
  * quantized in blocks of 32 along its ROWS; `out` is the quantized transpose,

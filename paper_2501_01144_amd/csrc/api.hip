@@ -134,6 +134,35 @@ int dfp4_quantize_b64(const void* x_bf16, int64_t rows, int64_t K, int64_t ld_el
     return launch_quantize(false, x_bf16, rows, K, ld_elems, out, static_cast<hipStream_t>(stream), true);
 }
 
+static bool block_size_ok(int b) { return b == 16 || b == 32 || b == 64; }
+
+int dfp4_quantize_block(const void* x_bf16, int64_t rows, int64_t K, int64_t ld_elems, int block_size, dfp4_tensor out,
+                        void* stream) {
+    if (!block_size_ok(block_size) || (block_size == 64 && K % 64 != 0)) return DFP4_ERR_SHAPE;
+    const int rc = check_quant_args(x_bf16, rows, K, ld_elems, out, true);
+    if (rc != DFP4_OK) return rc;
+    return launch_quantize(false, x_bf16, rows, K, ld_elems, out, static_cast<hipStream_t>(stream), block_size == 64,
+                           block_size == 16);
+}
+
+int dfp4_dequantize_block(dfp4_tensor in, int block_size, void* y, int y_dtype, int64_t ld_elems, void* stream) {
+    if (!block_size_ok(block_size)) return DFP4_ERR_SHAPE;
+    if (y_dtype != DFP4_F32 && y_dtype != DFP4_BF16) return DFP4_ERR_DTYPE;
+    const int rc = check_quant_args(y, in.rows, in.K, ld_elems, in, true);
+    if (rc != DFP4_OK) return rc;
+    return launch_dequantize(false, in, y, y_dtype, ld_elems, static_cast<hipStream_t>(stream), block_size == 16);
+}
+
+int dfp4_gemm_blocks(dfp4_tensor A, int block_a, dfp4_tensor W, int block_w, void* out, int out_dtype, int64_t ldc,
+                     void* workspace, size_t workspace_bytes, void* stream) {
+    if (!block_size_ok(block_a) || !block_size_ok(block_w)) return DFP4_ERR_SHAPE;
+    if (block_a != 16 && block_w != 16)               // blocks of 32 and 64 share the 32-element layout
+        return dfp4_gemm(A, W, out, out_dtype, ldc, workspace, workspace_bytes, stream);
+    const int rc = check_gemm_args(A, W, out, out_dtype, ldc, true, reinterpret_cast<void*>(uintptr_t{256}), ~(size_t)0);
+    if (rc != DFP4_OK) return rc;
+    return launch_gemm_block16(A, block_a == 16, W, block_w == 16, out, out_dtype, ldc, static_cast<hipStream_t>(stream));
+}
+
 int mxfp4_quantize(const void* x_bf16, int64_t rows, int64_t K, int64_t ld_elems, dfp4_tensor out,
                    void* stream) {
     const int rc = check_quant_args(x_bf16, rows, K, ld_elems, out, false);

@@ -22,14 +22,16 @@ int check_quant_args(const void* dense, int64_t rows, int64_t K, int64_t ld, con
 
 // kernels (defined in the .hip files)
 int launch_quantize(bool mx, const void* x, int64_t rows, int64_t K, int64_t ld, dfp4_tensor out,
-                    hipStream_t stream, bool wide = false);
+                    hipStream_t stream, bool wide = false, bool narrow = false);
 int launch_quantize_t(bool mx, const void* x, int64_t rows, int64_t cols, int64_t ld, dfp4_tensor out,
                       int64_t row_offset, hipStream_t stream);
 int launch_quantize_native(const void* x, int64_t rows, int64_t K, int64_t ld, void* packed, size_t sc_offset,
                            hipStream_t stream);
 size_t native_scale_offset(int64_t rows, int64_t K, bool fp6);
 int launch_quantize_mse(const void* x, int64_t rows, int64_t K, int64_t ld, dfp4_tensor out, hipStream_t stream);
-int launch_dequantize(bool mx, dfp4_tensor in, void* y, int y_dtype, int64_t ld, hipStream_t stream);
+int launch_dequantize(bool mx, dfp4_tensor in, void* y, int y_dtype, int64_t ld, hipStream_t stream, bool narrow = false);
+int launch_gemm_block16(dfp4_tensor A, bool a16, dfp4_tensor W, bool w16, void* out, int out_dtype, int64_t ldc,
+                        hipStream_t stream);
 int launch_gemm(bool mx, dfp4_tensor A, dfp4_tensor W, void* out, int out_dtype, int64_t ldc,
                 int64_t batch, int64_t strideA_rows, int64_t strideW_rows, int64_t strideC,
                 void* workspace, size_t workspace_bytes, hipStream_t stream, const dfp4_tensor* rq = nullptr);

@@ -32,14 +32,15 @@ template <bool MX, bool BF16, bool CONTIG>
 __global__ __launch_bounds__(kThreads) void dequantize_kernel(
     const uint32_t* __restrict__ codes, const uint8_t* __restrict__ dialect,
     const uint8_t* __restrict__ exponent, void* __restrict__ y, int64_t ld, uint32_t blocks_per_row,
-    uint32_t nblocks) {
+    uint32_t nblocks, uint32_t narrow /* 1: one exponent byte and dialect id per 16 elements */) {
     const uint64_t nlanes = (uint64_t)nblocks * 4u;
     const uint64_t stride = (uint64_t)gridDim.x * kThreads;
     for (uint64_t g = (uint64_t)blockIdx.x * kThreads + threadIdx.x; g < nlanes; g += stride) {
         const uint32_t b = (uint32_t)(g >> 2), sub = (uint32_t)(g & 3u);
         const uint32_t c = codes[g];
-        const int e = (int)exponent[b] - 128;              // 0.5 u 2^(byte-127) = u 2^(byte-128)
-        const uint32_t d = MX ? 7u : ((uint32_t)dialect[b] & 15u);
+        const size_t mb = narrow ? (size_t)b * 2u + (sub >> 1) : (size_t)b;
+        const int e = (int)exponent[mb] - 128;             // 0.5 u 2^(byte-127) = u 2^(byte-128)
+        const uint32_t d = MX ? 7u : ((uint32_t)dialect[mb] & 15u);
         const uint32_t lo = g_book_words.w[d][0], hi = g_book_words.w[d][1];
         const uint32_t mag_even = __builtin_amdgcn_perm(hi, lo, c & 0x07070707u);
         const uint32_t mag_odd = __builtin_amdgcn_perm(hi, lo, (c >> 4) & 0x07070707u);
@@ -74,7 +75,7 @@ __global__ __launch_bounds__(kThreads) void dequantize_kernel(
 
 }  // namespace
 
-int launch_dequantize(bool mx, dfp4_tensor in, void* y, int y_dtype, int64_t ld, hipStream_t stream) {
+int launch_dequantize(bool mx, dfp4_tensor in, void* y, int y_dtype, int64_t ld, hipStream_t stream, bool narrow) {
     const int64_t nblocks64 = in.rows * (in.K / kBlock);
     if (nblocks64 == 0) return DFP4_OK;
     if (nblocks64 >= (int64_t)1 << 31) return DFP4_ERR_SHAPE;
@@ -88,7 +89,7 @@ int launch_dequantize(bool mx, dfp4_tensor in, void* y, int y_dtype, int64_t ld,
     const uint32_t* cp = reinterpret_cast<const uint32_t*>(in.codes);
 #define DFP4_LAUNCH(MXV, BV, CV)                                                                  \
     hipLaunchKernelGGL((dequantize_kernel<MXV, BV, CV>), dim3(grid), dim3(kThreads), 0, stream, cp, \
-                       in.dialect, in.exponent, y, ld, kb, nblocks)
+                       in.dialect, in.exponent, y, ld, kb, nblocks, narrow ? 1u : 0u)
 #define DFP4_PICK(MXV)                                                             \
     do {                                                                           \
         if (y_dtype == DFP4_BF16) {                                                \

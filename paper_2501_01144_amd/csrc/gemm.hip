@@ -498,6 +498,113 @@ __device__ __forceinline__ void quantize_flushed_piece(const GemmParams& p, int6
 }
 
 // ---------------------------------------------------------------------------
+// Operands quantized in blocks of 16 (Section 4.2, Table 3: smaller blocks for the sublayers most
+// sensitive to quantization, possibly mixed with blocks of 32 on the other operand): the paper's
+// MAC with one exponent pair per pair of 16-element blocks.  A 32 x 32 x 32 matrix instruction adds
+// up both halves of a 32-element stretch, so each stretch takes two of them, one per half with the
+// other half's lanes zeroed, each followed by its own fp32 scale-and-add.  128 x 128 outputs per
+// workgroup, operands straight from global memory one stretch ahead.  a16 / w16: that operand's
+// dialect and exponent arrays hold one entry per 16 elements (otherwise per 32).
+// ---------------------------------------------------------------------------
+template <bool BF16>
+__global__ __launch_bounds__(256) void gemm_block16_kernel(GemmParams p, int a16, int w16) {
+    __shared__ uint8_t s_exp[2][512];                  // [buffer][A rows x 2 halves | W rows x 2 halves]
+    const int KB = p.KB;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int m0 = blockIdx.y * 128, n0 = blockIdx.x * 128;
+    const int half = lane >> 5, l32 = lane & 31;
+    int64_t a_row[2], w_row[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        a_row[i] = min(m0 + wm * 64 + i * 32 + l32, p.M - 1);
+        w_row[i] = min(n0 + wn * 64 + i * 32 + l32, p.N - 1);
+    }
+    // metadata index of (row, stretch kb, half h): per 16 elements (row * KB + kb) * 2 + h, per 32 row * KB + kb
+    auto meta_a = [&](int64_t row, int kb, int h) { return a16 ? (row * KB + kb) * 2 + h : row * KB + kb; };
+    auto meta_w = [&](int64_t row, int kb, int h) { return w16 ? (row * KB + kb) * 2 + h : row * KB + kb; };
+    const int t = threadIdx.x;
+    const bool t_is_a = t < 128;
+    const int64_t e_row = t_is_a ? min(m0 + t, p.M - 1) : min(n0 + t - 128, p.N - 1);
+
+    float acc[2][2][16];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int x = 0; x < 16; ++x) acc[i][j][x] = 0.0f;
+
+    struct Stretch { uint2 ca[2], cw[2]; uint32_t da[2], dw[2], e0, e1; };
+    auto load_stretch = [&](int kb) {
+        Stretch o;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            o.ca[i] = *reinterpret_cast<const uint2*>(p.a_codes + (a_row[i] * KB + kb) * 16 + half * 8);
+            o.cw[i] = *reinterpret_cast<const uint2*>(p.w_codes + (w_row[i] * KB + kb) * 16 + half * 8);
+            o.da[i] = (uint32_t)p.a_dial[meta_a(a_row[i], kb, half)] & 15u;
+            o.dw[i] = (uint32_t)p.w_dial[meta_w(w_row[i], kb, half)] & 15u;
+        }
+        o.e0 = t_is_a ? p.a_exp[meta_a(e_row, kb, 0)] : p.w_exp[meta_w(e_row, kb, 0)];
+        o.e1 = t_is_a ? p.a_exp[meta_a(e_row, kb, 1)] : p.w_exp[meta_w(e_row, kb, 1)];
+        return o;
+    };
+    Stretch nxt{};
+    if (KB > 0) nxt = load_stretch(0);
+    for (int kb = 0; kb < KB; ++kb) {
+        const Stretch cur = nxt;
+        if (kb + 1 < KB) nxt = load_stretch(kb + 1);
+        uint8_t* se = s_exp[kb & 1];
+        se[2 * t] = (uint8_t)cur.e0;
+        se[2 * t + 1] = (uint8_t)cur.e1;
+        v4i a[2], b[2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            a[i] = unpack16(cur.ca[i].x, cur.ca[i].y, *reinterpret_cast<const uint4*>(g_shifted_book.w[cur.da[i]][0]));
+            b[i] = unpack16(cur.cw[i].x, cur.cw[i].y, *reinterpret_cast<const uint4*>(g_shifted_book.w[cur.dw[i]][0]));
+        }
+        __syncthreads();
+#pragma unroll
+        for (int hh = 0; hh < 2; ++hh) {
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                // this half's 16 elements only: the lanes that hold the other half multiply zeros
+                const v4i ah = half == hh ? a[i] : v4i{0, 0, 0, 0};
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    v16i pr = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+                    pr = __builtin_amdgcn_mfma_i32_32x32x32_i8(ah, b[j], pr, 0, 0, 0);
+                    const int ew = se[2 * (128 + wn * 64 + j * 32 + l32) + hh];
+#pragma unroll
+                    for (int x = 0; x < 16; ++x) {
+                        const int row = 8 * (x >> 2) + 4 * half + (x & 3);
+                        const int ea = se[2 * (wm * 64 + i * 32 + row) + hh];
+                        acc[i][j][x] += ldexpf((float)pr[x], ea + ew - 256);
+                    }
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int n = n0 + wn * 64 + j * 32 + l32;
+#pragma unroll
+            for (int x = 0; x < 16; ++x) {
+                const int m = m0 + wm * 64 + i * 32 + 8 * (x >> 2) + 4 * half + (x & 3);
+                if (m < p.M && n < p.N) {
+                    const int64_t o = (int64_t)m * p.ldc + n;
+                    if constexpr (BF16)
+                        static_cast<uint16_t*>(p.out)[o] = f32_to_bf16_rne(acc[i][j][x]);
+                    else
+                        static_cast<float*>(p.out)[o] = acc[i][j][x];
+                }
+            }
+        }
+}
+
+// ---------------------------------------------------------------------------
 // Fast kernel: 512 x 128 outputs per workgroup, one int32 accumulator per output.
 // Wave w owns rows 128w .. 128w+127 and all 128 columns (16 accumulator tiles of
 // 32 x 32: tile i = 4 * gi + n is rows 32 gi .., columns 32 n ..).
@@ -1348,6 +1455,21 @@ int launch_gemm_prepare(bool mx, dfp4_tensor T, bool weight, void* prepared, hip
     }
     set_prepared(p, static_cast<uint8_t*>(prepared), 0, static_cast<uint8_t*>(prepared), 0);
     return launch_prep(mx, p, !weight, weight, 1, stream);
+}
+
+int launch_gemm_block16(dfp4_tensor A, bool a16, dfp4_tensor W, bool w16, void* out, int out_dtype, int64_t ldc,
+                        hipStream_t stream) {
+    const int64_t M = A.rows, N = W.rows, KB = A.K / kBlock;
+    if (M == 0 || N == 0) return DFP4_OK;
+    if (!shape_in_range(M, N, KB, 1, ldc) || (M + 127) / 128 > 65535) return DFP4_ERR_SHAPE;
+    GemmParams p{};
+    fill_params(p, A, W, out, ldc, 0, 0, 0, nullptr);
+    dim3 gb((unsigned)((N + 127) / 128), (unsigned)((M + 127) / 128), 1);
+    if (out_dtype == DFP4_BF16)
+        hipLaunchKernelGGL((gemm_block16_kernel<true>), gb, dim3(256), 0, stream, p, a16 ? 1 : 0, w16 ? 1 : 0);
+    else
+        hipLaunchKernelGGL((gemm_block16_kernel<false>), gb, dim3(256), 0, stream, p, a16 ? 1 : 0, w16 ? 1 : 0);
+    return check_launch();
 }
 
 int launch_gemm_prepared(bool mx, dfp4_tensor A, void* a_prepared, dfp4_tensor W, const void* w_prepared, void* out,

@@ -58,6 +58,19 @@ __device__ __forceinline__ uint32_t block_amax_bits(const uint32_t (&w)[4]) {
     return u >> 16;
 }
 
+// Maximum over the 16 elements of two neighbouring lanes (blocks of 16), as bf16 bits (sign cleared).
+__device__ __forceinline__ uint32_t pair_amax_bits(const uint32_t (&w)[4]) {
+    float m = 0.0f;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        m = __builtin_fmaxf(m, __builtin_fabsf(as_f(w[j] << 16)));
+        m = __builtin_fmaxf(m, __builtin_fabsf(as_f(w[j])));
+    }
+    uint32_t u = as_u(m);
+    u = max(u, quad<0xB1>(u));
+    return u >> 16;
+}
+
 // One lane's share (8 elements) of one DialectFP4 block.  WIDE: blocks of 64 elements (two
 // neighbouring quads share the exponent and the dialect; Section 4.2, Table 3 varies the block size).
 template <bool WIDE = false>
@@ -97,11 +110,14 @@ __device__ __forceinline__ void dfp4_pass(const uint4& wv, const uint8_t* __rest
 // The same with tables keyed by ONE 5-bit magnitude (768 bytes in all instead of 24 KiB: twice the
 // lookups, but a workgroup fills them with a single load): lut_i[d * 32 + t] = index of t under
 // dialect d, lut_v[p * 32 + t] = vote of t in pair p (+1 even dialect, -1 odd, as int8).
+// NARROW: blocks of 16 elements (Section 4.2, Table 3): two neighbouring lanes own a block, so the
+// maximum and the votes are reduced over the lane pair only.
+template <bool NARROW = false>
 __device__ __forceinline__ void dfp4_pass_small(const uint4& wv, const uint8_t* __restrict__ lut_v,
                                                 const uint8_t* __restrict__ lut_i, uint32_t& code,
                                                 uint32_t& ebyte, uint32_t& dial) {
     const uint32_t w[4] = {wv.x, wv.y, wv.z, wv.w};
-    const uint32_t ab = block_amax_bits<false>(w);
+    const uint32_t ab = NARROW ? pair_amax_bits(w) : block_amax_bits<false>(w);
     const int byte = max((int)(ab >> 7) - 2, 0);
     const int n = 129 - byte;
     const uint32_t tmax = (uint32_t)ldexpf(as_f(ab << 16), n);
@@ -119,7 +135,7 @@ __device__ __forceinline__ void dfp4_pass_small(const uint4& wv, const uint8_t* 
     for (int j = 0; j < 8; ++j) votes += (int)sv[t[j]];
     uint32_t v = (uint32_t)votes;
     v += quad<0xB1>(v);
-    v += quad<0x4E>(v);
+    if constexpr (!NARROW) v += quad<0x4E>(v);
     dial = 2u * pair + (v >> 31);
     const uint8_t* q = lut_i + dial * 32u;
     uint32_t c = 0;

@@ -60,7 +60,8 @@ __device__ __forceinline__ void load_super(const uint16_t* __restrict__ x, int64
 
 // WIDE: blocks of 64 (each 64-element block is two neighbouring quads; its exponent byte and dialect
 // id are written for both 32-element halves, so that the output reads as the 32-element format)
-template <bool MX, bool CONTIG, bool WIDE, bool SMALL = false>
+// NARROW: blocks of 16 (two lanes per block); `dialect` and `exponent` then hold one byte per 16 elements.
+template <bool MX, bool CONTIG, bool WIDE, bool SMALL = false, bool NARROW = false>
 __global__ __launch_bounds__(kThreads) void quantize_kernel(
     const uint16_t* __restrict__ x, int64_t ld, uint32_t blocks_per_row, uint32_t nblocks,
     uint32_t* __restrict__ codes, uint8_t* __restrict__ dialect, uint8_t* __restrict__ exponent) {
@@ -107,17 +108,28 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(
                     mxfp4_pass(w[p], lds_q, code, eb[p]);
                     dl[p] = 0;
                 } else if constexpr (SMALL) {
-                    dfp4_pass_small(w[p], lds_s, lds_q, code, eb[p], dl[p]);
+                    dfp4_pass_small<NARROW>(w[p], lds_s, lds_q, code, eb[p], dl[p]);
                 } else {
                     dfp4_pass<WIDE>(w[p], lds_s, lds_q, code, eb[p], dl[p]);
                 }
                 cdst[p * 64 + lane] = code;
                 w[p] = nbase[p * 64 + lane];
             }
-            // lane (quad_id, sub) stores the per-block bytes of pass `sub`:
-            // one byte-store instruction covers the wave's 64 consecutive blocks
-            exponent[bm] = (uint8_t)(sub == 0 ? eb[0] : sub == 1 ? eb[1] : sub == 2 ? eb[2] : eb[3]);
-            if constexpr (!MX) dialect[bm] = (uint8_t)(sub == 0 ? dl[0] : sub == 1 ? dl[1] : sub == 2 ? dl[2] : dl[3]);
+            if constexpr (NARROW) {
+                // 128 blocks of 16 per super-chunk: lane (quad, sub) holds the bytes of half sub / 2 of its
+                // quad's block in every pass; it stores pass sub % 2 and pass sub % 2 + 2, so that each
+                // byte-store instruction covers 64 consecutive blocks of 16
+                const uint32_t hb = sc * 128u + (sub & 1u) * 32u + quad_id * 2u + (sub >> 1);
+                exponent[hb] = (uint8_t)((sub & 1u) ? eb[1] : eb[0]);
+                exponent[hb + 64u] = (uint8_t)((sub & 1u) ? eb[3] : eb[2]);
+                dialect[hb] = (uint8_t)((sub & 1u) ? dl[1] : dl[0]);
+                dialect[hb + 64u] = (uint8_t)((sub & 1u) ? dl[3] : dl[2]);
+            } else {
+                // lane (quad_id, sub) stores the per-block bytes of pass `sub`:
+                // one byte-store instruction covers the wave's 64 consecutive blocks
+                exponent[bm] = (uint8_t)(sub == 0 ? eb[0] : sub == 1 ? eb[1] : sub == 2 ? eb[2] : eb[3]);
+                if constexpr (!MX) dialect[bm] = (uint8_t)(sub == 0 ? dl[0] : sub == 1 ? dl[1] : sub == 2 ? dl[2] : dl[3]);
+            }
         } else {
             const bool full = sc * 64u + 64u <= nblocks;          // wave-uniform
 #pragma unroll
@@ -127,14 +139,25 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(
                     mxfp4_pass(w[p], lds_q, code, eb[p]);
                     dl[p] = 0;
                 } else if constexpr (SMALL) {
-                    dfp4_pass_small(w[p], lds_s, lds_q, code, eb[p], dl[p]);
+                    dfp4_pass_small<NARROW>(w[p], lds_s, lds_q, code, eb[p], dl[p]);
                 } else {
                     dfp4_pass<WIDE>(w[p], lds_s, lds_q, code, eb[p], dl[p]);
                 }
                 if (full || sc * 64u + p * kBlocksPerPass + quad_id < nblocks) cdst[p * 64 + lane] = code;
             }
             if (nsc < nsuper) load_super<CONTIG>(x, ld, blocks_per_row, nblocks, nsc, lane, w);
-            if (full || bm < nblocks) {
+            if constexpr (NARROW) {
+#pragma unroll
+                for (int k = 0; k < 2; ++k) {
+                    const uint32_t pass = (sub & 1u) + 2u * k;
+                    const uint32_t b32 = sc * 64u + pass * kBlocksPerPass + quad_id;      // the 32-element block
+                    if (full || b32 < nblocks) {
+                        const uint32_t hb = b32 * 2u + (sub >> 1);
+                        exponent[hb] = (uint8_t)(k == 0 ? ((sub & 1u) ? eb[1] : eb[0]) : ((sub & 1u) ? eb[3] : eb[2]));
+                        dialect[hb] = (uint8_t)(k == 0 ? ((sub & 1u) ? dl[1] : dl[0]) : ((sub & 1u) ? dl[3] : dl[2]));
+                    }
+                }
+            } else if (full || bm < nblocks) {
                 exponent[bm] = (uint8_t)(sub == 0 ? eb[0] : sub == 1 ? eb[1] : sub == 2 ? eb[2] : eb[3]);
                 if constexpr (!MX)
                     dialect[bm] = (uint8_t)(sub == 0 ? dl[0] : sub == 1 ? dl[1] : sub == 2 ? dl[2] : dl[3]);
@@ -365,7 +388,7 @@ __global__ __launch_bounds__(256) void quantize_mse_kernel(
 }  // namespace
 
 int launch_quantize(bool mx, const void* x, int64_t rows, int64_t K, int64_t ld, dfp4_tensor out,
-                    hipStream_t stream, bool wide) {
+                    hipStream_t stream, bool wide, bool narrow) {
     const int64_t nblocks64 = rows * (K / kBlock);
     if (nblocks64 == 0) return DFP4_OK;
     if (nblocks64 >= (int64_t)1 << 31) return DFP4_ERR_SHAPE;
@@ -381,7 +404,14 @@ int launch_quantize(bool mx, const void* x, int64_t rows, int64_t K, int64_t ld,
 #define DFP4_LAUNCH(MXV, CV, WV, SV)                                                                    \
     hipLaunchKernelGGL((quantize_kernel<MXV, CV, WV, SV>), dim3(grid), dim3(kThreads), 0, stream, xp, ld, \
                        kb, nblocks, cp, out.dialect, out.exponent)
-    if (mx) {
+    if (narrow) {
+        if (contig)
+            hipLaunchKernelGGL((quantize_kernel<false, true, false, true, true>), dim3(grid), dim3(kThreads), 0, stream, xp,
+                               ld, kb, nblocks, cp, out.dialect, out.exponent);
+        else
+            hipLaunchKernelGGL((quantize_kernel<false, false, false, true, true>), dim3(grid), dim3(kThreads), 0, stream, xp,
+                               ld, kb, nblocks, cp, out.dialect, out.exponent);
+    } else if (mx) {
         if (contig) DFP4_LAUNCH(true, true, false, false); else DFP4_LAUNCH(true, false, false, false);
     } else if (wide) {
         if (contig) DFP4_LAUNCH(false, true, true, false); else DFP4_LAUNCH(false, false, true, false);

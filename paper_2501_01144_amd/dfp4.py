@@ -26,6 +26,7 @@ class _CTensor(ctypes.Structure):
 
 SYMBOLS = [
     "dfp4_quantize", "dfp4_quantize_b64", "dfp4_quantize_mse", "dfp4_quantize_t", "mxfp4_quantize_t", "dfp4_quantize_t_at", "dfp4_dequantize", "dfp4_gemm", "dfp4_gemm_batched", "dfp4_gemm_workspace_bytes", "dfp4_gemm_noalloc",
+    "dfp4_quantize_block", "dfp4_dequantize_block", "dfp4_gemm_blocks",
     "dfp4_gemm_prepared_bytes", "dfp4_gemm_prepare", "mxfp4_gemm_prepare", "dfp4_gemm_prepared_workspace_bytes",
     "dfp4_gemm_prepared", "mxfp4_gemm_prepared", "dfp4_gemm_declined_tiles",
     "mxfp4_gemm_native", "dfp4_gemm_native", "dfp4_gemm_native_workspace_bytes", "dfp4_native_packed_bytes",
@@ -63,6 +64,12 @@ def load():
     lib.mxfp4_gemm.argtypes = [_CTensor, _CTensor, vp, ci, i64, vp, ctypes.c_size_t, vp]
     lib.dfp4_gemm_batched.argtypes = [_CTensor, _CTensor, vp, ci, i64, i64, i64, i64, i64, vp,
                                       ctypes.c_size_t, vp]
+    lib.dfp4_quantize_block.argtypes = [vp, i64, i64, i64, ci, _CTensor, vp]
+    lib.dfp4_quantize_block.restype = ci
+    lib.dfp4_dequantize_block.argtypes = [_CTensor, ci, vp, ci, i64, vp]
+    lib.dfp4_dequantize_block.restype = ci
+    lib.dfp4_gemm_blocks.argtypes = [_CTensor, ci, _CTensor, ci, vp, ci, i64, vp, ctypes.c_size_t, vp]
+    lib.dfp4_gemm_blocks.restype = ci
     lib.dfp4_gemm_prepared_bytes.argtypes = [i64, i64, ci]
     lib.dfp4_gemm_prepared_bytes.restype = ctypes.c_size_t
     lib.dfp4_gemm_prepared_workspace_bytes.argtypes = [i64, i64, i64]
@@ -172,6 +179,41 @@ def quantize(x, out=None):
 def quantize_b64(x, out=None):
     """dfp4_quantize_b64: blocks of 64 elements, output in the layout of the 32-element format."""
     return _quantize(load().dfp4_quantize_b64, "dfp4_quantize_b64", x, out, False)
+
+
+def quantize_block(x, block, out=None):
+    """dfp4_quantize_block: block size 16, 32 or 64.  Blocks of 16 carry dialect / exponent arrays [rows, K/16]."""
+    assert x.dtype == torch.bfloat16 and x.dim() == 2 and x.is_cuda and x.stride(1) == 1
+    rows, K = x.shape
+    if out is None:
+        out = empty_qtensor(rows, K, x.device)
+        if block == 16:
+            out.dialect = torch.empty((rows, K // 16), dtype=torch.uint8, device=x.device)
+            out.exponent = torch.empty((rows, K // 16), dtype=torch.uint8, device=x.device)
+    ld = x.stride(0) if rows > 1 else K
+    _check(load().dfp4_quantize_block(_ptr(x), rows, K, ld, block, out.c(), _stream()), "dfp4_quantize_block")
+    return out
+
+
+def dequantize_block(q, block, dtype=torch.float32, out=None):
+    """dfp4_dequantize_block: the inverse of quantize_block for the same block size."""
+    if out is None:
+        out = torch.empty((q.rows, q.K), dtype=dtype, device=q.codes.device)
+    ld = out.stride(0) if q.rows > 1 else q.K
+    _check(load().dfp4_dequantize_block(q.c(), block, _ptr(out), F32 if out.dtype == torch.float32 else BF16, ld,
+                                        _stream()), "dfp4_dequantize_block")
+    return out
+
+
+def gemm_blocks(a, block_a, w, block_w, dtype=torch.float32, out=None, workspace=None):
+    """dfp4_gemm_blocks: product of operands quantized with block sizes block_a / block_w (16, 32 or 64)."""
+    if out is None:
+        out = torch.empty((a.rows, w.rows), dtype=dtype, device=a.codes.device)
+    workspace, nbytes = _workspace(a.rows, w.rows, a.K, out.device, workspace)
+    ldc = out.stride(0) if a.rows > 1 else w.rows
+    _check(load().dfp4_gemm_blocks(a.c(), block_a, w.c(), block_w, _ptr(out), F32 if out.dtype == torch.float32 else BF16,
+                                   ldc, _ptr(workspace), nbytes, _stream()), "dfp4_gemm_blocks")
+    return out
 
 
 def quantize_mse(x, out=None):

@@ -146,3 +146,17 @@ def test_gemm_noalloc_argument_errors(lib):
     assert lib.dfp4_gemm_noalloc(_t(16, 16, 16, 4, 64), _t(16, 16, 16, 4, 64), vp(16), 9, 4, vp(0)) == -4
     assert lib.dfp4_gemm_noalloc(_t(16, 16, 16, 4, 64), _t(16, 16, 16, 4, 64), vp(0), 0, 4, vp(0)) == -1
     assert lib.dfp4_gemm_noalloc(_t(0, 0, 0, 0, 64), _t(16, 16, 16, 4, 64), vp(0), 0, 4, vp(0)) == 0
+
+
+def test_block_size_entry_points_argument_errors(lib):
+    vp, sz = ctypes.c_void_p, ctypes.c_size_t
+    q = _t(16, 16, 16, 4, 64)
+    assert lib.dfp4_quantize_block(vp(16), 4, 64, 64, 8, q, vp(0)) == -2          # block size not 16 / 32 / 64
+    assert lib.dfp4_quantize_block(vp(16), 4, 96, 96, 64, _t(16, 16, 16, 4, 96), vp(0)) == -2   # K % 64
+    assert lib.dfp4_quantize_block(vp(0), 4, 64, 64, 16, q, vp(0)) == -1
+    assert lib.dfp4_quantize_block(vp(16), 0, 64, 64, 16, _t(0, 0, 0, 0, 64), vp(0)) == 0
+    assert lib.dfp4_dequantize_block(q, 48, vp(16), 0, 64, vp(0)) == -2
+    assert lib.dfp4_dequantize_block(q, 16, vp(16), 5, 64, vp(0)) == -4
+    assert lib.dfp4_gemm_blocks(q, 16, _t(16, 16, 16, 4, 96), 16, vp(16), 0, 4, vp(0), sz(0), vp(0)) == -2
+    assert lib.dfp4_gemm_blocks(q, 16, q, 24, vp(16), 0, 4, vp(0), sz(0), vp(0)) == -2
+    assert lib.dfp4_gemm_blocks(q, 16, q, 16, vp(0), 0, 4, vp(0), sz(0), vp(0)) == -1

@@ -1031,3 +1031,56 @@ def test_gemm_native_few_rows(M, N, K):
     outm = dfp4.mxfp4_gemm_native(dfp4.mxfp4_quantize(_dev(a)), dfp4.mxfp4_quantize(_dev(w)))
     torch.cuda.synchronize()
     _assert_gemm_close(outm, refm, absm, "native few rows mxfp4")
+
+
+# --------------------------------------------------------------------------
+# blocks of 16 and mixed block sizes (Section 4.2, Table 3)
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("rows,K", [(1, 32), (7, 96), (33, 4096), (257, 1056), (2048, 4096)])
+def test_quantize_and_dequantize_block16(rows, K):
+    print(f"quantize parity: blocks of 16, {rows}x{K}", flush=True)
+    x = torch.cat([synth.student_t(rows, K, 3.0, seed=60 + rows)[: rows - rows // 2],
+                   synth.gaussian_outlier_channels(rows // 2, K, max(1, K // 100), 50.0, 1.0, seed=61 + rows)])
+    q = dfp4.quantize_block(_dev(x), 16)
+    torch.cuda.synchronize()
+    assert q.dialect.shape == (rows, K // 16) and q.exponent.shape == (rows, K // 16)
+    ref = O.dfp4_quantize_block16(synth.to_f64(x))
+    _assert_quant_equal(q, ref, "block16")
+    for dtype in (torch.float32, torch.bfloat16):
+        back = dfp4.dequantize_block(q, 16, dtype=dtype)
+        torch.cuda.synchronize()
+        assert np.array_equal(back.cpu().double().numpy(), O.dfp4_dequantize_block(*ref, 16))
+    # block sizes 32 and 64 through the same entry point
+    _assert_quant_equal(dfp4.quantize_block(_dev(x), 32), O.dfp4_quantize(synth.to_f64(x)), "block32 via quantize_block")
+    if K % 64 == 0:
+        _assert_quant_equal(dfp4.quantize_block(_dev(x), 64), O.dfp4_quantize_block64(synth.to_f64(x)), "block64")
+
+
+def test_quantize_block16_every_bf16_value_and_strided_rows():
+    vals = synth.all_bf16_bit_patterns()                     # [2040, 32]: two blocks of 16 per row
+    q = dfp4.quantize_block(_dev(vals), 16)
+    torch.cuda.synchronize()
+    _assert_quant_equal(q, O.dfp4_quantize_block16(synth.to_f64(vals)), "every bf16 value, blocks of 16")
+    base = synth.gaussian_outlier_channels(70, 1024, 4, 30.0, 1.0, seed=67)
+    qs = dfp4.quantize_block(_dev(base)[:, 128:128 + 512], 16)
+    torch.cuda.synchronize()
+    _assert_quant_equal(qs, O.dfp4_quantize_block16(synth.to_f64(base[:, 128:128 + 512].contiguous())), "strided, blocks of 16")
+
+
+@pytest.mark.parametrize("M,N,K,ba,bw", [(70, 200, 160, 16, 16), (129, 257, 1024, 16, 32), (300, 130, 512, 32, 16),
+                                         (64, 96, 256, 16, 64), (512, 256, 4096, 16, 16), (100, 100, 256, 64, 32)])
+def test_gemm_mixed_block_sizes(M, N, K, ba, bw):
+    print(f"gemm parity: blocks {ba} x {bw}, {M}x{N}x{K}", flush=True)
+    a = synth.gaussian_outlier_channels(M, K, max(1, K // 100), 50.0, 1.0, seed=70 + M)
+    w = synth.gaussian(N, K, 0.02, seed=71 + N)
+    qa, qw = dfp4.quantize_block(_dev(a), ba), dfp4.quantize_block(_dev(w), bw)
+    def oracle_q(x, b):
+        x = synth.to_f64(x)
+        return (O.dfp4_quantize_block16(x), 16) if b == 16 else ((O.dfp4_quantize_block64(x) if b == 64 else O.dfp4_quantize(x)), 32)
+    (ra, la), (rw, lw) = oracle_q(a, ba), oracle_q(w, bw)
+    ad, wd = O.dfp4_dequantize_block(*ra, la), O.dfp4_dequantize_block(*rw, lw)
+    ref, absdot = O.dfp4_gemm_blocks(ra, la, rw, lw), np.abs(ad) @ np.abs(wd).T
+    for dtype in (torch.float32, torch.bfloat16):
+        out = dfp4.gemm_blocks(qa, ba, qw, bw, dtype=dtype)
+        torch.cuda.synchronize()
+        _assert_gemm_close(out, ref, absdot, f"blocks {ba}x{bw} {dtype}", bf16=dtype == torch.bfloat16)
