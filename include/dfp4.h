@@ -325,6 +325,15 @@ int dfp4_gemm_requant(dfp4_tensor A, dfp4_tensor W, dfp4_tensor out, void* works
 int mxfp4_gemm_requant(dfp4_tensor A, dfp4_tensor W, dfp4_tensor out, void* workspace,
                        size_t workspace_bytes, void* stream);
 size_t dfp4_gemm_requant_workspace_bytes(int64_t M, int64_t N, int64_t K);
+/*
+ * The same for `batch` independent problems of equal shape (Appendix C: the attention products
+ * are quantized along their multiplication dimensions too, so the scores Q K^T feed the next
+ * product as a quantized tensor).  Problem b reads A and W as dfp4_gemm_batched does; `out` is
+ * the quantized [batch * M, N] result, problem after problem (out.rows = batch * M, out.K = N).
+ *   workspace   at least batch * dfp4_gemm_requant_workspace_bytes(M, N, K) bytes
+ */
+int dfp4_gemm_requant_batched(dfp4_tensor A, dfp4_tensor W, dfp4_tensor out, int64_t batch, int64_t strideA_rows,
+                              int64_t strideW_rows, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * MXFP4 comparison path (Section 4.1, baseline): FP4 E2M1 elements

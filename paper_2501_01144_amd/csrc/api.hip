@@ -428,33 +428,43 @@ size_t dfp4_gemm_native_workspace_bytes(int64_t M, int64_t N, int64_t K) {
     return gemm_native_workspace_bytes(M, N, K, true);       // covers the FP4 form as well
 }
 
-static int gemm_requant_common(bool mx, dfp4_tensor A, dfp4_tensor W, dfp4_tensor out, void* workspace,
-                               size_t workspace_bytes, void* stream) {
+// out: quantized [batch * M, N] (problem after problem); A.rows = M and W.rows = N per problem
+static int gemm_requant_common(bool mx, dfp4_tensor A, dfp4_tensor W, dfp4_tensor out, int64_t batch,
+                               int64_t strideA_rows, int64_t strideW_rows, void* workspace, size_t workspace_bytes,
+                               void* stream) {
+    if (batch < 0 || strideA_rows < 0 || strideW_rows < 0) return DFP4_ERR_SHAPE;
     if (A.rows < 0 || W.rows < 0 || A.K < 0 || A.K != W.K || A.K % kBlock != 0 || W.rows % kBlock != 0 ||
-        out.rows != A.rows || out.K != W.rows)
+        out.rows != A.rows * batch || out.K != W.rows)
         return DFP4_ERR_SHAPE;
-    if (A.rows == 0 || W.rows == 0) return DFP4_OK;
+    if (A.rows == 0 || W.rows == 0 || batch == 0) return DFP4_OK;
     if (!out.codes || !out.exponent || (!mx && !out.dialect)) return DFP4_ERR_NULL;
     if (!aligned(out.codes, 4)) return DFP4_ERR_ALIGN;
-    const size_t need = gemm_requant_workspace_bytes(A.rows, W.rows, A.K);
-    if (!workspace || workspace_bytes < need) return DFP4_ERR_WORKSPACE;
-    // the bf16 [M, N] temporary sits behind the plain GEMM's workspace
-    const size_t gemm_ws = need - (size_t)(((A.rows * W.rows * 2) + 255) & ~(int64_t)255);
+    // per problem: the plain GEMM's workspace, then the bf16 [M, N] temporaries of all problems
+    const size_t gemm_ws = (size_t)((gemm_workspace_bytes(A.rows, W.rows, A.K) + 255) & ~(size_t)255) * (size_t)batch;
+    const size_t temp_bytes = (size_t)(((A.rows * W.rows * 2) + 255) & ~(int64_t)255) * (size_t)batch;
+    if (!workspace || workspace_bytes < gemm_ws + temp_bytes) return DFP4_ERR_WORKSPACE;
     void* temp = static_cast<uint8_t*>(workspace) + gemm_ws;
-    const int rc = check_gemm_args(A, W, temp, DFP4_BF16, W.rows, !mx, workspace, gemm_ws);
+    int rc = check_gemm_args(A, W, temp, DFP4_BF16, W.rows, !mx, workspace, gemm_ws > 0 ? gemm_ws : 1);
     if (rc != DFP4_OK) return rc;
-    return launch_gemm(mx, A, W, temp, DFP4_BF16, W.rows, 1, 0, 0, A.rows * W.rows, workspace, gemm_ws,
-                       static_cast<hipStream_t>(stream), &out);
+    rc = gemm_shape_check(A, W, W.rows, batch, true);
+    if (rc != DFP4_OK) return rc;
+    return launch_gemm(mx, A, W, temp, DFP4_BF16, W.rows, batch, strideA_rows, strideW_rows, A.rows * W.rows, workspace,
+                       gemm_ws, static_cast<hipStream_t>(stream), &out);
 }
 
 int dfp4_gemm_requant(dfp4_tensor A, dfp4_tensor W, dfp4_tensor out, void* workspace, size_t workspace_bytes,
                       void* stream) {
-    return gemm_requant_common(false, A, W, out, workspace, workspace_bytes, stream);
+    return gemm_requant_common(false, A, W, out, 1, 0, 0, workspace, workspace_bytes, stream);
 }
 
 int mxfp4_gemm_requant(dfp4_tensor A, dfp4_tensor W, dfp4_tensor out, void* workspace, size_t workspace_bytes,
                        void* stream) {
-    return gemm_requant_common(true, A, W, out, workspace, workspace_bytes, stream);
+    return gemm_requant_common(true, A, W, out, 1, 0, 0, workspace, workspace_bytes, stream);
+}
+
+int dfp4_gemm_requant_batched(dfp4_tensor A, dfp4_tensor W, dfp4_tensor out, int64_t batch, int64_t strideA_rows,
+                              int64_t strideW_rows, void* workspace, size_t workspace_bytes, void* stream) {
+    return gemm_requant_common(false, A, W, out, batch, strideA_rows, strideW_rows, workspace, workspace_bytes, stream);
 }
 
 size_t dfp4_gemm_requant_workspace_bytes(int64_t M, int64_t N, int64_t K) {

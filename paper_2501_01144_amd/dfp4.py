@@ -32,7 +32,7 @@ SYMBOLS = [
     "mxfp4_gemm_native", "dfp4_gemm_native", "dfp4_gemm_native_workspace_bytes", "dfp4_native_packed_bytes",
     "dfp4_quantize_native", "dfp4_native_pack", "mxfp4_native_pack", "dfp4_gemm_native_packed_w", "mxfp4_gemm_native_packed_w",
     "dfp4_gemm_native_packed", "mxfp4_gemm_native_packed", "dfp4_gemm_native_splitk_bytes",
-    "dfp4_gemm_requant", "mxfp4_gemm_requant", "dfp4_gemm_requant_workspace_bytes",
+    "dfp4_gemm_requant", "mxfp4_gemm_requant", "dfp4_gemm_requant_workspace_bytes", "dfp4_gemm_requant_batched",
     "mxfp4_quantize", "mxfp4_dequantize", "mxfp4_gemm", "dfp4_formatbook", "dfp4_strerror",
 ]
 
@@ -109,6 +109,8 @@ def load():
         getattr(lib, name).restype = ci
     lib.dfp4_gemm_requant.argtypes = [_CTensor, _CTensor, _CTensor, vp, ctypes.c_size_t, vp]
     lib.mxfp4_gemm_requant.argtypes = [_CTensor, _CTensor, _CTensor, vp, ctypes.c_size_t, vp]
+    lib.dfp4_gemm_requant_batched.argtypes = [_CTensor, _CTensor, _CTensor, i64, i64, i64, vp, ctypes.c_size_t, vp]
+    lib.dfp4_gemm_requant_batched.restype = ci
     lib.dfp4_gemm_requant.restype = ci
     lib.mxfp4_gemm_requant.restype = ci
     lib.dfp4_gemm_requant_workspace_bytes.argtypes = [i64, i64, i64]
@@ -373,6 +375,20 @@ def _gemm_requant(fn, what, a, w, out, workspace, mx):
 def gemm_requant(a, w, out=None, workspace=None):
     """dfp4_gemm_requant: quantize(bf16(A W^T)) in blocks of 32 along N -> QTensor [M, N]."""
     return _gemm_requant(load().dfp4_gemm_requant, "dfp4_gemm_requant", a, w, out, workspace, False)
+
+
+def gemm_requant_batched(a, w, batch, M, N, out=None, workspace=None):
+    """dfp4_gemm_requant_batched: a holds batch*M rows, w batch*N rows; returns the quantized [batch*M, N] result."""
+    if out is None:
+        out = empty_qtensor(batch * M, N, a.codes.device)
+    need = int(load().dfp4_gemm_requant_workspace_bytes(M, N, a.K)) * batch
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=a.codes.device)
+    ac, wc = a.c(), w.c()
+    ac.rows, wc.rows = M, N
+    _check(load().dfp4_gemm_requant_batched(ac, wc, out.c(), batch, M, N, _ptr(workspace), workspace.numel(), _stream()),
+           "dfp4_gemm_requant_batched")
+    return out
 
 
 def mxfp4_gemm_requant(a, w, out=None, workspace=None):

@@ -160,3 +160,12 @@ def test_block_size_entry_points_argument_errors(lib):
     assert lib.dfp4_gemm_blocks(q, 16, _t(16, 16, 16, 4, 96), 16, vp(16), 0, 4, vp(0), sz(0), vp(0)) == -2
     assert lib.dfp4_gemm_blocks(q, 16, q, 24, vp(16), 0, 4, vp(0), sz(0), vp(0)) == -2
     assert lib.dfp4_gemm_blocks(q, 16, q, 16, vp(0), 0, 4, vp(0), sz(0), vp(0)) == -1
+
+
+def test_gemm_requant_batched_argument_errors(lib):
+    vp, sz = ctypes.c_void_p, ctypes.c_size_t
+    a, w = _t(16, 16, 16, 64, 64), _t(16, 16, 16, 64, 64)
+    assert lib.dfp4_gemm_requant_batched(a, w, _t(16, 16, 16, 64, 64), 2, 64, 64, vp(256), sz(1 << 30), vp(0)) == -2   # out.rows != batch * M
+    assert lib.dfp4_gemm_requant_batched(a, w, _t(16, 16, 16, 128, 64), 2, 64, 64, vp(0), sz(0), vp(0)) == -5
+    assert lib.dfp4_gemm_requant_batched(a, w, _t(16, 16, 16, 128, 64), -1, 64, 64, vp(256), sz(1 << 30), vp(0)) == -2
+    assert lib.dfp4_gemm_requant_batched(a, w, _t(16, 16, 16, 0, 64), 0, 64, 64, vp(0), sz(0), vp(0)) == 0

@@ -747,6 +747,33 @@ def test_gemm_requant_split_k_bit_exact():
     _assert_quant_equal(q, _requant_ref(a, w), "requant split K")
 
 
+@pytest.mark.parametrize("B,M,N,K", [(3, 600, 352, 128), (5, 40, 64, 256), (2, 2048, 2048, 128)])
+def test_gemm_requant_batched(B, M, N, K):
+    # attention-like batches: every problem's quantized scores against the oracle, bit for bit where the
+    # sums are exact (more than 64 rows), to the fp32-accumulation bar otherwise
+    print(f"gemm_requant_batched parity: {B} x {M}x{N}x{K}", flush=True)
+    a = synth.gaussian_outlier_channels(B * M, K, 2, 30.0, 1.0, seed=310 + M)
+    w = synth.gaussian_outlier_channels(B * N, K, 2, 30.0, 1.0, seed=311 + N)
+    q = dfp4.gemm_requant_batched(dfp4.quantize(_dev(a)), dfp4.quantize(_dev(w)), B, M, N)
+    torch.cuda.synchronize()
+    for b in (range(B) if M <= 600 else (0, B - 1)):
+        rows = slice(b * M, (b + 1) * M) if M <= 600 else slice(b * M + 1000, b * M + 1032)
+        ab = a[rows]
+        wb = w[b * N:(b + 1) * N]
+        if M > 64:
+            codes, dialect, expo = _requant_ref(ab, wb)
+            assert np.array_equal(_np(q.exponent)[rows], expo), f"problem {b}"
+            assert np.array_equal(_np(q.dialect)[rows], dialect), f"problem {b}"
+            assert np.array_equal(_np(q.codes)[rows], codes), f"problem {b}"
+        else:
+            ref, _ = _gemm_ref(synth.to_f64(ab), synth.to_f64(wb))
+            codes, dialect, expo = O.dfp4_quantize(O.round_to_bf16(ref))
+            same = np.array_equal(_np(q.codes)[rows], codes)
+            # few rows accumulate in fp32: nearly all blocks reproduce the oracle's
+            agree = (_np(q.exponent)[rows] == expo).mean()
+            assert agree > 0.99 and (same or (_np(q.codes)[rows] == codes).mean() > 0.99)
+
+
 def test_gemm_requant_handworked_block(golden_dir):
     # the hand-worked product of tests/golden (products on and just below a bf16 midpoint)
     import json, os
