@@ -17,16 +17,22 @@
 //     is summed exactly in ONE int32 accumulator per output and the only
 //     rounding is the final int32 -> fp32 conversion, scaled by
 //     2^(refA[m] + refW[n] - 2).
-//   A block appears once for every class present among the rows that share
-//   the tile (its other rows contribute zeros).  With activations that have
-//   outlier channels, that is a second visit for the few outlier blocks.
+//   Both operands have classes.  A block is visited once for every pair (class
+//   present among the tile's 512 rows of A, class present among its 128 rows of
+//   W) -- rows of other classes contribute zeros -- and the pair's class sum is
+//   the number of shifts the product still receives; sums above 2 cannot be
+//   taken.  With activations that have outlier channels, that is a second visit
+//   for the few outlier blocks.
 //
-// Three kernels per call:
-//   gemm_prep_kernel     per-row reference exponents; for W also the spread and
-//                        one dword per block naming its table (dialect, shift);
-//                        per-(512 rows, block) class masks and A expanded to
-//                        pre-shifted int8 in MFMA fragment order (A is the
-//                        small operand; W stays 4-bit in HBM);
+// Kernels:
+//   gemm_prep_kernel     the per-operand part, once per call (dfp4_gemm) or once per
+//                        tensor (dfp4_gemm_prepare).  A: per-row reference exponents,
+//                        per-(512 rows, block) class masks, and A expanded to
+//                        pre-shifted int8 in MFMA fragment order (A is the small
+//                        operand; W stays 4-bit in HBM).  W: per-row reference
+//                        exponents, per-(128 rows, block) class masks, and per class
+//                        and block one dword naming the block's (dialect, shift)
+//                        table, or the all-zero table for blocks of another class;
 //   gemm_fast_kernel     512 x 128 outputs per workgroup, 4 waves, each wave
 //                        128 x 128 with 256 accumulator registers (one wave per
 //                        SIMD).  A fragments are private to a wave and come by
@@ -35,12 +41,18 @@
 //                        (v_perm_b32 lookups) and shares the int8 result through
 //                        LDS.  A lone wave issues one instruction per 4 cycles or
 //                        so; the whole main loop is generated assembly that places
-//                        the few non-MFMA instructions per MFMA in its shadow;
-//   gemm_block_kernel    always-correct per-block-flush kernel for tiles the
-//                        fast kernel declined (exponent spread above 3 classes,
-//                        W rows spreading over more than one class, K too long
-//                        for the int32 bound); with split K it also adds up the
-//                        K ranges of the other tiles.
+//                        the few non-MFMA instructions per MFMA in its shadow.
+//                        With few output tiles K is split between workgroups; the
+//                        last of a tile's workgroups to finish adds the others'
+//                        exact int32 sums.  A tile whose exponents spread too far
+//                        (or whose int32 sum could overflow) is computed by the same
+//                        workgroup with one fp32 scale-and-add per block;
+//   gemm_rows_kernel     the same exact scheme for at most 64 rows of A on prepared
+//                        operands (decode shapes): 32 x 32 outputs per workgroup, 16
+//                        waves share the visits;
+//   gemm_small_kernel    at most 64 rows of A, nothing prepared: per-block fp32 flush;
+//   gemm_block_kernel    whole products with K > 16384: per-block fp32 flush;
+//   gemm_block16_kernel  operands quantized in blocks of 16: per-block fp32 flush.
 //
 // The order of the elements inside an MFMA operand does not matter as long
 // as A and W use the same order; both sides go through unpack8() below.
