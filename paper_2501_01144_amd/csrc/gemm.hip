@@ -83,7 +83,10 @@ namespace {
 
 // Results leave the kernel once and are not read again by it: stored with the non-temporal hint so
 // that they do not push the operands other workgroups still need out of the caches.
-#ifdef DFP4_PLAIN_OUT_STORES
+#if defined(DFP4_TIMING_NO_OUT_STORES)   // timing experiments only: results are computed and dropped
+__device__ int g_timing_store_results = 0;
+#define DFP4_OUT_STORE(PTR, VAL) do { if (g_timing_store_results) *(PTR) = (VAL); } while (0)
+#elif defined(DFP4_PLAIN_OUT_STORES)
 #define DFP4_OUT_STORE(PTR, VAL) (*(PTR) = (VAL))
 #else
 #define DFP4_OUT_STORE(PTR, VAL) __builtin_nontemporal_store((VAL), (PTR))
@@ -986,7 +989,7 @@ __global__ __launch_bounds__(256, 1) void gemm_fast_kernel(GemmParams p) {
 // pair per block in fp32 as the paper does; the 16 partial tiles are added in a
 // fixed order through LDS.  No prepass and no workspace.
 // ---------------------------------------------------------------------------
-constexpr int kSmallWaves = 16;
+constexpr int kSmallWaves = 16;     // waves of a workgroup, at most (LDS is laid out for this many)
 constexpr int kSmallMaxKB = 512;      // LDS holds the 32 rows' exponent bytes of all blocks
 constexpr int kSmallMaxM = 64;
 static_assert(kSmallMaxM == 64 && kSmallMaxKB == 512, "takes_small_kernel() states these limits");
@@ -998,7 +1001,7 @@ struct SmallTileLds {
 };
 
 // One 32 x 32 output tile by a workgroup of 16 waves, one fp32 scale-and-add per block.
-template <bool MX, bool BF16>
+template <bool MX, bool BF16, int NW>
 __device__ __forceinline__ void small_tile(const GemmParams& p, int64_t bz, int m0, int n0, SmallTileLds& lds) {
     uint32_t (&s_tab)[kDialects * 4] = lds.tab;
     uint8_t (&s_ea)[kSmallMaxKB * 32] = lds.ea;
@@ -1014,11 +1017,11 @@ __device__ __forceinline__ void small_tile(const GemmParams& p, int64_t bz, int 
     const uint8_t* ad = MX ? nullptr : p.a_dial + arow * KB;
     const uint8_t* wd = MX ? nullptr : p.w_dial + wrow * KB;
     const uint8_t* we = p.w_exp + wrow * KB;
-    const int per = (KB + kSmallWaves - 1) / kSmallWaves;
+    const int per = (KB + NW - 1) / NW;
     const int kb_lo = wave * per, kb_hi = min(KB, kb_lo + per);
 
-    for (int i = tid; i < kDialects * 4; i += kSmallWaves * 64) s_tab[i] = g_shifted_book.w[i >> 2][0][i & 3];
-    for (int i = tid; i < 32 * KB; i += kSmallWaves * 64) {
+    for (int i = tid; i < kDialects * 4; i += NW * 64) s_tab[i] = g_shifted_book.w[i >> 2][0][i & 3];
+    for (int i = tid; i < 32 * KB; i += NW * 64) {
         const int row = i / KB, kb = i - row * KB;
         s_ea[kb * 32 + row] = p.a_exp[(a_row0 + min(m0 + row, p.M - 1)) * KB + kb];
     }
@@ -1058,22 +1061,23 @@ __device__ __forceinline__ void small_tile(const GemmParams& p, int64_t bz, int 
             }
         }
     }
-    // the 16 partial tiles, added in a fixed order: waves 8..15 hand theirs to waves 0..7
-    if (wave >= kSmallWaves / 2) {
+    // the NW partial tiles, added in a fixed order: the upper half of the waves hands theirs to the lower
+    if (wave >= NW / 2) {
 #pragma unroll
-        for (int x = 0; x < 16; ++x) s_red[wave - kSmallWaves / 2][x][lane] = acc[x];
+        for (int x = 0; x < 16; ++x) s_red[wave - NW / 2][x][lane] = acc[x];
     }
     __syncthreads();
-    if (wave < kSmallWaves / 2) {
+    if (wave < NW / 2) {
 #pragma unroll
         for (int x = 0; x < 16; ++x) s_red[wave][x][lane] += acc[x];
     }
     __syncthreads();
-    {
-        const int x = wave;                                    // thread (x, lane) finishes one output
+#pragma unroll
+    for (int i = 0; i < 16 / NW; ++i) {
+        const int x = wave + i * NW;                           // thread (x, lane) finishes one output
         float sum = 0.0f;
 #pragma unroll
-        for (int w = 0; w < kSmallWaves / 2; ++w) sum += s_red[w][x][lane];
+        for (int w = 0; w < NW / 2; ++w) sum += s_red[w][x][lane];
         const int m = m0 + 8 * (x >> 2) + 4 * h + (x & 3), n = n0 + r;
         if (m < p.M && n < p.N) {
             const int64_t o = bz * p.strideC + (int64_t)m * p.ldc + n;
@@ -1085,10 +1089,10 @@ __device__ __forceinline__ void small_tile(const GemmParams& p, int64_t bz, int 
     }
 }
 
-template <bool MX, bool BF16>
-__global__ __launch_bounds__(kSmallWaves * 64) void gemm_small_kernel(GemmParams p) {
+template <bool MX, bool BF16, int NW>
+__global__ __launch_bounds__(NW * 64) void gemm_small_kernel(GemmParams p) {
     __shared__ SmallTileLds lds;
-    small_tile<MX, BF16>(p, blockIdx.z, (int)blockIdx.y * 32, (int)blockIdx.x * 32, lds);
+    small_tile<MX, BF16, NW>(p, blockIdx.z, (int)blockIdx.y * 32, (int)blockIdx.x * 32, lds);
 }
 
 // ---------------------------------------------------------------------------
@@ -1101,8 +1105,8 @@ __global__ __launch_bounds__(kSmallWaves * 64) void gemm_small_kernel(GemmParams
 // int32 partial tiles are added through LDS.  No per-block floating-point work at all, so the
 // kernel follows the stream of W.  A tile the scheme cannot take is computed by small_tile().
 // ---------------------------------------------------------------------------
-template <bool MX, bool BF16>
-__global__ __launch_bounds__(kSmallWaves * 64) void gemm_rows_kernel(GemmParams p) {
+template <bool MX, bool BF16, int NW>
+__global__ __launch_bounds__(NW * 64) void gemm_rows_kernel(GemmParams p) {
     __shared__ __attribute__((aligned(16))) uint32_t s_tab[kDialects * 16 + 4];
     __shared__ uint16_t s_vl[kVisitCap];
     __shared__ int s_ctl[8];
@@ -1117,7 +1121,7 @@ __global__ __launch_bounds__(kSmallWaves * 64) void gemm_rows_kernel(GemmParams 
     const uint8_t* ap = p.a_prep;
     const uint8_t* wp = p.w_prep;
 
-    for (int i = tid; i < kDialects * 16 + 4; i += kSmallWaves * 64)
+    for (int i = tid; i < kDialects * 16 + 4; i += NW * 64)
         s_tab[i] = i < kDialects * 16 ? (&g_shifted_book.w[0][0][0])[i] : 0u;
     if (tid < 8) s_ctl[tid] = 0;
     if (wave == 0) {
@@ -1162,12 +1166,12 @@ __global__ __launch_bounds__(kSmallWaves * 64) void gemm_rows_kernel(GemmParams 
     if (s_ctl[4] != 0) {
         if (tid == 0 && blockIdx.x % (kTileN / 32) == 0)   // counted once per 512 x 128 tile, like the large kernel
             atomicAdd(reinterpret_cast<uint32_t*>(const_cast<uint8_t*>(ap) + p.off_cnt) + kMaxSplitTiles, 1u);
-        small_tile<MX, BF16>(p, 0, m0, n0, u.small);
+        small_tile<MX, BF16, NW>(p, 0, m0, n0, u.small);
         return;
     }
     // this wave's slice of the steps (a step = two visits of the same class sum)
     const int end2 = s_ctl[0] / 2, end1 = s_ctl[1] / 2, total = s_ctl[2] / 2;
-    const int per = (total + kSmallWaves - 1) / kSmallWaves;
+    const int per = (total + NW - 1) / NW;
     const int s_lo = min(total, wave * per), s_hi = min(total, s_lo + per);
 
     const uint32_t grp_stride = (uint32_t)(KB + 1) * 1024u;
@@ -1176,6 +1180,15 @@ __global__ __launch_bounds__(kSmallWaves * 64) void gemm_rows_kernel(GemmParams 
     const int ncol = min(n0 + r, p.N - 1);
     const uint8_t* wcodes = p.w_codes + (uint64_t)ncol * KB * 16u;
     const uint8_t* wmeta = wp + p.off_wmeta + (uint64_t)ncol * KB * 4u;
+
+    // reference exponents of the outputs this thread finishes (x = wave, wave + NW, ..): loaded now, used last
+    int ref_sum[16 / NW];
+#pragma unroll
+    for (int i = 0; i < 16 / NW; ++i) {
+        const int x = wave + i * NW;
+        const int m = min(m0 + 8 * (x >> 2) + 4 * h + (x & 3), p.M - 1);
+        ref_sum[i] = (int)ap[p.off_refa + m] + (int)wp[p.off_refw + ncol] - 256;
+    }
 
     v16i acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
     constexpr int kU = 4;                              // steps whose loads are issued together
@@ -1216,25 +1229,27 @@ __global__ __launch_bounds__(kSmallWaves * 64) void gemm_rows_kernel(GemmParams 
 #pragma unroll
         for (int x = 0; x < 16; ++x) acc[x] <<= 4 * shifts;
     }
-    // the 16 exact partial tiles: waves 8..15 hand theirs to waves 0..7, then thread (x, lane) finishes one output
-    if (wave >= kSmallWaves / 2) {
+    // the NW exact partial tiles: the upper half of the waves hands theirs to the lower, then thread
+    // (x, lane) finishes one output
+    if (wave >= NW / 2) {
 #pragma unroll
-        for (int x = 0; x < 16; ++x) u.red[wave - kSmallWaves / 2][x][lane] = acc[x];
+        for (int x = 0; x < 16; ++x) u.red[wave - NW / 2][x][lane] = acc[x];
     }
     __syncthreads();
-    if (wave < kSmallWaves / 2) {
+    if (wave < NW / 2) {
 #pragma unroll
         for (int x = 0; x < 16; ++x) u.red[wave][x][lane] += acc[x];
     }
     __syncthreads();
-    {
-        const int x = wave;
+#pragma unroll
+    for (int i = 0; i < 16 / NW; ++i) {
+        const int x = wave + i * NW;
         int sum = 0;
 #pragma unroll
-        for (int w = 0; w < kSmallWaves / 2; ++w) sum += u.red[w][x][lane];
+        for (int w = 0; w < NW / 2; ++w) sum += u.red[w][x][lane];
         const int m = m0 + 8 * (x >> 2) + 4 * h + (x & 3), n = n0 + r;
         if (m < p.M && n < p.N) {
-            const float f = ldexpf((float)sum, (int)ap[p.off_refa + m] + (int)wp[p.off_refw + n] - 256);
+            const float f = ldexpf((float)sum, ref_sum[i]);
             const int64_t o = (int64_t)m * p.ldc + n;
             if constexpr (BF16)
                 static_cast<uint16_t*>(p.out)[o] = f32_to_bf16_rne(f);
@@ -1369,9 +1384,16 @@ int launch_other(bool mx, bool bf16, GemmParams& p, int64_t batch, const dfp4_te
     if (batch > 65535) return DFP4_ERR_SHAPE;
     if (takes_small_kernel(p.M, p.KB)) {
         dim3 gs((unsigned)((p.N + 31) / 32), (unsigned)((p.M + 31) / 32), (unsigned)batch);
+        // 16 waves per tile while every tile finds a compute unit of its own; 8 beyond that, so that two
+        // workgroups share a unit (registers allow 16 waves per unit) instead of waiting for a second round
+        const bool narrow = (int64_t)gs.x * gs.y * gs.z > device_cu_count();
         dispatch_mx_bf16(mx, bf16, [&](auto mxc, auto bc) {
-            hipLaunchKernelGGL((gemm_small_kernel<decltype(mxc)::value, decltype(bc)::value>), gs,
-                               dim3(kSmallWaves * 64), 0, stream, p);
+            if (narrow)
+                hipLaunchKernelGGL((gemm_small_kernel<decltype(mxc)::value, decltype(bc)::value, 8>), gs,
+                                   dim3(8 * 64), 0, stream, p);
+            else
+                hipLaunchKernelGGL((gemm_small_kernel<decltype(mxc)::value, decltype(bc)::value, kSmallWaves>), gs,
+                                   dim3(kSmallWaves * 64), 0, stream, p);
         });
     } else {
         dim3 gb((unsigned)((p.N + 127) / 128), (unsigned)((p.M + 127) / 128), (unsigned)batch);
@@ -1498,9 +1520,14 @@ int launch_gemm_prepared(bool mx, dfp4_tensor A, void* a_prepared, dfp4_tensor W
     if (takes_small_kernel(M, KB)) {
         // few rows: the exact scheme in the shape of the few-rows kernel
         dim3 gs((unsigned)((N + 31) / 32), (unsigned)((M + 31) / 32), 1);
+        const bool narrow = (int64_t)gs.x * gs.y > device_cu_count();     // as for gemm_small_kernel
         dispatch_mx_bf16(mx, bf16, [&](auto mxc, auto bc) {
-            hipLaunchKernelGGL((gemm_rows_kernel<decltype(mxc)::value, decltype(bc)::value>), gs,
-                               dim3(kSmallWaves * 64), 0, stream, p);
+            if (narrow)
+                hipLaunchKernelGGL((gemm_rows_kernel<decltype(mxc)::value, decltype(bc)::value, 8>), gs,
+                                   dim3(8 * 64), 0, stream, p);
+            else
+                hipLaunchKernelGGL((gemm_rows_kernel<decltype(mxc)::value, decltype(bc)::value, kSmallWaves>), gs,
+                                   dim3(kSmallWaves * 64), 0, stream, p);
         });
         return check_launch();
     }
