@@ -145,6 +145,47 @@ def a_loads(aset, voff):
     return [f"global_load_dwordx4 {vr(ASET[aset] + 4 * f, 4)}, {vr(voff)}, {sr(S_ABASE + 2 * f, 2)}" for f in range(8)]
 
 
+# Slots (MFMA index within the step) after which the vector-memory loads of a step are issued.
+# DFP4_GEN_ASLOTS=early (timing experiments) issues the A loads in the first half of the step.
+A_LOAD_SLOT = ({1 + 2 * i: i for i in range(8)} if os.environ.get('DFP4_GEN_ASLOTS') == 'early'
+               else {1 + 4 * i: i for i in range(8)})                      # default: slots 1, 5, ..., 29
+CODES_SLOT, META_SLOT = 11, 15
+
+
+def vm_order():
+    """Tags of a step's vector-memory loads in issue order (the memory counter retires them in this
+    order): 'A0'..'A7', 'codes', 'meta'."""
+    o = []
+    for k in range(NSLOT):
+        if k in A_LOAD_SLOT and "noaload" not in EXP:
+            o.append(f"A{A_LOAD_SLOT[k]}")
+        if k == CODES_SLOT:
+            o.append("codes")
+        if k == META_SLOT:
+            o.append("meta")
+    return o
+
+
+class Vm:
+    """s_waitcnt vmcnt(n) for a load issued two steps ago, given how many loads this step has issued."""
+
+    def __init__(self):
+        self.order = vm_order()
+        self.issued = 0                 # loads issued so far in the current step
+        self.done = -1                  # index (two steps ago) known to have arrived
+
+    def issue(self):
+        self.issued += 1
+
+    def need(self, tag):
+        i = self.order.index(tag)
+        if i <= self.done:
+            return None
+        self.done = i
+        n = len(self.order)
+        return f"s_waitcnt vmcnt({(n - 1 - i) + n + self.issued})"
+
+
 def entry_code():
     o = []
     # global bases of the wave's 8 A fragments: a8w + gi * group stride + t * 512
@@ -167,10 +208,12 @@ def entry_code():
         o += [f"ds_read_u16 {vr(EA)}, {vr(VLADDR)} offset:{4 * p}",
               f"ds_read_u16 {vr(EW)}, {vr(VLADDR)} offset:{4 * (p + 2)}",
               "s_waitcnt lgkmcnt(0)"]
-        o += a_offset(EA, VOFF) + a_loads(p, VOFF)
-        o += w_offsets(EW, VCOFF, VMOFF)
-        o += [f"global_load_dwordx4 {vr(CODES[p], 4)}, {vr(VCOFF)}, {sr(S_WC, 2)}",
-              f"global_load_dword {vr(META[p])}, {vr(VMOFF)}, {sr(S_WM, 2)}"]
+        o += a_offset(EA, VOFF) + w_offsets(EW, VCOFF, VMOFF)
+        al = a_loads(p, VOFF)
+        for tag in vm_order():                         # same order as inside a step: the waits count on it
+            o.append(al[int(tag[1:])] if tag[0] == "A" else
+                     f"global_load_dwordx4 {vr(CODES[p], 4)}, {vr(VCOFF)}, {sr(S_WC, 2)}" if tag == "codes" else
+                     f"global_load_dword {vr(META[p])}, {vr(VMOFF)}, {sr(S_WM, 2)}")
     # offsets of the loads of step 0 (A of pair 2, W of pair 4)
     o += [f"ds_read_u16 {vr(EA)}, {vr(VLADDR)} offset:8", f"ds_read_u16 {vr(EW)}, {vr(VLADDR)} offset:16",
           "s_waitcnt lgkmcnt(0)"]
@@ -194,11 +237,13 @@ def step(v):
     o.append(f"s_cbranch_scc1 1{v}f")
     o.append(f"s_call_b64 {sr(S_RET, 2)}, 90f")
     o.append(f"1{v}:")
-    # everything issued two steps ago has arrived: this step's A fragments and W codes
-    o.append("s_waitcnt vmcnt(2)" if "noaload" in EXP else "s_waitcnt vmcnt(10)")
+    # Loads issued two steps ago are waited for where they are first used, not all at the step's
+    # start: the W codes now, the table offset at slot 3, A fragment f before MFMA slot 4 f.
+    vm = Vm()
+    o.append(vm.need("codes"))
     first, second = expansion_pieces(v)
     loads = a_loads(ld, VOFF)
-    a_load_slot = {1 + 4 * i: i for i in range(8)}                       # slots 1, 5, ..., 29
+    a_load_slot = A_LOAD_SLOT
     b_reads = {2: (1, 0), 6: (1, 1), 10: (1, 2), 14: (1, 3), 16: (0, 0), 20: (0, 1), 24: (0, 2), 27: (0, 3)}
     extra = {
         0: [f"v_add_u32 {vr(SB)}, {sr(S_BCUR)}, %[l16]", f"v_add_u32 {vr(SBN)}, {sr(S_BNXT)}, %[l16]"],
@@ -219,6 +264,10 @@ def step(v):
             if w:
                 o.append(w)
         acc = f"a[{16 * (4 * gi + n)}:{16 * (4 * gi + n) + 15}]"
+        if k % 4 == 0 and "noaload" not in EXP:
+            w = vm.need(f"A{k // 4}")
+            if w:
+                o.append(w)
         o.append(f"v_mfma_i32_32x32x32_i8 {acc}, {vr(ASET[v] + 4 * (4 * t + gi), 4)}, {vr(BBUF[t] + 4 * n, 4)}, {acc}")
         if k in b_reads and "nobread" not in EXP:
             bt, bn = b_reads[k]
@@ -236,12 +285,19 @@ def step(v):
             o.append(piece[0])
         if k in a_load_slot and "noaload" not in EXP:
             o.append(loads[a_load_slot[k]])
-        if k == 11:
+            vm.issue()
+        if k == CODES_SLOT:
             o.append(f"global_load_dwordx4 {vr(CODES[ld], 4)}, {vr(VCOFF)}, {sr(S_WC, 2)}")
-        if k == 15:
+            vm.issue()
+        if k == META_SLOT:
             o.append(f"global_load_dword {vr(META[ld])}, {vr(VMOFF)}, {sr(S_WM, 2)}")
+            vm.issue()
         if piece:
             o.append(piece[1])
+        if k == 3:                                    # the table offset of this step's expansion
+            w = vm.need("meta")
+            if w:
+                o.append(w)
         for ins in extra.get(k, []):
             o.append(ins)
             if ins.startswith("ds_read_u16") or ins.startswith("ds_read_b128"):
