@@ -1097,19 +1097,22 @@ __global__ __launch_bounds__(NW * 64) void gemm_small_kernel(GemmParams p) {
 
 // ---------------------------------------------------------------------------
 // Few rows of A on PREPARED operands (decode shapes with weights prepared offline): the exact
-// scheme of the large kernel -- exponent offsets folded into the int8 operands, classes handled by
-// shifting the int32 accumulators, one conversion at the end -- in the shape of the few-rows kernel:
-// a workgroup of 16 waves owns 32 rows of A x 32 rows of W, the waves share the list of (block,
-// class of A, class of W) visits in equal slices, each expands the 4-bit codes of W for its visits
-// (A comes expanded from the prepared form, which is small and stays in cache), and the 16 exact
-// int32 partial tiles are added through LDS.  No per-block floating-point work at all, so the
-// kernel follows the stream of W.  A tile the scheme cannot take is computed by small_tile().
+// scheme of the large kernel -- exponent offsets folded into the int8 operands, classes weighted
+// by 16^(class of A + class of W), one conversion at the end -- in the shape of the few-rows
+// kernel: a workgroup of NW waves owns 32 rows of A x 32 rows of W and the waves share K in
+// contiguous ranges of block pairs.  The kernel is bound by latency, so it keeps the chain of
+// dependent memory accesses short: there is no list of visits.  A wave issues, before anything
+// else, the loads of its first pairs for the common case (class 0 of both operands): class masks,
+// codes and table offsets of W, expanded fragments of A.  The masks come back first; a block that
+// has other classes as well (rare: outlier channels) gets extra products, each computed into a
+// temporary tile and added with its weight 16^(class sum), which is exact in int32 under the same
+// bound the large kernel checks.  Whether the tile can be taken at all is decided by every wave
+// from the masks of all of K (same data, same decision).  The NW exact partial tiles are added
+// through LDS.  A tile the scheme cannot take is computed by small_tile().
 // ---------------------------------------------------------------------------
 template <bool MX, bool BF16, int NW>
 __global__ __launch_bounds__(NW * 64) void gemm_rows_kernel(GemmParams p) {
     __shared__ __attribute__((aligned(16))) uint32_t s_tab[kDialects * 16 + 4];
-    __shared__ uint16_t s_vl[kVisitCap];
-    __shared__ int s_ctl[8];
     __shared__ union {
         int red[kSmallWaves / 2][16][64];
         SmallTileLds small;
@@ -1120,66 +1123,51 @@ __global__ __launch_bounds__(NW * 64) void gemm_rows_kernel(GemmParams p) {
     const int m0 = blockIdx.y * 32, n0 = blockIdx.x * 32;
     const uint8_t* ap = p.a_prep;
     const uint8_t* wp = p.w_prep;
-
-    for (int i = tid; i < kDialects * 16 + 4; i += NW * 64)
-        s_tab[i] = i < kDialects * 16 ? (&g_shifted_book.w[0][0][0])[i] : 0u;
-    if (tid < 8) s_ctl[tid] = 0;
-    if (wave == 0) {
-        // visits of all of K, ordered by class sum (see gemm_fast_kernel); the masks are those of the
-        // 512-row tile of A and the 128-row tile of W these rows belong to
-        const uint8_t* mask_a = ap + p.off_mask + (int64_t)(m0 / kTileM) * KB;
-        const uint8_t* mask_w = wp + p.off_wmask + (int64_t)(n0 / kTileN) * KB;
-        uint32_t ma[kMaxKB / 64], mw[kMaxKB / 64];
-        bool bad = false;
-#pragma unroll
-        for (int j = 0; j < kMaxKB / 64; ++j) {
-            const int kb = j * 64 + lane;
-            ma[j] = kb < KB ? mask_a[kb] : 0u;
-            mw[j] = kb < KB ? mask_w[kb] : 0u;
-            const int ha = 31 - __builtin_clz(ma[j] | 1u), hw = 31 - __builtin_clz(mw[j] | 1u);
-            bad |= ha + hw > kMaxClass;
-        }
-        int pos = 0, weight = 0;
-        for (int ct = kMaxClass; ct >= 0; --ct) {
-            for (int ca = 0; ca <= ct; ++ca) {
-                const int cw = ct - ca;
-#pragma unroll
-                for (int j = 0; j < kMaxKB / 64; ++j) {
-                    if (j * 64 >= KB) break;                          // uniform
-                    const int kb = j * 64 + lane;
-                    const bool f = ((ma[j] >> ca) & 1u) && ((mw[j] >> cw) & 1u);
-                    const unsigned long long bal = __ballot(f);
-                    weight += __popcll(bal) << (4 * ct);
-                    if (f) s_vl[pos + __popcll(bal & ((1ull << lane) - 1ull))] = (uint16_t)(kb | (ca << 10) | (cw << 12));
-                    pos += __popcll(bal);
-                }
-            }
-            if (pos & 1) {
-                if (lane == 0) s_vl[pos] = (uint16_t)KB;              // padding: the all-zero block of class 0
-                pos += 1;
-            }
-            if (lane == 0) s_ctl[kMaxClass - ct] = pos;               // ends of class sums 2, 1, 0
-        }
-        if ((__ballot(bad) != 0ull || weight > kIntBound) && lane == 0) s_ctl[4] = 1;
-    }
-    __syncthreads();
-    if (s_ctl[4] != 0) {
-        if (tid == 0 && blockIdx.x % (kTileN / 32) == 0)   // counted once per 512 x 128 tile, like the large kernel
-            atomicAdd(reinterpret_cast<uint32_t*>(const_cast<uint8_t*>(ap) + p.off_cnt) + kMaxSplitTiles, 1u);
-        small_tile<MX, BF16, NW>(p, 0, m0, n0, u.small);
-        return;
-    }
-    // this wave's slice of the steps (a step = two visits of the same class sum)
-    const int end2 = s_ctl[0] / 2, end1 = s_ctl[1] / 2, total = s_ctl[2] / 2;
-    const int per = (total + NW - 1) / NW;
-    const int s_lo = min(total, wave * per), s_hi = min(total, s_lo + per);
+    const uint8_t* mask_a = ap + p.off_mask + (int64_t)(m0 / kTileM) * KB;      // classes of the 512-row tile of A
+    const uint8_t* mask_w = wp + p.off_wmask + (int64_t)(n0 / kTileN) * KB;     // and of the 128-row tile of W
 
     const uint32_t grp_stride = (uint32_t)(KB + 1) * 1024u;
-    const uint32_t cls_stride = (uint32_t)p.tiles_m * kGroups * grp_stride;
+    const uint64_t cls_stride = (uint64_t)p.tiles_m * kGroups * grp_stride;
     const uint8_t* a8 = ap + p.off_a8 + (uint64_t)(m0 / 32) * grp_stride + (uint32_t)r * 16u;
     const int ncol = min(n0 + r, p.N - 1);
     const uint8_t* wcodes = p.w_codes + (uint64_t)ncol * KB * 16u;
     const uint8_t* wmeta = wp + p.off_wmeta + (uint64_t)ncol * KB * 4u;
+
+    // this wave's range of block pairs (lane half h takes block 2 * pair + h)
+    const int P = (KB + 1) / 2, per = (P + NW - 1) / NW;
+    const int p_lo = min(P, wave * per), p_hi = min(P, p_lo + per);
+    constexpr int kU = 4;                              // pairs whose loads are issued together
+    uint32_t mA[kU], mW[kU], meta[kU];
+    uint4 wc[kU];
+    v4i af[kU][2];
+    auto issue = [&](int g0) {
+#pragma unroll
+        for (int q = 0; q < kU; ++q) {                 // the masks first: they are needed first
+            const int kb = 2 * min(g0 + q, p_hi - 1) + h;
+            mA[q] = kb < KB ? mask_a[kb] : 0u;
+            mW[q] = kb < KB ? mask_w[kb] : 0u;
+        }
+#pragma unroll
+        for (int q = 0; q < kU; ++q) {
+            const int kb = 2 * min(g0 + q, p_hi - 1) + h, kbw = min(kb, KB - 1);
+            wc[q] = *reinterpret_cast<const uint4*>(wcodes + (uint32_t)kbw * 16u);
+            meta[q] = *reinterpret_cast<const uint32_t*>(wmeta + (uint32_t)kbw * 4u);          // class 0 of W
+            const uint8_t* src = a8 + (uint32_t)min(kb, KB) * 1024u;                          // class 0 of A; KB = zeros
+            af[q][0] = *reinterpret_cast<const v4i*>(src);
+            af[q][1] = *reinterpret_cast<const v4i*>(src + 512);
+        }
+    };
+    // loads in the order their values are needed: the masks of all of K (the decision below), the
+    // table, then the first pairs' operands
+    uint32_t da[kMaxKB / 64], dw[kMaxKB / 64];
+#pragma unroll
+    for (int j = 0; j < kMaxKB / 64; ++j) {
+        const int kb = j * 64 + lane;
+        da[j] = kb < KB ? mask_a[kb] : 0u;
+        dw[j] = kb < KB ? mask_w[kb] : 0u;
+    }
+    const uint32_t tab_word = tid < kDialects * 16 ? (&g_shifted_book.w[0][0][0])[tid] : 0u;
+    if (p_lo < p_hi) issue(p_lo);
 
     // reference exponents of the outputs this thread finishes (x = wave, wave + NW, ..): loaded now, used last
     int ref_sum[16 / NW];
@@ -1189,45 +1177,90 @@ __global__ __launch_bounds__(NW * 64) void gemm_rows_kernel(GemmParams p) {
         const int m = min(m0 + 8 * (x >> 2) + 4 * h + (x & 3), p.M - 1);
         ref_sum[i] = (int)ap[p.off_refa + m] + (int)wp[p.off_refw + ncol] - 256;
     }
+    // Can the tile be taken?  Classes beyond those kept, or a sum of weights an int32 accumulator
+    // could not hold.  Every wave decides from the masks of all of K.
+    bool declined;
+    {
+        bool bad = false;
+        int weight = 0;
+#pragma unroll
+        for (int j = 0; j < kMaxKB / 64; ++j) {
+            if (j * 64 >= KB) break;                   // uniform
+            const uint32_t a = da[j], w = dw[j];
+            const int ha = 31 - __builtin_clz(a | 1u), hw = 31 - __builtin_clz(w | 1u);
+            bad |= ha + hw > kMaxClass;
+#pragma unroll
+            for (int ct = 0; ct <= kMaxClass; ++ct)
+#pragma unroll
+                for (int ca = 0; ca <= ct; ++ca)
+                    weight += __popcll(__ballot(((a >> ca) & 1u) && ((w >> (ct - ca)) & 1u))) << (4 * ct);
+        }
+        declined = __ballot(bad) != 0ull || weight > kIntBound;
+    }
+    if (tid < kDialects * 16 + 4) s_tab[tid] = tab_word;        // NW * 64 >= 512 > 260 entries
+    __syncthreads();
+    if (declined) {
+        if (tid == 0 && blockIdx.x % (kTileN / 32) == 0)   // counted once per 512 x 128 tile, like the large kernel
+            atomicAdd(reinterpret_cast<uint32_t*>(const_cast<uint8_t*>(ap) + p.off_cnt) + kMaxSplitTiles, 1u);
+        small_tile<MX, BF16, NW>(p, 0, m0, n0, u.small);
+        return;
+    }
 
     v16i acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-    constexpr int kU = 4;                              // steps whose loads are issued together
-    for (int s0 = s_lo; s0 < s_hi; s0 += kU) {
-        uint4 wc[kU];
-        uint32_t meta[kU];
-        v4i af[kU][2];
+    const v4i zero4 = {0, 0, 0, 0};
+    bool any_odd = false;                              // some block of this wave's range has other classes too
+    for (int g0 = p_lo; g0 < p_hi; g0 += kU) {
+        if (g0 != p_lo) issue(g0);
+        bool odd = false;
+#pragma unroll
+        for (int q = 0; q < kU; ++q) odd |= g0 + q < p_hi && 2 * (g0 + q) + h < KB && (mA[q] != 1u || mW[q] != 1u);
+        const bool mixed = __ballot(odd) != 0ull;      // uniform
+        any_odd |= mixed;
 #pragma unroll
         for (int q = 0; q < kU; ++q) {
-            const int st = min(s0 + q, s_hi - 1);      // the tail repeats the last step (not used)
-            const uint32_t entry = s_vl[2 * st + h];
-            const uint32_t kb = entry & 1023u, kbw = min(kb, (uint32_t)KB - 1u);
-            wc[q] = *reinterpret_cast<const uint4*>(wcodes + kbw * 16u);
-            meta[q] = *reinterpret_cast<const uint32_t*>(wmeta + ((entry >> 12) & 3u) * (uint64_t)p.wmeta_cls_stride + kbw * 4u);
-            const uint8_t* af_src = a8 + ((entry >> 10) & 3u) * (uint64_t)cls_stride + kb * 1024u;
-            af[q][0] = *reinterpret_cast<const v4i*>(af_src);
-            af[q][1] = *reinterpret_cast<const v4i*>(af_src + 512);
-        }
-#pragma unroll
-        for (int q = 0; q < kU; ++q) {
-            const int st = s0 + q;
-            if (st >= s_hi) break;                     // wave-uniform
-            // between class sums the accumulators move up by four bits (Horner's scheme)
-            const int levels = (st == end2 ? 1 : 0) + (st == end1 ? 1 : 0);      // both when a class sum is absent
-            if (levels != 0 && st != s_lo) {
-#pragma unroll
-                for (int x = 0; x < 16; ++x) acc[x] <<= 4 * levels;
-            }
+            if (g0 + q >= p_hi) break;                 // wave-uniform
             const uint4 tab = *reinterpret_cast<const uint4*>(reinterpret_cast<const uint8_t*>(s_tab) + meta[q]);
             const v4i b0 = unpack16(wc[q].x, wc[q].y, tab), b1 = unpack16(wc[q].z, wc[q].w, tab);
-            acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[q][0], b0, acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[q][1], b1, acc, 0, 0, 0);
+            v4i a0 = af[q][0], a1 = af[q][1];
+            if (mixed) {                               // a class-0 fragment exists only where the tile has class 0
+                const bool have = (mA[q] & 1u) != 0u && 2 * (g0 + q) + h < KB;
+                a0 = have ? a0 : zero4;
+                a1 = have ? a1 : zero4;
+            }
+            acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(a0, b0, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(a1, b1, acc, 0, 0, 0);
         }
     }
-    // bring the slice's sum to the weight of class sum 0: one shift per class boundary at or after its end
-    if (s_hi > s_lo) {
-        const int shifts = (s_hi <= end2 ? 1 : 0) + (s_hi <= end1 ? 1 : 0);
+    // The other class pairs (rare: blocks with outliers), pair by pair: lanes whose block has the
+    // class pair bring its operands, the others zeros; the product goes to a temporary tile and is
+    // added with its weight.
+    if (any_odd) {
+        for (int pr = p_lo; pr < p_hi; ++pr) {
+            const int kb = 2 * pr + h;
+            const uint32_t kbw = (uint32_t)min(kb, KB - 1);
+            const uint32_t ma = kb < KB ? mask_a[kb] : 0u, mw = kb < KB ? mask_w[kb] : 0u;
+            if (__ballot((ma | mw) > 1u) == 0ull) continue;
+            const uint4 codes = *reinterpret_cast<const uint4*>(wcodes + kbw * 16u);
+            for (int ct = 1; ct <= kMaxClass; ++ct) {
+                for (int ca = 0; ca <= ct; ++ca) {
+                    const int cw = ct - ca;
+                    const bool part = ((ma >> ca) & 1u) && ((mw >> cw) & 1u);
+                    if (__ballot(part) == 0ull) continue;
+                    const uint8_t* src = a8 + (uint64_t)ca * cls_stride + kbw * 1024u;
+                    const v4i x0 = part ? *reinterpret_cast<const v4i*>(src) : zero4;
+                    const v4i x1 = part ? *reinterpret_cast<const v4i*>(src + 512) : zero4;
+                    const uint32_t mt = *reinterpret_cast<const uint32_t*>(
+                        wmeta + (uint64_t)cw * p.wmeta_cls_stride + kbw * 4u);
+                    const uint4 tab = *reinterpret_cast<const uint4*>(reinterpret_cast<const uint8_t*>(s_tab) + mt);
+                    const v4i b0 = unpack16(codes.x, codes.y, tab), b1 = unpack16(codes.z, codes.w, tab);
+                    v16i t16 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+                    t16 = __builtin_amdgcn_mfma_i32_32x32x32_i8(x0, b0, t16, 0, 0, 0);
+                    t16 = __builtin_amdgcn_mfma_i32_32x32x32_i8(x1, b1, t16, 0, 0, 0);
 #pragma unroll
-        for (int x = 0; x < 16; ++x) acc[x] <<= 4 * shifts;
+                    for (int x = 0; x < 16; ++x) acc[x] += t16[x] << (4 * ct);
+                }
+            }
+        }
     }
     // the NW exact partial tiles: the upper half of the waves hands theirs to the lower, then thread
     // (x, lane) finishes one output
