@@ -48,8 +48,9 @@
 //                        (or whose int32 sum could overflow) is computed by the same
 //                        workgroup with one fp32 scale-and-add per block;
 //   gemm_rows_kernel     the same exact scheme for at most 64 rows of A on prepared
-//                        operands (decode shapes): 32 x 32 outputs per workgroup, 16
-//                        waves share the visits;
+//                        operands (decode shapes): 32 x 32 outputs per workgroup, its 16
+//                        (or 8) waves share K; no list of visits, the class pairs other
+//                        than (0, 0) are added with their weights afterwards;
 //   gemm_small_kernel    at most 64 rows of A, nothing prepared: per-block fp32 flush;
 //   gemm_block_kernel    whole products with K > 16384: per-block fp32 flush;
 //   gemm_block16_kernel  operands quantized in blocks of 16: per-block fp32 flush.
