@@ -641,6 +641,14 @@ __global__ __launch_bounds__(256, 1) void gemm_fast_kernel(GemmParams p) {
     __shared__ int s_ctl[8];                 // segment ends (entries), feasibility
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+#ifdef DFP4_TIMING_STAMPS   // timing experiments only: 100 MHz timestamps of the kernel's phases, into the workspace
+#define DFP4_STAMP(I)                                                                                   \
+    if (tid == 0 && p.ksplit == 1 && p.part && blockIdx.y == 0 && blockIdx.z == 0 && blockIdx.x < 64)   \
+        reinterpret_cast<unsigned long long*>(p.part)[blockIdx.x * 8 + (I)] = wall_clock64();
+#else
+#define DFP4_STAMP(I)
+#endif
+    DFP4_STAMP(0)
     const int KB = p.KB;
     const int m0 = blockIdx.y * kTileM, n0 = blockIdx.x * kTileN;
     const int S = p.ksplit, sidx = (int)(blockIdx.z % (unsigned)S);
@@ -706,6 +714,7 @@ __global__ __launch_bounds__(256, 1) void gemm_fast_kernel(GemmParams p) {
         }
     }
     __syncthreads();
+    DFP4_STAMP(1)
     // segment ends in steps (uniform: they go to the loop in scalar registers)
     const int end2 = __builtin_amdgcn_readfirstlane(s_ctl[0] / 2), end1 = __builtin_amdgcn_readfirstlane(s_ctl[1] / 2),
               total = __builtin_amdgcn_readfirstlane(s_ctl[2] / 2);
@@ -747,7 +756,11 @@ __global__ __launch_bounds__(256, 1) void gemm_fast_kernel(GemmParams p) {
     const uint32_t grp_stride = (uint32_t)(KB + 1) * 1024u;
     const uint32_t cls_stride = (uint32_t)p.tiles_m * kGroups * grp_stride;
     const uint32_t tile_off = (uint32_t)blockIdx.y * kGroups * grp_stride;
+#ifdef DFP4_TIMING_SAME_A   // timing experiments only: every wave reads the fragments of wave 0 (wrong results)
+    const uint8_t* a8w = ap + p.off_a8;
+#else
     const uint8_t* a8w = ap + p.off_a8 + (uint64_t)wave_u * 4u * grp_stride;   // uniform per wave
+#endif
     const uint8_t* wcodes = p.w_codes + bz * p.strideW_rows * KB * 16;        // uniform
     const uint8_t* wmeta = wp + p.off_wmeta;                                  // uniform
     const int ncol = min(n0 + wave * 32 + r, p.N - 1);                        // this lane's W row
@@ -767,6 +780,7 @@ __global__ __launch_bounds__(256, 1) void gemm_fast_kernel(GemmParams p) {
         *reinterpret_cast<v4i*>(&s_b[s][(wave * 2 + 1) * 1024 + lane * 16]) = unpack16(c.z, c.w, tab);
     }
     __syncthreads();
+    DFP4_STAMP(2)
 
     // ---- main loop (gemm_step_asm.inc): accumulators in a[0:255]
     {
@@ -788,6 +802,7 @@ __global__ __launch_bounds__(256, 1) void gemm_fast_kernel(GemmParams p) {
                      : DFP4_LOOP_VGPR_CLOBBERS, DFP4_ACC_CLOBBERS, DFP4_LOOP_SGPR_CLOBBERS, "scc", "memory");
     }
 
+    DFP4_STAMP(3)
     // ---- epilogue (nothing to store or publish for a wave whose 128 rows lie beyond M)
     if constexpr (RQ) {
         if constexpr (MX) {
@@ -977,6 +992,8 @@ __global__ __launch_bounds__(256, 1) void gemm_fast_kernel(GemmParams p) {
         }
 #undef DFP4_FINISH
     }
+    DFP4_STAMP(4)
+#undef DFP4_STAMP
 #undef DFP4_FOR_TILES
 #undef DFP4_READ_TILE
 #undef DFP4_READ_ACC

@@ -63,7 +63,8 @@ S_ABASE, S_VC, S_SEGEND, S_SEG, S_RET, S_BCUR, S_BNXT, S_BW, S_T0, S_T1 = 60, 76
 S_WC, S_WM = 88, 90
 NSLOT = 32
 # Timing experiments only (results are wrong, every address stays the same): a comma-separated list in
-# DFP4_GEN_EXP drops parts of the step -- noexpand (W expansion), nobarrier, noaload (A loads), nobread (LDS reads of B).
+# DFP4_GEN_EXP drops parts of the step -- noexpand (W expansion), nobarrier, noaload (A loads), nobread (LDS reads of B),
+# nomfma (the MFMAs themselves).
 EXP = set(filter(None, os.environ.get('DFP4_GEN_EXP', '').split(',')))
 FRAG = 1024                    # bytes per operand fragment
 B_BUF_BYTES = 8 * FRAG
@@ -147,18 +148,27 @@ def a_loads(aset, voff):
 
 # Slots (MFMA index within the step) after which the vector-memory loads of a step are issued.
 # DFP4_GEN_ASLOTS=early (timing experiments) issues the A loads in the first half of the step.
+# Slots (MFMA index within the step) after which the eight A loads of a step are issued.  Measured and
+# found to make no difference: issuing them in the first half of the step (DFP4_GEN_ASLOTS=early), and
+# giving each wave its own copy of the loop with the loads one slot apart from the other waves'.
 A_LOAD_SLOT = ({1 + 2 * i: i for i in range(8)} if os.environ.get('DFP4_GEN_ASLOTS') == 'early'
                else {1 + 4 * i: i for i in range(8)})                      # default: slots 1, 5, ..., 29
-CODES_SLOT, META_SLOT = 11, 15
+CODES_SLOT, META_SLOT = ((0, 2) if os.environ.get('DFP4_GEN_WSLOTS') == 'early' else (11, 15))
+
+
+# LDS operations of a step that its own waits do not cover, in issue order: next step's phase-0 B
+# fragments (slots 16, 20, 24, 27) and the writes of the expanded operands (slots 22, 28)
+LDS_TAIL = (["w0", "w1"] if "nobread" in EXP else ["b00", "b01", "w0", "b02", "b03", "w1"])
 
 
 def vm_order():
     """Tags of a step's vector-memory loads in issue order (the memory counter retires them in this
     order): 'A0'..'A7', 'codes', 'meta'."""
+    slots = A_LOAD_SLOT
     o = []
     for k in range(NSLOT):
-        if k in A_LOAD_SLOT and "noaload" not in EXP:
-            o.append(f"A{A_LOAD_SLOT[k]}")
+        if k in slots and "noaload" not in EXP:
+            o.append(f"A{slots[k]}")
         if k == CODES_SLOT:
             o.append("codes")
         if k == META_SLOT:
@@ -226,24 +236,32 @@ def entry_code():
     return o
 
 
-def step(v):
-    """One step with A set v, code set v (both step % 3).  Everything that is not an MFMA is
+UNROLL = 3                      # steps per loop iteration (a multiple of the 3 register sets)
+
+
+def step(v, u=None):
+    """One step with A set v, code set v (both step % 3); u: its position in the unrolled loop.  Everything that is not an MFMA is
     spread over the MFMA slots, the barrier included, so that the matrix core never waits at
     the step boundary."""
     o = []
+    # LDS operations complete in order.  Those the previous step issued after its last wait may still
+    # be in flight (next-phase B fragments read from slot 16 on, the two writes of expanded operands):
+    # they are waited for where this step first needs them, not at the step boundary.
     lg = Lgkm()
+    lg.q = ["p:" + t for t in LDS_TAIL]
     ld = (v + 2) % 3
+    u = v if u is None else u
+    # the common path falls through; the end of a class segment (three times per tile) is handled out of line
     o.append(f"s_cmp_lt_u32 {sr(S_VC)}, {sr(S_SEGEND)}")
-    o.append(f"s_cbranch_scc1 1{v}f")
-    o.append(f"s_call_b64 {sr(S_RET, 2)}, 90f")
-    o.append(f"1{v}:")
+    o.append(f"s_cbranch_scc0 2{u}f")
+    o.append(f"1{u}:")
     # Loads issued two steps ago are waited for where they are first used, not all at the step's
     # start: the W codes now, the table offset at slot 3, A fragment f before MFMA slot 4 f.
+    a_load_slot = A_LOAD_SLOT
     vm = Vm()
     o.append(vm.need("codes"))
     first, second = expansion_pieces(v)
     loads = a_loads(ld, VOFF)
-    a_load_slot = A_LOAD_SLOT
     b_reads = {2: (1, 0), 6: (1, 1), 10: (1, 2), 14: (1, 3), 16: (0, 0), 20: (0, 1), 24: (0, 2), 27: (0, 3)}
     extra = {
         0: [f"v_add_u32 {vr(SB)}, {sr(S_BCUR)}, %[l16]", f"v_add_u32 {vr(SBN)}, {sr(S_BNXT)}, %[l16]"],
@@ -257,6 +275,10 @@ def step(v):
         # waited for at its end) and has finished reading the buffer this step overwrites
         12: [] if "nobarrier" in EXP else ["s_barrier"],
     }
+    if "skew" in EXP:      # timing experiment: after the barrier wave w idles about 20 w cycles
+        extra[12] = extra[12] + [f"s_mov_b32 {sr(S_T1)}, %[wv]", f"7{v}:", f"s_cmp_eq_u32 {sr(S_T1)}, 0",
+                                 f"s_cbranch_scc1 8{v}f", "s_nop 15", f"s_sub_u32 {sr(S_T1)}, {sr(S_T1)}, 1",
+                                 f"s_branch 7{v}b", f"8{v}:"]
     for k in range(NSLOT):
         t, gi, n = k // 16, (k % 16) // 4, k % 4
         if k >= 16:
@@ -264,11 +286,16 @@ def step(v):
             if w:
                 o.append(w)
         acc = f"a[{16 * (4 * gi + n)}:{16 * (4 * gi + n) + 15}]"
+        if k < 4:                                     # phase-0 fragment n, read during the previous step
+            w = lg.need(f"p:b0{n}")
+            if w:
+                o.append(w)
         if k % 4 == 0 and "noaload" not in EXP:
             w = vm.need(f"A{k // 4}")
             if w:
                 o.append(w)
-        o.append(f"v_mfma_i32_32x32x32_i8 {acc}, {vr(ASET[v] + 4 * (4 * t + gi), 4)}, {vr(BBUF[t] + 4 * n, 4)}, {acc}")
+        if "nomfma" not in EXP:
+            o.append(f"v_mfma_i32_32x32x32_i8 {acc}, {vr(ASET[v] + 4 * (4 * t + gi), 4)}, {vr(BBUF[t] + 4 * n, 4)}, {acc}")
         if k in b_reads and "nobread" not in EXP:
             bt, bn = b_reads[k]
             src = SB if bt == 1 else SBN
@@ -298,6 +325,10 @@ def step(v):
             w = vm.need("meta")
             if w:
                 o.append(w)
+        if k == 12:                                   # own writes of the previous step, before the barrier
+            w = lg.need("p:w1")
+            if w:
+                o.append(w)
         for ins in extra.get(k, []):
             o.append(ins)
             if ins.startswith("ds_read_u16") or ins.startswith("ds_read_b128"):
@@ -315,8 +346,8 @@ def step(v):
             o += a_offset(EA, VOFF)
         if k == 31:
             o += w_offsets(EW, VCOFF, VMOFF)
-    # the expanded operands are in LDS and next step's first B fragments have arrived
-    o.append("s_waitcnt lgkmcnt(0)")
+    # what is still in flight here is what the next step expects (LDS_TAIL)
+    assert lg.q == LDS_TAIL, (lg.q, LDS_TAIL)
     return o
 
 
@@ -349,9 +380,11 @@ def main_loop():
     o = [f"v_accvgpr_write_b32 a{n}, 0" for n in range(256)]
     o += entry_code()
     o.append("80:")
-    for v in range(3):
-        o += step(v)
+    for u in range(UNROLL):
+        o += step(u % 3, u)
     o.append("s_branch 80b")
+    for u in range(UNROLL):                      # out of line: the step counter has reached the segment's end
+        o += [f"2{u}:", f"s_call_b64 {sr(S_RET, 2)}, 90f", f"s_branch 1{u}b"]
     o += handler()
     o += ["99:", "s_waitcnt vmcnt(0) lgkmcnt(0)"] + DRAIN
     return o
