@@ -119,7 +119,7 @@ struct GemmParams {
     uint8_t* w_prep;
     int64_t a_prep_stride, w_prep_stride;
     int64_t off_refa, off_mask, off_cnt, off_a8;      // inside a prepared A
-    int64_t off_refw, off_wmask, off_wmeta;           // inside a prepared W
+    int64_t off_refw, off_wmask, off_wmeta, off_wcodes;   // inside a prepared W
     uint32_t wmeta_cls_stride;                        // bytes between the table dwords of two classes
     // exact int32 partial tiles of workgroups that share an output tile (split K)
     int* part;
@@ -149,17 +149,21 @@ inline PrepALayout prep_a_layout(int64_t M, int64_t KB) {
     return l;
 }
 // Prepared W [N, K]: per-row reference exponents (rows padded to 128), one class mask per
-// (128-row tile, block), and per class and block one dword naming the block's (dialect, shift)
-// table -- or the all-zero table where the block is of another class: [class][row][block].
-// W itself stays 4-bit.
-struct PrepWLayout { int64_t off_refw, off_wmask, off_wmeta, total; };
+// (128-row tile, block), per class and block one dword naming the block's (dialect, shift)
+// table -- or the all-zero table where the block is of another class -- and a copy of the 4-bit
+// codes.  Table dwords and codes are laid out by 32-row group and block, [group][block][row]
+// (codes: 16 bytes per row and block; dwords: [class][group][block][row]), so that what a wave
+// loads for one block of its 32 rows is one contiguous run of 512 (128) bytes: four (one) cache
+// lines instead of 32.  Rows of the last group beyond N carry the all-zero table.
+struct PrepWLayout { int64_t off_refw, off_wmask, off_wmeta, off_wcodes, total; };
 inline PrepWLayout prep_w_layout(int64_t N, int64_t KB) {
-    const int64_t tn = (N + kTileN - 1) / kTileN;
+    const int64_t tn = (N + kTileN - 1) / kTileN, rows = tn * kTileN;
     PrepWLayout l{};
     l.off_refw = 0;
-    l.off_wmask = align256(tn * kTileN);
+    l.off_wmask = align256(rows);
     l.off_wmeta = align256(l.off_wmask + tn * KB);
-    l.total = align256(l.off_wmeta + (kMaxClass + 1) * N * KB * 4);
+    l.off_wcodes = align256(l.off_wmeta + (kMaxClass + 1) * rows * KB * 4);
+    l.total = align256(l.off_wcodes + rows * KB * 16);
     return l;
 }
 // Workgroups per output tile: when there are fewer tiles than compute units, K is split
@@ -276,17 +280,27 @@ __global__ __launch_bounds__(1024) void gemm_prep_kernel(GemmParams p, int n_a, 
         mn = min(mn, __shfl_xor(mn, 2));
         mn = min(mn, __shfl_xor(mn, 4));
         __syncthreads();
-        if (valid) {
-            if (seg == 0 && chunk == 0) wp[p.off_refw + row] = (uint8_t)mn;
-            uint32_t* wmeta = reinterpret_cast<uint32_t*>(wp + p.off_wmeta) + (int64_t)row * KB;
-            const int64_t cls_stride = (int64_t)p.N * KB;                // dwords
+        {
+            if (valid && seg == 0 && chunk == 0) wp[p.off_refw + row] = (uint8_t)mn;
+            // [group of 32 rows][block][row]: this row's slot within block 0 of its group
+            const int64_t slot = (int64_t)(row >> 5) * KB * 32 + (row & 31);
+            uint32_t* wmeta = reinterpret_cast<uint32_t*>(wp + p.off_wmeta) + slot;
+            uint4* wct = reinterpret_cast<uint4*>(wp + p.off_wcodes) + slot;
+            const uint4* wcs = reinterpret_cast<const uint4*>(p.w_codes) + base;
+            const int64_t cls_stride = (int64_t)p.tiles_n * kTileN * KB;     // dwords
             for (int kb = kc + seg; kb < ke; kb += 8) {
-                const uint32_t delta = (uint32_t)we[kb] - (uint32_t)mn;
-                const uint32_t cls = min(delta >> 2, (uint32_t)kMaxClass + 1u), dd = MX ? 7u : ((uint32_t)wd[kb] & 15u);
-                const uint32_t tab = (dd * 4u + (delta & 3u)) * 16u;
+                uint32_t cls = kMaxClass + 2, tab = kZeroTab;               // rows beyond N: the all-zero table
+                if (valid) {
+                    const uint32_t delta = (uint32_t)we[kb] - (uint32_t)mn;
+                    const uint32_t dd = MX ? 7u : ((uint32_t)wd[kb] & 15u);
+                    cls = min(delta >> 2, (uint32_t)kMaxClass + 1u);
+                    tab = (dd * 4u + (delta & 3u)) * 16u;
+                    wct[(int64_t)kb * 32] = wcs[kb];
+                    atomicOr(&s_wmask[kb - kc], 1u << cls);
+                }
 #pragma unroll
-                for (uint32_t c = 0; c <= (uint32_t)kMaxClass; ++c) wmeta[c * cls_stride + kb] = cls == c ? tab : kZeroTab;
-                atomicOr(&s_wmask[kb - kc], 1u << cls);
+                for (uint32_t c = 0; c <= (uint32_t)kMaxClass; ++c)
+                    wmeta[c * cls_stride + (int64_t)kb * 32] = cls == c ? tab : kZeroTab;
             }
         }
         __syncthreads();
@@ -761,20 +775,21 @@ __global__ __launch_bounds__(256, 1) void gemm_fast_kernel(GemmParams p) {
 #else
     const uint8_t* a8w = ap + p.off_a8 + (uint64_t)wave_u * 4u * grp_stride;   // uniform per wave
 #endif
-    const uint8_t* wcodes = p.w_codes + bz * p.strideW_rows * KB * 16;        // uniform
-    const uint8_t* wmeta = wp + p.off_wmeta;                                  // uniform
-    const int ncol = min(n0 + wave * 32 + r, p.N - 1);                        // this lane's W row
-    const uint32_t w_row_codes = (uint32_t)ncol * (uint32_t)KB * 16u;
-    const uint32_t w_row_meta = (uint32_t)ncol * (uint32_t)KB * 4u;
+    const uint8_t* wcodes = wp + p.off_wcodes;                                // uniform; [group][block][row]
+    const uint8_t* wmeta = wp + p.off_wmeta;                                  // uniform; [class][group][block][row]
+    const int ncol = n0 + wave * 32 + r;                // this lane's W row (rows beyond N exist: all-zero tables)
+    // this lane's row of W: slot (row % 32) of block 0 of its 32-row group; a block further is 32 slots further
+    const uint32_t w_slot = (uint32_t)(ncol >> 5) * (uint32_t)KB * 32u + (uint32_t)(ncol & 31);
+    const uint32_t w_row_codes = w_slot * 16u, w_row_meta = w_slot * 4u;
 
     // W operands of the first two steps (the loop expands those of step s + 2 during step s)
 #pragma unroll
     for (int s = 0; s < 2; ++s) {
         const uint32_t entry = s_vl[2 * s + h];
         const uint32_t kb = min(entry & 1023u, (uint32_t)KB - 1u);
-        const uint4 c = *reinterpret_cast<const uint4*>(wcodes + w_row_codes + kb * 16u);
+        const uint4 c = *reinterpret_cast<const uint4*>(wcodes + w_row_codes + kb * 512u);
         const uint32_t meta = *reinterpret_cast<const uint32_t*>(wmeta + ((entry >> 12) & 3u) * p.wmeta_cls_stride +
-                                                                 w_row_meta + kb * 4u);
+                                                                 w_row_meta + kb * 128u);
         const uint4 tab = *reinterpret_cast<const uint4*>(reinterpret_cast<const uint8_t*>(s_tab) + meta);
         *reinterpret_cast<v4i*>(&s_b[s][(wave * 2 + 0) * 1024 + lane * 16]) = unpack16(c.x, c.y, tab);
         *reinterpret_cast<v4i*>(&s_b[s][(wave * 2 + 1) * 1024 + lane * 16]) = unpack16(c.z, c.w, tab);
@@ -1147,9 +1162,10 @@ __global__ __launch_bounds__(NW * 64) void gemm_rows_kernel(GemmParams p) {
     const uint32_t grp_stride = (uint32_t)(KB + 1) * 1024u;
     const uint64_t cls_stride = (uint64_t)p.tiles_m * kGroups * grp_stride;
     const uint8_t* a8 = ap + p.off_a8 + (uint64_t)(m0 / 32) * grp_stride + (uint32_t)r * 16u;
-    const int ncol = min(n0 + r, p.N - 1);
-    const uint8_t* wcodes = p.w_codes + (uint64_t)ncol * KB * 16u;
-    const uint8_t* wmeta = wp + p.off_wmeta + (uint64_t)ncol * KB * 4u;
+    const int ncol = n0 + r;                            // rows beyond N exist in the prepared W: all-zero tables
+    const uint64_t w_slot = (uint64_t)(ncol >> 5) * KB * 32u + (uint32_t)(ncol & 31);      // [group][block][row]
+    const uint8_t* wcodes = wp + p.off_wcodes + w_slot * 16u;
+    const uint8_t* wmeta = wp + p.off_wmeta + w_slot * 4u;
 
     // this wave's range of block pairs (lane half h takes block 2 * pair + h)
     const int P = (KB + 1) / 2, per = (P + NW - 1) / NW;
@@ -1168,8 +1184,8 @@ __global__ __launch_bounds__(NW * 64) void gemm_rows_kernel(GemmParams p) {
 #pragma unroll
         for (int q = 0; q < kU; ++q) {
             const int kb = 2 * min(g0 + q, p_hi - 1) + h, kbw = min(kb, KB - 1);
-            wc[q] = *reinterpret_cast<const uint4*>(wcodes + (uint32_t)kbw * 16u);
-            meta[q] = *reinterpret_cast<const uint32_t*>(wmeta + (uint32_t)kbw * 4u);          // class 0 of W
+            wc[q] = *reinterpret_cast<const uint4*>(wcodes + (uint32_t)kbw * 512u);
+            meta[q] = *reinterpret_cast<const uint32_t*>(wmeta + (uint32_t)kbw * 128u);        // class 0 of W
             const uint8_t* src = a8 + (uint32_t)min(kb, KB) * 1024u;                          // class 0 of A; KB = zeros
             af[q][0] = *reinterpret_cast<const v4i*>(src);
             af[q][1] = *reinterpret_cast<const v4i*>(src + 512);
@@ -1258,7 +1274,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_rows_kernel(GemmParams p) {
             const uint32_t kbw = (uint32_t)min(kb, KB - 1);
             const uint32_t ma = kb < KB ? mask_a[kb] : 0u, mw = kb < KB ? mask_w[kb] : 0u;
             if (__ballot((ma | mw) > 1u) == 0ull) continue;
-            const uint4 codes = *reinterpret_cast<const uint4*>(wcodes + kbw * 16u);
+            const uint4 codes = *reinterpret_cast<const uint4*>(wcodes + kbw * 512u);
             for (int ct = 1; ct <= kMaxClass; ++ct) {
                 for (int ca = 0; ca <= ct; ++ca) {
                     const int cw = ct - ca;
@@ -1268,7 +1284,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_rows_kernel(GemmParams p) {
                     const v4i x0 = part ? *reinterpret_cast<const v4i*>(src) : zero4;
                     const v4i x1 = part ? *reinterpret_cast<const v4i*>(src + 512) : zero4;
                     const uint32_t mt = *reinterpret_cast<const uint32_t*>(
-                        wmeta + (uint64_t)cw * p.wmeta_cls_stride + kbw * 4u);
+                        wmeta + (uint64_t)cw * p.wmeta_cls_stride + kbw * 128u);
                     const uint4 tab = *reinterpret_cast<const uint4*>(reinterpret_cast<const uint8_t*>(s_tab) + mt);
                     const v4i b0 = unpack16(codes.x, codes.y, tab), b1 = unpack16(codes.z, codes.w, tab);
                     v16i t16 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
@@ -1387,8 +1403,8 @@ void set_prepared(GemmParams& p, uint8_t* a_prep, int64_t a_stride, uint8_t* w_p
     p.a_prep = a_prep; p.a_prep_stride = a_stride;
     p.w_prep = w_prep; p.w_prep_stride = w_stride;
     p.off_refa = la.off_refa; p.off_mask = la.off_mask; p.off_cnt = la.off_cnt; p.off_a8 = la.off_a8;
-    p.off_refw = lw.off_refw; p.off_wmask = lw.off_wmask; p.off_wmeta = lw.off_wmeta;
-    p.wmeta_cls_stride = (uint32_t)((int64_t)p.N * p.KB * 4);
+    p.off_refw = lw.off_refw; p.off_wmask = lw.off_wmask; p.off_wmeta = lw.off_wmeta; p.off_wcodes = lw.off_wcodes;
+    p.wmeta_cls_stride = (uint32_t)((int64_t)p.tiles_n * kTileN * p.KB * 4);
 }
 
 // prepass: A workgroups (when do_a) and W workgroups (when do_w) in one launch

@@ -64,7 +64,7 @@ S_WC, S_WM = 88, 90
 NSLOT = 32
 # Timing experiments only (results are wrong, every address stays the same): a comma-separated list in
 # DFP4_GEN_EXP drops parts of the step -- noexpand (W expansion), nobarrier, noaload (A loads), nobread (LDS reads of B),
-# nomfma (the MFMAs themselves).
+# nomfma (the MFMAs themselves), nowload (loads of W codes and table offsets).
 EXP = set(filter(None, os.environ.get('DFP4_GEN_EXP', '').split(',')))
 FRAG = 1024                    # bytes per operand fragment
 B_BUF_BYTES = 8 * FRAG
@@ -135,8 +135,8 @@ def w_offsets(entry, dst_codes, dst_meta):
     (padding visits read the last block)"""
     return [f"v_and_b32 {vr(T1)}, 0x3ff, {vr(entry)}",
             f"v_min_u32 {vr(T1)}, %[kbm], {vr(T1)}",
-            f"v_lshl_add_u32 {vr(dst_codes)}, {vr(T1)}, 4, %[wrc]",
-            f"v_lshl_add_u32 {vr(dst_meta)}, {vr(T1)}, 2, %[wrm]",
+            f"v_lshl_add_u32 {vr(dst_codes)}, {vr(T1)}, 9, %[wrc]",      # [group][block][row]: 512 bytes of codes
+            f"v_lshl_add_u32 {vr(dst_meta)}, {vr(T1)}, 7, %[wrm]",       # and 128 bytes of table dwords per block
             f"v_bfe_u32 {vr(T0)}, {vr(entry)}, 12, 2",
             f"v_mul_lo_u32 {vr(T0)}, {vr(T0)}, %[wcs]",
             f"v_add_u32 {vr(dst_meta)}, {vr(dst_meta)}, {vr(T0)}"]
@@ -169,9 +169,9 @@ def vm_order():
     for k in range(NSLOT):
         if k in slots and "noaload" not in EXP:
             o.append(f"A{slots[k]}")
-        if k == CODES_SLOT:
+        if k == CODES_SLOT and "nowload" not in EXP:
             o.append("codes")
-        if k == META_SLOT:
+        if k == META_SLOT and "nowload" not in EXP:
             o.append("meta")
     return o
 
@@ -224,6 +224,8 @@ def entry_code():
             o.append(al[int(tag[1:])] if tag[0] == "A" else
                      f"global_load_dwordx4 {vr(CODES[p], 4)}, {vr(VCOFF)}, {sr(S_WC, 2)}" if tag == "codes" else
                      f"global_load_dword {vr(META[p])}, {vr(VMOFF)}, {sr(S_WM, 2)}")
+    if "nowload" in EXP:                             # the registers the loads would have filled: zeros
+        o += [f"v_mov_b32 {vr(r)}, 0" for r in list(range(CODES[0], CODES[2] + 4)) + META]
     # offsets of the loads of step 0 (A of pair 2, W of pair 4)
     o += [f"ds_read_u16 {vr(EA)}, {vr(VLADDR)} offset:8", f"ds_read_u16 {vr(EW)}, {vr(VLADDR)} offset:16",
           "s_waitcnt lgkmcnt(0)"]
@@ -259,7 +261,8 @@ def step(v, u=None):
     # start: the W codes now, the table offset at slot 3, A fragment f before MFMA slot 4 f.
     a_load_slot = A_LOAD_SLOT
     vm = Vm()
-    o.append(vm.need("codes"))
+    if "nowload" not in EXP:
+        o.append(vm.need("codes"))
     first, second = expansion_pieces(v)
     loads = a_loads(ld, VOFF)
     b_reads = {2: (1, 0), 6: (1, 1), 10: (1, 2), 14: (1, 3), 16: (0, 0), 20: (0, 1), 24: (0, 2), 27: (0, 3)}
@@ -313,15 +316,15 @@ def step(v, u=None):
         if k in a_load_slot and "noaload" not in EXP:
             o.append(loads[a_load_slot[k]])
             vm.issue()
-        if k == CODES_SLOT:
+        if k == CODES_SLOT and "nowload" not in EXP:
             o.append(f"global_load_dwordx4 {vr(CODES[ld], 4)}, {vr(VCOFF)}, {sr(S_WC, 2)}")
             vm.issue()
-        if k == META_SLOT:
+        if k == META_SLOT and "nowload" not in EXP:
             o.append(f"global_load_dword {vr(META[ld])}, {vr(VMOFF)}, {sr(S_WM, 2)}")
             vm.issue()
         if piece:
             o.append(piece[1])
-        if k == 3:                                    # the table offset of this step's expansion
+        if k == 3 and "nowload" not in EXP:           # the table offset of this step's expansion
             w = vm.need("meta")
             if w:
                 o.append(w)
