@@ -196,6 +196,27 @@ class Vm:
         return f"s_waitcnt vmcnt({(n - 1 - i) + n + self.issued})"
 
 
+# Timing experiment (DFP4_GEN_ADIST=3): A fragments three steps ahead instead of two, without a fourth
+# register set -- fragment f of the set a step multiplies with is loaded again, for the step three
+# later, right after its last MFMA (slot 4 f + 5; fragment 7 at slot 1 of the next step).
+ADIST3 = os.environ.get('DFP4_GEN_ADIST') == '3'
+ORDER3 = ["A7", "A0", "A1", "codes", "A2", "meta", "A3", "A4", "A5", "A6"]      # issue order of a step
+SLOT3 = {1: 7, 5: 0, 9: 1, 13: 2, 17: 3, 21: 4, 25: 5, 29: 6}
+
+
+class Vm3:
+    def __init__(self):
+        self.issued = 0
+
+    def issue(self):
+        self.issued += 1
+
+    def need(self, tag):
+        ago = 3 if tag[0] == "A" and tag != "A7" else 2
+        i, n = ORDER3.index(tag), len(ORDER3)
+        return f"s_waitcnt vmcnt({(n - 1 - i) + (ago - 1) * n + self.issued})"
+
+
 def entry_code():
     o = []
     # global bases of the wave's 8 A fragments: a8w + gi * group stride + t * 512
@@ -214,22 +235,32 @@ def entry_code():
           f"v_add_u32 {vr(VLADDR)}, %[vlb], %[h2]"]
     o += [f"s_mov_b32 {sr(S_VC)}, 0", f"s_mov_b32 {sr(S_SEG)}, 0", f"s_mov_b32 {sr(S_SEGEND)}, %[e2]"]
     # pipeline fill: A of pairs 0, 1; W codes and table offsets of pairs 2, 3
-    for p in range(2):
+    for p in range(3 if ADIST3 else 2):
         o += [f"ds_read_u16 {vr(EA)}, {vr(VLADDR)} offset:{4 * p}",
               f"ds_read_u16 {vr(EW)}, {vr(VLADDR)} offset:{4 * (p + 2)}",
               "s_waitcnt lgkmcnt(0)"]
         o += a_offset(EA, VOFF) + w_offsets(EW, VCOFF, VMOFF)
         al = a_loads(p, VOFF)
+        if p == 2:
+            o += al
+            continue
         for tag in vm_order():                         # same order as inside a step: the waits count on it
             o.append(al[int(tag[1:])] if tag[0] == "A" else
                      f"global_load_dwordx4 {vr(CODES[p], 4)}, {vr(VCOFF)}, {sr(S_WC, 2)}" if tag == "codes" else
                      f"global_load_dword {vr(META[p])}, {vr(VMOFF)}, {sr(S_WM, 2)}")
     if "nowload" in EXP:                             # the registers the loads would have filled: zeros
         o += [f"v_mov_b32 {vr(r)}, 0" for r in list(range(CODES[0], CODES[2] + 4)) + META]
-    # offsets of the loads of step 0 (A of pair 2, W of pair 4)
-    o += [f"ds_read_u16 {vr(EA)}, {vr(VLADDR)} offset:8", f"ds_read_u16 {vr(EW)}, {vr(VLADDR)} offset:16",
-          "s_waitcnt lgkmcnt(0)"]
-    o += a_offset(EA, VOFF) + w_offsets(EW, VCOFF, VMOFF)
+    if ADIST3:
+        # everything loaded so far has arrived (the experiment pays one memory latency per tile for it);
+        # VOFF stays that of pair 2 (slot 1 of step 0 loads its fragment 7 once more), EA = visit of step 3
+        o += ["s_waitcnt vmcnt(0)", f"ds_read_u16 {vr(EW)}, {vr(VLADDR)} offset:16", "s_waitcnt lgkmcnt(0)"]
+        o += w_offsets(EW, VCOFF, VMOFF)
+        o += [f"ds_read_u16 {vr(EA)}, {vr(VLADDR)} offset:12", "s_waitcnt lgkmcnt(0)"]
+    else:
+        # offsets of the loads of step 0 (A of pair 2, W of pair 4)
+        o += [f"ds_read_u16 {vr(EA)}, {vr(VLADDR)} offset:8", f"ds_read_u16 {vr(EW)}, {vr(VLADDR)} offset:16",
+              "s_waitcnt lgkmcnt(0)"]
+        o += a_offset(EA, VOFF) + w_offsets(EW, VCOFF, VMOFF)
     # B fragments of step 0, phase 0
     o.append(f"v_add_u32 {vr(SB)}, {sr(S_BCUR)}, %[l16]")
     for n in range(4):
@@ -250,7 +281,8 @@ def step(v, u=None):
     # be in flight (next-phase B fragments read from slot 16 on, the two writes of expanded operands):
     # they are waited for where this step first needs them, not at the step boundary.
     lg = Lgkm()
-    lg.q = ["p:" + t for t in LDS_TAIL]
+    tail = ["b00", "b01", "w0", "b02", "b03", "ea", "w1"] if ADIST3 else LDS_TAIL
+    lg.q = ["p:" + t for t in tail]
     ld = (v + 2) % 3
     u = v if u is None else u
     # the common path falls through; the end of a class segment (three times per tile) is handled out of line
@@ -259,17 +291,19 @@ def step(v, u=None):
     o.append(f"1{u}:")
     # Loads issued two steps ago are waited for where they are first used, not all at the step's
     # start: the W codes now, the table offset at slot 3, A fragment f before MFMA slot 4 f.
-    a_load_slot = A_LOAD_SLOT
-    vm = Vm()
+    a_load_slot = SLOT3 if ADIST3 else A_LOAD_SLOT
+    vm = Vm3() if ADIST3 else Vm()
     if "nowload" not in EXP:
         o.append(vm.need("codes"))
     first, second = expansion_pieces(v)
     loads = a_loads(ld, VOFF)
+    if ADIST3:                  # this step's own set, except fragment 7: that of the previous step's set
+        loads = a_loads(v, VOFF)[:7] + [a_loads(ld, VOFF)[7]]
     b_reads = {2: (1, 0), 6: (1, 1), 10: (1, 2), 14: (1, 3), 16: (0, 0), 20: (0, 1), 24: (0, 2), 27: (0, 3)}
     extra = {
         0: [f"v_add_u32 {vr(SB)}, {sr(S_BCUR)}, %[l16]", f"v_add_u32 {vr(SBN)}, {sr(S_BNXT)}, %[l16]"],
         1: [f"v_add_u32 {vr(SBW)}, {sr(S_BW)}, {vr(L16W)}"],
-        3: [f"ds_read_u16 {vr(EA)}, {vr(VLADDR)} offset:12", f"ds_read_u16 {vr(EW)}, {vr(VLADDR)} offset:20",
+        3: ([] if ADIST3 else [f"ds_read_u16 {vr(EA)}, {vr(VLADDR)} offset:12"]) + [f"ds_read_u16 {vr(EW)}, {vr(VLADDR)} offset:20",
             f"v_add_u32 {vr(TABADDR)}, %[tabb], {vr(META[v])}", f"ds_read_b128 {vr(TAB0, 4)}, {vr(TABADDR)}"],
         4: [f"s_mov_b32 {sr(S_T0)}, {sr(S_BCUR)}", f"s_mov_b32 {sr(S_BCUR)}, {sr(S_BNXT)}",
             f"s_mov_b32 {sr(S_BNXT)}, {sr(S_BW)}", f"s_mov_b32 {sr(S_BW)}, {sr(S_T0)}"],
@@ -278,10 +312,9 @@ def step(v, u=None):
         # waited for at its end) and has finished reading the buffer this step overwrites
         12: [] if "nobarrier" in EXP else ["s_barrier"],
     }
-    if "skew" in EXP:      # timing experiment: after the barrier wave w idles about 20 w cycles
-        extra[12] = extra[12] + [f"s_mov_b32 {sr(S_T1)}, %[wv]", f"7{v}:", f"s_cmp_eq_u32 {sr(S_T1)}, 0",
-                                 f"s_cbranch_scc1 8{v}f", "s_nop 15", f"s_sub_u32 {sr(S_T1)}, {sr(S_T1)}, 1",
-                                 f"s_branch 7{v}b", f"8{v}:"]
+    if ADIST3:
+        extra[2] = a_offset(EA, VOFF)                 # after fragment 7 of the previous visit (slot 1)
+        extra[28] = [f"ds_read_u16 {vr(EA)}, {vr(VLADDR)} offset:12"]     # the visit three steps after the next
     for k in range(NSLOT):
         t, gi, n = k // 16, (k % 16) // 4, k % 4
         if k >= 16:
@@ -332,6 +365,10 @@ def step(v, u=None):
             w = lg.need("p:w1")
             if w:
                 o.append(w)
+        if k == 2 and ADIST3:
+            w = lg.need("p:ea")
+            if w:
+                o.append(w)
         for ins in extra.get(k, []):
             o.append(ins)
             if ins.startswith("ds_read_u16") or ins.startswith("ds_read_b128"):
@@ -346,11 +383,12 @@ def step(v, u=None):
             w = lg.need("ew")
             if w:
                 o.append(w)
-            o += a_offset(EA, VOFF)
+            if not ADIST3:
+                o += a_offset(EA, VOFF)
         if k == 31:
             o += w_offsets(EW, VCOFF, VMOFF)
-    # what is still in flight here is what the next step expects (LDS_TAIL)
-    assert lg.q == LDS_TAIL, (lg.q, LDS_TAIL)
+    # what is still in flight here is what the next step expects
+    assert lg.q == tail, (lg.q, tail)
     return o
 
 
