@@ -210,7 +210,9 @@ size_t dfp4_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
  *   is_weight == 0   T is an A operand [M, K] (online, once per activation tensor, however
  *                    many products consume it: gate and up projections share one)
  *   prepared         device, 256-byte aligned, at least dfp4_gemm_prepared_bytes(rows, K,
- *                    is_weight) bytes; the layout is private to the library.  A size of 0
+ *                    is_weight) bytes; the layout is private to the library (for a weight:
+ *                    a copy of the codes and three table words per block, both in the order
+ *                    the kernels read them, about 0.9 bytes per element).  A size of 0
  *                    means nothing is prepared for this operand (K > 16384): NULL may be
  *                    passed then.
  * dfp4_gemm_prepared multiplies.  The quantized tensors are still passed: paths that do not
