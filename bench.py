@@ -222,6 +222,8 @@ def main():
 
     # register-only int8 MFMA loop in a child process, before this process touches the GPU
     peak = None if args.no_helpers else run_helper("mfma_peak")
+    # and what fits in an MFMA's shadow for the lone wave per SIMD the GEMM's main loop runs (ns per MFMA)
+    shadow = None if args.no_helpers else run_helper("mfma_shadow")
 
     import torch
     from paper_2501_01144_amd import dfp4, synth
@@ -357,6 +359,8 @@ def main():
             if more is not None and "sampled_gemm_operands" in more:
                 peak["sampled_gemm_operands"] = more["sampled_gemm_operands"]
             out["roofline"]["measured_mfma_loop"] = peak
+            if shadow is not None:
+                out["roofline"]["measured_mfma_shadow"] = shadow
             out["roofline"]["frac_of_measured_random_int8_loop"] = round(
                 gemm_tops / peak["random_int8_operands"]["TOPs"], 4)
             if "sampled_gemm_operands" in peak:

@@ -120,9 +120,9 @@ def build_library(verbose=True):
     gemm_s = os.path.join(objdir, "gemm.s")
     cmd = [hipcc, *FLAGS, "-S", "--cuda-device-only", os.path.join(CSRC, "gemm.hip"), "-o", gemm_s]
     procs.append(("gemm.hip (assembly)", subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
-    # measurement helpers used by bench.py: register-only int8 MFMA loop, plain streaming kernels
-    for name in ("mfma_peak", "stream_peak"):
-        cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", os.path.join(HELPERS, name + ".hip"),
+    # measurement helpers used by bench.py: register-only int8 MFMA loops, plain streaming kernels
+    for name in ("mfma_peak", "stream_peak", "mfma_shadow"):
+        cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Wno-inline-asm", os.path.join(HELPERS, name + ".hip"),
                "-o", os.path.join(HELPERS, name)]
         if verbose:
             print(" ".join(cmd), flush=True)
