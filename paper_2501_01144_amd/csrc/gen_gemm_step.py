@@ -196,11 +196,14 @@ class Vm:
         return f"s_waitcnt vmcnt({(n - 1 - i) + n + self.issued})"
 
 
-# Timing experiment (DFP4_GEN_ADIST=3): A fragments three steps ahead instead of two, without a fourth
+# Timing experiment (DFP4_GEN_ADIST=3): every load three steps ahead instead of two, without a fourth
 # register set -- fragment f of the set a step multiplies with is loaded again, for the step three
-# later, right after its last MFMA (slot 4 f + 5; fragment 7 at slot 1 of the next step).
+# later, right after its last MFMA (slot 4 f + 5; fragment 7 at slot 1 of the next step), and the
+# W codes and table offset of the set a step expands at slot 16, once the expansion has read them.
+# Results are bit-identical to the default schedule; measured, it is no faster (the pipeline fill of
+# this variant waits for all its loads once per tile, which costs about what the deeper prefetch gains).
 ADIST3 = os.environ.get('DFP4_GEN_ADIST') == '3'
-ORDER3 = ["A7", "A0", "A1", "codes", "A2", "meta", "A3", "A4", "A5", "A6"]      # issue order of a step
+ORDER3 = ["A7", "A0", "A1", "A2", "codes", "meta", "A3", "A4", "A5", "A6"]      # issue order of a step
 SLOT3 = {1: 7, 5: 0, 9: 1, 13: 2, 17: 3, 21: 4, 25: 5, 29: 6}
 
 
@@ -212,7 +215,8 @@ class Vm3:
         self.issued += 1
 
     def need(self, tag):
-        ago = 3 if tag[0] == "A" and tag != "A7" else 2
+        ago = 2 if tag == "A7" else 3                 # codes and table offsets too: their set is loaded
+                                                      # again at slot 16, once the expansion has read it
         i, n = ORDER3.index(tag), len(ORDER3)
         return f"s_waitcnt vmcnt({(n - 1 - i) + (ago - 1) * n + self.issued})"
 
@@ -242,7 +246,8 @@ def entry_code():
         o += a_offset(EA, VOFF) + w_offsets(EW, VCOFF, VMOFF)
         al = a_loads(p, VOFF)
         if p == 2:
-            o += al
+            o += al + [f"global_load_dwordx4 {vr(CODES[p], 4)}, {vr(VCOFF)}, {sr(S_WC, 2)}",
+                       f"global_load_dword {vr(META[p])}, {vr(VMOFF)}, {sr(S_WM, 2)}"]
             continue
         for tag in vm_order():                         # same order as inside a step: the waits count on it
             o.append(al[int(tag[1:])] if tag[0] == "A" else
@@ -253,9 +258,7 @@ def entry_code():
     if ADIST3:
         # everything loaded so far has arrived (the experiment pays one memory latency per tile for it);
         # VOFF stays that of pair 2 (slot 1 of step 0 loads its fragment 7 once more), EA = visit of step 3
-        o += ["s_waitcnt vmcnt(0)", f"ds_read_u16 {vr(EW)}, {vr(VLADDR)} offset:16", "s_waitcnt lgkmcnt(0)"]
-        o += w_offsets(EW, VCOFF, VMOFF)
-        o += [f"ds_read_u16 {vr(EA)}, {vr(VLADDR)} offset:12", "s_waitcnt lgkmcnt(0)"]
+        o += ["s_waitcnt vmcnt(0)", f"ds_read_u16 {vr(EA)}, {vr(VLADDR)} offset:12", "s_waitcnt lgkmcnt(0)"]
     else:
         # offsets of the loads of step 0 (A of pair 2, W of pair 4)
         o += [f"ds_read_u16 {vr(EA)}, {vr(VLADDR)} offset:8", f"ds_read_u16 {vr(EW)}, {vr(VLADDR)} offset:16",
@@ -349,11 +352,12 @@ def step(v, u=None):
         if k in a_load_slot and "noaload" not in EXP:
             o.append(loads[a_load_slot[k]])
             vm.issue()
-        if k == CODES_SLOT and "nowload" not in EXP:
-            o.append(f"global_load_dwordx4 {vr(CODES[ld], 4)}, {vr(VCOFF)}, {sr(S_WC, 2)}")
+        wset = v if ADIST3 else ld
+        if k == (16 if ADIST3 else CODES_SLOT) and "nowload" not in EXP:
+            o.append(f"global_load_dwordx4 {vr(CODES[wset], 4)}, {vr(VCOFF)}, {sr(S_WC, 2)}")
             vm.issue()
-        if k == META_SLOT and "nowload" not in EXP:
-            o.append(f"global_load_dword {vr(META[ld])}, {vr(VMOFF)}, {sr(S_WM, 2)}")
+        if k == (16 if ADIST3 else META_SLOT) and "nowload" not in EXP:
+            o.append(f"global_load_dword {vr(META[wset])}, {vr(VMOFF)}, {sr(S_WM, 2)}")
             vm.issue()
         if piece:
             o.append(piece[1])
@@ -379,13 +383,13 @@ def step(v, u=None):
         if k == 28:
             o.append(f"ds_write_b128 {vr(SBW)}, {vr(OUT0 + 4, 4)} offset:{FRAG}")
             lg.issue("w1")
-        if k == 30:                                   # after the last A load of this step
+        if k == (13 if ADIST3 else 30):               # after the last A load of this step
             w = lg.need("ew")
             if w:
                 o.append(w)
             if not ADIST3:
                 o += a_offset(EA, VOFF)
-        if k == 31:
+        if k == (13 if ADIST3 else 31):
             o += w_offsets(EW, VCOFF, VMOFF)
     # what is still in flight here is what the next step expects
     assert lg.q == tail, (lg.q, tail)
