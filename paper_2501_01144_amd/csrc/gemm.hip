@@ -656,6 +656,9 @@ __global__ __launch_bounds__(256, 1) void gemm_fast_kernel(GemmParams p) {
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
 #ifdef DFP4_TIMING_STAMPS   // timing experiments only: 100 MHz timestamps of the kernel's phases, into the workspace
+#ifndef DFP4_STAMP_ROW      // which row of tiles (blockIdx.y) writes them
+#define DFP4_STAMP_ROW 0
+#endif
 #define DFP4_STAMP(I)                                                                                   \
     if (tid == 0 && p.ksplit == 1 && p.part && blockIdx.y == (DFP4_STAMP_ROW) && blockIdx.z == 0 && blockIdx.x < 64)   \
         reinterpret_cast<unsigned long long*>(p.part)[blockIdx.x * 8 + (I)] = wall_clock64();
