@@ -142,8 +142,12 @@ def w_offsets(entry, dst_codes, dst_meta):
             f"v_add_u32 {vr(dst_meta)}, {vr(dst_meta)}, {vr(T0)}"]
 
 
+AFLAGS = os.environ.get('DFP4_GEN_AFLAGS', '')        # timing experiments: cache-policy bits of the A loads
+
+
 def a_loads(aset, voff):
-    return [f"global_load_dwordx4 {vr(ASET[aset] + 4 * f, 4)}, {vr(voff)}, {sr(S_ABASE + 2 * f, 2)}" for f in range(8)]
+    return [f"global_load_dwordx4 {vr(ASET[aset] + 4 * f, 4)}, {vr(voff)}, {sr(S_ABASE + 2 * f, 2)}" + (" " + AFLAGS if AFLAGS else "")
+            for f in range(8)]
 
 
 # Slots (MFMA index within the step) after which the vector-memory loads of a step are issued.
