@@ -682,9 +682,27 @@ __global__ __launch_bounds__(256, 1) void gemm_fast_kernel(GemmParams p) {
     const int kb_lo = sidx * kb_per, kb_hi = min(KB, kb_lo + kb_per);
 
     // ---- prologue: tables, references, list of (block, class of A, class of W) visits
-    for (int i = tid; i < kDialects * 16 + 4; i += 256) s_tab[i] = i < kDialects * 16 ? (&g_shifted_book.w[0][0][0])[i] : 0u;
-    for (int i = tid; i < kTileM; i += 256) s_refa[i] = ap[p.off_refa + m0 + i];
-    if (tid < kTileN) s_refw[tid] = n0 + tid < p.N ? wp[p.off_refw + n0 + tid] : 0;
+    // every global load of the prologue is issued before the first value is used: one memory round trip, not four
+    const uint8_t* mask_a = ap + p.off_mask + (int64_t)ty * KB;
+    const uint8_t* mask_w = wp + p.off_wmask + (int64_t)tx * KB;
+    uint32_t ma[kMaxKB / 64], mw[kMaxKB / 64];
+    if (wave == 0) {
+#pragma unroll
+        for (int j = 0; j < kMaxKB / 64; ++j) {
+            const int kb = j * 64 + lane;
+            ma[j] = kb < KB ? mask_a[kb] : 0u;
+            mw[j] = kb < KB ? mask_w[kb] : 0u;
+        }
+    }
+    static_assert(kDialects * 16 == 256 && kTileM == 512, "one table word and two reference bytes per thread");
+    const uint32_t tab_word = (&g_shifted_book.w[0][0][0])[tid];
+    const uint8_t refa0 = ap[p.off_refa + m0 + tid], refa1 = ap[p.off_refa + m0 + 256 + tid];   // rows padded to 512
+    const uint8_t refw0 = tid < kTileN && n0 + tid < p.N ? wp[p.off_refw + n0 + tid] : (uint8_t)0;
+    s_tab[tid] = tab_word;
+    if (tid < 4) s_tab[kDialects * 16 + tid] = 0u;
+    s_refa[tid] = refa0;
+    s_refa[256 + tid] = refa1;
+    if (tid < kTileN) s_refw[tid] = refw0;
     if (tid < 8) s_ctl[tid] = 0;
     if (wave == 0) {
         // A block is visited once for every pair (class present among the tile's 512 rows of A, class
@@ -693,15 +711,9 @@ __global__ __launch_bounds__(256, 1) void gemm_fast_kernel(GemmParams p) {
         // receive.  The list holds the visits of this workgroup's range of blocks; whether the tile
         // can be taken at all is decided from ALL blocks, so that every workgroup sharing the tile
         // decides the same.
-        const uint8_t* mask_a = ap + p.off_mask + (int64_t)ty * KB;
-        const uint8_t* mask_w = wp + p.off_wmask + (int64_t)tx * KB;
-        uint32_t ma[kMaxKB / 64], mw[kMaxKB / 64];
         bool bad = false;
 #pragma unroll
         for (int j = 0; j < kMaxKB / 64; ++j) {
-            const int kb = j * 64 + lane;
-            ma[j] = kb < KB ? mask_a[kb] : 0u;
-            mw[j] = kb < KB ? mask_w[kb] : 0u;
             // highest classes present: their sum must not exceed the classes kept
             const int ha = 31 - __builtin_clz(ma[j] | 1u), hw = 31 - __builtin_clz(mw[j] | 1u);
             bad |= ha + hw > kMaxClass;
