@@ -219,9 +219,10 @@ size_t dfp4_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
  * use the prepared form read them.  a_prepared is written to (arrival counters of tiles
  * whose K is split between workgroups), so one prepared A serves one product at a time:
  * products on one stream are ordered by the stream, products that may overlap in time need
- * their own prepared copy.  Results are bit-identical to dfp4_gemm, except for products with
- * at most 64 rows of A: there dfp4_gemm adds one fp32 term per block, while the prepared
- * form lets the few-rows kernel use the exact scheme too (one rounding of the exact sum).
+ * their own prepared copy.  Results are bit-identical to dfp4_gemm, except possibly for
+ * products with at most 64 rows of A: there both take the exact scheme (one rounding of the
+ * exact sum) where the exponents allow it, but dfp4_gemm decides that per 32 x 32 output
+ * tile from the tile's own rows, and a tile it cannot take gets one fp32 term per block.
  *   workspace   at least dfp4_gemm_prepared_workspace_bytes(M, N, K) bytes (partial tiles
  *               where K is split; 0 for products with many output tiles), 256-byte aligned
  * Limits: ceil(rows / 512) * (K/32 + 1) * 49152 < 2^31 for A, rows * K / 2 < 2^31 for W

@@ -51,7 +51,9 @@
 //                        operands (decode shapes): 32 x 32 outputs per workgroup, its 16
 //                        (or 8) waves share K; no list of visits, the class pairs other
 //                        than (0, 0) are added with their weights afterwards;
-//   gemm_small_kernel    at most 64 rows of A, nothing prepared: per-block fp32 flush;
+//   gemm_small_kernel    at most 64 rows of A, nothing prepared: the exact scheme with the tile's
+//                        own reference exponents found in the kernel; per-block fp32 flush
+//                        for a tile whose exponents spread too far;
 //   gemm_block_kernel    whole products with K > 16384: per-block fp32 flush;
 //   gemm_block16_kernel  operands quantized in blocks of 16: per-block fp32 flush.
 //
@@ -1036,10 +1038,11 @@ __global__ __launch_bounds__(256, 1) void gemm_fast_kernel(GemmParams p) {
 // ---------------------------------------------------------------------------
 // Few rows of A (decode shapes, M <= 64): W is streamed once per 32 rows of A and
 // the time goes into expanding W, so the tile is 32 (A rows) x 32 (W rows) per
-// workgroup and the workgroup's 16 waves share K: wave w takes a contiguous range
-// of blocks, multiplies block by block (one MFMA each) and applies the exponent
-// pair per block in fp32 as the paper does; the 16 partial tiles are added in a
-// fixed order through LDS.  No prepass and no workspace.
+// workgroup and the workgroup's 16 (or 8) waves share K: wave w takes a contiguous
+// range of blocks and multiplies block by block (one MFMA each); the partial tiles
+// are added in a fixed order through LDS.  No prepass and no workspace.
+// small_tile() applies the exponent pair per block in fp32 as the paper does;
+// small_exact_tile() (tried first) folds the exponents into the operands instead.
 // ---------------------------------------------------------------------------
 constexpr int kSmallWaves = 16;     // waves of a workgroup, at most (LDS is laid out for this many)
 constexpr int kSmallMaxKB = 512;      // LDS holds the 32 rows' exponent bytes of all blocks
@@ -1141,10 +1144,161 @@ __device__ __forceinline__ void small_tile(const GemmParams& p, int64_t bz, int 
     }
 }
 
+// The same tile with the exact scheme of the large kernel, nothing prepared: the workgroup finds the
+// reference exponents of its 32 rows of A and 32 rows of W itself (both tiles' exponent bytes go to
+// LDS), folds each block's offset into the int8 operands (shift) and a class (weight 16^class sum),
+// and sums all of K in int32 -- no floating-point work per block, which is what bounds small_tile().
+// Blocks whose rows are all of class 0 on both sides (the common case) take one MFMA; others take one
+// per pair of classes present, rows of other classes zeroed, added with the pair's weight.  Returns
+// false, having stored nothing, when the exponents spread beyond what an int32 sum can hold (decided
+// from the largest offsets of the two tiles, the same for every thread): small_tile() computes the tile.
+struct SmallExactLds {
+    __attribute__((aligned(16))) uint32_t tab[kDialects * 16 + 4];     // [dialect][shift] tables
+    __attribute__((aligned(16))) uint8_t ea[kSmallMaxKB * 32];         // [block][row] exponent bytes of A
+    __attribute__((aligned(16))) uint8_t ew[kSmallMaxKB * 32];         // and of W; later the partial tiles
+    int mn[64], mx[64];                                                // per row of A (0..31) and of W (32..63)
+};
+static_assert(sizeof(int) * (kSmallWaves / 2) * 16 * 64 <= 2 * kSmallMaxKB * 32, "partial tiles reuse ea and ew");
+
+template <bool MX, bool BF16, int NW>
+__device__ __forceinline__ bool small_exact_tile(const GemmParams& p, int64_t bz, int m0, int n0, SmallExactLds& lds) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int h = lane >> 5, r = lane & 31;
+    const int KB = p.KB;
+    const int64_t a_row0 = bz * p.strideA_rows, w_row0 = bz * p.strideW_rows;
+    const int64_t arow = a_row0 + min(m0 + r, p.M - 1), wrow = w_row0 + min(n0 + r, p.N - 1);
+    const uint8_t* ac = p.a_codes + arow * KB * 16 + h * 8;
+    const uint8_t* wc = p.w_codes + wrow * KB * 16 + h * 8;
+    const uint8_t* ad = MX ? nullptr : p.a_dial + arow * KB;
+    const uint8_t* wd = MX ? nullptr : p.w_dial + wrow * KB;
+    const int per = (KB + NW - 1) / NW;
+    const int kb_lo = wave * per, kb_hi = min(KB, kb_lo + per);
+
+    for (int i = tid; i < kDialects * 16 + 4; i += NW * 64) lds.tab[i] = i < kDialects * 16 ? (&g_shifted_book.w[0][0][0])[i] : 0u;
+    for (int i = tid; i < 32 * KB; i += NW * 64) {
+        const int row = i / KB, kb = i - row * KB;
+        lds.ea[kb * 32 + row] = p.a_exp[(a_row0 + min(m0 + row, p.M - 1)) * KB + kb];
+        lds.ew[kb * 32 + row] = p.w_exp[(w_row0 + min(n0 + row, p.N - 1)) * KB + kb];
+    }
+    if (tid < 64) {
+        lds.mn[tid] = 255;
+        lds.mx[tid] = 0;
+    }
+    __syncthreads();
+    {
+        // smallest and largest exponent byte of every row: thread (row, part) scans every (2 NW)-th block
+        const int row = tid & 31, part = tid >> 5;
+        int amn = 255, amx = 0, wmn = 255, wmx = 0;
+        for (int kb = part; kb < KB; kb += 2 * NW) {
+            const int a = lds.ea[kb * 32 + row], w = lds.ew[kb * 32 + row];
+            amn = min(amn, a); amx = max(amx, a);
+            wmn = min(wmn, w); wmx = max(wmx, w);
+        }
+        if (part < KB) {
+            atomicMin(&lds.mn[row], amn); atomicMax(&lds.mx[row], amx);
+            atomicMin(&lds.mn[32 + row], wmn); atomicMax(&lds.mx[32 + row], wmx);
+        }
+    }
+    __syncthreads();
+    {
+        // Can every class pair that may occur be taken, and the worst-case sum be held?  From the largest
+        // offsets only: classes up to ca_max and cw_max may meet in any block.
+        int da = 0, dw = 0;
+        for (int i = 0; i < 32; ++i) {
+            da = max(da, lds.mx[i] - lds.mn[i]);
+            dw = max(dw, lds.mx[32 + i] - lds.mn[32 + i]);
+        }
+        const int ca_max = da >> 2, cw_max = dw >> 2;
+        if (ca_max + cw_max > kMaxClass) return false;
+        int per_block = 0;
+        for (int ca = 0; ca <= ca_max; ++ca)
+            for (int cw = 0; cw <= cw_max; ++cw) per_block += 1 << (4 * (ca + cw));
+        if (per_block * KB > kIntBound) return false;
+    }
+    const int refa = lds.mn[r], refw = lds.mn[32 + r];
+
+    v16i acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+    const v4i zero4 = {0, 0, 0, 0};
+    constexpr int kU = 4;              // blocks whose loads are issued together
+    for (int kb0 = kb_lo; kb0 < kb_hi; kb0 += kU) {
+        uint2 ca[kU], cw[kU];
+        uint32_t da[kU], dw[kU];
+#pragma unroll
+        for (int u = 0; u < kU; ++u) {
+            const int kb = min(kb0 + u, kb_hi - 1);            // the tail repeats the last block (not used)
+            ca[u] = *reinterpret_cast<const uint2*>(ac + (int64_t)kb * 16);
+            cw[u] = *reinterpret_cast<const uint2*>(wc + (int64_t)kb * 16);
+            da[u] = MX ? 7u : ((uint32_t)ad[kb] & 15u);
+            dw[u] = MX ? 7u : ((uint32_t)wd[kb] & 15u);
+        }
+#pragma unroll
+        for (int u = 0; u < kU; ++u) {
+            const int kb = kb0 + u;
+            if (kb >= kb_hi) break;                            // wave-uniform
+            const int oa = (int)lds.ea[kb * 32 + r] - refa, ow = (int)lds.ew[kb * 32 + r] - refw;   // offsets >= 0
+            const int cla = oa >> 2, clw = ow >> 2;
+            const uint4 ta = *reinterpret_cast<const uint4*>(&lds.tab[(da[u] * 4 + (oa & 3)) * 4]);
+            const uint4 tw = *reinterpret_cast<const uint4*>(&lds.tab[(dw[u] * 4 + (ow & 3)) * 4]);
+            const v4i a = unpack16(ca[u].x, ca[u].y, ta), b = unpack16(cw[u].x, cw[u].y, tw);
+            if (__ballot((cla | clw) != 0) == 0ull) {
+                acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, acc, 0, 0, 0);
+            } else {
+                for (int ct = 0; ct <= kMaxClass; ++ct) {
+                    for (int c1 = 0; c1 <= ct; ++c1) {
+                        const int c2 = ct - c1;
+                        if (__ballot(cla == c1) == 0ull || __ballot(clw == c2) == 0ull) continue;
+                        const v4i pa = cla == c1 ? a : zero4, pb = clw == c2 ? b : zero4;
+                        v16i t16 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+                        t16 = __builtin_amdgcn_mfma_i32_32x32x32_i8(pa, pb, t16, 0, 0, 0);
+#pragma unroll
+                        for (int x = 0; x < 16; ++x) acc[x] += t16[x] << (4 * ct);
+                    }
+                }
+            }
+        }
+    }
+    // the NW exact partial tiles, added through LDS (over the exponent bytes, which are no longer needed)
+    __syncthreads();
+    int (*red)[16][64] = reinterpret_cast<int (*)[16][64]>(lds.ea);
+    if (wave >= NW / 2) {
+#pragma unroll
+        for (int x = 0; x < 16; ++x) red[wave - NW / 2][x][lane] = acc[x];
+    }
+    __syncthreads();
+    if (wave < NW / 2) {
+#pragma unroll
+        for (int x = 0; x < 16; ++x) red[wave][x][lane] += acc[x];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 16 / NW; ++i) {
+        const int x = wave + i * NW;                           // thread (x, lane) finishes one output
+        int sum = 0;
+#pragma unroll
+        for (int w = 0; w < NW / 2; ++w) sum += red[w][x][lane];
+        const int lr = 8 * (x >> 2) + 4 * h + (x & 3), m = m0 + lr, n = n0 + r;
+        if (m < p.M && n < p.N) {
+            const float f = ldexpf((float)sum, lds.mn[lr] + lds.mn[32 + r] - 256);
+            const int64_t o = bz * p.strideC + (int64_t)m * p.ldc + n;
+            if constexpr (BF16)
+                static_cast<uint16_t*>(p.out)[o] = f32_to_bf16_rne(f);
+            else
+                static_cast<float*>(p.out)[o] = f;
+        }
+    }
+    return true;
+}
+
 template <bool MX, bool BF16, int NW>
 __global__ __launch_bounds__(NW * 64) void gemm_small_kernel(GemmParams p) {
-    __shared__ SmallTileLds lds;
-    small_tile<MX, BF16, NW>(p, blockIdx.z, (int)blockIdx.y * 32, (int)blockIdx.x * 32, lds);
+    __shared__ union {
+        SmallExactLds exact;
+        SmallTileLds flush;
+    } lds;
+    const int m0 = (int)blockIdx.y * 32, n0 = (int)blockIdx.x * 32;
+    if (small_exact_tile<MX, BF16, NW>(p, blockIdx.z, m0, n0, lds.exact)) return;
+    __syncthreads();
+    small_tile<MX, BF16, NW>(p, blockIdx.z, m0, n0, lds.flush);
 }
 
 // ---------------------------------------------------------------------------

@@ -426,6 +426,24 @@ def test_gemm_few_rows(M, N, K):
     _assert_gemm_close(outm, refm, absm, "few rows mxfp4")
 
 
+@pytest.mark.parametrize("scale,K,exact", [(30.0, 4096, True), (2.0 ** 13, 512, False)])
+def test_gemm_few_rows_both_forms_of_the_tile(scale, K, exact):
+    # Nothing prepared, at most 64 rows: a tile whose exponents allow it is summed exactly in int32 (one
+    # rounding of the exact sum, checked here to half an ulp); a tile with outliers 13 binades above the
+    # rest cannot be and takes one fp32 term per block (held to the usual tolerance).
+    M, N = 32, 96
+    print(f"gemm parity: few rows {M}x{N}x{K}, outliers x{scale}, exact={exact}", flush=True)
+    a = synth.gaussian_outlier_channels(M, K, 4, scale, 1.0, seed=901)
+    w = synth.gaussian(N, K, 0.02, seed=902)
+    ref, absdot = _gemm_ref(synth.to_f64(a), synth.to_f64(w))
+    out = dfp4.gemm(dfp4.quantize(_dev(a)), dfp4.quantize(_dev(w)))
+    torch.cuda.synchronize()
+    _assert_gemm_close(out, ref, absdot, "few rows, both forms")
+    if exact:
+        err = np.abs(out.cpu().double().numpy() - ref)
+        assert (err <= np.abs(ref) * 2.0 ** -24 + 1e-300).all(), "more than one rounding of the exact sum"
+
+
 def test_gemm_very_long_k_takes_block_flush_kernel():
     # K beyond the single-accumulator kernel's range (more than 512 blocks): every tile is
     # computed block by block with fp32 accumulation
