@@ -383,7 +383,7 @@ def main():
             ph = dfp4.gemm_prepare(qhm, weight=False, mx=True, buf=hbuf)
             dfp4.gemm_prepared(ph, wpm["w_down"], out=down, workspace=ws)
 
-        for _ in range(3):
+        for _ in range(60):          # untimed: the clock has to settle after the previous section
             step_mx()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
@@ -422,7 +422,7 @@ def main():
                 if ev is not None:
                     ev[i][1].record()
 
-        for _ in range(3):
+        for _ in range(60):          # untimed: the clock has to settle after the previous section
             step_native()
         torch.cuda.synchronize()
         nev = [_events(len(nnames), torch) if s % EVERY == 0 else None for s in range(nside)]
@@ -462,7 +462,7 @@ def main():
             ph = dfp4.native_pack(qhm, mx=True, buf=nhbuf)
             dfp4.gemm_native_packed(ph, wpm["w_down"], out=down, workspace=ws_n)
 
-        for _ in range(3):
+        for _ in range(60):          # untimed: the clock has to settle after the previous section
             step_native_mx()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
