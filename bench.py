@@ -41,8 +41,25 @@ def _events(n, torch):
     return [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
 
 
+SIDE_RAMP_MS = [0.0]     # set from --ramp-ms: untimed load before every side measurement
+
+
+def settle(fns, torch):
+    """The GPU's clock follows the load with a delay of some hundred milliseconds, and between the sections of
+    this file the GPU idles while the host prepares inputs: run the calls untimed until the clock has settled."""
+    if SIDE_RAMP_MS[0] <= 0:
+        return
+    t0 = time.perf_counter()
+    while (time.perf_counter() - t0) * 1e3 < SIDE_RAMP_MS[0]:
+        for _ in range(4):
+            for fn in fns:
+                fn()
+        torch.cuda.synchronize()
+
+
 def median_ms(fn, torch, n=20, warm=5):
     """Median duration of fn() from HIP events on the launch stream."""
+    settle([fn], torch)
     for _ in range(warm):
         fn()
     ev = _events(n, torch)
@@ -58,6 +75,7 @@ def stream_ms(fns, torch, reps=4, batches=5):
     """Per-call duration of the calls in `fns` issued back to back (reps rounds over the list between
     one pair of HIP events; median over batches).  With a list whose operands together exceed the
     memory-side cache every call finds its operands in HBM, as a decode loop over many layers does."""
+    settle(fns, torch)
     for fn in fns:
         fn()
     ts = []
@@ -220,6 +238,7 @@ def main():
             print(f"bench.py: unknown section {s}", file=sys.stderr)
             sys.exit(2)
 
+    SIDE_RAMP_MS[0] = min(args.ramp_ms, 120.0)
     # register-only int8 MFMA loop in a child process, before this process touches the GPU
     peak = None if args.no_helpers else run_helper("mfma_peak")
     # and what fits in an MFMA's shadow for the lone wave per SIMD the GEMM's main loop runs (ns per MFMA)
@@ -537,6 +556,7 @@ def main():
                 q = dfp4.empty_qtensor(rows, K, dev, mx)
                 nbytes = quant_bytes(rows, K, mx)
                 for mode in ("warm", "cold"):
+                    settle([(lambda b=b: fn(b, out=q)) for b in (bufs if mode == "cold" else bufs[:1])], torch)
                     for i in range(3):
                         fn(bufs[i % nrot if mode == "cold" else 0], out=q)
                     n = 24
